@@ -1,0 +1,199 @@
+"""Benchmark of the ASER per-layer calibration path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c1]
+
+One step = one pass of the whole hot path over one synthetic layer whose inputs already sit in
+HBM: reset statistics, Gram accumulation (+ channel |x| sums), outlier selection / smoothing
+diagonal, per-channel RTN and target T, Cholesky whitening, rank-r truncated SVD and L_A, L_B.
+The default workload is the 4096 x 4096 Llama-7B-shaped projection (N = 32768 bf16 tokens, W4,
+r = 64, f = 32).  Prints ONE JSON line.  The "roofline" object prices the dominant kernel (the
+bf16 MFMA Gram update) by its algorithmic flops N n (n + 1); "cpu_baseline" times the CPU
+oracle on a bounded sample on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "per-layer ASER calibration ms + Gram/GEMM MFMA util %, 4096×4096 layer"
+BF16_PEAK_TFLOPS = 2500.0
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(spec):
+    """The CPU oracle on a reduced layer with the same statistics and the same tokens/channel
+    ratio; every dominant stage is cubic in the size, so time scales with (n / n_sample)^3."""
+    import numpy as np
+    import aser_synth as synth
+    from oracle import aser_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    ns = 1536 if spec.n >= 1536 else spec.n
+    ratio = spec.tokens / spec.n
+    sample = spec.with_(m=max(ns * spec.m // spec.n, 64), n=ns, tokens=int(ns * ratio))
+    W = synth.make_weight(sample)
+    X = synth.activations_as_f32(sample, synth.make_activations(sample))
+    timings = {}
+    t0 = time.perf_counter()
+    orc.calibrate_layer(W, X, sample.bits, min(sample.f, ns), min(sample.r, ns), timings=timings)
+    dt = time.perf_counter() - t0
+    scale = (spec.n / ns) ** 3
+    return {
+        "value": dt * 1e3 * scale, "unit": "ms", "cores": int(threads), "kind": "oracle",
+        "sample": "oracle.calibrate_layer on a %dx%d layer with %d tokens (same statistics), %.1f s measured, "
+                  "scaled by (n/n_sample)^3 = %.2f" % (sample.m, sample.n, sample.tokens, dt, scale),
+        "stages_s_measured": {k: round(v, 3) for k, v in timings.items()},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="c1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import aser_synth as synth
+    import paper_2411_07762_amd as aser
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    spec = synth.CONFIGS[args.config]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    log("generating %s: W %dx%d, X %dx%d %s" % (spec.name, spec.m, spec.n, spec.tokens, spec.n, spec.x_dtype))
+    W_np = synth.make_weight(spec)
+    n_rot = 4                                   # rotate weight buffers so the 256 MB cache does not flatter RTN
+    Ws = [torch.from_numpy(W_np).to(dev) for _ in range(n_rot)]
+    x_np = synth.make_activations(spec)
+    if spec.x_dtype == "bf16":
+        X = torch.from_numpy(x_np.view(np.int16)).to(dev).view(torch.bfloat16)
+    else:
+        X = torch.from_numpy(x_np).to(dev)
+    del x_np
+
+    ctx = aser.Context(0)
+    buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed=True)
+    ctx.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, spec.r))
+    layout = aser.ASER_CODES_INT4_PACKED
+    stage_names = ["reset", "gram", "smooth", "rtn", "whiten", "reconstruct"]
+
+    def step(i, ev=None):
+        W = Ws[i % n_rot]
+
+        def mark(k):
+            if ev is not None:
+                ev[k].record()
+
+        mark(0)
+        buf.reset_statistics()
+        mark(1)
+        ctx.check(aser.aser_gram_accumulate(ctx, X, buf.G, buf.abs_sum, buf.count))
+        mark(2)
+        ctx.check(aser.aser_smooth_outliers(ctx, W, buf.abs_sum, buf.count, buf.f, buf.idx, buf.mdiag))
+        mark(3)
+        ctx.check(aser.aser_quantize_rtn(ctx, W, buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes, buf.scales, buf.T))
+        mark(4)
+        st, info = aser.aser_whiten(ctx, buf.G, buf.mdiag, 0.0, buf.S)
+        ctx.check(st)
+        mark(5)
+        st, err, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma)
+        ctx.check(st)
+        mark(6)
+        return err
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    stage_ms = [0.0] * len(stage_names)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
+        err = step(i, ev)
+        torch.cuda.synchronize()
+        for k in range(6):
+            stage_ms[k] += ev[k].elapsed_time(ev[k + 1])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    stage_ms = [s / args.steps for s in stage_ms]
+
+    # Dominant kernel alone: the Gram MFMA kernel (no statistics pass), HIP events on the launch stream.
+    reps = max(5, args.steps)
+    G2 = torch.zeros_like(buf.G)
+    ctx.check(aser.aser_gram_accumulate(ctx, X, G2))
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        ctx.check(aser.aser_gram_accumulate(ctx, X, G2))
+    e1.record()
+    torch.cuda.synchronize()
+    gram_ms = e0.elapsed_time(e1) / reps
+    gram_flops = float(spec.tokens) * spec.n * (spec.n + 1)
+    gram_tflops = gram_flops / (gram_ms * 1e-3) / 1e12
+
+    # Bandwidth kernel: RTN + target (algorithmic bytes 8.5 m n + 4 m), rotating weight buffers.
+    e0.record()
+    for i in range(reps):
+        ctx.check(aser.aser_quantize_rtn(ctx, Ws[i % n_rot], buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes,
+                                         buf.scales, buf.T))
+    e1.record()
+    torch.cuda.synchronize()
+    rtn_ms = e0.elapsed_time(e1) / reps
+    rtn_bytes = 8.5 * spec.m * spec.n + 4.0 * spec.m
+    rtn_gbs = rtn_bytes / (rtn_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": METRIC, "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if spec.x_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "%s: W %dx%d fp32, X %dx%d %s, W%d per-channel RTN, r=%d, f=%d" %
+                               (spec.name, spec.m, spec.n, spec.tokens, spec.n, spec.x_dtype, spec.bits, spec.r, spec.f),
+                   "svd_block": 2 * spec.r if 2 * spec.r <= 128 else 128, "svd_iters": 12},
+        "layers_per_s": 1e3 / ms_per_step,
+        "calibration_tokens_per_s": spec.tokens * 1e3 / ms_per_step,
+        "stage_ms": {k: round(v, 4) for k, v in zip(stage_names, stage_ms)},
+        "gram_mfma_util_pct": 100.0 * gram_tflops / BF16_PEAK_TFLOPS,
+        "whitened_error": err,
+        "roofline": {"kernel": "gemm_tn_kernel<bf16,256,256> (Gram update G += X^T X, lower-triangle tiles)",
+                     "bound": "mfma", "achieved": gram_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gram_tflops / BF16_PEAK_TFLOPS, "traffic": None,
+                     "algorithmic_flops_per_launch": gram_flops, "avg_launch_ms": gram_ms},
+        "roofline_hbm": {"kernel": "rtn_kernel (per-channel RTN + target T)", "bound": "hbm", "achieved": rtn_gbs,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rtn_gbs / HBM_PEAK_GBS, "traffic": None,
+                         "algorithmic_bytes_per_launch": rtn_bytes, "avg_launch_ms": rtn_ms},
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(spec)
+    log("stage ms:", out["stage_ms"], "gram %.3f ms = %.1f TFLOP/s" % (gram_ms, gram_tflops),
+        "rtn %.1f us = %.0f GB/s" % (rtn_ms * 1e3, rtn_gbs))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

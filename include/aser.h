@@ -1,0 +1,164 @@
+/*
+ * aser.h - C ABI of the MI355X (gfx950) implementation of ASER's per-linear-layer
+ * calibration path (arXiv 2411.07762, "ASER: Activation Smoothing and Error Reconstruction
+ * for Large Language Model Quantization").
+ *
+ * The calls follow the loop body of Algorithm 1 for one layer y = W x:
+ *
+ *   aser_gram_accumulate    G += X_c^T X_c over token chunks              (Eq. 5, Alg. 1)
+ *   aser_smooth_outliers    outlier set I_f and smoothing diagonal m      (Sec. 4.2, Eq. 10-11)
+ *   aser_quantize_rtn       Q(W_s) and the target T = W M - Q(W_s)        (Eq. 12, Sec. 3.1)
+ *   aser_whiten             S = chol(M^-1 G M^-1)                         (Eq. 5, Alg. 1)
+ *   aser_error_reconstruct  rank-r SVD of T S, L_A = U_r Sigma_r,
+ *                           L_B = V_r^T S^-1                              (Eq. 6, Sec. 4.1)
+ *   aser_quantize_act_rtn   per-token RTN of X M^-1 (evaluation only)     (Sec. 5.1)
+ *
+ * Orientation.  The paper stores activations as (in x tokens) and writes the Gram matrix
+ * X X^T.  This library stores activations tokens x in (N x n, row-major, channel
+ * contiguous); the same n x n matrix is then G = X^T X.  W is m x n (out x in), row-major.
+ *
+ * Conventions.
+ *   - Every matrix pointer is a DEVICE pointer owned by the caller; the library never
+ *     allocates, frees or retains caller-visible buffers.  Scratch memory comes from the
+ *     workspace bound with aser_set_workspace (device memory, 256-byte aligned).
+ *   - Row-major with explicit leading dimensions in ELEMENTS (ld >= number of columns).
+ *   - All work is enqueued on the hipStream_t given to aser_create.  Calls are asynchronous
+ *     unless they return a host scalar (aser_whiten's info, aser_error_reconstruct's err and
+ *     n_iter), in which case they synchronise that stream before returning.
+ *   - Every call returns an aser_status.  Arguments are validated on the host before any
+ *     HIP call is made; on error nothing has been enqueued.  No exception or abort crosses
+ *     the ABI.  aser_last_error(ctx) returns a text for the last failing call on ctx.
+ *   - One GPU, one stream per context; calls on one context must not overlap.
+ */
+#ifndef ASER_H
+#define ASER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct aser_ctx aser_ctx;
+
+typedef enum aser_status {
+    ASER_OK = 0,
+    ASER_ERR_INVALID_ARG = 1,   /* null pointer, bad enum, bad alignment                 */
+    ASER_ERR_SHAPE = 2,         /* non-positive size, ld < cols, f > n, r > min(m, n) ... */
+    ASER_ERR_DTYPE = 3,         /* unsupported dtype / bit width                          */
+    ASER_ERR_NOT_SPD = 4,       /* Cholesky met a non-positive pivot                      */
+    ASER_ERR_NO_CONVERGE = 5,   /* reserved                                               */
+    ASER_ERR_WORKSPACE = 6,     /* workspace missing or too small                         */
+    ASER_ERR_HIP = 7            /* a HIP runtime call failed                              */
+} aser_status;
+
+typedef enum aser_dtype { ASER_DTYPE_BF16 = 0, ASER_DTYPE_F32 = 1 } aser_dtype;
+
+typedef enum aser_code_layout {
+    ASER_CODES_INT8 = 0,        /* one int8 per weight, row pitch n bytes                     */
+    ASER_CODES_INT4_PACKED = 1  /* two's-complement nibbles, even column in the low nibble,
+                                   row pitch n/2 bytes; n must be even; needs bits == 4       */
+} aser_code_layout;
+
+/* Options of the truncated SVD.  Zero in any field selects its default. */
+typedef struct aser_svd_opts {
+    int32_t block;      /* subspace width b (multiple of 32, r <= b <= 128); default: the
+                           smallest multiple of 32 that is >= min(2 r, 128) and >= r        */
+    int32_t max_iter;   /* number of subspace iterations (A A^T applications); default 12  */
+    uint32_t seed;      /* seed of the random start block; default 1                       */
+    int32_t reserved;
+} aser_svd_opts;
+
+const char* aser_status_string(int status);
+
+/* Creates a context bound to `device` and to `hip_stream` (a hipStream_t, may be NULL for
+ * the default stream).  No HIP call is made until the first compute call. */
+int aser_create(aser_ctx** out, int device, void* hip_stream);
+int aser_destroy(aser_ctx* ctx);
+const char* aser_last_error(const aser_ctx* ctx);
+
+/* Binds `bytes` of device memory at `dev_ptr` (256-byte aligned) as scratch space.  The
+ * caller keeps ownership and must keep it alive while calls on ctx may use it. */
+int aser_set_workspace(aser_ctx* ctx, void* dev_ptr, size_t bytes);
+
+/* Workspace needed by the calls below for a layer of m x n with rank r (opts may be NULL).
+ * aser_gram_accumulate and aser_quantize_rtn need none. */
+size_t aser_workspace_bytes(int64_t m, int64_t n, int32_t r, const aser_svd_opts* opts);
+
+/* Stage 1 (Eq. 5; Alg. 1 "Cholesky decomposition on (M^-1 X)(M^-1 X)^T" needs X X^T).
+ * Accumulates one chunk of calibration tokens into caller-zeroed running sums:
+ *     G[i][j]    += sum_t X[t][i] * X[t][j]        for i >= j   (fp32)
+ *     abs_sum[i] += sum_t |X[t][i]|                             (fp64, may be NULL)
+ *     *count     += rows                                        (device int64, may be NULL)
+ * X: rows x n, dtype x_dtype (bf16 or fp32), leading dimension ldx.  G: n x n fp32, ldg.
+ * Only the lower triangle of G (i >= j) is defined afterwards; entries above the diagonal
+ * may or may not have been touched.  bf16 inputs are multiplied exactly and accumulated in
+ * fp32; fp32 inputs are split into two bf16 terms (three MFMA products per term pair,
+ * relative error about 2^-16 per product).  Partial sums are added with fp32 atomics, so
+ * G is reproducible only up to summation order.  rows == 0 is a no-op. */
+int aser_gram_accumulate(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int64_t n, int64_t ldx,
+                         float* G, int64_t ldg, double* abs_sum, int64_t* count);
+
+/* Stage 2 (Sec. 4.2, Eq. 10, Eq. 11; Alg. 1 "Compute m_i = Xbar_i / Xbar_min for i in I_f").
+ *     Xbar_i = abs_sum[i] / *count,  Wbar_i = mean_o |W[o][i]|,  score_i = Xbar_i * Wbar_i  (fp64)
+ *     idx    = the f channels with the largest score, in descending score order, ties
+ *              resolved towards the lower channel index
+ *     mdiag  = Xbar_i / min_{j in I_f} Xbar_j for i in I_f, else 1                   (fp32, n)
+ *     W_o    = W[:, idx] * mdiag[idx]   (m x f, row-major, ld = f; may be NULL)
+ *     score  = the n scores (fp64; may be NULL)
+ * f == 0 is the branch without activation smoothing: mdiag = 1, idx untouched.
+ * Needs workspace (aser_workspace_bytes). */
+int aser_smooth_outliers(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                         const double* abs_sum, const int64_t* count, int32_t f,
+                         int32_t* idx, float* mdiag, float* W_o, double* score);
+
+/* Stage 3 (Sec. 3.1 E_q = W - W_q; Eq. 12; per-channel RTN, Sec. 5.1).
+ * W_s = W with the idx columns set to zero.  Per output row o, in IEEE fp32:
+ *     scale_o = max_j |W_s[o][j]| / qmax,  qmax = 2^(bits-1) - 1   (1 if the row is zero)
+ *     code    = clamp(rint_half_even(W_s[o][j] / scale_o), -qmax, qmax)
+ *     T[o][j] = W[o][j] * mdiag[j] - code * scale_o       ( = E_q + W_o of Eq. 12 )
+ * codes: layout as aser_code_layout; scales: m fp32; T: m x n fp32, ldt (may be NULL).
+ * idx/mdiag may be NULL when f == 0.  bits is 4 or 8. */
+int aser_quantize_rtn(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                      const int32_t* idx, const float* mdiag, int32_t f, int32_t bits, int32_t layout,
+                      void* codes, float* scales, float* T, int64_t ldt);
+
+/* Stage 4a (Eq. 5: S^-1 X X^T S^-T = I, S by Cholesky decomposition; Alg. 1 uses M^-1 X).
+ *     G'[i][j] = G[i][j] / (mdiag[i] * mdiag[j])  (+ damp * mean(diag G') on the diagonal)
+ *     S = lower Cholesky factor, S S^T = G'
+ * Reads the lower triangle of G (n x n, ldg); writes S (n x n, lds) with zeros above the
+ * diagonal.  S may alias G (in place).  mdiag may be NULL (M = I).  damp >= 0, normally 0.
+ * *info (host, may be NULL): 0, or the 1-based index of the first non-positive pivot, in
+ * which case ASER_ERR_NOT_SPD is returned and S is unspecified.  Synchronises the stream.
+ * Needs workspace. */
+int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n, const float* mdiag, float damp,
+                float* S, int64_t lds, int32_t* info);
+
+/* Stage 4b/4c (Eq. 6; Sec. 4.1 L_A = U_r Sigma_r, L_B = V_r^T S^-1; Alg. 1 last lines).
+ * Rank-r truncated SVD of A = T S by blocked subspace iteration and Rayleigh-Ritz.
+ *     L_A   = U_r Sigma_r                  (m x r, ld = r)
+ *     L_B   = V_r^T S^-1                   (r x n, ld = n), evaluated as Sigma_r^-1 U_r^T T,
+ *             which is the same matrix because V_r^T = Sigma_r^-1 U_r^T T S
+ *     sigma = the r Ritz singular values, descending (fp32, device)
+ *     *err  (host, may be NULL) = ||A - U_r U_r^T A||_F evaluated as an explicit residual: the
+ *             whitened layer-output error ||(T - L_A L_B) S||_F of Eq. 8
+ *     *n_iter (host, may be NULL) = subspace iterations performed
+ * T: m x n fp32 (ldt); S: n x n fp32 lower triangular with zeros above the diagonal (lds).
+ * 0 < r <= min(m, n, 128).  Synchronises the stream.  Needs workspace. */
+int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt,
+                           const float* S, int64_t lds, int32_t r, const aser_svd_opts* opts,
+                           float* L_A, float* L_B, float* sigma, double* err, int32_t* n_iter);
+
+/* Per-token activation quantizer of the W4A8 setting (Sec. 5.1 "per-token for activations").
+ * It does not feed L_A / L_B; it serves the layer-output error under activation quantization.
+ *     X'[t][i] = X[t][i] / mdiag[i]  (IEEE fp32),  s_t = max_i |X'[t][i]| / qmax  (1 if zero)
+ *     codes[t][i] = clamp(rint_half_even(X'[t][i] / s_t), -qmax, qmax)     (int8, ld = n)
+ * mdiag may be NULL (M = I).  bits in [2, 8]. */
+int aser_quantize_act_rtn(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int64_t n, int64_t ldx,
+                          const float* mdiag, int32_t bits, int8_t* codes, float* scales);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASER_H */

@@ -1,0 +1,277 @@
+"""Python binding of libaser.so: the MI355X implementation of ASER's per-layer calibration path.
+
+Argument marshalling only.  Every function has the name and the meaning of the C entry point
+declared in include/aser.h; tensors are torch tensors on the GPU (torch provides device memory
+and the stream, nothing else) or raw integer device addresses.  There is no CPU fallback: if
+the HIP library has not been built, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libaser.so")
+
+ASER_OK = 0
+ASER_ERR_INVALID_ARG = 1
+ASER_ERR_SHAPE = 2
+ASER_ERR_DTYPE = 3
+ASER_ERR_NOT_SPD = 4
+ASER_ERR_NO_CONVERGE = 5
+ASER_ERR_WORKSPACE = 6
+ASER_ERR_HIP = 7
+
+ASER_DTYPE_BF16 = 0
+ASER_DTYPE_F32 = 1
+ASER_CODES_INT8 = 0
+ASER_CODES_INT4_PACKED = 1
+
+EXPORTS = (
+    "aser_status_string", "aser_create", "aser_destroy", "aser_last_error", "aser_set_workspace",
+    "aser_workspace_bytes", "aser_gram_accumulate", "aser_smooth_outliers", "aser_quantize_rtn",
+    "aser_whiten", "aser_error_reconstruct", "aser_quantize_act_rtn",
+)
+
+
+class aser_svd_opts(ctypes.Structure):
+    _fields_ = [("block", ctypes.c_int32), ("max_iter", ctypes.c_int32), ("seed", ctypes.c_uint32),
+                ("reserved", ctypes.c_int32)]
+
+
+class AserError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("aser status %d (%s): %s" % (status, status_string(status), message))
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libaser.so built in-tree by paper_2411_07762_amd.build; raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libaser.so is not built: run `python -m paper_2411_07762_amd.build` "
+                           "(there is no CPU fallback for the HIP path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float
+    lib.aser_status_string.restype = ctypes.c_char_p
+    lib.aser_status_string.argtypes = [ctypes.c_int]
+    lib.aser_create.restype = ctypes.c_int
+    lib.aser_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, vp]
+    lib.aser_destroy.restype = ctypes.c_int
+    lib.aser_destroy.argtypes = [vp]
+    lib.aser_last_error.restype = ctypes.c_char_p
+    lib.aser_last_error.argtypes = [vp]
+    lib.aser_set_workspace.restype = ctypes.c_int
+    lib.aser_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
+    lib.aser_workspace_bytes.restype = ctypes.c_size_t
+    lib.aser_workspace_bytes.argtypes = [i64, i64, i32, ctypes.POINTER(aser_svd_opts)]
+    lib.aser_gram_accumulate.restype = ctypes.c_int
+    lib.aser_gram_accumulate.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, vp, i64, vp, vp]
+    lib.aser_smooth_outliers.restype = ctypes.c_int
+    lib.aser_smooth_outliers.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, vp, vp, vp, vp]
+    lib.aser_quantize_rtn.restype = ctypes.c_int
+    lib.aser_quantize_rtn.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, i32, i32, vp, vp, vp, i64]
+    lib.aser_whiten.restype = ctypes.c_int
+    lib.aser_whiten.argtypes = [vp, vp, i64, i64, vp, f32, vp, i64, ctypes.POINTER(ctypes.c_int32)]
+    lib.aser_error_reconstruct.restype = ctypes.c_int
+    lib.aser_error_reconstruct.argtypes = [vp, vp, i64, i64, i64, vp, i64, i32, ctypes.POINTER(aser_svd_opts),
+                                           vp, vp, vp, ctypes.POINTER(ctypes.c_double),
+                                           ctypes.POINTER(ctypes.c_int32)]
+    lib.aser_quantize_act_rtn.restype = ctypes.c_int
+    lib.aser_quantize_act_rtn.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, vp, i32, vp, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().aser_status_string(int(status)).decode()
+
+
+# ----------------------------------------------------------------------------------- marshalling
+def _ptr(t) -> Optional[int]:
+    """Device address of a tensor (or a raw int address, or None)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _ld(t, cols: int) -> int:
+    if isinstance(t, int) or t is None:
+        return cols
+    if t.dim() == 1:
+        return cols
+    if t.stride(-1) != 1:
+        raise ValueError("matrices must be row-major with unit column stride")
+    return t.stride(0)
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return ASER_DTYPE_BF16
+    if t.dtype == torch.float32:
+        return ASER_DTYPE_F32
+    raise TypeError("activations must be bfloat16 or float32")
+
+
+class Context:
+    """Owns an aser_ctx bound to a device and a HIP stream (torch's current stream by default)."""
+
+    def __init__(self, device: int = 0, stream: Optional[int] = None):
+        self._lib = load_library()
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream(device).cuda_stream
+        h = ctypes.c_void_p()
+        st = self._lib.aser_create(ctypes.byref(h), int(device), ctypes.c_void_p(stream))
+        if st != ASER_OK:
+            raise AserError(st, "aser_create failed")
+        self.handle = h
+        self.device = device
+        self._ws = None
+
+    def close(self):
+        if self.handle:
+            self._lib.aser_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def check(self, status: int):
+        if status != ASER_OK:
+            raise AserError(status, self._lib.aser_last_error(self.handle).decode())
+
+    def ensure_workspace(self, nbytes: int):
+        """Allocates (with torch) and binds a workspace of at least nbytes."""
+        import torch
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device="cuda:%d" % self.device)
+            base = self._ws.data_ptr()
+            off = (-base) % 256
+            self.check(self._lib.aser_set_workspace(self.handle, ctypes.c_void_p(base + off), int(nbytes)))
+
+
+def aser_workspace_bytes(m: int, n: int, r: int, opts: Optional[aser_svd_opts] = None) -> int:
+    return int(load_library().aser_workspace_bytes(m, n, r, ctypes.byref(opts) if opts is not None else None))
+
+
+def aser_set_workspace(ctx: Context, dev_ptr, nbytes: int) -> int:
+    return ctx._lib.aser_set_workspace(ctx.handle, ctypes.c_void_p(_ptr(dev_ptr)), int(nbytes))
+
+
+def aser_gram_accumulate(ctx: Context, X, G, abs_sum=None, count=None, *, rows=None, n=None, ldx=None, ldg=None,
+                         x_dtype=None) -> int:
+    rows = X.shape[0] if rows is None else rows
+    n = X.shape[1] if n is None else n
+    return ctx._lib.aser_gram_accumulate(
+        ctx.handle, _ptr(X), _dtype_code(X) if x_dtype is None else x_dtype, rows, n,
+        _ld(X, n) if ldx is None else ldx, _ptr(G), _ld(G, n) if ldg is None else ldg, _ptr(abs_sum), _ptr(count))
+
+
+def aser_smooth_outliers(ctx: Context, W, abs_sum, count, f: int, idx, mdiag, W_o=None, score=None, *, m=None, n=None,
+                         ldw=None) -> int:
+    m = W.shape[0] if m is None else m
+    n = W.shape[1] if n is None else n
+    return ctx._lib.aser_smooth_outliers(ctx.handle, _ptr(W), m, n, _ld(W, n) if ldw is None else ldw, _ptr(abs_sum),
+                                         _ptr(count), f, _ptr(idx), _ptr(mdiag), _ptr(W_o), _ptr(score))
+
+
+def aser_quantize_rtn(ctx: Context, W, idx, mdiag, f: int, bits: int, layout: int, codes, scales, T=None, *, m=None,
+                      n=None, ldw=None, ldt=None) -> int:
+    m = W.shape[0] if m is None else m
+    n = W.shape[1] if n is None else n
+    return ctx._lib.aser_quantize_rtn(ctx.handle, _ptr(W), m, n, _ld(W, n) if ldw is None else ldw, _ptr(idx),
+                                      _ptr(mdiag), f, bits, layout, _ptr(codes), _ptr(scales), _ptr(T),
+                                      (_ld(T, n) if T is not None else n) if ldt is None else ldt)
+
+
+def aser_whiten(ctx: Context, G, mdiag, damp: float, S, *, n=None, ldg=None, lds=None):
+    """Returns (status, info)."""
+    n = G.shape[0] if n is None else n
+    info = ctypes.c_int32(0)
+    st = ctx._lib.aser_whiten(ctx.handle, _ptr(G), _ld(G, n) if ldg is None else ldg, n, _ptr(mdiag), float(damp),
+                              _ptr(S), _ld(S, n) if lds is None else lds, ctypes.byref(info))
+    return st, info.value
+
+
+def aser_error_reconstruct(ctx: Context, T, S, r: int, L_A, L_B, sigma, opts: Optional[aser_svd_opts] = None, *,
+                           m=None, n=None, ldt=None, lds=None):
+    """Returns (status, err, n_iter)."""
+    m = T.shape[0] if m is None else m
+    n = T.shape[1] if n is None else n
+    err = ctypes.c_double(0.0)
+    nit = ctypes.c_int32(0)
+    st = ctx._lib.aser_error_reconstruct(ctx.handle, _ptr(T), m, n, _ld(T, n) if ldt is None else ldt, _ptr(S),
+                                         _ld(S, n) if lds is None else lds, r,
+                                         ctypes.byref(opts) if opts is not None else None, _ptr(L_A), _ptr(L_B),
+                                         _ptr(sigma), ctypes.byref(err), ctypes.byref(nit))
+    return st, err.value, nit.value
+
+
+def aser_quantize_act_rtn(ctx: Context, X, mdiag, bits: int, codes, scales, *, rows=None, n=None, ldx=None,
+                          x_dtype=None) -> int:
+    rows = X.shape[0] if rows is None else rows
+    n = X.shape[1] if n is None else n
+    return ctx._lib.aser_quantize_act_rtn(ctx.handle, _ptr(X), _dtype_code(X) if x_dtype is None else x_dtype, rows, n,
+                                          _ld(X, n) if ldx is None else ldx, _ptr(mdiag), bits, _ptr(codes),
+                                          _ptr(scales))
+
+
+# ----------------------------------------------------------------------------------- one layer, end to end
+class LayerBuffers:
+    """Device buffers of one layer's calibration state and outputs (allocated with torch)."""
+
+    def __init__(self, m: int, n: int, r: int, f: int, bits: int, packed: bool, device: int = 0):
+        import torch
+        dev = "cuda:%d" % device
+        self.m, self.n, self.r, self.f, self.bits, self.packed = m, n, r, f, bits, packed
+        self.G = torch.zeros((n, n), dtype=torch.float32, device=dev)
+        self.abs_sum = torch.zeros(n, dtype=torch.float64, device=dev)
+        self.count = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.idx = torch.zeros(max(f, 1), dtype=torch.int32, device=dev)
+        self.mdiag = torch.empty(n, dtype=torch.float32, device=dev)
+        self.codes = torch.empty((m, n // 2 if packed else n), dtype=torch.uint8 if packed else torch.int8, device=dev)
+        self.scales = torch.empty(m, dtype=torch.float32, device=dev)
+        self.T = torch.empty((m, n), dtype=torch.float32, device=dev)
+        self.S = torch.empty((n, n), dtype=torch.float32, device=dev)
+        self.L_A = torch.empty((m, r), dtype=torch.float32, device=dev)
+        self.L_B = torch.empty((r, n), dtype=torch.float32, device=dev)
+        self.sigma = torch.empty(r, dtype=torch.float32, device=dev)
+        self.err = float("nan")
+
+    def reset_statistics(self):
+        self.G.zero_()
+        self.abs_sum.zero_()
+        self.count.zero_()
+
+
+def calibrate_layer(ctx: Context, W, X, buf: LayerBuffers, opts: Optional[aser_svd_opts] = None, damp: float = 0.0,
+                    accumulate: bool = True):
+    """The loop body of Algorithm 1 for one layer: five ABI calls on buffers in `buf`.
+
+    With accumulate=False the Gram statistics already in `buf` are used (layers sharing an input).
+    """
+    ctx.ensure_workspace(aser_workspace_bytes(buf.m, buf.n, buf.r, opts))
+    layout = ASER_CODES_INT4_PACKED if buf.packed else ASER_CODES_INT8
+    if accumulate:
+        ctx.check(aser_gram_accumulate(ctx, X, buf.G, buf.abs_sum, buf.count))
+    ctx.check(aser_smooth_outliers(ctx, W, buf.abs_sum, buf.count, buf.f, buf.idx, buf.mdiag))
+    ctx.check(aser_quantize_rtn(ctx, W, buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes, buf.scales, buf.T))
+    st, info = aser_whiten(ctx, buf.G, buf.mdiag, damp, buf.S)
+    ctx.check(st)
+    st, err, _ = aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, opts)
+    ctx.check(st)
+    buf.err = err
+    return buf

@@ -1,0 +1,105 @@
+// Internal declarations shared by the translation units of libaser.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "aser.h"
+
+struct aser_ctx {
+    int device;
+    hipStream_t stream;
+    void* ws;
+    size_t ws_bytes;
+    bool device_ready;
+    char err[256];
+};
+
+#define ASER_FAIL(ctx, code, ...)                                   \
+    do {                                                            \
+        if (ctx) snprintf((ctx)->err, sizeof((ctx)->err), __VA_ARGS__); \
+        return (code);                                              \
+    } while (0)
+
+#define ASER_HIP(ctx, call)                                                              \
+    do {                                                                                 \
+        hipError_t e__ = (call);                                                         \
+        if (e__ != hipSuccess) ASER_FAIL(ctx, ASER_ERR_HIP, "%s: %s", #call, hipGetErrorString(e__)); \
+    } while (0)
+
+#define ASER_TRY(expr)                   \
+    do {                                 \
+        int s__ = (expr);                \
+        if (s__ != ASER_OK) return s__;  \
+    } while (0)
+
+static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t aser_reconstruct_workspace(int64_t m, int64_t n, int r, const aser_svd_opts* o);
+
+// Makes ctx's device current (first compute call) and checks a launch.
+int aser_prepare_device(aser_ctx* ctx);
+int aser_check_launch(aser_ctx* ctx, const char* what);
+
+// ---------------------------------------------------------------------------------------------
+// C (op)= alpha * A^T B with both operands stored K-major ("TN" form):
+//   A: K x M row-major (lda), B: K x N row-major (ldb), C: M x N row-major (ldc), all device.
+// Input types: bf16 (one exact MFMA product, fp32 accumulate) or fp32 split on the fly into
+// bf16 hi + lo (three MFMA products: hi*hi + hi*lo + lo*hi).
+enum GemmIn { GEMM_IN_BF16 = 0, GEMM_IN_F32X3 = 1 };
+enum GemmEpi {
+    GEMM_EPI_STORE = 0,    // C = alpha * acc            (needs k_parts == 1)
+    GEMM_EPI_ATOMIC = 1,   // atomicAdd(C, alpha * acc)  (any k_parts)
+    GEMM_EPI_RMW = 2       // C += alpha * acc           (needs k_parts == 1, disjoint tiles)
+};
+enum GemmTiles {
+    GEMM_TILES_ALL = 0,    // every BM x BN tile of C
+    GEMM_TILES_LOWER = 1,  // tiles meeting the lower triangle (needs M == N, BM == BN)
+    GEMM_TILES_UPPER = 2   // tiles meeting the upper triangle
+};
+enum GemmKRange {
+    GEMM_K_FULL = 0,
+    GEMM_K_GE_COL = 1      // B[k][j] == 0 for k < j (B lower triangular): start at k = tile's first column
+};
+
+struct GemmArgs {
+    const void* A; int64_t lda;
+    const void* B; int64_t ldb;
+    float* C; int64_t ldc;
+    float* Ct; int64_t ldct;   // optional transposed copy of the result: Ct[j][i] = C[i][j] (STORE only)
+    int64_t M, N, K;
+    float alpha;
+    int in_type, epi, tiles, krange;
+    int k_parts;               // split of the K range over blockIdx.y
+    int bm, bn;                // tile: 256x256, 128x256, 256x128 or 128x128
+};
+int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g);
+
+// Gram update G(lower) += X^T X with the XCD-aware persistent schedule (bf16 or fp32 X).
+int aser_syrk_gram(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int64_t n, int64_t ldx,
+                   float* G, int64_t ldg);
+
+// ---------------------------------------------------------------------------------------------
+// Bandwidth-bound kernels
+int aser_fill_f32(aser_ctx* ctx, float* p, int64_t rows, int64_t cols, int64_t ld, float v);
+int aser_fill_bytes(aser_ctx* ctx, void* p, size_t bytes);   // zero fill
+int aser_col_abs_sum_x(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int64_t n, int64_t ldx,
+                       double* abs_sum, int64_t* count);
+int aser_col_abs_sum_w(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw, double* wsum);
+int aser_transpose_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols, int64_t lda, float* At, int64_t ldat);
+int aser_sumsq_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols, int64_t lda, double* out /*device, accumulates*/);
+
+// Small dense kernels (one workgroup, matrices in LDS)
+// Upper Cholesky of the b x b block D (ld) in place: upper part <- R (D = R^T R), lower part <- R^T;
+// Rinv (b x b, ld = b) <- R^-1 (upper).  b <= 128.  On a non-positive pivot at column j,
+// atomicMin(info, pivot_base + j + 1) and the pivot is replaced by 1.
+int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base);
+// Symmetric eigen-decomposition of the b x b matrix Mb (ld = b) by cyclic Jacobi: eigenvalues
+// descending into lambda (b), eigenvectors as columns of V (b x b, ld = b).  b <= 128, b even.
+int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float* V);
+// C (rows x c) = A (rows x k) * B (k x c), plain fp32 FMA; k, c <= 256.  C may not alias A.
+int aser_gemm_small_f32(aser_ctx* ctx, const float* A, int64_t lda, const float* B, int64_t ldb,
+                        float* C, int64_t ldc, int64_t rows, int k, int c);

@@ -1,0 +1,161 @@
+// Activation smoothing via outlier analysis (Sec. 4.2): channel scores Xbar * Wbar, the index set
+// I_f of the f largest scores, the diagonal m of Eq. 11 and the outlier part W_o of W M.
+// All statistics are fp64 so that the selected indices do not depend on summation order in
+// any realistic case; ties go to the lower channel index.
+#include "aser_internal.h"
+
+namespace {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelPerThread = 32;           // supports n <= 32768
+
+struct Cand {
+    double s;
+    int i;
+};
+
+// a beats b: larger score, or equal score and lower index
+__device__ __forceinline__ bool beats(double sa, int ia, double sb, int ib) {
+    return (sa > sb) || (sa == sb && ia < ib);
+}
+
+__global__ __launch_bounds__(256) void score_kernel(const double* abs_sum, const int64_t* count, const double* wsum,
+                                                    int64_t m, int64_t n, double* score) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const double xbar = abs_sum[i] / (double)(*count);
+    const double wbar = wsum[i] / (double)m;
+    score[i] = xbar * wbar;
+}
+
+// One workgroup.  Every thread keeps its scores (channels tid, tid + 1024, ...) in registers with
+// its current local best; each of the f rounds is a workgroup arg-max, after which only the
+// winner's owner rescans its registers.  Then the smoothing diagonal of Eq. 11 is written.
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const double* __restrict__ score,
+                                                             const double* __restrict__ abs_sum,
+                                                             const int64_t* __restrict__ count, int n, int f,
+                                                             int32_t* __restrict__ idx, float* __restrict__ mdiag) {
+    __shared__ double red_s[kSelThreads / 64];
+    __shared__ int red_i[kSelThreads / 64];
+    __shared__ double win_s;
+    __shared__ int win_i;
+    __shared__ double xmin_sh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    for (int i = tid; i < n; i += kSelThreads) mdiag[i] = 1.0f;
+
+    double sc[kSelPerThread];
+#pragma unroll
+    for (int u = 0; u < kSelPerThread; ++u) {
+        const int c = u * kSelThreads + tid;
+        sc[u] = (c < n) ? score[c] : -1.0;          // scores are >= 0; -1 marks "absent / taken"
+    }
+    double best_s = -1.0;
+    int best_i = 0x7FFFFFFF;
+#pragma unroll
+    for (int u = 0; u < kSelPerThread; ++u) {
+        const int c = u * kSelThreads + tid;
+        if (sc[u] >= 0.0 && beats(sc[u], c, best_s, best_i)) { best_s = sc[u]; best_i = c; }
+    }
+
+    for (int round = 0; round < f; ++round) {
+        double s = best_s;
+        int i = best_i;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double s2 = __shfl_xor(s, o, 64);
+            const int i2 = __shfl_xor(i, o, 64);
+            if (beats(s2, i2, s, i)) { s = s2; i = i2; }
+        }
+        if (lane == 0) { red_s[wave] = s; red_i[wave] = i; }
+        __syncthreads();
+        if (tid == 0) {
+            double ws = red_s[0];
+            int wi = red_i[0];
+            for (int w = 1; w < kSelThreads / 64; ++w)
+                if (beats(red_s[w], red_i[w], ws, wi)) { ws = red_s[w]; wi = red_i[w]; }
+            win_s = ws;
+            win_i = wi;
+            idx[round] = wi;
+        }
+        __syncthreads();
+        const int wi = win_i;
+        if ((wi % kSelThreads) == tid) {             // owner: retire the winner, rescan
+            best_s = -1.0;
+            best_i = 0x7FFFFFFF;
+#pragma unroll
+            for (int u = 0; u < kSelPerThread; ++u) {
+                const int c = u * kSelThreads + tid;
+                if (c == wi) sc[u] = -1.0;
+                if (sc[u] >= 0.0 && beats(sc[u], c, best_s, best_i)) { best_s = sc[u]; best_i = c; }
+            }
+        }
+    }
+    __syncthreads();
+    if (f > 0) {
+        if (tid == 0) {
+            const double cnt = (double)(*count);
+            double xmin = abs_sum[idx[0]] / cnt;
+            for (int k = 1; k < f; ++k) {
+                const double x = abs_sum[idx[k]] / cnt;
+                xmin = x < xmin ? x : xmin;
+            }
+            xmin_sh = xmin;
+        }
+        __syncthreads();
+        const double cnt = (double)(*count);
+        for (int k = tid; k < f; k += kSelThreads) {
+            const int c = idx[k];
+            mdiag[c] = (float)((abs_sum[c] / cnt) / xmin_sh);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void gather_wo_kernel(const float* __restrict__ W, int64_t m, int64_t ldw,
+                                                        const int32_t* __restrict__ idx, const float* __restrict__ mdiag,
+                                                        int f, float* __restrict__ W_o) {
+    const int64_t total = m * f;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t o = t / f;
+        const int k = (int)(t % f);
+        const int c = idx[k];
+        W_o[t] = W[o * ldw + c] * mdiag[c];
+    }
+}
+
+}  // namespace
+
+extern "C" int aser_smooth_outliers(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                                    const double* abs_sum, const int64_t* count, int32_t f,
+                                    int32_t* idx, float* mdiag, float* W_o, double* score) {
+    if (!ctx) return ASER_ERR_INVALID_ARG;
+    if (!W || !abs_sum || !count || !mdiag) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: null pointer");
+    if (m <= 0 || n <= 0 || ldw < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: bad shape");
+    if (f < 0 || f > n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: f must be in [0, n]");
+    if (f > 0 && !idx) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: idx is null");
+    if (n > kSelThreads * kSelPerThread) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: n > 32768 is not supported");
+    if (((uintptr_t)abs_sum & 7) || ((uintptr_t)count & 7) || (score && ((uintptr_t)score & 7)))
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: misaligned fp64/int64 pointer");
+    const size_t need = align_up((size_t)n * 8, 256) * 2;
+    if (!ctx->ws || ctx->ws_bytes < need) ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "smooth_outliers: workspace too small");
+    ASER_TRY(aser_prepare_device(ctx));
+
+    double* wsum = (double*)ctx->ws;
+    double* sc = score ? score : (double*)((char*)ctx->ws + align_up((size_t)n * 8, 256));
+    ASER_TRY(aser_fill_bytes(ctx, wsum, (size_t)n * 8));
+    ASER_TRY(aser_col_abs_sum_w(ctx, W, m, n, ldw, wsum));
+    hipLaunchKernelGGL(score_kernel, dim3((unsigned)ceil_div64(n, 256)), dim3(256), 0, ctx->stream, abs_sum, count,
+                       (const double*)wsum, m, n, sc);
+    ASER_TRY(aser_check_launch(ctx, "score"));
+    hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), 0, ctx->stream, (const double*)sc, abs_sum, count,
+                       (int)n, (int)f, idx, mdiag);
+    ASER_TRY(aser_check_launch(ctx, "select"));
+    if (W_o && f > 0) {
+        const int64_t total = m * f;
+        const int blocks = (int)(ceil_div64(total, 256) < 2048 ? ceil_div64(total, 256) : 2048);
+        hipLaunchKernelGGL(gather_wo_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, m, ldw, (const int32_t*)idx,
+                           (const float*)mdiag, (int)f, W_o);
+        ASER_TRY(aser_check_launch(ctx, "gather_wo"));
+    }
+    return ASER_OK;
+}

@@ -1,0 +1,139 @@
+// Whitening factor of Eq. 5 / Algorithm 1: S = chol(M^-1 G M^-1), blocked right-looking.
+//
+// The factorisation runs on the upper triangle (G' = R^T R, R = S^T) so that every contraction
+// has the K-major "A^T B" form of the MFMA kernel:
+//   diagonal block   R11 = chol(D), R11^-1                       (one workgroup, LDS)
+//   row panel        R12 = (R11^-1)^T * G'[k, k+b:]              (A = R11^-1, B = the panel, in place)
+//   trailing update  G'[k+b:, k+b:] -= R12^T R12  (upper tiles)  (A = B = R12)
+// The panel kernel also writes R12^T below the diagonal, so the lower triangle fills up with
+// S = R^T as the factorisation proceeds; a final pass clears the strict upper triangle.
+#include <limits.h>
+
+#include "aser_internal.h"
+
+namespace {
+
+constexpr int kNb = 128;
+
+// S[i][j] = S[j][i] = G[i][j] / (m_i m_j) for i >= j, plus the damping term on the diagonal.
+__global__ __launch_bounds__(256) void whiten_prep_kernel(const float* G, int64_t ldg, int64_t n, const float* mdiag,
+                                                          float* S, int64_t lds, const double* diag_sum, float damp) {
+    __shared__ float tile[64][65];
+    // blockIdx.x enumerates tile pairs (bi >= bj)
+    const int64_t t = blockIdx.x;
+    int64_t bi = (int64_t)((sqrt(8.0 * (double)t + 1.0) - 1.0) * 0.5);
+    while (bi * (bi + 1) / 2 > t) --bi;
+    while ((bi + 1) * (bi + 2) / 2 <= t) ++bi;
+    const int64_t bj = t - bi * (bi + 1) / 2;
+    const int64_t r0 = bi * 64, c0 = bj * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const float add = (damp > 0.f && diag_sum) ? (float)((double)damp * (*diag_sum) / (double)n) : 0.f;
+    for (int i = ty; i < 64; i += 4) {
+        const int64_t r = r0 + i, c = c0 + tx;
+        float v = 0.f;
+        if (r < n && c < n) {
+            const float g = (r >= c) ? G[r * ldg + c] : G[c * ldg + r];
+            const float mi = mdiag ? mdiag[r] : 1.f, mj = mdiag ? mdiag[c] : 1.f;
+            v = g / (mi * mj);
+            if (r == c) v += add;
+        }
+        tile[i][tx] = v;
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        const int64_t r = r0 + i, c = c0 + tx;
+        if (r < n && c < n) S[r * lds + c] = tile[i][tx];
+    }
+    if (bi != bj) {
+        for (int i = ty; i < 64; i += 4) {
+            const int64_t r = c0 + i, c = r0 + tx;      // transposed tile
+            if (r < n && c < n) S[r * lds + c] = tile[tx][i];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void diag_scaled_sum_kernel(const float* G, int64_t ldg, int64_t n, const float* mdiag,
+                                                              double* out) {
+    __shared__ double red[4];
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += 256) {
+        const double mi = mdiag ? (double)mdiag[i] : 1.0;
+        acc += (double)G[i * ldg + i] / (mi * mi);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) *out = red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
+
+__global__ __launch_bounds__(256) void zero_strict_upper_kernel(float* S, int64_t n, int64_t lds) {
+    const int64_t r = blockIdx.y;
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c < n && c > r) S[r * lds + c] = 0.f;
+}
+
+}  // namespace
+
+extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n, const float* mdiag, float damp,
+                           float* S, int64_t lds, int32_t* info) {
+    if (!ctx) return ASER_ERR_INVALID_ARG;
+    if (!G || !S) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "whiten: null pointer");
+    if (n <= 0 || ldg < n || lds < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "whiten: bad shape");
+    if (!(damp >= 0.f)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "whiten: damp must be >= 0");
+    if (((uintptr_t)G & 3) || ((uintptr_t)S & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "whiten: misaligned pointer");
+    const size_t need = (size_t)kNb * kNb * 4 + 512;
+    if (!ctx->ws || ctx->ws_bytes < need) ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "whiten: workspace too small");
+    ASER_TRY(aser_prepare_device(ctx));
+
+    float* Rinv = (float*)ctx->ws;
+    int32_t* info_dev = (int32_t*)((char*)ctx->ws + (size_t)kNb * kNb * 4);
+    double* diag_sum = (double*)((char*)ctx->ws + (size_t)kNb * kNb * 4 + 256);
+
+    hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, info_dev, (int32_t)INT_MAX);
+    ASER_TRY(aser_check_launch(ctx, "set_info"));
+    if (damp > 0.f) {
+        hipLaunchKernelGGL(diag_scaled_sum_kernel, dim3(1), dim3(256), 0, ctx->stream, G, ldg, n, mdiag, diag_sum);
+        ASER_TRY(aser_check_launch(ctx, "diag_sum"));
+    }
+    const int64_t t64 = ceil_div64(n, 64);
+    hipLaunchKernelGGL(whiten_prep_kernel, dim3((unsigned)(t64 * (t64 + 1) / 2)), dim3(256), 0, ctx->stream, G, ldg, n,
+                       mdiag, S, lds, (const double*)diag_sum, damp);
+    ASER_TRY(aser_check_launch(ctx, "whiten_prep"));
+
+    for (int64_t k0 = 0; k0 < n; k0 += kNb) {
+        const int b = (int)((n - k0 < kNb) ? n - k0 : kNb);
+        float* D = S + k0 * lds + k0;
+        ASER_TRY(aser_chol_block(ctx, D, lds, b, Rinv, info_dev, (int32_t)k0));
+        const int64_t rem = n - k0 - b;
+        if (rem <= 0) break;
+        float* S12 = S + k0 * lds + (k0 + b);
+        GemmArgs p{};
+        p.A = Rinv; p.lda = b; p.B = S12; p.ldb = lds; p.C = S12; p.ldc = lds;
+        p.Ct = S + (k0 + b) * lds + k0; p.ldct = lds;
+        p.M = b; p.N = rem; p.K = b; p.alpha = 1.f;
+        p.in_type = GEMM_IN_F32X3; p.epi = GEMM_EPI_STORE; p.tiles = GEMM_TILES_ALL; p.krange = GEMM_K_FULL;
+        p.k_parts = 1; p.bm = 128; p.bn = (rem > 128) ? 256 : 128;
+        ASER_TRY(aser_gemm_tn(ctx, p));
+        GemmArgs u{};
+        u.A = S12; u.lda = lds; u.B = S12; u.ldb = lds;
+        u.C = S + (k0 + b) * lds + (k0 + b); u.ldc = lds; u.Ct = nullptr; u.ldct = 0;
+        u.M = rem; u.N = rem; u.K = b; u.alpha = -1.f;
+        u.in_type = GEMM_IN_F32X3; u.epi = GEMM_EPI_RMW; u.tiles = GEMM_TILES_UPPER; u.krange = GEMM_K_FULL;
+        u.k_parts = 1; u.bm = u.bn = (rem > 2048) ? 256 : 128;
+        ASER_TRY(aser_gemm_tn(ctx, u));
+    }
+    hipLaunchKernelGGL(zero_strict_upper_kernel, dim3((unsigned)ceil_div64(n, 256), (unsigned)n), dim3(256), 0, ctx->stream,
+                       S, n, lds);
+    ASER_TRY(aser_check_launch(ctx, "zero_upper"));
+
+    int32_t h_info = 0;
+    ASER_HIP(ctx, hipMemcpyAsync(&h_info, info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    const int32_t res = (h_info == INT_MAX) ? 0 : h_info;
+    if (info) *info = res;
+    if (res != 0) ASER_FAIL(ctx, ASER_ERR_NOT_SPD, "whiten: non-positive pivot at index %d", res);
+    return ASER_OK;
+}

@@ -1,0 +1,130 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol declared in
+include/aser.h, and rejects bad arguments before any HIP call is made."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2411_07762_amd as aser
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = 0x7F0000001000  # a fake, aligned "device address": validation must fail before it is touched
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    lib = aser.load_library()
+    h = ctypes.c_void_p()
+    assert lib.aser_create(ctypes.byref(h), 0, None) == aser.ASER_OK
+    c = aser.Context.__new__(aser.Context)
+    c._lib, c.handle, c.device, c._ws = lib, h, 0, None
+    yield c
+    c.close()
+
+
+def test_every_declared_symbol_is_exported():
+    text = open(os.path.join(ROOT, "include", "aser.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(aser_[a-z0-9_]+)\s*\(", text))
+    assert {"aser_gram_accumulate", "aser_smooth_outliers", "aser_quantize_rtn", "aser_whiten",
+            "aser_error_reconstruct"} <= declared
+    lib = aser.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(aser.EXPORTS)
+
+
+def test_status_strings():
+    assert aser.status_string(aser.ASER_OK) == "ok"
+    assert "positive definite" in aser.status_string(aser.ASER_ERR_NOT_SPD)
+    assert aser.status_string(99) == "unknown status"
+
+
+def test_create_rejects_bad_arguments():
+    lib = aser.load_library()
+    assert lib.aser_create(None, 0, None) == aser.ASER_ERR_INVALID_ARG
+    h = ctypes.c_void_p()
+    assert lib.aser_create(ctypes.byref(h), -1, None) == aser.ASER_ERR_INVALID_ARG
+    assert lib.aser_destroy(None) == aser.ASER_ERR_INVALID_ARG
+
+
+def test_workspace_rules(ctx):
+    assert aser.aser_set_workspace(ctx, P + 8, 1024) == aser.ASER_ERR_INVALID_ARG      # not 256-byte aligned
+    assert aser.aser_set_workspace(ctx, None, 0) == aser.ASER_OK
+    need = aser.aser_workspace_bytes(4096, 4096, 64)
+    assert need >= 2 * 4096 * 4096 * 4
+    assert aser.aser_workspace_bytes(0, 16, 4) == 0
+    # a call that needs scratch fails cleanly without one
+    st = aser.aser_smooth_outliers(ctx, P, P, P, 4, P, P, m=16, n=16, ldw=16)
+    assert st == aser.ASER_ERR_WORKSPACE
+    st, _ = aser.aser_whiten(ctx, P, None, 0.0, P, n=64, ldg=64, lds=64)
+    assert st == aser.ASER_ERR_WORKSPACE
+    st, _, _ = aser.aser_error_reconstruct(ctx, P, P, 4, P, P, P, m=64, n=64, ldt=64, lds=64)
+    assert st == aser.ASER_ERR_WORKSPACE
+    assert "workspace" in ctx._lib.aser_last_error(ctx.handle).decode()
+
+
+def test_gram_validation(ctx):
+    g = aser.aser_gram_accumulate
+    assert g(ctx, None, P, rows=8, n=8, ldx=8, ldg=8, x_dtype=0) == aser.ASER_ERR_INVALID_ARG
+    assert g(ctx, P, P, rows=8, n=8, ldx=4, ldg=8, x_dtype=0) == aser.ASER_ERR_SHAPE
+    assert g(ctx, P, P, rows=8, n=8, ldx=8, ldg=7, x_dtype=0) == aser.ASER_ERR_SHAPE
+    assert g(ctx, P, P, rows=-1, n=8, ldx=8, ldg=8, x_dtype=0) == aser.ASER_ERR_SHAPE
+    assert g(ctx, P, P, rows=8, n=8, ldx=8, ldg=8, x_dtype=5) == aser.ASER_ERR_DTYPE
+    assert g(ctx, P + 1, P, rows=8, n=8, ldx=8, ldg=8, x_dtype=0) == aser.ASER_ERR_INVALID_ARG
+    assert g(ctx, P, P, P + 4, None, rows=8, n=8, ldx=8, ldg=8, x_dtype=0) == aser.ASER_ERR_INVALID_ARG
+    assert g(ctx, P, P, rows=0, n=8, ldx=8, ldg=8, x_dtype=0) == aser.ASER_OK           # empty chunk: no-op
+
+
+def test_smooth_validation(ctx):
+    s = aser.aser_smooth_outliers
+    assert s(ctx, P, P, P, 9, P, P, m=4, n=8, ldw=8) == aser.ASER_ERR_SHAPE              # f > n
+    assert s(ctx, P, P, P, -1, P, P, m=4, n=8, ldw=8) == aser.ASER_ERR_SHAPE
+    assert s(ctx, P, P, P, 2, None, P, m=4, n=8, ldw=8) == aser.ASER_ERR_INVALID_ARG     # idx missing
+    assert s(ctx, P, P, P, 2, P, P, m=4, n=8, ldw=4) == aser.ASER_ERR_SHAPE
+    assert s(ctx, P, None, P, 2, P, P, m=4, n=8, ldw=8) == aser.ASER_ERR_INVALID_ARG
+
+
+def test_rtn_validation(ctx):
+    q = aser.aser_quantize_rtn
+    assert q(ctx, P, P, P, 2, 3, 0, P, P, P, m=4, n=8) == aser.ASER_ERR_DTYPE            # bits
+    assert q(ctx, P, P, P, 2, 8, 1, P, P, P, m=4, n=8) == aser.ASER_ERR_SHAPE            # packed needs 4 bits
+    assert q(ctx, P, P, P, 2, 4, 1, P, P, P, m=4, n=7) == aser.ASER_ERR_SHAPE            # packed needs even n
+    assert q(ctx, P, P, P, 2, 4, 7, P, P, P, m=4, n=8) == aser.ASER_ERR_INVALID_ARG      # layout
+    assert q(ctx, P, None, None, 2, 4, 0, P, P, P, m=4, n=8) == aser.ASER_ERR_INVALID_ARG
+    assert q(ctx, P, P, P, 2, 4, 0, P, P, P, m=4, n=8, ldt=4) == aser.ASER_ERR_SHAPE
+    assert q(ctx, P, P, P, 2, 4, 0, None, P, P, m=4, n=8) == aser.ASER_ERR_INVALID_ARG
+    assert q(ctx, P, P, P, 2, 4, 0, P, P, P, m=4, n=40000) == aser.ASER_ERR_SHAPE
+
+
+def test_whiten_and_reconstruct_validation(ctx):
+    st, _ = aser.aser_whiten(ctx, P, None, -1.0, P, n=8, ldg=8, lds=8)
+    assert st == aser.ASER_ERR_INVALID_ARG
+    st, _ = aser.aser_whiten(ctx, P, None, 0.0, P, n=8, ldg=4, lds=8)
+    assert st == aser.ASER_ERR_SHAPE
+    st, _ = aser.aser_whiten(ctx, None, None, 0.0, P, n=8, ldg=8, lds=8)
+    assert st == aser.ASER_ERR_INVALID_ARG
+    r = aser.aser_error_reconstruct
+    assert r(ctx, P, P, 0, P, P, P, m=64, n=64)[0] == aser.ASER_ERR_SHAPE
+    assert r(ctx, P, P, 65, P, P, P, m=64, n=256)[0] == aser.ASER_ERR_SHAPE             # r > min(m, n)
+    assert r(ctx, P, P, 129, P, P, P, m=512, n=512)[0] == aser.ASER_ERR_SHAPE
+    assert r(ctx, P, P, 8, None, P, P, m=64, n=64)[0] == aser.ASER_ERR_INVALID_ARG
+    o = aser.aser_svd_opts(block=48, max_iter=0, seed=0, reserved=0)
+    assert r(ctx, P, P, 8, P, P, P, o, m=64, n=64)[0] == aser.ASER_ERR_SHAPE             # block not multiple of 32
+
+
+def test_act_rtn_validation(ctx):
+    a = aser.aser_quantize_act_rtn
+    assert a(ctx, P, None, 9, P, P, rows=4, n=8, ldx=8, x_dtype=0) == aser.ASER_ERR_DTYPE
+    assert a(ctx, P, None, 8, P, P, rows=4, n=8, ldx=8, x_dtype=3) == aser.ASER_ERR_DTYPE
+    assert a(ctx, P, None, 8, P, P, rows=4, n=8, ldx=4, x_dtype=0) == aser.ASER_ERR_SHAPE
+    assert a(ctx, P, None, 8, P, P, rows=0, n=8, ldx=8, x_dtype=0) == aser.ASER_OK
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2411_07762_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                assert "oracle" not in open(os.path.join(dirpath, fn)).read().lower().replace("no cpu fallback", ""), fn

@@ -1,0 +1,359 @@
+"""Parity of the HIP path against the CPU oracle, stage by stage and end to end, through the C ABI.
+
+Bars: int4/int8 codes, scales and outlier indices bit-exact; the whitened layer-output error
+||(T - L_A L_B) S||_F, recomputed in fp64 from the GPU's L_A and L_B, within 1e-4 relative of
+the oracle's; the product L_A L_B within 1e-3 relative Frobenius when the oracle's
+sigma_r / sigma_{r+1} exceeds 1.05.  Tolerances of the fp32 intermediates are derived in the
+design notes (Gram: fp32 accumulation over N tokens; fp32 inputs: bf16 hi/lo split, 2^-16 per product).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import aser_synth as synth
+import paper_2411_07762_amd as aser
+from oracle import aser_oracle as orc
+
+from gpu_util import DEV, lower, new_ctx, padded, run_gram, to_dev_x, unpack_int4
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def oracle_layer(spec, W, x_np, r=None, f=None):
+    X = synth.activations_as_f32(spec, x_np)
+    return orc.calibrate_layer(W, X, spec.bits, spec.f if f is None else f, spec.r if r is None else r)
+
+
+GRAM_CASES = [
+    ("c0", synth.CONFIGS["c0"], 1, 0),
+    ("ragged_bf16", synth.mini("g1", 8, 200, 777), 1, 0),
+    ("ragged_bf16_chunks_pad", synth.mini("g2", 8, 520, 2000), 3, 8),
+    ("odd_n_bf16", synth.mini("g3", 8, 77, 300), 2, 3),
+    ("f32_ragged", synth.mini("g4", 8, 300, 1111, x_dtype="f32"), 2, 4),
+    ("multi_tile_bf16", synth.mini("g5", 8, 1300, 4500), 1, 0),
+]
+
+
+@pytest.mark.parametrize("name,spec,chunks,pad", GRAM_CASES, ids=[c[0] for c in GRAM_CASES])
+def test_gram_accumulate(name, spec, chunks, pad):
+    say("gram case %s n=%d N=%d dtype=%s chunks=%d pad=%d" % (name, spec.n, spec.tokens, spec.x_dtype, chunks, pad))
+    x_np = synth.make_activations(spec)
+    G_ref, abs_ref, cnt = orc.gram(synth.activations_as_f32(spec, x_np))
+    ctx = new_ctx()
+    G, abs_sum, count = run_gram(ctx, spec, x_np, chunks, pad)
+    G = G.cpu().numpy().astype(np.float64)
+    d = np.sqrt(np.diag(G_ref))
+    tol = (2e-5 if spec.x_dtype == "bf16" else 4e-5) * np.outer(d, d)
+    bad = np.abs(lower(G) - lower(G_ref)) > lower(tol)
+    assert not bad.any(), "max rel err %g" % (np.abs(lower(G) - lower(G_ref)) / np.outer(d, d)).max()
+    assert int(count.item()) == cnt
+    assert np.allclose(abs_sum.cpu().numpy(), abs_ref, rtol=1e-13, atol=0)
+
+
+def test_gram_empty_chunk_and_stats_optional():
+    spec = synth.mini("g6", 8, 64, 128)
+    x = to_dev_x(spec, synth.make_activations(spec))
+    ctx = new_ctx()
+    G = torch.zeros((64, 64), dtype=torch.float32, device=DEV)
+    ctx.check(aser.aser_gram_accumulate(ctx, x, G, rows=0, n=64, ldx=64))
+    torch.cuda.synchronize()
+    assert float(G.abs().max()) == 0.0
+    count = torch.zeros(1, dtype=torch.int64, device=DEV)
+    ctx.check(aser.aser_gram_accumulate(ctx, x, G, None, count))
+    torch.cuda.synchronize()
+    assert int(count.item()) == 128 and float(G.abs().max()) > 0
+
+
+SMOOTH_CASES = [
+    ("c0", synth.CONFIGS["c0"]),
+    ("ragged", synth.mini("s1", 50, 333, 500, f=7)),
+    ("wide", synth.mini("s2", 96, 2500, 640, f=32, n_outliers=16)),
+    ("no_smoothing", synth.mini("s3", 40, 128, 256, f=0)),
+    ("all_channels", synth.mini("s4", 16, 24, 64, f=24)),
+]
+
+
+@pytest.mark.parametrize("name,spec", SMOOTH_CASES, ids=[c[0] for c in SMOOTH_CASES])
+def test_smooth_outliers(name, spec):
+    say("smooth case %s m=%d n=%d f=%d" % (name, spec.m, spec.n, spec.f))
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    G_ref, abs_ref, cnt = orc.gram(synth.activations_as_f32(spec, x_np))
+    ref = orc.smooth_outliers(W, abs_ref, cnt, spec.f)
+    ctx = new_ctx()
+    ctx.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, 0))
+    Wd = padded(torch.from_numpy(W).to(DEV), 4)
+    abs_sum = torch.from_numpy(abs_ref).to(DEV)
+    count = torch.tensor([cnt], dtype=torch.int64, device=DEV)
+    idx = torch.full((max(spec.f, 1),), -1, dtype=torch.int32, device=DEV)
+    mdiag = torch.empty(spec.n, dtype=torch.float32, device=DEV)
+    W_o = torch.empty((spec.m, max(spec.f, 1)), dtype=torch.float32, device=DEV)
+    score = torch.empty(spec.n, dtype=torch.float64, device=DEV)
+    ctx.check(aser.aser_smooth_outliers(ctx, Wd, abs_sum, count, spec.f, idx, mdiag, W_o, score))
+    torch.cuda.synchronize()
+    assert np.allclose(score.cpu().numpy(), ref.score, rtol=1e-12, atol=0)
+    if spec.f:
+        assert ref.margin > 1e-9
+        assert idx.cpu().numpy()[:spec.f].tolist() == ref.idx.tolist()
+        assert np.allclose(W_o.cpu().numpy()[:, :spec.f], ref.W_o, rtol=1e-6, atol=0)
+    md = mdiag.cpu().numpy()
+    ulp = np.abs(md.view(np.int32).astype(np.int64) - ref.mdiag.view(np.int32).astype(np.int64))
+    assert ulp.max() <= 1, "mdiag differs by %d ulp" % ulp.max()
+
+
+def test_smooth_tie_break_lower_index():
+    # identical channels 5 and 9 (same |x| sum, same |w| sum): the lower index must win the last slot
+    n, m = 16, 8
+    W = np.ones((m, n), dtype=np.float32)
+    abs_sum = np.linspace(1.0, 2.0, n)
+    abs_sum[5] = abs_sum[9] = 7.0
+    abs_sum[2] = 9.0
+    ref = orc.smooth_outliers(W, abs_sum, 10, 2)
+    assert ref.idx.tolist() == [2, 5]
+    ctx = new_ctx()
+    ctx.ensure_workspace(aser.aser_workspace_bytes(m, n, 0))
+    idx = torch.zeros(2, dtype=torch.int32, device=DEV)
+    mdiag = torch.empty(n, dtype=torch.float32, device=DEV)
+    ctx.check(aser.aser_smooth_outliers(ctx, torch.from_numpy(W).to(DEV), torch.from_numpy(abs_sum).to(DEV),
+                                        torch.tensor([10], dtype=torch.int64, device=DEV), 2, idx, mdiag))
+    torch.cuda.synchronize()
+    assert idx.cpu().numpy().tolist() == [2, 5]
+    assert np.array_equal(mdiag.cpu().numpy(), ref.mdiag)
+
+
+RTN_CASES = [
+    ("c0_int4_packed", synth.CONFIGS["c0"], 4, True),
+    ("c0_int8", synth.CONFIGS["c0"], 8, False),
+    ("ragged_int4", synth.mini("q1", 37, 331, 400, f=5), 4, False),
+    ("even_packed", synth.mini("q2", 65, 1030, 300, f=9), 4, True),
+    ("wide_int8", synth.mini("q3", 20, 9000, 64, f=32, n_outliers=8), 8, False),
+    ("very_wide_int4", synth.mini("q4", 6, 28672, 32, f=64, n_outliers=8), 4, True),
+    ("no_outliers", synth.mini("q5", 33, 256, 128, f=0), 4, True),
+]
+
+
+@pytest.mark.parametrize("name,spec,bits,packed", RTN_CASES, ids=[c[0] for c in RTN_CASES])
+def test_quantize_rtn(name, spec, bits, packed):
+    say("rtn case %s m=%d n=%d bits=%d packed=%s f=%d" % (name, spec.m, spec.n, bits, packed, spec.f))
+    W = synth.make_weight(spec)
+    if spec.m > 3:
+        W[3, :] = 0.0                                            # an all-zero output row: scale 1, codes 0
+    x_np = synth.make_activations(spec)
+    _, abs_ref, cnt = orc.gram(synth.activations_as_f32(spec, x_np))
+    sm = orc.smooth_outliers(W, abs_ref, cnt, spec.f)
+    ref = orc.quantize_rtn(W, sm.idx, sm.mdiag, bits)
+    ctx = new_ctx()
+    Wd = padded(torch.from_numpy(W).to(DEV), 0 if packed else 4)
+    idx = torch.from_numpy(sm.idx if spec.f else np.zeros(1, np.int32)).to(DEV)
+    mdiag = torch.from_numpy(sm.mdiag).to(DEV)
+    codes = torch.zeros((spec.m, spec.n // 2 if packed else spec.n), dtype=torch.uint8 if packed else torch.int8, device=DEV)
+    scales = torch.empty(spec.m, dtype=torch.float32, device=DEV)
+    T = torch.empty((spec.m, spec.n), dtype=torch.float32, device=DEV)
+    layout = aser.ASER_CODES_INT4_PACKED if packed else aser.ASER_CODES_INT8
+    ctx.check(aser.aser_quantize_rtn(ctx, Wd, idx, mdiag, spec.f, bits, layout, codes, scales, T))
+    torch.cuda.synchronize()
+    got = codes.cpu().numpy()
+    if packed:
+        assert np.array_equal(got, orc.pack_int4(ref.codes))
+        got = unpack_int4(got)
+    assert np.array_equal(got, ref.codes)
+    assert np.array_equal(scales.cpu().numpy(), ref.scales)
+    Tg = T.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(Tg - ref.T) <= 2.0 ** -23 * np.abs(ref.T) + 1e-30)
+    if spec.m > 3:
+        assert ref.scales[3] == 1.0 and not got[3].any()
+
+
+ACT_CASES = [("bf16", synth.mini("a1", 8, 333, 70, f=5)), ("f32", synth.mini("a2", 8, 520, 33, x_dtype="f32", f=3)),
+             ("wide_bf16", synth.mini("a3", 8, 4096, 16, f=8))]
+
+
+@pytest.mark.parametrize("name,spec", ACT_CASES, ids=[c[0] for c in ACT_CASES])
+def test_quantize_act_rtn(name, spec):
+    say("act rtn case %s n=%d tokens=%d" % (name, spec.n, spec.tokens))
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    X = synth.activations_as_f32(spec, x_np)
+    X[1, :] = 0.0
+    if spec.x_dtype == "bf16":
+        x_np = synth.f32_to_bf16_bits(X)
+    else:
+        x_np = X
+    _, abs_ref, cnt = orc.gram(X)
+    sm = orc.smooth_outliers(W, abs_ref, cnt, spec.f)
+    ref_codes, ref_scales = orc.quantize_act_rtn(X, sm.mdiag, 8)
+    ctx = new_ctx()
+    xd = to_dev_x(spec, x_np)
+    codes = torch.zeros((spec.tokens, spec.n), dtype=torch.int8, device=DEV)
+    scales = torch.empty(spec.tokens, dtype=torch.float32, device=DEV)
+    ctx.check(aser.aser_quantize_act_rtn(ctx, xd, torch.from_numpy(sm.mdiag).to(DEV), 8, codes, scales))
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), ref_codes)
+    assert np.array_equal(scales.cpu().numpy(), ref_scales)
+    assert ref_scales[1] == 1.0
+
+
+WHITEN_CASES = [
+    ("c0", synth.CONFIGS["c0"], True),
+    ("ragged", synth.mini("w1", 16, 333, 1200, f=6), True),
+    ("multi_panel", synth.mini("w2", 16, 700, 2800, f=8), True),
+    ("no_smoothing_ill_conditioned", synth.mini("w3", 16, 300, 900, f=0), False),
+]
+
+
+@pytest.mark.parametrize("name,spec,smooth", WHITEN_CASES, ids=[c[0] for c in WHITEN_CASES])
+def test_whiten(name, spec, smooth):
+    say("whiten case %s n=%d" % (name, spec.n))
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    G_ref, abs_ref, cnt = orc.gram(synth.activations_as_f32(spec, x_np))
+    sm = orc.smooth_outliers(W, abs_ref, cnt, spec.f)
+    S_ref = orc.whiten(G_ref, sm.mdiag)
+    ctx = new_ctx()
+    ctx.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, 0))
+    # only the lower triangle of G is defined by the ABI: poison the rest
+    G32 = np.tril(G_ref).astype(np.float32) + np.triu(np.full_like(G_ref, 1e30, dtype=np.float32), 1)
+    Gd = padded(torch.from_numpy(G32).to(DEV), 4)
+    S = torch.empty_like(Gd)
+    st, info = aser.aser_whiten(ctx, Gd, torch.from_numpy(sm.mdiag).to(DEV), 0.0, S)
+    ctx.check(st)
+    assert info == 0
+    Sg = S.cpu().numpy().astype(np.float64)
+    assert np.array_equal(Sg, np.tril(Sg)) and np.all(np.diag(Sg) > 0)
+    Gp = S_ref @ S_ref.T
+    assert np.linalg.norm(Sg @ Sg.T - Gp) / np.linalg.norm(Gp) < 2e-5
+    assert np.linalg.norm(Sg - S_ref) / np.linalg.norm(S_ref) < 5e-4
+    # in place, with damping
+    st, info = aser.aser_whiten(ctx, Gd, torch.from_numpy(sm.mdiag).to(DEV), 0.01, Gd)
+    ctx.check(st)
+    Sd = orc.whiten(G_ref, sm.mdiag, damp=0.01)
+    Sg = Gd.cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(Sg - Sd) / np.linalg.norm(Sd) < 5e-4
+
+
+def test_whiten_reports_non_spd():
+    n = 200
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((400, n)).astype(np.float32)
+    X[:, 150] = 0.0                                              # a dead channel: zero pivot at index 151
+    G = (X.astype(np.float64).T @ X.astype(np.float64)).astype(np.float32)
+    ctx = new_ctx()
+    ctx.ensure_workspace(aser.aser_workspace_bytes(8, n, 0))
+    Gd = torch.from_numpy(G).to(DEV)
+    S = torch.empty_like(Gd)
+    st, info = aser.aser_whiten(ctx, Gd, None, 0.0, S)
+    assert st == aser.ASER_ERR_NOT_SPD and info == 151
+    st, info = aser.aser_whiten(ctx, Gd, None, 0.01, S)            # damping repairs it
+    assert st == aser.ASER_OK and info == 0
+
+
+def check_reconstruction(spec, ref, L_A, L_B, sigma, err_gpu, label):
+    """The parity bars on L_A, L_B, evaluated against the oracle's fp64 T and S."""
+    r = L_A.shape[1]
+    rec = ref.rec if ref.rec.L_A.shape[1] == r else orc.error_reconstruct(ref.quant.T, ref.S, r)
+    e = orc.whitened_error(ref.quant.T, ref.S, L_A, L_B)
+    rel = abs(e - rec.err) / rec.err
+    say("%s: r=%d gap=%.4f oracle err=%.6g gpu(recomputed)=%.6g rel=%.2e gpu scalar rel=%.2e" %
+        (label, r, rec.gap, rec.err, e, rel, abs(err_gpu - rec.err) / rec.err))
+    assert rel <= 1e-4
+    assert abs(err_gpu - rec.err) / rec.err <= 1e-4
+    assert np.allclose(sigma[:min(r, spec.f)], rec.sigma[:min(r, spec.f)], rtol=1e-3)
+    assert np.all(np.diff(sigma) <= 1e-6 * sigma[0])
+    if rec.gap > 1.05:
+        P = L_A.astype(np.float64) @ L_B.astype(np.float64)
+        Pr = rec.L_A @ rec.L_B
+        relP = np.linalg.norm(P - Pr) / np.linalg.norm(Pr)
+        say("%s: product rel Frobenius %.2e" % (label, relP))
+        assert relP <= 1e-3
+    return rec
+
+
+REC_CASES = [
+    ("c0", synth.CONFIGS["c0"], None),
+    ("c0_r_eq_f", synth.CONFIGS["c0"], 4),
+    ("ragged", synth.mini("r1", 150, 333, 1200, r=24, f=6), None),
+    ("ragged_r_eq_f", synth.mini("r1", 150, 333, 1200, r=24, f=6), 6),
+    ("wide", synth.mini("r2", 96, 700, 2800, r=16, f=8), None),
+    ("tall_silu", synth.mini("r3", 600, 260, 1024, r=32, f=8, x_dist="silu_prod", out=(40.0, 40.0)), None),
+]
+
+
+@pytest.mark.parametrize("name,spec,r", REC_CASES, ids=[c[0] for c in REC_CASES])
+def test_error_reconstruct_from_oracle_inputs(name, spec, r):
+    """Stage 4b/4c alone: T and S come from the oracle (rounded to fp32)."""
+    r = spec.r if r is None else r
+    say("reconstruct case %s m=%d n=%d r=%d" % (name, spec.m, spec.n, r))
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    ref = oracle_layer(spec, W, x_np, r=r)
+    ctx = new_ctx()
+    ctx.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, r))
+    T = padded(torch.from_numpy(ref.quant.T.astype(np.float32)).to(DEV), 4)
+    S = torch.from_numpy(ref.S.astype(np.float32)).to(DEV)
+    L_A = torch.empty((spec.m, r), dtype=torch.float32, device=DEV)
+    L_B = torch.empty((r, spec.n), dtype=torch.float32, device=DEV)
+    sigma = torch.empty(r, dtype=torch.float32, device=DEV)
+    st, err, nit = aser.aser_error_reconstruct(ctx, T, S, r, L_A, L_B, sigma)
+    ctx.check(st)
+    assert nit > 0
+    check_reconstruction(spec, ref, L_A.cpu().numpy(), L_B.cpu().numpy(), sigma.cpu().numpy(), err, name)
+
+
+E2E_CASES = [
+    ("c0", synth.CONFIGS["c0"], True),
+    ("c0_int8_no_smoothing", synth.CONFIGS["c0"].with_(bits=8, f=0), False),
+    ("ragged", synth.mini("e1", 130, 333, 1500, r=24, f=6), False),
+    ("c1_shape_small", synth.CONFIGS["c1"].with_(m=512, n=768, tokens=3072, r=32, f=16), True),
+    ("c2_shape_small", synth.CONFIGS["c2"].with_(m=384, n=1032, tokens=4096, r=32, f=16, n_outliers=8), True),
+]
+
+
+def run_e2e(name, spec, packed, x_np=None, ref=None):
+    W = synth.make_weight(spec)
+    if x_np is None:
+        x_np = synth.make_activations(spec)
+    if ref is None:
+        ref = oracle_layer(spec, W, x_np)
+    ctx = new_ctx()
+    buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed)
+    aser.calibrate_layer(ctx, torch.from_numpy(W).to(DEV), to_dev_x(spec, x_np), buf)
+    torch.cuda.synchronize()
+    if spec.f:
+        assert buf.idx.cpu().numpy()[:spec.f].tolist() == ref.smooth.idx.tolist()
+        planted, _ = synth.outlier_channels(spec)
+        assert set(planted.tolist()) <= set(ref.smooth.idx.tolist())
+    codes = buf.codes.cpu().numpy()
+    if packed:
+        codes = unpack_int4(codes)
+    assert np.array_equal(codes, ref.quant.codes)
+    assert np.array_equal(buf.scales.cpu().numpy(), ref.quant.scales)
+    check_reconstruction(spec, ref, buf.L_A.cpu().numpy(), buf.L_B.cpu().numpy(), buf.sigma.cpu().numpy(), buf.err, name)
+    return buf, ref
+
+
+@pytest.mark.parametrize("name,spec,packed", E2E_CASES, ids=[c[0] for c in E2E_CASES])
+def test_end_to_end_layer(name, spec, packed):
+    say("e2e case %s m=%d n=%d N=%d r=%d f=%d" % (name, spec.m, spec.n, spec.tokens, spec.r, spec.f))
+    run_e2e(name, spec, packed)
+
+
+def test_deterministic_integer_outputs():
+    spec = synth.mini("d1", 130, 520, 1500, r=16, f=8)
+    W = torch.from_numpy(synth.make_weight(spec)).to(DEV)
+    X = to_dev_x(spec, synth.make_activations(spec))
+    outs = []
+    for _ in range(2):
+        ctx = new_ctx()
+        buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, True)
+        aser.calibrate_layer(ctx, W, X, buf)
+        torch.cuda.synchronize()
+        outs.append((buf.idx.cpu().numpy().copy(), buf.codes.cpu().numpy().copy(), buf.scales.cpu().numpy().copy()))
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
