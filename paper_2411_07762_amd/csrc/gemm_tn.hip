@@ -230,27 +230,56 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t
     }
 
     // Epilogue.  acc[i][j][e] is C(row, col) with row = 32 i + 8 (e / 4) + 4 (lane / 32) + e % 4,
-    // col = 32 j + lane % 32 inside the wave's sub-tile.
+    // col = 32 j + lane % 32 inside the wave's sub-tile.  The read-modify-write form loads a whole
+    // 32 x 32 block before it stores, so that the loads overlap instead of forming a chain.
     const float alpha = g.alpha;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int64_t col = J0 + wn0 + 32 * j + (lane & 31);
+            const int64_t rbase = I0 + wm0 + 32 * i + 4 * (lane >> 5);
             if (col >= g.N) continue;
+            float* cbase = g.C + rbase * g.ldc + col;
+            if (g.epi == GEMM_EPI_RMW) {
+                float old[16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int64_t row = I0 + wm0 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                if (row >= g.M) continue;
-                const float v = alpha * acc[i][j][e];
-                float* c = g.C + row * g.ldc + col;
-                if (g.epi == GEMM_EPI_STORE) {
-                    *c = v;
-                    if (g.Ct) g.Ct[col * g.ldct + row] = v;
-                } else if (g.epi == GEMM_EPI_ATOMIC) {
-                    unsafeAtomicAdd(c, v);
-                } else {
-                    *c += v;
+                for (int e = 0; e < 16; ++e) {
+                    const int dr = 8 * (e >> 2) + (e & 3);
+                    old[e] = (rbase + dr < g.M) ? cbase[(int64_t)dr * g.ldc] : 0.f;
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int dr = 8 * (e >> 2) + (e & 3);
+                    if (rbase + dr < g.M) cbase[(int64_t)dr * g.ldc] = old[e] + alpha * acc[i][j][e];
+                }
+            } else if (g.epi == GEMM_EPI_ATOMIC) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int dr = 8 * (e >> 2) + (e & 3);
+                    if (rbase + dr < g.M) unsafeAtomicAdd(cbase + (int64_t)dr * g.ldc, alpha * acc[i][j][e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int dr = 8 * (e >> 2) + (e & 3);
+                    if (rbase + dr < g.M) cbase[(int64_t)dr * g.ldc] = alpha * acc[i][j][e];
+                }
+                if (g.Ct) {
+                    // transposed copy: the 4 consecutive rows of one accumulator group are contiguous in Ct
+                    float* tbase = g.Ct + col * g.ldct + rbase;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int dr = 8 * q;
+                        if (rbase + dr + 3 < g.M && ((((uintptr_t)(tbase + dr)) & 15) == 0)) {
+                            *(float4*)(tbase + dr) = make_float4(alpha * acc[i][j][4 * q], alpha * acc[i][j][4 * q + 1],
+                                                                 alpha * acc[i][j][4 * q + 2], alpha * acc[i][j][4 * q + 3]);
+                        } else {
+#pragma unroll
+                            for (int u = 0; u < 4; ++u)
+                                if (rbase + dr + u < g.M) tbase[dr + u] = alpha * acc[i][j][4 * q + u];
+                        }
+                    }
                 }
             }
         }

@@ -91,10 +91,12 @@ int gemm_tn_atomic(aser_ctx* ctx, const float* A, int64_t lda, const float* B, i
     g.M = M; g.N = N; g.K = K; g.alpha = 1.f;
     g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_ATOMIC; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
     g.bm = bm; g.bn = bn;
+    // Split K so that about 256 workgroups run, but keep at least 16 K steps (512 values) per part:
+    // every part pays a pipeline fill and an atomic flush of its whole tile.
     const int64_t tiles = ceil_div64(M, bm) * ceil_div64(N, bn);
-    int64_t parts = ceil_div64(512, tiles);
+    int64_t parts = ceil_div64(256, tiles);
     const int64_t ksteps = ceil_div64(K, 32);
-    const int64_t max_parts = ksteps / 4 > 0 ? ksteps / 4 : 1;
+    const int64_t max_parts = ksteps / 16 > 0 ? ksteps / 16 : 1;
     if (parts > max_parts) parts = max_parts;
     g.k_parts = (int)(parts < 1 ? 1 : parts);
     return aser_gemm_tn(ctx, g);
@@ -180,7 +182,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     float* Zp = Z;
     float* tp = tmp;
     ASER_TRY(chol_qr(ctx, &Qp, &tp, m, b, Mb, Rinv, info));
-    const int bmA = 256, bnB = 128;
+    const int bmA = 128, bnB = 128;
     for (int it = 0; it < p.iters; ++it) {
         ASER_TRY(gemm_tn_atomic(ctx, A, n, Qp, b, Zp, b, n, b, m, bmA, bnB));      // Z = A^T Q
         ASER_TRY(chol_qr(ctx, &Zp, &tp, n, b, Mb, Rinv, info));
