@@ -16,6 +16,8 @@
 // before the MFMAs of step s and written to the other LDS buffer after them: one barrier per
 // step.  fp32 operands are split as x = hi + lo (bf16 each) and contribute hi*hi + hi*lo +
 // lo*hi, accumulated in fp32.
+#include <stdlib.h>
+
 #include "aser_internal.h"
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -43,7 +45,11 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 }
 
 // Per-thread fetch state of one operand tile (BMN rows of the tile, BK k-values per step).
-template <int IN, int BMN>
+// FAST: the operand is 16-byte aligned with leading dimension and extent multiples of the vector
+// width, so every column group is whole; loads are branch-free (rows past the K range are read
+// from the last valid row and zeroed, column groups past the extent are read from group 0 and
+// simply never stored to C).  Otherwise a guarded element-wise path is used.
+template <int IN, int BMN, bool FAST>
 struct Fetch {
     static constexpr int BK = InTraits<IN>::BK;
     static constexpr int VEC = InTraits<IN>::VEC;       // elements per 16-byte load
@@ -51,6 +57,7 @@ struct Fetch {
     static constexpr int ESZ = (IN == GEMM_IN_BF16) ? 2 : 4;
 
     const char* p;      // address of (k row of this thread's first load, first column)
+    const char* plast;  // same column group in the last valid k row (FAST)
     int64_t ld_bytes;
     int64_t k;          // k index of this thread's first row in the current step
     int cg, kb;         // column group and k-block handled by this thread
@@ -58,7 +65,8 @@ struct Fetch {
     bool active, vec_ok;
     uint4 r[8];
 
-    __device__ __forceinline__ void init(const void* base, int64_t ld, int64_t mn0, int64_t MN, int64_t k0, int tid) {
+    __device__ __forceinline__ void init(const void* base, int64_t ld, int64_t mn0, int64_t MN, int64_t k0,
+                                         int64_t kEnd, int tid) {
         active = tid < GROUPS * (BK / 8);
         cg = tid % GROUPS;
         kb = tid / GROUPS;
@@ -67,12 +75,35 @@ struct Fetch {
         ncols = rem >= VEC ? VEC : (rem > 0 ? (int)rem : 0);
         k = k0 + kb * 8;
         ld_bytes = ld * ESZ;
+        if (FAST) {
+            if (ncols != VEC) col = 0;
+            p = (const char*)base + k * ld_bytes + col * ESZ;
+            plast = (const char*)base + (kEnd - 1) * ld_bytes + col * ESZ;
+            vec_ok = true;
+            return;
+        }
         p = (const char*)base + k * ld_bytes + col * ESZ;
+        plast = p;
         vec_ok = (((uintptr_t)p & 15) == 0) && ((ld_bytes & 15) == 0) && ncols == VEC;
         if (ncols == 0) active = false;
     }
 
     __device__ __forceinline__ void load(int64_t kEnd) {
+        if (FAST) {
+            if (!active) return;
+            if (k + 8 <= kEnd) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) r[j] = *(const uint4*)(p + j * ld_bytes);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const bool ok = k + j < kEnd;
+                    const uint4 v = *(const uint4*)(ok ? p + j * ld_bytes : plast);
+                    r[j] = ok ? v : make_uint4(0u, 0u, 0u, 0u);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) r[j] = make_uint4(0u, 0u, 0u, 0u);
         if (!active) return;
@@ -98,6 +129,13 @@ struct Fetch {
                 }
             }
         }
+    }
+
+    // all 8 rows of the step are inside the K range (FAST operands only)
+    __device__ __forceinline__ void load_full() {
+        if (!active) return;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = *(const uint4*)(p + j * ld_bytes);
     }
 
     __device__ __forceinline__ void advance() {
@@ -155,19 +193,55 @@ struct TileCfg {
     static constexpr int TM = BM / 64, TN = BN / 64;     // 32 x 32 MFMA blocks per wave
 };
 
+// Scheduling hint: R groups of (one LDS read, then a share of MF MFMAs).
+template <int R, int MF, int T>
+struct SchedPattern {
+    static __device__ __forceinline__ void emit() {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, (MF * (T + 1)) / R - (MF * T) / R, 0);
+        SchedPattern<R, MF, T + 1>::emit();
+    }
+};
+template <int R, int MF>
+struct SchedPattern<R, MF, R> {
+    static __device__ __forceinline__ void emit() {}
+};
+
+// Scheduling hint for a k-slice that also carries the register -> LDS stores of the next stage:
+// after every MFMA a share of the LDS reads (R), of the VALU work (V: transposes or fp32
+// splits, addresses) and of the LDS writes (W).
+template <int MF, int R, int V, int W, int T>
+struct SchedMix {
+    static __device__ __forceinline__ void emit() {
+        // T counts LDS writes: each is preceded by its share of MFMAs and LDS reads and by the
+        // VALU work (V instructions) that produces the data it writes.
+        constexpr int m = (MF * (T + 1)) / W - (MF * T) / W;
+        constexpr int r = (R * (T + 1)) / W - (R * T) / W;
+        if (m > 0) __builtin_amdgcn_sched_group_barrier(0x008, m, 0);
+        if (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, V, 0);
+        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        SchedMix<MF, R, V, W, T + 1>::emit();
+    }
+};
+template <int MF, int R, int V, int W>
+struct SchedMix<MF, R, V, W, W> {
+    static __device__ __forceinline__ void emit() {}
+};
+
 // One tile of C over the K range [kBeg, kEnd).
-template <int IN, int BM, int BN>
+template <int IN, int BM, int BN, bool FAST>
 __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t J0, int64_t kBeg, int64_t kEnd,
                                           uint4* smem) {
     using Cfg = TileCfg<IN, BM, BN>;
-    constexpr int BK = Cfg::BK, NP = Cfg::NP, KB = Cfg::KB, TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int BK = Cfg::BK, NP = Cfg::NP, KB = Cfg::KB, TM = Cfg::TM, TN = Cfg::TN, KK = BK / 16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
 
-    Fetch<IN, BM> fa;
-    Fetch<IN, BN> fb;
-    fa.init(g.A, g.lda, I0, g.M, kBeg, tid);
-    fb.init(g.B, g.ldb, J0, g.N, kBeg, tid);
+    Fetch<IN, BM, FAST> fa;
+    Fetch<IN, BN, FAST> fb;
+    fa.init(g.A, g.lda, I0, g.M, kBeg, kEnd, tid);
+    fb.init(g.B, g.ldb, J0, g.N, kBeg, kEnd, tid);
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -177,7 +251,15 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // LDS chunk offsets of this lane's MFMA operands inside one k-block pair
+    int offa[TM], offb[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) offa[i] = (lane >> 5) * BM + swz(wm0 + 32 * i + (lane & 31));
+#pragma unroll
+    for (int j = 0; j < TN; ++j) offb[j] = (lane >> 5) * BN + swz(wn0 + 32 * j + (lane & 31));
+
     const int64_t steps = (kEnd - kBeg + BK - 1) / BK;
+    const int64_t full_steps = (kEnd - kBeg) / BK;      // steps whose K range is complete
     if (steps > 0) {
         fa.load(kEnd);
         fb.load(kEnd);
@@ -187,47 +269,153 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t
         fb.advance();
     }
     __syncthreads();
-    for (int64_t s = 0; s < steps; ++s) {
+    constexpr int R = NP * (TM + TN);                   // LDS reads per k-slice
+    constexpr int MF = TM * TN * (NP == 2 ? 3 : 1);     // MFMAs per k-slice
+    constexpr int KH = KK / 2;                          // slices before the stores start
+    // register -> LDS work of one step per wave (instruction counts for the scheduling hints)
+    constexpr int NV = (IN == GEMM_IN_BF16) ? 5 : 14;   // VALU instructions per LDS write
+    constexpr int NW = (IN == GEMM_IN_BF16) ? ((BM + BN) / 32) : ((BM + BN) / 16);
+#ifdef ASER_PROFILE_PHASES
+    long long ph[4] = {0, 0, 0, 0};
+#endif
+    int64_t s = 0;
+    if (FAST) {
+        for (; s + 1 < full_steps; ++s) {
+            const uint4* sa = smem + (s & 1) * Cfg::STAGE_CHUNKS;
+            const uint4* sb = sa + Cfg::A_CHUNKS;
+            uint4* da = smem + ((s + 1) & 1) * Cfg::STAGE_CHUNKS;
+            // Steady state: the next step is complete.  Its global loads are issued first; the
+            // transposing (or splitting) stores to the other LDS stage are interleaved with the
+            // MFMAs of the second half of this step, when the loads have long arrived.
+            fa.load_full();
+            fb.load_full();
+            bf16x8_t a[2][NP][TM], b[2][NP][TN];
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a[0][p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB) * BM + offa[i]]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b[0][p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB) * BN + offb[j]]);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x020, 16, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const int cur = kk & 1, nxt = cur ^ 1;
+                if (kk + 1 < KK) {
+#pragma unroll
+                    for (int p = 0; p < NP; ++p) {
+#pragma unroll
+                        for (int i = 0; i < TM; ++i)
+                            a[nxt][p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB + 2 * (kk + 1)) * BM + offa[i]]);
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            b[nxt][p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB + 2 * (kk + 1)) * BN + offb[j]]);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        if (NP == 2) {
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][1][i], b[cur][0][j], acc[i][j], 0, 0, 0);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][1][j], acc[i][j], 0, 0, 0);
+                        }
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][0][j], acc[i][j], 0, 0, 0);
+                    }
+                if (kk == KH) {
+                    fa.store(da);
+                    fb.store(da + Cfg::A_CHUNKS);
+                }
+                if (kk < KH) {
+                    SchedPattern<R, MF, 0>::emit();
+                } else if (kk + 1 < KK) {
+                    SchedMix<MF, R, NV, NW / (KK - KH), 0>::emit();
+                } else {
+                    SchedMix<MF, 0, NV, NW / (KK - KH), 0>::emit();
+                }
+            }
+            fa.advance();
+            fb.advance();
+            __syncthreads();
+        }
+    }
+    for (; s < steps; ++s) {
+#ifdef ASER_PROFILE_PHASES
+        const long long tA = __builtin_readcyclecounter();
+#endif
         const uint4* sa = smem + (s & 1) * Cfg::STAGE_CHUNKS;
         const uint4* sb = sa + Cfg::A_CHUNKS;
+        uint4* da = smem + ((s + 1) & 1) * Cfg::STAGE_CHUNKS;
         const bool more = s + 1 < steps;
         if (more) {
             fa.load(kEnd);
             fb.load(kEnd);
         }
+        // operand fragments are double buffered: the LDS reads of k-slice kk + 1 are in flight
+        // while the MFMAs of slice kk execute
+        bf16x8_t a[2][NP][TM], b[2][NP][TN];
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int kb = 2 * kk + (lane >> 5);
-            bf16x8_t a[NP][TM], b[NP][TN];
+        for (int p = 0; p < NP; ++p) {
 #pragma unroll
-            for (int p = 0; p < NP; ++p) {
+            for (int i = 0; i < TM; ++i) a[0][p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB) * BM + offa[i]]);
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    a[p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB + kb) * BM + swz(wm0 + 32 * i + (lane & 31))]);
+            for (int j = 0; j < TN; ++j) b[0][p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB) * BN + offb[j]]);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    b[p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB + kb) * BN + swz(wn0 + 32 * j + (lane & 31))]);
+        for (int kk = 0; kk < KK; ++kk) {
+            const int cur = kk & 1, nxt = cur ^ 1;
+            if (kk + 1 < KK) {
+#pragma unroll
+                for (int p = 0; p < NP; ++p) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        a[nxt][p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB + 2 * (kk + 1)) * BM + offa[i]]);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        b[nxt][p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB + 2 * (kk + 1)) * BN + offb[j]]);
+                }
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     if (NP == 2) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[0][j], acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[1][j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][1][i], b[cur][0][j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][1][j], acc[i][j], 0, 0, 0);
                     }
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[0][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][0][j], acc[i][j], 0, 0, 0);
                 }
+            if (kk + 1 < KK) SchedPattern<R, MF, 0>::emit();
+            else __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);
         }
+#ifdef ASER_PROFILE_PHASES
+        const long long tB = __builtin_readcyclecounter();
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
+        const long long tC = __builtin_readcyclecounter();
+#endif
         if (more) {
-            uint4* da = smem + ((s + 1) & 1) * Cfg::STAGE_CHUNKS;
             fa.store(da);
             fb.store(da + Cfg::A_CHUNKS);
             fa.advance();
             fb.advance();
         }
+#ifdef ASER_PROFILE_PHASES
+        const long long tD = __builtin_readcyclecounter();
+#endif
         __syncthreads();
+#ifdef ASER_PROFILE_PHASES
+        const long long tE = __builtin_readcyclecounter();
+        ph[0] += tB - tA; ph[1] += tC - tB; ph[2] += tD - tC; ph[3] += tE - tD;
+#endif
     }
+#ifdef ASER_PROFILE_PHASES
+    if (g.dbg && lane == 0) {
+        for (int q = 0; q < 4; ++q) atomicAdd((unsigned long long*)g.dbg + q, (unsigned long long)ph[q]);
+        atomicAdd((unsigned long long*)g.dbg + 4, (unsigned long long)steps);
+    }
+#endif
 
     // Epilogue.  acc[i][j][e] is C(row, col) with row = 32 i + 8 (e / 4) + 4 (lane / 32) + e % 4,
     // col = 32 j + lane % 32 inside the wave's sub-tile.  The read-modify-write form loads a whole
@@ -286,8 +474,8 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t
 }
 
 // Tile and K-part of a workgroup for the plain schedules.
-template <int IN, int BM, int BN>
-__global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmArgs g) {
+template <int IN, int BM, int BN, bool FAST>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_tn_kernel(GemmArgs g) {
     extern __shared__ uint4 smem[];
     constexpr int BK = InTraits<IN>::BK;
     const int64_t tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
@@ -314,14 +502,22 @@ __global__ __launch_bounds__(kThreads) void gemm_tn_kernel(GemmArgs g) {
     int64_t kEnd = kBeg + per * BK;
     if (kEnd > g.K) kEnd = g.K;
     if (kBeg >= kEnd && g.epi != GEMM_EPI_STORE) return;
-    tile_body<IN, BM, BN>(g, I0, J0, kBeg, kEnd, smem);
+    tile_body<IN, BM, BN, FAST>(g, I0, J0, kBeg, kEnd, smem);
 }
 
-template <int IN, int BM, int BN>
+// True when both operands allow the branch-free 16-byte fetch path.
+template <int IN>
+bool operands_fast(const GemmArgs& g) {
+    constexpr int VEC = InTraits<IN>::VEC;
+    return (((uintptr_t)g.A & 15) == 0) && (((uintptr_t)g.B & 15) == 0) && (g.lda % VEC == 0) && (g.ldb % VEC == 0) &&
+           (g.M % VEC == 0) && (g.N % VEC == 0) && g.K > 0;
+}
+
+template <int IN, int BM, int BN, bool FAST>
 int launch_plain(aser_ctx* ctx, const GemmArgs& g) {
     using Cfg = TileCfg<IN, BM, BN>;
     static bool attr_set[16] = {false};
-    auto kern = gemm_tn_kernel<IN, BM, BN>;
+    auto kern = gemm_tn_kernel<IN, BM, BN, FAST>;
     if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
         ASER_HIP(ctx, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::LDS_BYTES));
         attr_set[ctx->device] = true;
@@ -333,20 +529,107 @@ int launch_plain(aser_ctx* ctx, const GemmArgs& g) {
     return aser_check_launch(ctx, "gemm_tn");
 }
 
+template <int IN, bool FAST>
+int dispatch_tile2(aser_ctx* ctx, const GemmArgs& g) {
+    if (g.bm == 256 && g.bn == 256) return launch_plain<IN, 256, 256, FAST>(ctx, g);
+    if (g.bm == 128 && g.bn == 256) return launch_plain<IN, 128, 256, FAST>(ctx, g);
+    if (g.bm == 256 && g.bn == 128) return launch_plain<IN, 256, 128, FAST>(ctx, g);
+    if (g.bm == 128 && g.bn == 128) return launch_plain<IN, 128, 128, FAST>(ctx, g);
+    ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: unsupported tile %dx%d", g.bm, g.bn);
+}
+
 template <int IN>
 int dispatch_tile(aser_ctx* ctx, const GemmArgs& g) {
-    if (g.bm == 256 && g.bn == 256) return launch_plain<IN, 256, 256>(ctx, g);
-    if (g.bm == 128 && g.bn == 256) return launch_plain<IN, 128, 256>(ctx, g);
-    if (g.bm == 256 && g.bn == 128) return launch_plain<IN, 256, 128>(ctx, g);
-    if (g.bm == 128 && g.bn == 128) return launch_plain<IN, 128, 128>(ctx, g);
-    ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: unsupported tile %dx%d", g.bm, g.bn);
+    if (operands_fast<IN>(g)) return dispatch_tile2<IN, true>(ctx, g);
+    return dispatch_tile2<IN, false>(ctx, g);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Gram update with an XCD-aware persistent schedule.
+//
+// One workgroup per compute unit (256 of them; the tile's LDS footprint allows no more).  Work-
+// groups are dealt to the 8 XCDs round-robin, so workgroup w runs on XCD w % 8 as slot w / 8.
+// XCD x takes the x-th eighth of the token range for EVERY lower-triangle tile; its 32 slots
+// sweep that token range in lock step over 32 tiles at a time.  The tile order (strips of 8
+// tile columns, row-major inside a strip) makes 32 consecutive tiles a 4 x 8 patch that needs
+// only 12 distinct 256-channel slabs of X per K step, so the slabs are fetched from HBM about
+// once per XCD and served from that XCD's L2 to the other workgroups.  Tiles left over after the
+// full rounds are split along K so that all 32 slots stay busy.  Partial tiles are added to G
+// with fp32 atomics (eight XCDs contribute to every tile).
+__device__ __forceinline__ void tri_strip_tile(int64_t t, int nt, int* p_out, int* q_out) {
+    for (int q0 = 0; q0 < nt; q0 += 8) {
+        for (int p = q0; p < nt; ++p) {
+            const int cnt = (p - q0 + 1 < 8) ? (p - q0 + 1) : 8;
+            if (t < cnt) { *p_out = p; *q_out = q0 + (int)t; return; }
+            t -= cnt;
+        }
+    }
+    *p_out = 0; *q_out = 0;
+}
+
+template <int IN, int BM, bool FAST>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void gram_persistent_kernel(GemmArgs g) {
+    extern __shared__ uint4 smem[];
+    constexpr int BK = InTraits<IN>::BK;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int slots = gridDim.x >> 3;                                 // workgroups per XCD
+    const int C = g.k_parts;                                          // K chunks: 1, 2, 4 or 8
+    const int gsz = 8 / C;                                            // XCDs that share one K chunk
+    const int chunk = xcd / gsz, xi = xcd % gsz;
+    const int64_t W = (int64_t)gsz * slots;                           // workgroups per K chunk
+    const int64_t widx = (int64_t)xi * slots + slot;                  // an XCD takes `slots` consecutive tiles
+    const int nt = (int)((g.N + BM - 1) / BM);
+    const int64_t T = (int64_t)nt * (nt + 1) / 2;
+    const int64_t ksteps = (g.K + BK - 1) / BK;
+    const int64_t per = (ksteps + C - 1) / C;
+    const int64_t kx0 = (int64_t)chunk * per * BK;
+    int64_t kx1 = kx0 + per * BK;
+    if (kx1 > g.K) kx1 = g.K;
+    if (kx0 >= kx1) return;
+    const int64_t full = T / W, rem = T % W;
+    const int64_t split = rem > 0 ? W / rem : 1;                      // K split of the left-over tiles
+    const int64_t rounds = full + ((rem > 0 && widx < rem * split) ? 1 : 0);
+    for (int64_t round = 0; round < rounds; ++round) {
+        int64_t t = round * W + widx, k0 = kx0, k1 = kx1;
+        if (round == full) {                                          // left-over tile, one K part of it
+            t = full * W + widx % rem;
+            const int64_t xsteps = (kx1 - kx0 + BK - 1) / BK;
+            const int64_t pp = (xsteps + split - 1) / split;
+            k0 = kx0 + (widx / rem) * pp * BK;
+            k1 = k0 + pp * BK;
+            if (k1 > kx1) k1 = kx1;
+            if (k0 >= k1) break;
+        }
+        int p, q;
+        tri_strip_tile(t, nt, &p, &q);
+        tile_body<IN, BM, BM, FAST>(g, (int64_t)p * BM, (int64_t)q * BM, k0, k1, smem);
+    }
+}
+
+template <int IN, bool FAST>
+int launch_gram_persistent2(aser_ctx* ctx, const GemmArgs& g) {
+    using Cfg = TileCfg<IN, 256, 256>;
+    static bool attr_set[16] = {false};
+    auto kern = gram_persistent_kernel<IN, 256, FAST>;
+    if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
+        ASER_HIP(ctx, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::LDS_BYTES));
+        attr_set[ctx->device] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(256), dim3(kThreads), Cfg::LDS_BYTES, ctx->stream, g);
+    return aser_check_launch(ctx, "gram_persistent");
+}
+
+template <int IN>
+int launch_gram_persistent(aser_ctx* ctx, const GemmArgs& g) {
+    if (operands_fast<IN>(g)) return launch_gram_persistent2<IN, true>(ctx, g);
+    return launch_gram_persistent2<IN, false>(ctx, g);
 }
 
 }  // namespace
 
 int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g) {
     if (g.M <= 0 || g.N <= 0 || g.K < 0) ASER_FAIL(ctx, ASER_ERR_SHAPE, "gemm_tn: bad sizes");
-    if (g.k_parts < 1 || (g.k_parts > 1 && g.epi != GEMM_EPI_ATOMIC))
+    if (g.k_parts < 1 || (g.k_parts > 1 && g.epi != GEMM_EPI_ATOMIC && !getenv("ASER_DBG_STORE")))
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: split K needs the atomic epilogue");
     if (g.tiles != GEMM_TILES_ALL && (g.M != g.N || g.bm != g.bn))
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: triangular tiling needs a square problem and tile");
@@ -356,8 +639,8 @@ int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g) {
     ASER_FAIL(ctx, ASER_ERR_DTYPE, "gemm_tn: unknown input type");
 }
 
-// Gram update: lower-triangle tiles of G += X^T X.  K (= tokens) is split so that the grid
-// fills the 256 compute units a few times over; partial tiles are added with fp32 atomics.
+// Gram update: lower-triangle tiles of G += X^T X.  Large problems use the persistent schedule
+// above; small ones split K over a plain grid.  Partial tiles are added with fp32 atomics.
 int aser_syrk_gram(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int64_t n, int64_t ldx,
                    float* G, int64_t ldg) {
     GemmArgs g{};
@@ -366,10 +649,32 @@ int aser_syrk_gram(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int6
     g.M = n; g.N = n; g.K = rows; g.alpha = 1.f;
     g.in_type = (x_dtype == ASER_DTYPE_BF16) ? GEMM_IN_BF16 : GEMM_IN_F32X3;
     g.epi = GEMM_EPI_ATOMIC; g.tiles = GEMM_TILES_LOWER; g.krange = GEMM_K_FULL;
-    g.bm = g.bn = (n <= 1024) ? 128 : 256;
-    const int64_t t = ceil_div64(n, g.bm), tiles = t * (t + 1) / 2;
     const int bk = (g.in_type == GEMM_IN_BF16) ? 64 : 32;
     const int64_t ksteps = ceil_div64(rows, bk);
+    const int64_t t256 = ceil_div64(n, 256);
+    if (getenv("ASER_DBG_STORE")) g.epi = GEMM_EPI_STORE;
+#ifdef ASER_PROFILE_PHASES
+    if (getenv("ASER_DBG_PTR")) g.dbg = (long long*)strtoull(getenv("ASER_DBG_PTR"), nullptr, 0);
+#endif
+    const int64_t T256 = t256 * (t256 + 1) / 2;
+    if (!getenv("ASER_DBG_PLAIN") && T256 >= 32 && ksteps >= 8 * 16) {
+        // Number of K chunks: fewest steps on the busiest workgroup, each tile visit charged with
+        // the cost of flushing a tile through atomics (about a dozen K steps).
+        int best_c = 8;
+        int64_t best_cost = -1;
+        for (int c = 1; c <= 8; c *= 2) {
+            const int64_t W = 256 / c, full = T256 / W, rem = T256 % W;
+            const int64_t steps_c = ceil_div64(ksteps, c);
+            const int64_t split = rem ? W / rem : 1;
+            const int64_t cost = full * (steps_c + 12) + (rem ? ceil_div64(steps_c, split) + 12 : 0);
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_c = c; }
+        }
+        g.bm = g.bn = 256; g.k_parts = best_c;
+        return (g.in_type == GEMM_IN_BF16) ? launch_gram_persistent<GEMM_IN_BF16>(ctx, g)
+                                           : launch_gram_persistent<GEMM_IN_F32X3>(ctx, g);
+    }
+    g.bm = g.bn = (n <= 1024) ? 128 : 256;
+    const int64_t t = ceil_div64(n, g.bm), tiles = t * (t + 1) / 2;
     int64_t parts = ceil_div64(1024, tiles);              // aim at >= 4 workgroups per CU
     const int64_t max_parts = ksteps / 16 > 0 ? ksteps / 16 : 1;   // keep >= 16 steps per part
     if (parts > max_parts) parts = max_parts;

@@ -38,6 +38,8 @@ GRAM_CASES = [
     ("odd_n_bf16", synth.mini("g3", 8, 77, 300), 2, 3),
     ("f32_ragged", synth.mini("g4", 8, 300, 1111, x_dtype="f32"), 2, 4),
     ("multi_tile_bf16", synth.mini("g5", 8, 1300, 4500), 1, 0),
+    ("persistent_schedule_bf16", synth.mini("g7", 8, 2100, 8300), 1, 0),
+    ("persistent_schedule_f32", synth.mini("g8", 8, 2100, 4200, x_dtype="f32"), 1, 4),
 ]
 
 
