@@ -243,27 +243,27 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const float* Mb, int b, fl
 }
 
 // ------------------------------------------------------------------------------------ small fp32 product
-// C (rows x c) = A (rows x k) * B (k x c) in plain fp32 FMAs.  A workgroup owns 64 rows x 128
-// columns; a thread owns 4 rows x 8 columns and reads its operands from LDS as float4.
+// C (rows x c) = A (rows x k) * B (k x c) in plain fp32 FMAs.  A workgroup owns 32 rows x 128
+// columns; a thread owns 2 rows x 8 columns and reads its operands from LDS as float2 / float4.
 __global__ __launch_bounds__(256) void gemm_small_kernel(const float* __restrict__ A, int64_t lda,
                                                          const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
                                                          int64_t ldc, int64_t rows, int k, int c) {
-    __shared__ __attribute__((aligned(16))) float As[32][68];     // [kk][row]
+    __shared__ __attribute__((aligned(16))) float As[32][34];     // [kk][row]
     __shared__ __attribute__((aligned(16))) float Bs[32][132];    // [kk][col]
     const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
-    const int64_t r0 = (int64_t)blockIdx.x * 64;
+    const int64_t r0 = (int64_t)blockIdx.x * 32;
     const int c0 = blockIdx.y * 128;
-    float acc[4][8];
+    float acc[2][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
     for (int k0 = 0; k0 < k; k0 += 32) {
         {
-            const int r = tid >> 2, kq = (tid & 3) * 8;
+            const int r = tid >> 3, kq = (tid & 7) * 4;
             const int64_t gr = r0 + r;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
+            for (int e = 0; e < 4; ++e) {
                 const int kk = kq + e;
                 As[kk][r] = (gr < rows && k0 + kk < k) ? A[gr * lda + k0 + kk] : 0.f;
             }
@@ -279,21 +279,21 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(const float* __restrict
         __syncthreads();
 #pragma unroll 8
         for (int kk = 0; kk < 32; ++kk) {
-            const float4 av = *(const float4*)&As[kk][4 * ty];
+            const float2 av = *(const float2*)&As[kk][2 * ty];
             const float4 b0 = *(const float4*)&Bs[kk][8 * tx];
             const float4 b1 = *(const float4*)&Bs[kk][8 * tx + 4];
-            const float a4[4] = {av.x, av.y, av.z, av.w};
+            const float a2[2] = {av.x, av.y};
             const float b8[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[i][j] = fmaf(a4[i], b8[j], acc[i][j]);
+                for (int j = 0; j < 8; ++j) acc[i][j] = fmaf(a2[i], b8[j], acc[i][j]);
         }
         __syncthreads();
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int64_t gr = r0 + 4 * ty + i;
+    for (int i = 0; i < 2; ++i) {
+        const int64_t gr = r0 + 2 * ty + i;
         if (gr >= rows) continue;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -333,7 +333,7 @@ int aser_gemm_small_f32(aser_ctx* ctx, const float* A, int64_t lda, const float*
                         int64_t rows, int k, int c) {
     if (rows <= 0) return ASER_OK;
     if (k <= 0 || c <= 0) ASER_FAIL(ctx, ASER_ERR_SHAPE, "gemm_small: k > 0 and c > 0 required");
-    dim3 grid((unsigned)ceil_div64(rows, 64), (unsigned)((c + 127) / 128));
+    dim3 grid((unsigned)ceil_div64(rows, 32), (unsigned)((c + 127) / 128));
     hipLaunchKernelGGL(gemm_small_kernel, grid, dim3(256), 0, ctx->stream, A, lda, B, ldb, C, ldc, rows, k, c);
     return aser_check_launch(ctx, "gemm_small");
 }

@@ -44,6 +44,11 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     return __builtin_bit_cast(uint32_t, h);
 }
 
+// Eight 16-byte rows of one operand block in flight between global memory and LDS.
+struct Staged {
+    uint4 r[8];
+};
+
 // Per-thread fetch state of one operand tile (BMN rows of the tile, BK k-values per step).
 // FAST: the operand is 16-byte aligned with leading dimension and extent multiples of the vector
 // width, so every column group is whole; loads are branch-free (rows past the K range are read
@@ -56,14 +61,13 @@ struct Fetch {
     static constexpr int GROUPS = BMN / VEC;            // 16-byte column groups across the tile
     static constexpr int ESZ = (IN == GEMM_IN_BF16) ? 2 : 4;
 
-    const char* p;      // address of (k row of this thread's first load, first column)
+    const char* p;      // address of (k row of this thread's first load in the next step, first column)
     const char* plast;  // same column group in the last valid k row (FAST)
     int64_t ld_bytes;
-    int64_t k;          // k index of this thread's first row in the current step
+    int64_t k;          // k index of this thread's first row in the next step to be loaded
     int cg, kb;         // column group and k-block handled by this thread
     int ncols;          // valid columns at this thread's group (0..VEC)
     bool active, vec_ok;
-    uint4 r[8];
 
     __device__ __forceinline__ void init(const void* base, int64_t ld, int64_t mn0, int64_t MN, int64_t k0,
                                          int64_t kEnd, int tid) {
@@ -88,7 +92,15 @@ struct Fetch {
         if (ncols == 0) active = false;
     }
 
-    __device__ __forceinline__ void load(int64_t kEnd) {
+    // Issues the loads of the next step into `st` and moves on by one step.
+    __device__ __forceinline__ void load(Staged& st, int64_t kEnd) {
+        load_rows(st, kEnd);
+        p += (int64_t)BK * ld_bytes;
+        k += BK;
+    }
+
+    __device__ __forceinline__ void load_rows(Staged& st, int64_t kEnd) {
+        uint4* r = st.r;
         if (FAST) {
             if (!active) return;
             if (k + 8 <= kEnd) {
@@ -131,24 +143,12 @@ struct Fetch {
         }
     }
 
-    // all 8 rows of the step are inside the K range (FAST operands only)
-    __device__ __forceinline__ void load_full() {
-        if (!active) return;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = *(const uint4*)(p + j * ld_bytes);
-    }
-
-    __device__ __forceinline__ void advance() {
-        p += (int64_t)BK * ld_bytes;
-        k += BK;
-    }
-
-    // Writes this thread's block as k-contiguous chunks into the operand's LDS area.
-    __device__ __forceinline__ void store(uint4* lds) const {
+    // Writes a staged block as k-contiguous chunks into the operand's LDS area.
+    __device__ __forceinline__ void store(const Staged& st, uint4* lds) const {
         if (!active) return;
         constexpr int KB = BK / 8;
         if (IN == GEMM_IN_BF16) {
-            const uint32_t* w = (const uint32_t*)r;       // w[4*j + d]: row j, channel pair d
+            const uint32_t* w = (const uint32_t*)st.r;    // w[4*j + d]: row j, channel pair d
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 const int d = c >> 1;
@@ -161,7 +161,7 @@ struct Fetch {
                 lds[kb * BMN + swz(cg * 8 + c)] = o;
             }
         } else {
-            const float* x = (const float*)r;             // x[4*j + c]: row j, column c
+            const float* x = (const float*)st.r;          // x[4*j + c]: row j, column c
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 uint32_t hi[4], lo[4];
@@ -207,34 +207,65 @@ struct SchedPattern<R, MF, R> {
     static __device__ __forceinline__ void emit() {}
 };
 
-// Scheduling hint for a k-slice that also carries the register -> LDS stores of the next stage:
-// after every MFMA a share of the LDS reads (R), of the VALU work (V: transposes or fp32
-// splits, addresses) and of the LDS writes (W).
-template <int MF, int R, int V, int W, int T>
-struct SchedMix {
-    static __device__ __forceinline__ void emit() {
-        // T counts LDS writes: each is preceded by its share of MFMAs and LDS reads and by the
-        // VALU work (V instructions) that produces the data it writes.
-        constexpr int m = (MF * (T + 1)) / W - (MF * T) / W;
-        constexpr int r = (R * (T + 1)) / W - (R * T) / W;
-        if (m > 0) __builtin_amdgcn_sched_group_barrier(0x008, m, 0);
-        if (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, V, 0);
-        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-        SchedMix<MF, R, V, W, T + 1>::emit();
+// All MFMAs of one K step from LDS stage (sa, sb).  Operand fragments are double buffered: the
+// LDS reads of k-slice kk + 1 are in flight while the MFMAs of slice kk execute (one wave per
+// SIMD: nothing else hides the LDS latency), and the scheduling hints spread them evenly.
+template <int IN, int BM, int BN>
+__device__ __forceinline__ void mfma_step(f32x16_t (&acc)[BM / 64][BN / 64], const uint4* sa, const uint4* sb,
+                                          const int (&offa)[BM / 64], const int (&offb)[BN / 64]) {
+    using Cfg = TileCfg<IN, BM, BN>;
+    constexpr int NP = Cfg::NP, KB = Cfg::KB, TM = Cfg::TM, TN = Cfg::TN, KK = Cfg::BK / 16;
+    constexpr int R = NP * (TM + TN);                   // LDS reads per k-slice
+    constexpr int MF = TM * TN * (NP == 2 ? 3 : 1);     // MFMAs per k-slice
+    bf16x8_t a[2][NP][TM], b[2][NP][TN];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[0][p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB) * BM + offa[i]]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[0][p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB) * BN + offb[j]]);
     }
-};
-template <int MF, int R, int V, int W>
-struct SchedMix<MF, R, V, W, W> {
-    static __device__ __forceinline__ void emit() {}
-};
+    __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        const int cur = kk & 1, nxt = cur ^ 1;
+        if (kk + 1 < KK) {
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    a[nxt][p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB + 2 * (kk + 1)) * BM + offa[i]]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    b[nxt][p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB + 2 * (kk + 1)) * BN + offb[j]]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (NP == 2) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][1][i], b[cur][0][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][1][j], acc[i][j], 0, 0, 0);
+                }
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][0][j], acc[i][j], 0, 0, 0);
+            }
+        if (kk + 1 < KK) SchedPattern<R, MF, 0>::emit();
+        else __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);
+    }
+}
 
 // One tile of C over the K range [kBeg, kEnd).
+//
+// Pipeline: while step s is multiplied out of LDS stage s % 2, the operand blocks of step s + 1
+// (loaded two steps earlier) are transposed/split into stage (s + 1) % 2 and the global loads of
+// step s + 3 are issued into the register set that just became free.  Two register sets per
+// operand keep two steps of global loads in flight, which covers an HBM round trip.
 template <int IN, int BM, int BN, bool FAST>
 __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t J0, int64_t kBeg, int64_t kEnd,
                                           uint4* smem) {
     using Cfg = TileCfg<IN, BM, BN>;
-    constexpr int BK = Cfg::BK, NP = Cfg::NP, KB = Cfg::KB, TM = Cfg::TM, TN = Cfg::TN, KK = BK / 16;
+    constexpr int BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
 
@@ -259,168 +290,99 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t
     for (int j = 0; j < TN; ++j) offb[j] = (lane >> 5) * BN + swz(wn0 + 32 * j + (lane & 31));
 
     const int64_t steps = (kEnd - kBeg + BK - 1) / BK;
-    const int64_t full_steps = (kEnd - kBeg) / BK;      // steps whose K range is complete
-    if (steps > 0) {
-        fa.load(kEnd);
-        fb.load(kEnd);
-        fa.store(smem);
-        fb.store(smem + Cfg::A_CHUNKS);
-        fa.advance();
-        fb.advance();
-    }
-    __syncthreads();
-    constexpr int R = NP * (TM + TN);                   // LDS reads per k-slice
-    constexpr int MF = TM * TN * (NP == 2 ? 3 : 1);     // MFMAs per k-slice
-    constexpr int KH = KK / 2;                          // slices before the stores start
-    // register -> LDS work of one step per wave (instruction counts for the scheduling hints)
-    constexpr int NV = (IN == GEMM_IN_BF16) ? 5 : 14;   // VALU instructions per LDS write
-    constexpr int NW = (IN == GEMM_IN_BF16) ? ((BM + BN) / 32) : ((BM + BN) / 16);
-#ifdef ASER_PROFILE_PHASES
-    long long ph[4] = {0, 0, 0, 0};
-#endif
-    int64_t s = 0;
-    if (FAST) {
-        for (; s + 1 < full_steps; ++s) {
+    // The 256 x 256 tile has no registers left for a second set: one step of loads in flight.
+    constexpr bool TWO_SETS = !(BM == 256 && BN == 256);
+    if (TWO_SETS) {
+        Staged a0, b0, a1, b1;                          // set 0 holds odd steps, set 1 even steps (>= 2)
+        if (steps > 0) {
+            fa.load(a0, kEnd);
+            fb.load(b0, kEnd);
+            fa.store(a0, smem);
+            fb.store(b0, smem + Cfg::A_CHUNKS);
+            if (steps > 1) { fa.load(a0, kEnd); fb.load(b0, kEnd); }
+            if (steps > 2) { fa.load(a1, kEnd); fb.load(b1, kEnd); }
+        }
+        __syncthreads();
+        for (int64_t s = 0; s < steps; s += 2) {
+            {   // even step: next data in set 0
+                const uint4* sa = smem;
+                uint4* da = smem + Cfg::STAGE_CHUNKS;
+                mfma_step<IN, BM, BN>(acc, sa, sa + Cfg::A_CHUNKS, offa, offb);
+                if (s + 1 < steps) {
+                    fa.store(a0, da);
+                    fb.store(b0, da + Cfg::A_CHUNKS);
+                    if (s + 3 < steps) { fa.load(a0, kEnd); fb.load(b0, kEnd); }
+                }
+                __syncthreads();
+            }
+            if (s + 1 < steps) {   // odd step: next data in set 1
+                const uint4* sa = smem + Cfg::STAGE_CHUNKS;
+                uint4* da = smem;
+                mfma_step<IN, BM, BN>(acc, sa, sa + Cfg::A_CHUNKS, offa, offb);
+                if (s + 2 < steps) {
+                    fa.store(a1, da);
+                    fb.store(b1, da + Cfg::A_CHUNKS);
+                    if (s + 4 < steps) { fa.load(a1, kEnd); fb.load(b1, kEnd); }
+                }
+                __syncthreads();
+            }
+        }
+    } else {
+        Staged a0, b0;
+        if (steps > 0) {
+            fa.load(a0, kEnd);
+            fb.load(b0, kEnd);
+            fa.store(a0, smem);
+            fb.store(b0, smem + Cfg::A_CHUNKS);
+            if (steps > 1) { fa.load(a0, kEnd); fb.load(b0, kEnd); }
+        }
+        __syncthreads();
+        for (int64_t s = 0; s < steps; ++s) {
             const uint4* sa = smem + (s & 1) * Cfg::STAGE_CHUNKS;
-            const uint4* sb = sa + Cfg::A_CHUNKS;
             uint4* da = smem + ((s + 1) & 1) * Cfg::STAGE_CHUNKS;
-            // Steady state: the next step is complete.  Its global loads are issued first; the
-            // transposing (or splitting) stores to the other LDS stage are interleaved with the
-            // MFMAs of the second half of this step, when the loads have long arrived.
-            fa.load_full();
-            fb.load_full();
-            bf16x8_t a[2][NP][TM], b[2][NP][TN];
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) a[0][p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB) * BM + offa[i]]);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) b[0][p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB) * BN + offb[j]]);
+            mfma_step<IN, BM, BN>(acc, sa, sa + Cfg::A_CHUNKS, offa, offb);
+            if (s + 1 < steps) {
+                fa.store(a0, da);
+                fb.store(b0, da + Cfg::A_CHUNKS);
+                if (s + 2 < steps) { fa.load(a0, kEnd); fb.load(b0, kEnd); }
             }
-            __builtin_amdgcn_sched_group_barrier(0x020, 16, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                const int cur = kk & 1, nxt = cur ^ 1;
-                if (kk + 1 < KK) {
-#pragma unroll
-                    for (int p = 0; p < NP; ++p) {
-#pragma unroll
-                        for (int i = 0; i < TM; ++i)
-                            a[nxt][p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB + 2 * (kk + 1)) * BM + offa[i]]);
-#pragma unroll
-                        for (int j = 0; j < TN; ++j)
-                            b[nxt][p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB + 2 * (kk + 1)) * BN + offb[j]]);
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        if (NP == 2) {
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][1][i], b[cur][0][j], acc[i][j], 0, 0, 0);
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][1][j], acc[i][j], 0, 0, 0);
-                        }
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][0][j], acc[i][j], 0, 0, 0);
-                    }
-                if (kk == KH) {
-                    fa.store(da);
-                    fb.store(da + Cfg::A_CHUNKS);
-                }
-                if (kk < KH) {
-                    SchedPattern<R, MF, 0>::emit();
-                } else if (kk + 1 < KK) {
-                    SchedMix<MF, R, NV, NW / (KK - KH), 0>::emit();
-                } else {
-                    SchedMix<MF, 0, NV, NW / (KK - KH), 0>::emit();
-                }
-            }
-            fa.advance();
-            fb.advance();
             __syncthreads();
         }
     }
-    for (; s < steps; ++s) {
-#ifdef ASER_PROFILE_PHASES
-        const long long tA = __builtin_readcyclecounter();
-#endif
-        const uint4* sa = smem + (s & 1) * Cfg::STAGE_CHUNKS;
-        const uint4* sb = sa + Cfg::A_CHUNKS;
-        uint4* da = smem + ((s + 1) & 1) * Cfg::STAGE_CHUNKS;
-        const bool more = s + 1 < steps;
-        if (more) {
-            fa.load(kEnd);
-            fb.load(kEnd);
-        }
-        // operand fragments are double buffered: the LDS reads of k-slice kk + 1 are in flight
-        // while the MFMAs of slice kk execute
-        bf16x8_t a[2][NP][TM], b[2][NP][TN];
+
+    // Epilogue.  acc[i][j][e] is C(row, col) with row = 32 i + 8 (e / 4) + 4 (lane / 32) + e % 4,
+    // col = 32 j + lane % 32 inside the wave's sub-tile.
+    const float alpha = g.alpha;
+    if (g.epi == GEMM_EPI_RMW) {
+        // read-modify-write: one row of 32 x 32 blocks (up to 64 values per lane) is loaded before
+        // anything is stored, so that the loads overlap instead of forming a chain
 #pragma unroll
-        for (int p = 0; p < NP; ++p) {
+        for (int i = 0; i < TM; ++i) {
+            const int64_t rbase = I0 + wm0 + 32 * i + 4 * (lane >> 5);
+            float old[TN][16];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[0][p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB) * BM + offa[i]]);
+            for (int j = 0; j < TN; ++j) {
+                const int64_t col = J0 + wn0 + 32 * j + (lane & 31);
+                const float* cbase = g.C + rbase * g.ldc + col;
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[0][p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB) * BN + offb[j]]);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            const int cur = kk & 1, nxt = cur ^ 1;
-            if (kk + 1 < KK) {
-#pragma unroll
-                for (int p = 0; p < NP; ++p) {
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-                        a[nxt][p][i] = __builtin_bit_cast(bf16x8_t, sa[(p * KB + 2 * (kk + 1)) * BM + offa[i]]);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        b[nxt][p][j] = __builtin_bit_cast(bf16x8_t, sb[(p * KB + 2 * (kk + 1)) * BN + offb[j]]);
+                for (int e = 0; e < 16; ++e) {
+                    const int dr = 8 * (e >> 2) + (e & 3);
+                    old[j][e] = (col < g.N && rbase + dr < g.M) ? cbase[(int64_t)dr * g.ldc] : 0.f;
                 }
             }
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int j = 0; j < TN; ++j) {
+                const int64_t col = J0 + wn0 + 32 * j + (lane & 31);
+                float* cbase = g.C + rbase * g.ldc + col;
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    if (NP == 2) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][1][i], b[cur][0][j], acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][1][j], acc[i][j], 0, 0, 0);
-                    }
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][0][j], acc[i][j], 0, 0, 0);
+                for (int e = 0; e < 16; ++e) {
+                    const int dr = 8 * (e >> 2) + (e & 3);
+                    if (col < g.N && rbase + dr < g.M) cbase[(int64_t)dr * g.ldc] = old[j][e] + alpha * acc[i][j][e];
                 }
-            if (kk + 1 < KK) SchedPattern<R, MF, 0>::emit();
-            else __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);
+            }
         }
-#ifdef ASER_PROFILE_PHASES
-        const long long tB = __builtin_readcyclecounter();
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
-        const long long tC = __builtin_readcyclecounter();
-#endif
-        if (more) {
-            fa.store(da);
-            fb.store(da + Cfg::A_CHUNKS);
-            fa.advance();
-            fb.advance();
-        }
-#ifdef ASER_PROFILE_PHASES
-        const long long tD = __builtin_readcyclecounter();
-#endif
-        __syncthreads();
-#ifdef ASER_PROFILE_PHASES
-        const long long tE = __builtin_readcyclecounter();
-        ph[0] += tB - tA; ph[1] += tC - tB; ph[2] += tD - tC; ph[3] += tE - tD;
-#endif
+        return;
     }
-#ifdef ASER_PROFILE_PHASES
-    if (g.dbg && lane == 0) {
-        for (int q = 0; q < 4; ++q) atomicAdd((unsigned long long*)g.dbg + q, (unsigned long long)ph[q]);
-        atomicAdd((unsigned long long*)g.dbg + 4, (unsigned long long)steps);
-    }
-#endif
-
-    // Epilogue.  acc[i][j][e] is C(row, col) with row = 32 i + 8 (e / 4) + 4 (lane / 32) + e % 4,
-    // col = 32 j + lane % 32 inside the wave's sub-tile.  The read-modify-write form loads a whole
-    // 32 x 32 block before it stores, so that the loads overlap instead of forming a chain.
-    const float alpha = g.alpha;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -429,19 +391,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t
             const int64_t rbase = I0 + wm0 + 32 * i + 4 * (lane >> 5);
             if (col >= g.N) continue;
             float* cbase = g.C + rbase * g.ldc + col;
-            if (g.epi == GEMM_EPI_RMW) {
-                float old[16];
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int dr = 8 * (e >> 2) + (e & 3);
-                    old[e] = (rbase + dr < g.M) ? cbase[(int64_t)dr * g.ldc] : 0.f;
-                }
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int dr = 8 * (e >> 2) + (e & 3);
-                    if (rbase + dr < g.M) cbase[(int64_t)dr * g.ldc] = old[e] + alpha * acc[i][j][e];
-                }
-            } else if (g.epi == GEMM_EPI_ATOMIC) {
+            if (g.epi == GEMM_EPI_ATOMIC) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int dr = 8 * (e >> 2) + (e & 3);
