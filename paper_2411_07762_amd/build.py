@@ -22,7 +22,7 @@ OBJDIR = os.path.join(PKG, "_build")
 SOURCES = ["api.hip", "gemm_tn.hip", "bandwidth.hip", "smooth.hip", "dense_small.hip", "whiten.hip", "reconstruct.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument", "-I", INCLUDE, "-I", CSRC] + os.environ.get("ASER_EXTRA_HIPCC_FLAGS", "").split()
+         "-Wno-unused-command-line-argument", "-I", INCLUDE, "-I", CSRC]
 
 
 def _hipcc() -> str:

@@ -75,9 +75,6 @@ struct GemmArgs {
     int in_type, epi, tiles, krange;
     int k_parts;               // split of the K range over blockIdx.y
     int bm, bn;                // tile: 256x256, 128x256, 256x128 or 128x128
-#ifdef ASER_PROFILE_PHASES
-    long long* dbg;            // phase cycle counters (profiling builds only)
-#endif
 };
 int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g);
 

@@ -12,12 +12,10 @@
 // k-contiguous 8 x bf16 chunks (a byte-permute transpose for bf16; for fp32 the hi/lo split
 // packs pairs along k directly), and stores the chunks to LDS in the order the MFMA operands
 // are read: chunk (k-block, row) at [kb][swizzle(row)].  v_mfma_f32_32x32x16_bf16 reads one
-// chunk per lane (row = lane % 32, k-block = lane / 32).  Global loads for step s+1 are issued
-// before the MFMAs of step s and written to the other LDS buffer after them: one barrier per
-// step.  fp32 operands are split as x = hi + lo (bf16 each) and contribute hi*hi + hi*lo +
-// lo*hi, accumulated in fp32.
-#include <stdlib.h>
-
+// chunk per lane (row = lane % 32, k-block = lane / 32).  Global loads run one step (256 x 256
+// tile) or two steps (smaller tiles, two register sets) ahead of the MFMAs; LDS is double
+// buffered with one barrier per step.  fp32 operands are split as x = hi + lo (bf16 each) and
+// contribute hi*hi + hi*lo + lo*hi, accumulated in fp32.
 #include "aser_internal.h"
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -499,13 +497,14 @@ int dispatch_tile(aser_ctx* ctx, const GemmArgs& g) {
 //
 // One workgroup per compute unit (256 of them; the tile's LDS footprint allows no more).  Work-
 // groups are dealt to the 8 XCDs round-robin, so workgroup w runs on XCD w % 8 as slot w / 8.
-// XCD x takes the x-th eighth of the token range for EVERY lower-triangle tile; its 32 slots
-// sweep that token range in lock step over 32 tiles at a time.  The tile order (strips of 8
-// tile columns, row-major inside a strip) makes 32 consecutive tiles a 4 x 8 patch that needs
-// only 12 distinct 256-channel slabs of X per K step, so the slabs are fetched from HBM about
-// once per XCD and served from that XCD's L2 to the other workgroups.  Tiles left over after the
-// full rounds are split along K so that all 32 slots stay busy.  Partial tiles are added to G
-// with fp32 atomics (eight XCDs contribute to every tile).
+// The token range is cut into C chunks (C = 1, 2, 4 or 8, chosen on the host); 8 / C XCDs share
+// a chunk and split the lower-triangle tiles among them, each XCD taking 32 consecutive tiles of
+// the tile order per round.  The tile order (strips of 8 tile columns, row-major inside a strip)
+// makes 32 consecutive tiles a 4 x 8 patch that needs only 12 distinct 256-channel slabs of X
+// per K step, and the 32 workgroups of an XCD sweep their chunk in lock step, so a slab is
+// fetched from HBM about once per XCD and served to the other workgroups from that XCD's L2.
+// Tiles left over after the full rounds are split along K so that every workgroup stays busy.
+// Partial tiles are added to G with fp32 atomics (C chunks contribute to every tile).
 __device__ __forceinline__ void tri_strip_tile(int64_t t, int nt, int* p_out, int* q_out) {
     for (int q0 = 0; q0 < nt; q0 += 8) {
         for (int p = q0; p < nt; ++p) {
@@ -579,7 +578,7 @@ int launch_gram_persistent(aser_ctx* ctx, const GemmArgs& g) {
 
 int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g) {
     if (g.M <= 0 || g.N <= 0 || g.K < 0) ASER_FAIL(ctx, ASER_ERR_SHAPE, "gemm_tn: bad sizes");
-    if (g.k_parts < 1 || (g.k_parts > 1 && g.epi != GEMM_EPI_ATOMIC && !getenv("ASER_DBG_STORE")))
+    if (g.k_parts < 1 || (g.k_parts > 1 && g.epi != GEMM_EPI_ATOMIC))
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: split K needs the atomic epilogue");
     if (g.tiles != GEMM_TILES_ALL && (g.M != g.N || g.bm != g.bn))
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: triangular tiling needs a square problem and tile");
@@ -602,12 +601,8 @@ int aser_syrk_gram(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int6
     const int bk = (g.in_type == GEMM_IN_BF16) ? 64 : 32;
     const int64_t ksteps = ceil_div64(rows, bk);
     const int64_t t256 = ceil_div64(n, 256);
-    if (getenv("ASER_DBG_STORE")) g.epi = GEMM_EPI_STORE;
-#ifdef ASER_PROFILE_PHASES
-    if (getenv("ASER_DBG_PTR")) g.dbg = (long long*)strtoull(getenv("ASER_DBG_PTR"), nullptr, 0);
-#endif
     const int64_t T256 = t256 * (t256 + 1) / 2;
-    if (!getenv("ASER_DBG_PLAIN") && T256 >= 32 && ksteps >= 8 * 16) {
+    if (T256 >= 32 && ksteps >= 8 * 16) {
         // Number of K chunks: fewest steps on the busiest workgroup, each tile visit charged with
         // the cost of flushing a tile through atomics (about a dozen K steps).
         int best_c = 8;
