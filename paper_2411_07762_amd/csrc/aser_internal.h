@@ -99,7 +99,13 @@ int aser_sumsq_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols, in
 int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base);
 // Symmetric eigen-decomposition of the b x b matrix Mb (ld = b) by cyclic Jacobi: eigenvalues
 // descending into lambda (b), eigenvectors as columns of V (b x b, ld = b).  b <= 128, b even.
-int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float* V);
+// `gate` (device, may be null): the kernel returns at once when *gate == 0.
+int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float* V, const int* gate);
+// Same result by tridiagonalisation + multisection + twisted factorisation (much faster).  Scratch: refl
+// (b * 128 floats) and tri (384 floats).  *cluster_flag (device) is written: 1 when two eigenvalues are too
+// close for that method, else 0; the caller then runs aser_jacobi_eig gated on the flag.  2 <= b <= 128.
+int aser_tridiag_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float* V, float* refl, float* tri,
+                     int* cluster_flag);
 // C (rows x c) = A (rows x k) * B (k x c), plain fp32 FMA; k, c <= 256.  C may not alias A.
 int aser_gemm_small_f32(aser_ctx* ctx, const float* A, int64_t lda, const float* B, int64_t ldb,
                         float* C, int64_t ldc, int64_t rows, int k, int c);

@@ -7,6 +7,9 @@
 
 namespace {
 
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
@@ -41,20 +44,22 @@ __global__ void fill_zero_kernel(uint32_t* p, int64_t words) {
 }
 
 // ------------------------------------------------------------------------------------ column |.| sums
-// Each thread owns one 16-byte column group and a strip of rows; fp64 partial sums go to
-// abs_sum with one fp64 atomic per column and strip.
+// A workgroup is 64 column groups (16 bytes each) x 4 row lanes over a strip of rows.  Each thread
+// sums its rows in fp64; the four row lanes are combined through LDS and one fp64 atomic per
+// column and strip goes to abs_sum.
 template <bool BF16>
 __global__ __launch_bounds__(256) void col_abs_sum_kernel(const void* X, int64_t rows, int64_t n, int64_t ld,
                                                           int64_t rows_per_block, double* out, int64_t* count,
                                                           int64_t count_add) {
     constexpr int VEC = BF16 ? 8 : 4;
     constexpr int ESZ = BF16 ? 2 : 4;
+    __shared__ double part[3][64][VEC];
     if (count && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
         atomicAdd((unsigned long long*)count, (unsigned long long)count_add);
     if (!out) return;
-    const int64_t col = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
-    if (col >= n) return;
-    const int nc = (n - col >= VEC) ? VEC : (int)(n - col);
+    const int cgl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+    const int64_t col = ((int64_t)blockIdx.x * 64 + cgl) * VEC;
+    const int nc = (col >= n) ? 0 : ((n - col >= VEC) ? VEC : (int)(n - col));
     const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
     const int64_t r1 = (r0 + rows_per_block < rows) ? r0 + rows_per_block : rows;
     const char* base = (const char*)X + col * ESZ;
@@ -63,11 +68,11 @@ __global__ __launch_bounds__(256) void col_abs_sum_kernel(const void* X, int64_t
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
     if (vec_ok) {
-        int64_t r = r0;
-        for (; r + 4 <= r1; r += 4) {
+        int64_t r = r0 + rl;
+        for (; r + 12 < r1; r += 16) {
             uint4 v[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = *(const uint4*)(base + (r + u) * ld * ESZ);
+            for (int u = 0; u < 4; ++u) v[u] = *(const uint4*)(base + (r + 4 * u) * ld * ESZ);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
@@ -82,7 +87,7 @@ __global__ __launch_bounds__(256) void col_abs_sum_kernel(const void* X, int64_t
                 }
             }
         }
-        for (; r < r1; ++r) {
+        for (; r < r1; r += 4) {
             const uint4 v = *(const uint4*)(base + r * ld * ESZ);
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -95,8 +100,8 @@ __global__ __launch_bounds__(256) void col_abs_sum_kernel(const void* X, int64_t
                 }
             }
         }
-    } else {
-        for (int64_t r = r0; r < r1; ++r) {
+    } else if (nc > 0) {
+        for (int64_t r = r0 + rl; r < r1; r += 4) {
             const char* q = base + r * ld * ESZ;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
@@ -108,9 +113,18 @@ __global__ __launch_bounds__(256) void col_abs_sum_kernel(const void* X, int64_t
             }
         }
     }
+    if (rl > 0) {
 #pragma unroll
-    for (int e = 0; e < VEC; ++e)
-        if (e < nc) atomicAdd(out + col + e, acc[e]);
+        for (int e = 0; e < VEC; ++e) part[rl - 1][cgl][e] = acc[e];
+    }
+    __syncthreads();
+    if (rl == 0) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const double t = acc[e] + part[0][cgl][e] + part[1][cgl][e] + part[2][cgl][e];
+            if (e < nc) atomicAdd(out + col + e, t);
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------ transpose
@@ -147,10 +161,12 @@ __global__ __launch_bounds__(256) void sumsq_kernel(const float* A, int64_t rows
 }
 
 // ------------------------------------------------------------------------------------ weight RTN
-// One workgroup per output row.  The row stays in registers between the absmax reduction and
-// the quantization, so W is read from HBM once.  Integer decisions (scale, codes) are taken in
-// IEEE fp32 with correctly rounded division and round-half-to-even.
-template <int VPT>   // float4 per thread
+// One workgroup per output row.  A thread owns groups of 8 consecutive columns; the row stays in
+// registers between the absmax reduction and the quantization, so W is read from HBM once.  The
+// global loads are issued before the outlier-column bitmask is built in LDS, so that its two
+// barriers overlap the load latency.  Integer decisions (scale, codes) are taken in IEEE fp32 with
+// correctly rounded division and round-half-to-even.
+template <int VPT>   // 8-column groups per thread
 __global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ W, int64_t n, int64_t ldw,
                                                   const int32_t* __restrict__ idx, const float* __restrict__ mdiag, int f,
                                                   float qmax, int layout, uint8_t* __restrict__ codes, int64_t code_pitch,
@@ -160,6 +176,27 @@ __global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ W, i
     float* red = (float*)(smem_u32 + ((n + 31) / 32));
     const int64_t row = blockIdx.x;
     const int tid = threadIdx.x;
+    const float* wrow = W + row * ldw;
+    const bool vec_ok = (((uintptr_t)wrow & 15) == 0) && ((n & 7) == 0);
+    float v[VPT][8];
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+        const int64_t c = ((int64_t)u * 256 + tid) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[u][e] = 0.f;
+        if (c < n) {
+            if (vec_ok) {
+                const f32x4_t x0 = __builtin_nontemporal_load((const f32x4_t*)(wrow + c));
+                const f32x4_t x1 = __builtin_nontemporal_load((const f32x4_t*)(wrow + c + 4));
+                v[u][0] = x0.x; v[u][1] = x0.y; v[u][2] = x0.z; v[u][3] = x0.w;
+                v[u][4] = x1.x; v[u][5] = x1.y; v[u][6] = x1.z; v[u][7] = x1.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (c + e < n) v[u][e] = wrow[c + e];
+            }
+        }
+    }
     const int mask_words = (int)((n + 31) / 32);
     for (int i = tid; i < mask_words; i += 256) mask[i] = 0u;
     __syncthreads();
@@ -169,30 +206,16 @@ __global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ W, i
     }
     __syncthreads();
 
-    const float* wrow = W + row * ldw;
-    const bool vec_ok = (((uintptr_t)wrow & 15) == 0) && ((n & 3) == 0);
-    float4 v[VPT];
-    uint32_t om[VPT];                                 // 4 outlier bits per float4
+    uint32_t om[VPT];                                 // 8 outlier bits per group
     float amax = 0.f;
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int64_t c = ((int64_t)u * 256 + tid) * 4;
-        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int64_t c = ((int64_t)u * 256 + tid) * 8;
         om[u] = 0u;
         if (c < n) {
-            if (vec_ok) {
-                v[u] = *(const float4*)(wrow + c);
-            } else {
-                float t[4] = {0.f, 0.f, 0.f, 0.f};
-                for (int e = 0; e < 4; ++e)
-                    if (c + e < n) t[e] = wrow[c + e];
-                v[u] = make_float4(t[0], t[1], t[2], t[3]);
-            }
-            // c is a multiple of 4, so the four bits sit in one mask word
-            om[u] = (mask[c >> 5] >> (c & 31)) & 0xFu;
-            const float a0 = (om[u] & 1u) ? 0.f : fabsf(v[u].x), a1 = (om[u] & 2u) ? 0.f : fabsf(v[u].y);
-            const float a2 = (om[u] & 4u) ? 0.f : fabsf(v[u].z), a3 = (om[u] & 8u) ? 0.f : fabsf(v[u].w);
-            amax = fmaxf(amax, fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)));
+            om[u] = (mask[c >> 5] >> (c & 31)) & 0xFFu;   // c is a multiple of 8: one mask word
+#pragma unroll
+            for (int e = 0; e < 8; ++e) amax = fmaxf(amax, ((om[u] >> e) & 1u) ? 0.f : fabsf(v[u][e]));
         }
     }
     amax = block_max(amax, red);
@@ -201,44 +224,60 @@ __global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ W, i
 
     uint8_t* crow = codes + row * code_pitch;
     float* trow = T ? T + row * ldt : nullptr;
-    const bool t_vec = T && (((uintptr_t)trow & 15) == 0) && ((n & 3) == 0);
+    const bool t_vec = T && (((uintptr_t)trow & 15) == 0) && ((n & 7) == 0);
+    const bool c_vec = vec_ok && (((uintptr_t)crow & 7) == 0);
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int64_t c = ((int64_t)u * 256 + tid) * 4;
+        const int64_t c = ((int64_t)u * 256 + tid) * 8;
         if (c >= n) continue;
-        const float w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-        float t[4];
-        int q[4];
+        float t[8];
+        int q[8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+        for (int e = 0; e < 8; ++e) {
             if ((om[u] >> e) & 1u) {
                 q[e] = 0;
-                t[e] = (c + e < n) ? w[e] * mdiag[c + e] : 0.f;
+                t[e] = (c + e < n) ? v[u][e] * mdiag[c + e] : 0.f;
             } else {
-                float qf = rintf(w[e] / scale);
+                float qf = rintf(v[u][e] / scale);
                 qf = fminf(fmaxf(qf, -qmax), qmax);
                 q[e] = (int)qf;
-                t[e] = __fmaf_rn(-qf, scale, w[e]);
+                t[e] = __fmaf_rn(-qf, scale, v[u][e]);
             }
         }
         if (layout == ASER_CODES_INT8) {
-            if (vec_ok && (((uintptr_t)crow & 3) == 0)) {
-                const uint32_t packed = (uint32_t)(q[0] & 0xFF) | ((uint32_t)(q[1] & 0xFF) << 8) |
-                                        ((uint32_t)(q[2] & 0xFF) << 16) | ((uint32_t)(q[3] & 0xFF) << 24);
-                *(uint32_t*)(crow + c) = packed;
+            if (c_vec) {
+                uint2 pk;
+                pk.x = (uint32_t)(q[0] & 0xFF) | ((uint32_t)(q[1] & 0xFF) << 8) | ((uint32_t)(q[2] & 0xFF) << 16) |
+                       ((uint32_t)(q[3] & 0xFF) << 24);
+                pk.y = (uint32_t)(q[4] & 0xFF) | ((uint32_t)(q[5] & 0xFF) << 8) | ((uint32_t)(q[6] & 0xFF) << 16) |
+                       ((uint32_t)(q[7] & 0xFF) << 24);
+                const u32x2_t pkv = {pk.x, pk.y};
+                __builtin_nontemporal_store(pkv, (u32x2_t*)(crow + c));
             } else {
-                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
                     if (c + e < n) crow[c + e] = (uint8_t)(q[e] & 0xFF);
             }
         } else {   // int4, n even: columns (c, c+1) -> byte c/2, low nibble = even column
-            if (c + 1 < n) crow[c / 2] = (uint8_t)((q[0] & 0xF) | ((q[1] & 0xF) << 4));
-            if (c + 3 < n) crow[c / 2 + 1] = (uint8_t)((q[2] & 0xF) | ((q[3] & 0xF) << 4));
+            if (c_vec) {
+                uint32_t pk = 0u;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pk |= (uint32_t)(q[e] & 0xF) << (4 * e);
+                __builtin_nontemporal_store(pk, (uint32_t*)(crow + c / 2));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; e += 2)
+                    if (c + e + 1 < n) crow[(c + e) / 2] = (uint8_t)((q[e] & 0xF) | ((q[e + 1] & 0xF) << 4));
+            }
         }
         if (trow) {
             if (t_vec) {
-                *(float4*)(trow + c) = make_float4(t[0], t[1], t[2], t[3]);
+                const f32x4_t t0 = {t[0], t[1], t[2], t[3]}, t1 = {t[4], t[5], t[6], t[7]};
+                __builtin_nontemporal_store(t0, (f32x4_t*)(trow + c));
+                __builtin_nontemporal_store(t1, (f32x4_t*)(trow + c + 4));
             } else {
-                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
                     if (c + e < n) trow[c + e] = t[e];
             }
         }
@@ -315,9 +354,8 @@ int aser_fill_bytes(aser_ctx* ctx, void* p, size_t bytes) {
 int aser_col_abs_sum_x(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int64_t n, int64_t ldx,
                        double* abs_sum, int64_t* count) {
     const int vec = (x_dtype == ASER_DTYPE_BF16) ? 8 : 4;
-    const int64_t groups = ceil_div64(n, vec);
-    const int64_t gx = ceil_div64(groups, 256);
-    int64_t rpb = 64;
+    const int64_t gx = ceil_div64(ceil_div64(n, vec), 64);
+    int64_t rpb = 256;
     while (ceil_div64(rows, rpb) > 65535) rpb *= 2;
     const int64_t gy = ceil_div64(rows, rpb);
     dim3 grid((unsigned)gx, (unsigned)gy);
@@ -329,8 +367,8 @@ int aser_col_abs_sum_x(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, 
 }
 
 int aser_col_abs_sum_w(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw, double* wsum) {
-    const int64_t gx = ceil_div64(ceil_div64(n, 4), 256);
-    int64_t rpb = 32;
+    const int64_t gx = ceil_div64(ceil_div64(n, 4), 64);
+    int64_t rpb = 128;
     while (ceil_div64(m, rpb) > 65535) rpb *= 2;
     dim3 grid((unsigned)gx, (unsigned)ceil_div64(m, rpb));
     hipLaunchKernelGGL(col_abs_sum_kernel<false>, grid, dim3(256), 0, ctx->stream, (const void*)W, m, n, ldw, rpb, wsum,
@@ -372,15 +410,15 @@ extern "C" int aser_quantize_rtn(aser_ctx* ctx, const float* W, int64_t m, int64
     const float qmax = (float)((1 << (bits - 1)) - 1);
     const int64_t pitch = (layout == ASER_CODES_INT8) ? n : n / 2;
     const size_t lds = (size_t)((n + 31) / 32) * 4 + 64;
-    const int64_t groups = ceil_div64(n, 4);
+    const int64_t groups = ceil_div64(n, 8);
     dim3 grid((unsigned)m);
 #define ASER_RTN_LAUNCH(V)                                                                                     \
     hipLaunchKernelGGL(rtn_kernel<V>, grid, dim3(256), lds, ctx->stream, W, n, ldw, idx, mdiag, (int)f, qmax, \
                        (int)layout, (uint8_t*)codes, pitch, scales, T, ldt)
-    if (groups <= 256 * 4) ASER_RTN_LAUNCH(4);
+    if (groups <= 256 * 2) ASER_RTN_LAUNCH(2);
+    else if (groups <= 256 * 4) ASER_RTN_LAUNCH(4);
     else if (groups <= 256 * 8) ASER_RTN_LAUNCH(8);
-    else if (groups <= 256 * 16) ASER_RTN_LAUNCH(16);
-    else ASER_RTN_LAUNCH(32);
+    else ASER_RTN_LAUNCH(16);
 #undef ASER_RTN_LAUNCH
     return aser_check_launch(ctx, "rtn");
 }

@@ -137,7 +137,9 @@ __global__ __launch_bounds__(256) void chol_block_kernel(float* D, int64_t ld, i
 // ------------------------------------------------------------------------------------ Jacobi
 // Cyclic Jacobi with the round-robin pairing: b / 2 disjoint rotations per round, b - 1 rounds
 // per sweep.  M and V live in LDS.
-__global__ __launch_bounds__(1024) void jacobi_kernel(const float* Mb, int b, float* lambda, float* Vout, int max_sweeps) {
+__global__ __launch_bounds__(1024) void jacobi_kernel(const float* Mb, int b, float* lambda, float* Vout, int max_sweeps,
+                                                      const int* gate) {
+    if (gate && *gate == 0) return;                  // the fast solver already delivered the result
     extern __shared__ float sm[];
     float* M = sm;
     float* V = sm + kMaxB * kLdsPitch;
@@ -317,7 +319,7 @@ int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int
     return aser_check_launch(ctx, "chol_block");
 }
 
-int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float* V) {
+int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float* V, const int* gate) {
     if (b <= 0 || b > kMaxB || (b & 1)) ASER_FAIL(ctx, ASER_ERR_SHAPE, "jacobi: block size must be even and <= 128");
     static bool attr_set[16] = {false};
     const size_t lds = (size_t)(2 * kMaxB * kLdsPitch + kMaxB + kMaxB + 32) * 4;
@@ -325,7 +327,7 @@ int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float*
         ASER_HIP(ctx, hipFuncSetAttribute((const void*)jacobi_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set[ctx->device] = true;
     }
-    hipLaunchKernelGGL(jacobi_kernel, dim3(1), dim3(1024), lds, ctx->stream, Mb, b, lambda, V, 30);
+    hipLaunchKernelGGL(jacobi_kernel, dim3(1), dim3(1024), lds, ctx->stream, Mb, b, lambda, V, 30, gate);
     return aser_check_launch(ctx, "jacobi");
 }
 

@@ -8,7 +8,7 @@
 //     Q   = A Z     (m x b)      K = n, operands A^T and Z
 //     Z^T Z, Q^T Q  (b x b)      Gram matrices of the Cholesky-QR orthogonalisation
 //     C^T = T^T Q   (n x b)      for L_B
-// The b x b work (Cholesky, inverse, Jacobi eigen-solver) runs in one workgroup in LDS.
+// The b x b work (Cholesky, inverse, symmetric eigen-solver) runs in one workgroup in LDS.
 #include <math.h>
 
 #include "aser_internal.h"
@@ -68,7 +68,7 @@ int make_plan(int64_t m, int64_t n, int r, const aser_svd_opts* o, Plan* p) {
     p->off_Q = off; off += align_up((size_t)mx * p->b * 4, 256);
     p->off_Z = off; off += align_up((size_t)mx * p->b * 4, 256);
     p->off_tmp = off; off += align_up((size_t)mx * p->b * 4, 256);
-    p->off_small = off; off += align_up((size_t)p->b * p->b * 4, 256) * 3 + 4096 + align_up((size_t)p->b * 128 * 4, 256) * 2;
+    p->off_small = off; off += align_up((size_t)p->b * p->b * 4, 256) * 3 + 8192 + align_up((size_t)p->b * 128 * 4, 256) * 3;
     p->total = off;
     return ASER_OK;
 }
@@ -154,8 +154,12 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     float* lambda = (float*)(sm + 3 * bb);                 // b floats
     double* normA2 = (double*)(sm + 3 * bb + 1024);
     int32_t* info = (int32_t*)(sm + 3 * bb + 2048);
-    float* WA = (float*)(sm + 3 * bb + 4096);
-    float* WBt = (float*)(sm + 3 * bb + 4096 + align_up((size_t)b * 128 * 4, 256));
+    int32_t* cluster = (int32_t*)(sm + 3 * bb + 3072);
+    float* tri = (float*)(sm + 3 * bb + 4096);             // 384 floats
+    const size_t b128 = align_up((size_t)b * 128 * 4, 256);
+    float* WA = (float*)(sm + 3 * bb + 8192);
+    float* WBt = (float*)(sm + 3 * bb + 8192 + b128);
+    float* refl = (float*)(sm + 3 * bb + 8192 + 2 * b128);
 
     // A = T S through T^T (K-major operand), A^T
     ASER_TRY(aser_transpose_f32(ctx, T, m, n, ldt, big0, m));
@@ -195,7 +199,8 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     // Rayleigh-Ritz: Z = A^T Q, eigen-pairs of Z^T Z = Q^T A A^T Q
     ASER_TRY(gemm_tn_atomic(ctx, A, n, Qp, b, Zp, b, n, b, m, bmA, bnB));
     ASER_TRY(gemm_tn_atomic(ctx, Zp, b, Zp, b, Mb, b, b, b, n, 128, 128));
-    ASER_TRY(aser_jacobi_eig(ctx, Mb, b, lambda, Uhat));
+    ASER_TRY(aser_tridiag_eig(ctx, Mb, b, lambda, Uhat, refl, tri, cluster));
+    ASER_TRY(aser_jacobi_eig(ctx, Mb, b, lambda, Uhat, cluster));      // only runs if eigenvalues cluster
     hipLaunchKernelGGL(ritz_factors_kernel, dim3(16), dim3(256), 0, ctx->stream, (const float*)lambda, (const float*)Uhat, b,
                        (int)r, sigma, WA, WBt);
     ASER_TRY(aser_check_launch(ctx, "ritz_factors"));

@@ -346,6 +346,15 @@ def test_end_to_end_layer(name, spec, packed):
     run_e2e(name, spec, packed)
 
 
+def test_headline_layer_full_size():
+    """The 4096 x 4096 layer with 32768 calibration tokens (the configuration the bench times),
+    every output against the oracle: this is the only case where the persistent Gram schedule,
+    32 Cholesky panels and the 128-wide subspace iteration all run at their real shapes."""
+    spec = synth.CONFIGS["c1"]
+    say("e2e case c1 full size m=%d n=%d N=%d r=%d f=%d" % (spec.m, spec.n, spec.tokens, spec.r, spec.f))
+    run_e2e("c1_full", spec, True)
+
+
 def test_deterministic_integer_outputs():
     spec = synth.mini("d1", 130, 520, 1500, r=16, f=8)
     W = torch.from_numpy(synth.make_weight(spec)).to(DEV)
