@@ -1,0 +1,199 @@
+// Cholesky factor and its inverse for one diagonal block (b <= 128) of the blocked Cholesky of
+// the whitening step (Eq. 5) and of the Cholesky-QR steps of the truncated SVD (Eq. 6).
+//
+// One workgroup of 8 wavefronts, the block in LDS, blocked again into 32-wide sub-blocks k = 0..3.
+// All arithmetic is fp32: the products run on the fp32 MFMA instructions.
+//
+//   1. one wavefront factors the 32 x 32 diagonal sub-block A_kk with the sub-block and an identity
+//      next to it held in two 32 x 32 MFMA accumulators.  Pivot j: reciprocal square root of the
+//      diagonal entry, row j scaled (that is row j of R_kk and, in the second accumulator, row j of
+//      L_kk^-1 with R_kk = L_kk^T), then one rank-1 MFMA update per accumulator.  An accumulator
+//      register holds row j in one half of the lanes and row j +- 4 in the other; the MFMA's second
+//      k-slot takes a zero multiplier for that half, so no lane exchange is needed.
+//   2. everyone, 16 x 16 MFMA tiles: row panel R[k, right] = L_kk^-1 A[k, right] and, for the
+//      inverse, Y = R[above, k] X_kk with X_kk = R_kk^-1.
+//   3. everyone: trailing update A[right, right] -= R[k, right]^T R[k, right] over the upper
+//      triangle of tiles, and the new block column of the inverse X[above, k] = -X[above, above] Y.
+//
+// A non-positive pivot at column j is reported as atomicMin(info, pivot_base + j + 1) and replaced
+// by 1.  Rows and columns beyond b are padded with the identity.
+#include "aser_internal.h"
+
+namespace {
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef float f4v __attribute__((ext_vector_type(4)));
+
+constexpr int kN = 128;       // largest block
+constexpr int kP = 133;       // odd LDS pitch: a wavefront reads along a row or a column without bank conflicts
+constexpr int kPY = 33;
+constexpr int kSub = 32;
+constexpr int kThreads = 512;
+constexpr int kWaves = kThreads / 64;
+
+__device__ __forceinline__ float lane_bcast(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// acc(16 x 16) += sum over nk4 * 4 values of k of  sa * Aop(i, k) * Bop(k, c).  pa points at
+// Aop(lane & 15, lane >> 4), pb at Bop(lane >> 4, lane & 15); sak / sbk are the strides along k.
+__device__ __forceinline__ f4v mma16(f4v acc, const float* pa, int sak, const float* pb, int sbk, int nk4, float sa) {
+#pragma unroll 4
+    for (int s = 0; s < nk4; ++s) {
+        const float a = pa[s * 4 * sak] * sa, bv = pb[s * 4 * sbk];
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv, acc, 0, 0, 0);
+    }
+    return acc;
+}
+
+__global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t ld, int b, float* Rinv, int32_t* info,
+                                                              int32_t pivot_base) {
+    extern __shared__ __align__(16) float sm[];
+    float* As = sm;                      // working matrix, upper triangle -> R
+    float* Xs = As + kN * kP;            // R^-1 (upper), zero elsewhere
+    float* Ys = Xs + kN * kP;            // 96 x 32 scratch
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nsub = (b + kSub - 1) / kSub;
+    const int nb = nsub * kSub;          // padded with the identity up to here
+    // 16 x 16 tile roles of this lane
+    const int t_i = lane & 15, t_q = lane >> 4;
+
+    for (int t = tid; t < nb * kN; t += kThreads) {
+        const int i = t >> 7, k = t & 127;
+        float v = (k == i) ? 1.f : 0.f;
+        if (k >= i && k < b && i < b) v = D[(int64_t)i * ld + k];
+        As[i * kP + k] = v;
+        Xs[i * kP + k] = 0.f;
+    }
+    __syncthreads();
+
+    for (int kb = 0; kb < nsub; ++kb) {
+        const int o = kb * kSub;
+        const int ncb = nsub - 1 - kb;             // 32-column blocks to the right
+
+        // ---- 1. diagonal sub-block: accumulator register e of lane l holds row 8 (e / 4) + 4 (l / 32) + e % 4, column l % 32
+        if (wave == 0) {
+            const int h = lane >> 5, col = lane & 31;
+            f16v a1, a2;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = 8 * (e / 4) + 4 * h + e % 4;
+                a1[e] = As[(o + row) * kP + o + col];
+                a2[e] = (row == col) ? 1.f : 0.f;
+            }
+            int bad = kSub;
+#pragma unroll
+            for (int j = 0; j < kSub; ++j) {
+                const int e = 4 * (j / 8) + j % 4, hj = (j / 4) & 1;
+                float piv = lane_bcast(a1[e], 32 * hj + j);
+                if (!(piv > 0.f)) {
+                    if (bad > j) bad = j;
+                    piv = 1.f;
+                    a1[e] = (lane == 32 * hj + j) ? 1.f : a1[e];
+                }
+                const float rs = __builtin_amdgcn_rsqf(piv);      // 1 ulp: as good as the fp32 data it scales
+                const float rv = a1[e] * rs, lv = a2[e] * rs;
+                if (h == hj) {
+                    As[(o + j) * kP + o + col] = rv;              // row j of R_kk (entries left of the diagonal are dead)
+                    Xs[(o + col) * kP + o + j] = lv;              // X_kk = (L_kk^-1)^T
+                }
+                if (j + 1 < kSub) {
+                    const float mult = (h == hj) ? -rv : 0.f;
+                    a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, rv, a1, 0, 0, 0);
+                    a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, lv, a2, 0, 0, 0);
+                }
+            }
+            if (bad < kSub && lane == 0 && o + bad < b && info) atomicMin(info, pivot_base + o + bad + 1);
+        }
+        __syncthreads();
+
+        // ---- 2. panel (one job per 16-column tile, both row halves) and Y (one job per 16 x 16 tile)
+        {
+            const int npan = 2 * ncb, ny = (o / 16) * 2;
+            for (int job = wave; job < npan + ny; job += kWaves) {
+                if (job < npan) {
+                    // P[i][c] = sum_{k <= i} Linv[i][k] A[o + k][c],  Linv[i][k] = Xs[o + k][o + i]
+                    float* colbase = As + o * kP + o + kSub + 16 * job;
+                    const float* pb = colbase + t_q * kP + t_i;
+                    const float* pa = Xs + (o + t_q) * kP + o + t_i;
+                    f4v p0 = {0.f, 0.f, 0.f, 0.f}, p1 = {0.f, 0.f, 0.f, 0.f};
+                    p0 = mma16(p0, pa, kP, pb, kP, 4, 1.f);            // rows 0..15: k < 16
+                    p1 = mma16(p1, pa + 16, kP, pb, kP, 8, 1.f);       // rows 16..31: k < 32
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        colbase[(4 * t_q + e) * kP + t_i] = p0[e];
+                        colbase[(16 + 4 * t_q + e) * kP + t_i] = p1[e];
+                    }
+                } else {
+                    // Y[i][c] = sum_{k <= c} R[i][o + k] X_kk[k][c]
+                    const int jy = job - npan, it = jy >> 1, cj = jy & 1;
+                    const float* pa = As + (16 * it + t_i) * kP + o + t_q;
+                    const float* pb = Xs + (o + t_q) * kP + o + 16 * cj + t_i;
+                    f4v y = {0.f, 0.f, 0.f, 0.f};
+                    y = mma16(y, pa, 1, pb, kP, cj ? 8 : 4, 1.f);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) Ys[(16 * it + 4 * t_q + e) * kPY + 16 * cj + t_i] = y[e];
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- 3. new block column of the inverse (long jobs first), then the trailing update
+        {
+            const int nx = (o / 16) * 2;
+            const int nt = 2 * ncb, ntri = nt * (nt + 1) / 2;
+            for (int job = wave; job < nx + ntri; job += kWaves) {
+                if (job < nx) {
+                    // X[i][o + c] = -sum_{t >= i} X[i][t] Y[t][c]
+                    const int it = job >> 1, cj = job & 1;
+                    const float* pa = Xs + (16 * it + t_i) * kP + 16 * it + t_q;
+                    const float* pb = Ys + (16 * it + t_q) * kPY + 16 * cj + t_i;
+                    f4v x = {0.f, 0.f, 0.f, 0.f};
+                    x = mma16(x, pa, 1, pb, kPY, (o - 16 * it) / 4, -1.f);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) Xs[(16 * it + 4 * t_q + e) * kP + o + 16 * cj + t_i] = x[e];
+                } else {
+                    // A[i][c] -= sum_k P[k][i] P[k][c] on tile (ti <= tc): rows ar and nt-1-ar of the
+                    // triangle together hold nt + 1 tiles
+                    const int idx = job - nx;
+                    const int ar = idx / (nt + 1), cc = idx - ar * (nt + 1);
+                    int ti, tc;
+                    if (cc < nt - ar) { ti = ar; tc = ar + cc; }
+                    else { ti = nt - 1 - ar; tc = ti + (cc - (nt - ar)); }
+                    const float* prow = As + o * kP + o + kSub;
+                    float* out = As + (o + kSub + 16 * ti + 4 * t_q) * kP + o + kSub + 16 * tc + t_i;
+                    f4v c;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) c[e] = out[e * kP];
+                    c = mma16(c, prow + t_q * kP + 16 * ti + t_i, kP, prow + t_q * kP + 16 * tc + t_i, kP, 8, -1.f);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) out[e * kP] = c[e];
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // write out: R above the diagonal, R^T below it, and R^-1
+    for (int t = tid; t < b * kN; t += kThreads) {
+        const int i = t >> 7, k = t & 127;
+        if (k < b) {
+            D[(int64_t)i * ld + k] = (k >= i) ? As[i * kP + k] : As[k * kP + i];
+            Rinv[i * b + k] = (k >= i) ? Xs[i * kP + k] : 0.f;
+        }
+    }
+}
+
+}  // namespace
+
+int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base) {
+    if (b <= 0 || b > kN) ASER_FAIL(ctx, ASER_ERR_SHAPE, "chol_block: block size out of range");
+    static bool attr_set[16] = {false};
+    const size_t lds = (size_t)(2 * kN * kP + 96 * kPY) * sizeof(float);
+    if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
+        ASER_HIP(ctx, hipFuncSetAttribute((const void*)chol_block_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set[ctx->device] = true;
+    }
+    hipLaunchKernelGGL(chol_block_kernel, dim3(1), dim3(kThreads), lds, ctx->stream, D, ld, b, Rinv, info, pivot_base);
+    return aser_check_launch(ctx, "chol_block");
+}

@@ -1,138 +1,11 @@
-// Small dense factorisations that run in one workgroup with their matrices in LDS: the diagonal
-// blocks of the blocked Cholesky (Eq. 5), the b x b Cholesky of the orthogonalisation, and the
-// Jacobi eigen-solver of the Rayleigh-Ritz step of the truncated SVD (Eq. 6).  Plus a plain
-// fp32 FMA product for "tall times small" updates.
+// The Jacobi eigen-solver (fallback of the Rayleigh-Ritz step of the truncated SVD, Eq. 6), one
+// workgroup with its matrices in LDS, and a plain fp32 FMA product for "tall times small" updates.
 #include "aser_internal.h"
 
 namespace {
 
 constexpr int kMaxB = 128;
 constexpr int kLdsPitch = kMaxB + 1;
-
-// ------------------------------------------------------------------------------------ Cholesky block
-// D = R^T R on the upper part of a b x b block (b <= 128) together with R^-1, in one sweep.
-//
-// The 128 x 128 matrix lives in registers: thread (bi, bj) of the 16 x 16 thread grid holds the
-// 8 x 8 block (bi, bj), upper blocks only.  Step j eliminates with pivot a_jj:
-//   rows i > j  (Cholesky, right-looking):   a[i][k] -= a[j][i] * a[j][k] / a_jj      for k > j
-//   rows i < j  (Gauss-Jordan on R):         c[i][k] -= c[i][j] * a[j][k] / a_jj      for k > j
-// where rows above j are kept in the scaled form c[i][k] = a[i][k] / a_ii.  Both updates are the
-// same rank-1 update with the "cross" through (j, j): column j above the diagonal and row j to
-// its right.  The owners of the cross publish it through LDS (double buffered, one barrier per
-// step).  Row j of R is cross / sqrt(a_jj); column j of R^-1 is -c[i][j] / sqrt(a_jj) above the
-// diagonal and 1 / sqrt(a_jj) on it.  Rows and columns beyond b are padded with the identity.
-// Publishes the cross of step jn = 8 jbn + jln (jln is a compile-time constant at every call site):
-// column jn above the diagonal from the blocks (bi <= jbn, jbn), row jn from the blocks (jbn, bj >= jbn).
-template <int JLN>
-__device__ __forceinline__ void publish_cross(float* cross, const float (&a)[8][8], int bi, int bj, int jbn) {
-    if (bj == jbn) {
-        if (bi < jbn) {
-            float4* dst = (float4*)(cross + 8 * bi);
-            dst[0] = make_float4(a[0][JLN], a[1][JLN], a[2][JLN], a[3][JLN]);
-            dst[1] = make_float4(a[4][JLN], a[5][JLN], a[6][JLN], a[7][JLN]);
-        } else if (bi == jbn) {
-#pragma unroll
-            for (int r = 0; r < JLN; ++r) cross[8 * bi + r] = a[r][JLN];
-#pragma unroll
-            for (int c = JLN; c < 8; ++c) cross[8 * bj + c] = a[JLN][c];
-        }
-    } else if (bi == jbn && bj > jbn) {
-        float4* dst = (float4*)(cross + 8 * bj);
-        dst[0] = make_float4(a[JLN][0], a[JLN][1], a[JLN][2], a[JLN][3]);
-        dst[1] = make_float4(a[JLN][4], a[JLN][5], a[JLN][6], a[JLN][7]);
-    }
-}
-
-template <int JL>
-__device__ __forceinline__ void chol_step(float (&a)[8][8], float (*cross)[128], float* Rs, float* Xs, int jb, int tid,
-                                          int bi, int bj, bool upper, int b, int32_t* info, int32_t pivot_base) {
-    const int j = 8 * jb + JL;
-    const float* cr = cross[j & 1];
-    float piv = cr[j];
-    if (!(piv > 0.f)) {
-        if (tid == 0 && j < b && info) atomicMin(info, pivot_base + j + 1);
-        piv = 1.f;
-    }
-    const float rs = __builtin_amdgcn_rsqf(piv);      // 1 ulp: as good as the fp32 data it scales
-    const float pinv = rs * rs;
-    if (tid < 128) {
-        const int k = tid;
-        const float cv = cr[k];
-        const float rv = (k == j) ? piv * rs : cv * rs;
-        if (k >= j) Rs[j * kLdsPitch + k] = rv;
-        Xs[k * kLdsPitch + j] = (k > j) ? 0.f : ((k == j) ? rs : -cv * rs);
-    }
-    if (upper) {
-        // One uniform 8 x 8 rank-1 update per thread; factors outside the active region (columns
-        // <= j, the pivot row) are zeroed instead of branching on the block position.
-        const float4 v0 = *(const float4*)(cr + 8 * bi), v1 = *(const float4*)(cr + 8 * bi + 4);
-        const float4 w0 = *(const float4*)(cr + 8 * bj), w1 = *(const float4*)(cr + 8 * bj + 4);
-        float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-        float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-        const float wscale = (bj < jb) ? 0.f : pinv;
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            w[c] *= wscale;
-            if (c <= JL) w[c] = (bj == jb) ? 0.f : w[c];
-        }
-        const float vpiv = v[JL];
-        v[JL] = (bi == jb) ? 0.f : vpiv;
-#pragma unroll
-        for (int r = 0; r < 8; ++r)
-#pragma unroll
-            for (int c = 0; c < 8; ++c) a[r][c] -= v[r] * w[c];
-        if (bi == jb) {                               // pivot row: keep it in the scaled form a[j][k] / a_jj
-#pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const bool on = (bj > jb) || (c > JL);
-                a[JL][c] *= on ? pinv : 1.f;
-            }
-        }
-        const int jbn = jb + (JL == 7 ? 1 : 0);
-        if (8 * jb + JL + 1 < 128) publish_cross<(JL + 1) & 7>(cross[(j + 1) & 1], a, bi, bj, jbn);
-    }
-    __syncthreads();
-}
-
-__global__ __launch_bounds__(256) void chol_block_kernel(float* D, int64_t ld, int b, float* Rinv, int32_t* info,
-                                                         int32_t pivot_base) {
-    // Results are staged in LDS and written out once at the end.
-    extern __shared__ float sm[];
-    float* Rs = sm;                                   // R, row j at Rs[j * pitch + k]
-    float* Xs = sm + kMaxB * kLdsPitch;               // R^-1, entry (i, j) at Xs[i * pitch + j]
-    float (*cross)[128] = (float (*)[128])(Xs + kMaxB * kLdsPitch);
-    const int tid = threadIdx.x, bi = tid >> 4, bj = tid & 15;
-    const bool upper = bi <= bj;
-    float a[8][8];
-#pragma unroll
-    for (int r = 0; r < 8; ++r)
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            const int i = 8 * bi + r, k = 8 * bj + c;
-            float v = (i == k) ? 1.f : 0.f;
-            if (upper && i < b && k < b && k >= i) v = D[(int64_t)i * ld + k];
-            a[r][c] = v;
-        }
-    if (upper) publish_cross<0>(cross[0], a, bi, bj, 0);
-    __syncthreads();
-    const int nblk = (b + 7) / 8;
-    for (int jb = 0; jb < nblk; ++jb) {
-        chol_step<0>(a, cross, Rs, Xs, jb, tid, bi, bj, upper, b, info, pivot_base);
-        chol_step<1>(a, cross, Rs, Xs, jb, tid, bi, bj, upper, b, info, pivot_base);
-        chol_step<2>(a, cross, Rs, Xs, jb, tid, bi, bj, upper, b, info, pivot_base);
-        chol_step<3>(a, cross, Rs, Xs, jb, tid, bi, bj, upper, b, info, pivot_base);
-        chol_step<4>(a, cross, Rs, Xs, jb, tid, bi, bj, upper, b, info, pivot_base);
-        chol_step<5>(a, cross, Rs, Xs, jb, tid, bi, bj, upper, b, info, pivot_base);
-        chol_step<6>(a, cross, Rs, Xs, jb, tid, bi, bj, upper, b, info, pivot_base);
-        chol_step<7>(a, cross, Rs, Xs, jb, tid, bi, bj, upper, b, info, pivot_base);
-    }
-    // write out: R above the diagonal, R^T below it, and R^-1
-    for (int t = tid; t < b * b; t += 256) {
-        const int i = t / b, k = t % b;
-        D[(int64_t)i * ld + k] = (k >= i) ? Rs[i * kLdsPitch + k] : Rs[k * kLdsPitch + i];
-        Rinv[t] = (k >= i) ? Xs[i * kLdsPitch + k] : 0.f;
-    }
-}
 
 // ------------------------------------------------------------------------------------ Jacobi
 // Cyclic Jacobi with the round-robin pairing: b / 2 disjoint rotations per round, b - 1 rounds
@@ -306,18 +179,6 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(const float* __restrict
 }
 
 }  // namespace
-
-int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base) {
-    if (b <= 0 || b > kMaxB) ASER_FAIL(ctx, ASER_ERR_SHAPE, "chol_block: block size out of range");
-    static bool attr_set[16] = {false};
-    const size_t lds = (size_t)(2 * kMaxB * kLdsPitch + 2 * 128) * 4;
-    if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
-        ASER_HIP(ctx, hipFuncSetAttribute((const void*)chol_block_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set[ctx->device] = true;
-    }
-    hipLaunchKernelGGL(chol_block_kernel, dim3(1), dim3(256), lds, ctx->stream, D, ld, b, Rinv, info, pivot_base);
-    return aser_check_launch(ctx, "chol_block");
-}
 
 int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float* V, const int* gate) {
     if (b <= 0 || b > kMaxB || (b & 1)) ASER_FAIL(ctx, ASER_ERR_SHAPE, "jacobi: block size must be even and <= 128");
