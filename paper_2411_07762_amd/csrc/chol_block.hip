@@ -1,7 +1,7 @@
 // Cholesky factor and its inverse for one diagonal block (b <= 128) of the blocked Cholesky of
 // the whitening step (Eq. 5) and of the Cholesky-QR steps of the truncated SVD (Eq. 6).
 //
-// One workgroup of 8 wavefronts, the block in LDS, blocked again into 32-wide sub-blocks k = 0..3.
+// One workgroup of 16 wavefronts, the block in LDS, blocked again into 32-wide sub-blocks k = 0..3.
 // All arithmetic is fp32: the products run on the fp32 MFMA instructions.
 //
 //   1. one wavefront factors the 32 x 32 diagonal sub-block A_kk with the sub-block and an identity
@@ -28,7 +28,7 @@ constexpr int kN = 128;       // largest block
 constexpr int kP = 133;       // odd LDS pitch: a wavefront reads along a row or a column without bank conflicts
 constexpr int kPY = 33;
 constexpr int kSub = 32;
-constexpr int kThreads = 512;
+constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
 
 __device__ __forceinline__ float lane_bcast(float v, int lane) {
@@ -58,12 +58,22 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
     // 16 x 16 tile roles of this lane
     const int t_i = lane & 15, t_q = lane >> 4;
 
-    for (int t = tid; t < nb * kN; t += kThreads) {
-        const int i = t >> 7, k = t & 127;
-        float v = (k == i) ? 1.f : 0.f;
-        if (k >= i && k < b && i < b) v = D[(int64_t)i * ld + k];
-        As[i * kP + k] = v;
-        Xs[i * kP + k] = 0.f;
+    // all global loads of a thread are issued before the first LDS store
+    {
+        constexpr int kPer = kN * kN / kThreads;
+        float v[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int t = tid + u * kThreads, i = t >> 7, k = t & 127;
+            v[u] = (k == i) ? 1.f : 0.f;
+            if (k >= i && k < b && i < b) v[u] = D[(int64_t)i * ld + k];
+        }
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int t = tid + u * kThreads, i = t >> 7, k = t & 127;
+            As[i * kP + k] = v[u];
+            Xs[i * kP + k] = 0.f;
+        }
     }
     __syncthreads();
 
@@ -92,16 +102,19 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
                     a1[e] = (lane == 32 * hj + j) ? 1.f : a1[e];
                 }
                 const float rs = __builtin_amdgcn_rsqf(piv);      // 1 ulp: as good as the fp32 data it scales
-                const float rv = a1[e] * rs, lv = a2[e] * rs;
+                // The update of the first accumulator is issued before the second one is touched:
+                // the next pivot only waits for the first.
+                const float rv = a1[e] * rs;
+                const float mult = (h == hj) ? -rv : 0.f;
+                if (j + 1 < kSub) a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, rv, a1, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                const float lv = a2[e] * rs;
+                if (j + 1 < kSub) a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, lv, a2, 0, 0, 0);
                 if (h == hj) {
                     As[(o + j) * kP + o + col] = rv;              // row j of R_kk (entries left of the diagonal are dead)
                     Xs[(o + col) * kP + o + j] = lv;              // X_kk = (L_kk^-1)^T
                 }
-                if (j + 1 < kSub) {
-                    const float mult = (h == hj) ? -rv : 0.f;
-                    a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, rv, a1, 0, 0, 0);
-                    a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, lv, a2, 0, 0, 0);
-                }
+                __builtin_amdgcn_sched_barrier(0);
             }
             if (bad < kSub && lane == 0 && o + bad < b && info) atomicMin(info, pivot_base + o + bad + 1);
         }

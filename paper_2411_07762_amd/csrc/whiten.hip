@@ -1,10 +1,10 @@
-// Whitening factor of Eq. 5 / Algorithm 1: S = chol(M^-1 G M^-1), blocked right-looking.
+// Whitening factor of Eq. 5 / Algorithm 1: S = chol(M^-1 G M^-1), blocked, one block row at a time.
 //
 // The factorisation runs on the upper triangle (G' = R^T R, R = S^T) so that every contraction
-// has the K-major "A^T B" form of the MFMA kernel:
+// has the K-major "A^T B" form of the MFMA kernel.  For block row k (rows k .. k+b):
+//   update           G'[k:k+b, k:] -= R[:k, k:k+b]^T R[:k, k:]   (A, B = the finished rows above; K = k)
 //   diagonal block   R11 = chol(D), R11^-1                       (one workgroup, LDS)
 //   row panel        R12 = (R11^-1)^T * G'[k, k+b:]              (A = R11^-1, B = the panel, in place)
-//   trailing update  G'[k+b:, k+b:] -= R12^T R12  (upper tiles)  (A = B = R12)
 // The panel kernel also writes R12^T below the diagonal, so the lower triangle fills up with
 // S = R^T as the factorisation proceeds; a final pass clears the strict upper triangle.
 #include <limits.h>
@@ -103,9 +103,27 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
                        mdiag, S, lds, (const double*)diag_sum, damp);
     ASER_TRY(aser_check_launch(ctx, "whiten_prep"));
 
+    // Up-looking blocked Cholesky on the upper triangle (R = S^T): block row j first receives the
+    // contribution of all finished rows above it in one product with a long K (split over
+    // workgroups, fp32 atomics), then its diagonal block is factored and the row is multiplied by
+    // the inverse of that factor.  Every entry of the matrix is updated once, by one launch.
     for (int64_t k0 = 0; k0 < n; k0 += kNb) {
         const int b = (int)((n - k0 < kNb) ? n - k0 : kNb);
         float* D = S + k0 * lds + k0;
+        if (k0 > 0) {
+            GemmArgs u{};
+            u.A = S + k0; u.lda = lds; u.B = S + k0; u.ldb = lds;
+            u.C = D; u.ldc = lds; u.Ct = nullptr; u.ldct = 0;
+            u.M = b; u.N = n - k0; u.K = k0; u.alpha = -1.f;
+            u.in_type = GEMM_IN_F32X3; u.epi = GEMM_EPI_ATOMIC; u.tiles = GEMM_TILES_ALL; u.krange = GEMM_K_FULL;
+            u.bm = 128; u.bn = 128;
+            const int64_t tiles = ceil_div64(u.N, u.bn), ksteps = ceil_div64(k0, 32);
+            int64_t parts = ceil_div64(256, tiles);
+            const int64_t max_parts = ksteps / 4 > 0 ? ksteps / 4 : 1;
+            if (parts > max_parts) parts = max_parts;
+            u.k_parts = (int)parts;
+            ASER_TRY(aser_gemm_tn(ctx, u));
+        }
         ASER_TRY(aser_chol_block(ctx, D, lds, b, Rinv, info_dev, (int32_t)k0));
         const int64_t rem = n - k0 - b;
         if (rem <= 0) break;
@@ -117,13 +135,6 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
         p.in_type = GEMM_IN_F32X3; p.epi = GEMM_EPI_STORE; p.tiles = GEMM_TILES_ALL; p.krange = GEMM_K_FULL;
         p.k_parts = 1; p.bm = 128; p.bn = (rem > 128) ? 256 : 128;
         ASER_TRY(aser_gemm_tn(ctx, p));
-        GemmArgs u{};
-        u.A = S12; u.lda = lds; u.B = S12; u.ldb = lds;
-        u.C = S + (k0 + b) * lds + (k0 + b); u.ldc = lds; u.Ct = nullptr; u.ldct = 0;
-        u.M = rem; u.N = rem; u.K = b; u.alpha = -1.f;
-        u.in_type = GEMM_IN_F32X3; u.epi = GEMM_EPI_RMW; u.tiles = GEMM_TILES_UPPER; u.krange = GEMM_K_FULL;
-        u.k_parts = 1; u.bm = u.bn = (rem > 2048) ? 256 : 128;
-        ASER_TRY(aser_gemm_tn(ctx, u));
     }
     hipLaunchKernelGGL(zero_strict_upper_kernel, dim3((unsigned)ceil_div64(n, 256), (unsigned)n), dim3(256), 0, ctx->stream,
                        S, n, lds);
