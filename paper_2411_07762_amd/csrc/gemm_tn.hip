@@ -568,6 +568,239 @@ int launch_gram_persistent2(aser_ctx* ctx, const GemmArgs& g) {
     return aser_check_launch(ctx, "gram_persistent");
 }
 
+// ---------------------------------------------------------------------------------------------
+// Gram tiles for bf16 X without a register stage (the main path of the Gram update).
+//
+// X is tokens x channels, so a slab of 32 tokens x 256 channels is 32 rows of 512 contiguous
+// bytes.  global_load_lds_dwordx4 copies it straight into LDS: a wavefront instruction moves
+// 64 x 16 bytes to 1 KB of consecutive LDS (two slab rows), and each lane chooses which 16-byte
+// chunk of the row it fetches, which is how the layout gets its XOR swizzle: chunk c of slab row
+// k sits at chunk slot c ^ 2 (k & 3).  The MFMA operands (8 consecutive tokens of one channel
+// per lane) come out of that token-major layout through ds_read_b64_tr_b16: 16 lanes read a
+// 4 token x 16 channel block (4 lanes per row, 8 bytes each) and each lane receives the 4 tokens
+// of its channel; with the swizzle the 4 rows of a block fall into different bank groups.  So
+// there is no transpose in registers, no LDS store instruction and no staging VGPRs; a ring of
+// four 32 KB stages keeps three steps of loads in flight.  Rows past the token range and
+// channels past n are fetched from a block of zeros.
+__device__ uint4 g_zero_chunk[4];
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+
+constexpr int kDmaBK = 32;
+constexpr int kDmaStages = 4;
+constexpr int kDmaSlabBytes = kDmaBK * 512;
+constexpr int kDmaStageBytes = 2 * kDmaSlabBytes;
+constexpr size_t kDmaLdsBytes = (size_t)kDmaStages * kDmaStageBytes;
+
+__device__ __forceinline__ bf16x8_t lds_tr_frag(const char* p, int off_lo, int off_hi) {
+    typedef s16x4_t __attribute__((address_space(3))) * lds_s4p;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4p)(p + off_lo));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4p)(p + off_hi));
+    const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// One 256 x 256 tile of G over tokens [kBeg, kEnd): G[I0.., J0..] += X[:, I0..]^T X[:, J0..].
+//
+// Step s multiplies stage s % 4 in two 16-token slices of 16 MFMAs each.  One wave per SIMD means
+// nothing but instruction order hides latencies, so the order is pinned by hand: the operand reads
+// of slice 1 are interleaved with the MFMAs of slice 0; the wait for the next stage, the barrier,
+// the loads of stage s + 3 and the operand reads of the next step's slice 0 are interleaved with
+// the MFMAs of slice 1.
+__device__ __forceinline__ void gram_tile_dma(const GemmArgs& g, int64_t I0, int64_t J0, int64_t kBeg, int64_t kEnd,
+                                              char* smem) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+
+    // ---- fetch roles: this wave issues instructions 4 wave .. 4 wave + 3 of each slab; instruction i
+    // covers slab rows 2 i and 2 i + 1, lane l is chunk slot l % 32 of row 2 i + l / 32
+    const int drow = lane >> 5, slot = lane & 31;
+    const char* zero = (const char*)g_zero_chunk;
+    const int64_t ld_bytes = g.lda * 2;
+    const int row0 = 8 * wave + drow;                    // slab row of this lane in its wave's first instruction
+    const char* gp[2][4];                                // next source address per (operand, instruction)
+    int64_t gstep[2][2];                                 // its advance per step (0 for chunks past n: they stay on the zeros)
+    int64_t tok_next = kBeg + row0;                      // token of gp[.][0]
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const int chunk = slot ^ (2 * ((2 * par + drow) & 3));
+        const int64_t ca = I0 + 8 * chunk, cb = J0 + 8 * chunk;
+        gstep[0][par] = (ca < g.M) ? kDmaBK * ld_bytes : 0;
+        gstep[1][par] = (cb < g.N) ? kDmaBK * ld_bytes : 0;
+#pragma unroll
+        for (int t = par; t < 4; t += 2) {
+            gp[0][t] = (ca < g.M) ? (const char*)g.A + ca * 2 + (tok_next + 2 * t) * ld_bytes : zero;
+            gp[1][t] = (cb < g.N) ? (const char*)g.B + cb * 2 + (tok_next + 2 * t) * ld_bytes : zero;
+        }
+    }
+    // LDS byte address of the ring (what M0 must hold for the LDS-direct loads)
+    const uint32_t ring = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + wave * 4096;
+    // One load of stage `step` (op, t fixed at compile time by the callers' unrolling).  Written as
+    // inline assembly on purpose: the compiler makes every LDS read wait for all LDS-direct loads it
+    // knows of (it cannot tell the ring stages apart), which would undo the prefetch.  The stages are
+    // kept apart by the explicit vmcnt waits and barriers below instead.
+    auto issue_one = [&](int64_t step, int op, int t, bool tail) {
+        const char* src = gp[op][t];
+        if (tail && tok_next + 2 * t >= kEnd) src = zero;
+        const uint32_t dst = ring + (uint32_t)(step & (kDmaStages - 1)) * kDmaStageBytes + op * kDmaSlabBytes + t * 1024;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(src) : "memory", "m0");
+        gp[op][t] += gstep[op][t & 1];
+    };
+    auto issue_all = [&](int64_t step) {
+        const bool tail = kBeg + (step + 1) * kDmaBK > kEnd;
+#pragma unroll
+        for (int op = 0; op < 2; ++op)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) issue_one(step, op, t, tail);
+        tok_next += kDmaBK;
+    };
+
+    // ---- operand read offsets inside a stage (bytes), first of the four (k16 slice, half) reads
+    int offa[4], offb[4];
+    {
+        const int krow = 8 * (lane >> 5) + ((lane & 15) >> 2);
+        const int xr = 2 * ((lane & 15) >> 2);
+        const int msub = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ma = wm0 + 32 * i + msub, mb = wn0 + 32 * i + msub;
+            offa[i] = krow * 512 + (((ma >> 3) ^ xr) * 16) + (ma & 7) * 2;
+            offb[i] = kDmaSlabBytes + krow * 512 + (((mb >> 3) ^ xr) * 16) + (mb & 7) * 2;
+        }
+    }
+
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int64_t nsteps = (kEnd - kBeg + kDmaBK - 1) / kDmaBK;
+    __syncthreads();                                     // the previous tile's readers are done with the ring
+    for (int64_t s = 0; s < kDmaStages - 1 && s < nsteps; ++s) issue_all(s);
+    if (nsteps >= 3) __builtin_amdgcn_s_waitcnt(0x4F70);             // vmcnt(16): stage 0 landed
+    else if (nsteps == 2) __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                         // vmcnt(0)
+    __syncthreads();
+    bf16x8_t a0[4], b0[4], a1[4], b1[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a0[i] = lds_tr_frag(smem + offa[i], 0, 4 * 512);
+        b0[i] = lds_tr_frag(smem + offb[i], 0, 4 * 512);
+    }
+    for (int64_t s = 0; s < nsteps; ++s) {
+        const char* st = smem + (int)(s & (kDmaStages - 1)) * kDmaStageBytes;
+        const char* sn = smem + (int)((s + 1) & (kDmaStages - 1)) * kDmaStageBytes;
+        const bool more = s + 1 < nsteps;
+        const bool fetch = s + kDmaStages - 1 < nsteps;
+        const bool tail = fetch && (kBeg + (s + kDmaStages) * kDmaBK > kEnd);
+        // slice 0: 16 MFMAs, one operand fragment of slice 1 read after every second one
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], b0[j], acc[i][j], 0, 0, 0);
+                if (j == 1) a1[i] = lds_tr_frag(st + offa[i], 16 * 512, 20 * 512);
+                if (j == 3) b1[i] = lds_tr_frag(st + offb[i], 16 * 512, 20 * 512);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // slice 1: row 0 of MFMAs covers the wait and the barrier, rows 1 and 2 the eight loads of
+        // stage s + 3, rows 2 and 3 the reads of the next step's slice 0
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
+                if (i == 0 && j == 1 && more) {
+                    // stage s + 1 has landed when at most the loads of stage s + 2 are in flight
+                    if (s + 2 < nsteps) __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8)
+                    else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
+                    __syncthreads();                      // everyone's share landed; stage s - 1 is free
+                }
+                if (fetch && i == 1) { issue_one(s + kDmaStages - 1, 0, j, tail); }
+                if (fetch && i == 2 && j < 2) { issue_one(s + kDmaStages - 1, 1, 2 * j, tail); issue_one(s + kDmaStages - 1, 1, 2 * j + 1, tail); }
+                if (more && i == 2 && j >= 2) {
+                    a0[2 * (j - 2)] = lds_tr_frag(sn + offa[2 * (j - 2)], 0, 4 * 512);
+                    a0[2 * (j - 2) + 1] = lds_tr_frag(sn + offa[2 * (j - 2) + 1], 0, 4 * 512);
+                }
+                if (more && i == 3) b0[j] = lds_tr_frag(sn + offb[j], 0, 4 * 512);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (fetch) tok_next += kDmaBK;
+    }
+
+    // acc[i][j][e] is G(row, col) with row = 32 i + 8 (e / 4) + 4 (lane / 32) + e % 4, col = 32 j + lane % 32
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t col = J0 + wn0 + 32 * j + (lane & 31);
+            const int64_t rbase = I0 + wm0 + 32 * i + 4 * (lane >> 5);
+            if (col >= g.N) continue;
+            float* cbase = g.C + rbase * g.ldc + col;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int dr = 8 * (e >> 2) + (e & 3);
+                if (rbase + dr < g.M) unsafeAtomicAdd(cbase + (int64_t)dr * g.ldc, g.alpha * acc[i][j][e]);
+            }
+        }
+}
+
+// The persistent XCD-aware schedule of gram_persistent_kernel with the LDS-direct tile body.
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void gram_dma_kernel(GemmArgs g) {
+    extern __shared__ uint4 smem[];
+    constexpr int BK = kDmaBK, BM = 256;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int slots = gridDim.x >> 3;
+    const int C = g.k_parts;
+    const int gsz = 8 / C;
+    const int chunk = xcd / gsz, xi = xcd % gsz;
+    const int64_t W = (int64_t)gsz * slots;
+    const int64_t widx = (int64_t)xi * slots + slot;
+    const int nt = (int)((g.N + BM - 1) / BM);
+    const int64_t T = (int64_t)nt * (nt + 1) / 2;
+    const int64_t ksteps = (g.K + BK - 1) / BK;
+    const int64_t per = (ksteps + C - 1) / C;
+    const int64_t kx0 = (int64_t)chunk * per * BK;
+    int64_t kx1 = kx0 + per * BK;
+    if (kx1 > g.K) kx1 = g.K;
+    if (kx0 >= kx1) return;
+    const int64_t full = T / W, rem = T % W;
+    const int64_t split = rem > 0 ? W / rem : 1;
+    const int64_t rounds = full + ((rem > 0 && widx < rem * split) ? 1 : 0);
+    for (int64_t round = 0; round < rounds; ++round) {
+        int64_t t = round * W + widx, k0 = kx0, k1 = kx1;
+        if (round == full) {
+            t = full * W + widx % rem;
+            const int64_t xsteps = (kx1 - kx0 + BK - 1) / BK;
+            const int64_t pp = (xsteps + split - 1) / split;
+            k0 = kx0 + (widx / rem) * pp * BK;
+            k1 = k0 + pp * BK;
+            if (k1 > kx1) k1 = kx1;
+            if (k0 >= k1) break;
+        }
+        int p, q;
+        tri_strip_tile(t, nt, &p, &q);
+        gram_tile_dma(g, (int64_t)p * BM, (int64_t)q * BM, k0, k1, (char*)smem);
+    }
+}
+
+int launch_gram_dma(aser_ctx* ctx, const GemmArgs& g) {
+    static bool attr_set[16] = {false};
+    if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
+        ASER_HIP(ctx, hipFuncSetAttribute((const void*)gram_dma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDmaLdsBytes));
+        attr_set[ctx->device] = true;
+    }
+    hipLaunchKernelGGL(gram_dma_kernel, dim3(256), dim3(kThreads), kDmaLdsBytes, ctx->stream, g);
+    return aser_check_launch(ctx, "gram_dma");
+}
+
 template <int IN>
 int launch_gram_persistent(aser_ctx* ctx, const GemmArgs& g) {
     if (operands_fast<IN>(g)) return launch_gram_persistent2<IN, true>(ctx, g);
@@ -615,6 +848,7 @@ int aser_syrk_gram(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int6
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_c = c; }
         }
         g.bm = g.bn = 256; g.k_parts = best_c;
+        if (g.in_type == GEMM_IN_BF16 && operands_fast<GEMM_IN_BF16>(g)) return launch_gram_dma(ctx, g);
         return (g.in_type == GEMM_IN_BF16) ? launch_gram_persistent<GEMM_IN_BF16>(ctx, g)
                                            : launch_gram_persistent<GEMM_IN_F32X3>(ctx, g);
     }
