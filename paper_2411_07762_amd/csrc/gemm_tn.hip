@@ -16,6 +16,8 @@
 // tile) or two steps (smaller tiles, two register sets) ahead of the MFMAs; LDS is double
 // buffered with one barrier per step.  fp32 operands are split as x = hi + lo (bf16 each) and
 // contribute hi*hi + hi*lo + lo*hi, accumulated in fp32.
+#include <type_traits>
+
 #include "aser_internal.h"
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -692,12 +694,14 @@ __device__ __forceinline__ void gram_tile_dma(const GemmArgs& g, int64_t I0, int
         a0[i] = lds_tr_frag(smem + offa[i], 0, 4 * 512);
         b0[i] = lds_tr_frag(smem + offb[i], 0, 4 * 512);
     }
-    for (int64_t s = 0; s < nsteps; ++s) {
+    // STEADY steps have a successor, a stage to fetch and no ragged rows in it: no branch in the body.
+    auto step = [&](int64_t s, auto steady_tag) {
+        constexpr bool STEADY = decltype(steady_tag)::value;
         const char* st = smem + (int)(s & (kDmaStages - 1)) * kDmaStageBytes;
         const char* sn = smem + (int)((s + 1) & (kDmaStages - 1)) * kDmaStageBytes;
-        const bool more = s + 1 < nsteps;
-        const bool fetch = s + kDmaStages - 1 < nsteps;
-        const bool tail = fetch && (kBeg + (s + kDmaStages) * kDmaBK > kEnd);
+        const bool more = STEADY || s + 1 < nsteps;
+        const bool fetch = STEADY || s + kDmaStages - 1 < nsteps;
+        const bool tail = !STEADY && fetch && (kBeg + (s + kDmaStages) * kDmaBK > kEnd);
         // slice 0: 16 MFMAs, one operand fragment of slice 1 read after every second one
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -718,8 +722,8 @@ __device__ __forceinline__ void gram_tile_dma(const GemmArgs& g, int64_t I0, int
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
                 if (i == 0 && j == 1 && more) {
                     // stage s + 1 has landed when at most the loads of stage s + 2 are in flight
-                    if (s + 2 < nsteps) __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8)
-                    else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
+                    if (STEADY || s + 2 < nsteps) __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8)
+                    else __builtin_amdgcn_s_waitcnt(0x0F70);                             // vmcnt(0)
                     __syncthreads();                      // everyone's share landed; stage s - 1 is free
                 }
                 if (fetch && i == 1) { issue_one(s + kDmaStages - 1, 0, j, tail); }
@@ -733,7 +737,11 @@ __device__ __forceinline__ void gram_tile_dma(const GemmArgs& g, int64_t I0, int
             }
         }
         if (fetch) tok_next += kDmaBK;
-    }
+    };
+    const int64_t full_steps = (kEnd - kBeg) / kDmaBK;               // stages without ragged rows
+    int64_t s = 0;
+    for (; s + kDmaStages - 1 < full_steps; ++s) step(s, std::true_type{});
+    for (; s < nsteps; ++s) step(s, std::false_type{});
 
     // acc[i][j][e] is G(row, col) with row = 32 i + 8 (e / 4) + 4 (lane / 32) + e % 4, col = 32 j + lane % 32
 #pragma unroll
