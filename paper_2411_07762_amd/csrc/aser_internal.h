@@ -95,8 +95,10 @@ int aser_sumsq_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols, in
 // Small dense kernels (one workgroup, matrices in LDS)
 // Upper Cholesky of the b x b block D (ld) in place: upper part <- R (D = R^T R), lower part <- R^T;
 // Rinv (b x b, ld = b) <- R^-1 (upper).  b <= 128.  On a non-positive pivot at column j,
-// atomicMin(info, pivot_base + j + 1) and the pivot is replaced by 1.
-int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base);
+// atomicMin(info, pivot_base + j + 1) and the pivot is replaced by 1.  clear_d: D is overwritten with
+// zeros instead of the factor (callers that only need R^-1 and reuse D as an accumulation target).
+int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base,
+                    bool clear_d = false);
 // Symmetric eigen-decomposition of the b x b matrix Mb (ld = b) by cyclic Jacobi: eigenvalues
 // descending into lambda (b), eigenvectors as columns of V (b x b, ld = b).  b <= 128, b even.
 // `gate` (device, may be null): the kernel returns at once when *gate == 0.
@@ -106,6 +108,8 @@ int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float*
 // close for that method, else 0; the caller then runs aser_jacobi_eig gated on the flag.  2 <= b <= 128.
 int aser_tridiag_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float* V, float* refl, float* tri,
                      int* cluster_flag);
-// C (rows x c) = A (rows x k) * B (k x c), plain fp32 FMA; k, c <= 256.  C may not alias A.
-int aser_gemm_small_f32(aser_ctx* ctx, const float* A, int64_t lda, const float* B, int64_t ldb,
-                        float* C, int64_t ldc, int64_t rows, int k, int c);
+// C (rows x c) = A (rows x k) * B (k x c), plain fp32 FMA; k, c <= 128, k % 4 == 0, A 16-byte aligned with
+// lda % 4 == 0.  C may not alias A.  The first clear_rows rows of A (k columns each; may exceed `rows`) are
+// set to zero after they have been read.
+int aser_gemm_small_f32(aser_ctx* ctx, float* A, int64_t lda, const float* B, int64_t ldb,
+                        float* C, int64_t ldc, int64_t rows, int k, int c, int64_t clear_rows = 0);

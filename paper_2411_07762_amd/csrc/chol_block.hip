@@ -47,7 +47,7 @@ __device__ __forceinline__ f4v mma16(f4v acc, const float* pa, int sak, const fl
 }
 
 __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t ld, int b, float* Rinv, int32_t* info,
-                                                              int32_t pivot_base) {
+                                                              int32_t pivot_base, int clear_d) {
     extern __shared__ __align__(16) float sm[];
     float* As = sm;                      // working matrix, upper triangle -> R
     float* Xs = As + kN * kP;            // R^-1 (upper), zero elsewhere
@@ -187,11 +187,11 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
         __syncthreads();
     }
 
-    // write out: R above the diagonal, R^T below it, and R^-1
+    // write out: R above the diagonal, R^T below it (or zeros over the input when clear_d), and R^-1
     for (int t = tid; t < b * kN; t += kThreads) {
         const int i = t >> 7, k = t & 127;
         if (k < b) {
-            D[(int64_t)i * ld + k] = (k >= i) ? As[i * kP + k] : As[k * kP + i];
+            D[(int64_t)i * ld + k] = clear_d ? 0.f : ((k >= i) ? As[i * kP + k] : As[k * kP + i]);
             Rinv[i * b + k] = (k >= i) ? Xs[i * kP + k] : 0.f;
         }
     }
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
 
 }  // namespace
 
-int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base) {
+int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base, bool clear_d) {
     if (b <= 0 || b > kN) ASER_FAIL(ctx, ASER_ERR_SHAPE, "chol_block: block size out of range");
     static bool attr_set[16] = {false};
     const size_t lds = (size_t)(2 * kN * kP + 96 * kPY) * sizeof(float);
@@ -207,6 +207,7 @@ int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int
         ASER_HIP(ctx, hipFuncSetAttribute((const void*)chol_block_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set[ctx->device] = true;
     }
-    hipLaunchKernelGGL(chol_block_kernel, dim3(1), dim3(kThreads), lds, ctx->stream, D, ld, b, Rinv, info, pivot_base);
+    hipLaunchKernelGGL(chol_block_kernel, dim3(1), dim3(kThreads), lds, ctx->stream, D, ld, b, Rinv, info, pivot_base,
+                       clear_d ? 1 : 0);
     return aser_check_launch(ctx, "chol_block");
 }

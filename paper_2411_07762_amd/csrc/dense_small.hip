@@ -118,62 +118,89 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const float* Mb, int b, fl
 }
 
 // ------------------------------------------------------------------------------------ small fp32 product
-// C (rows x c) = A (rows x k) * B (k x c) in plain fp32 FMAs.  A workgroup owns 32 rows x 128
-// columns; a thread owns 2 rows x 8 columns and reads its operands from LDS as float2 / float4.
-__global__ __launch_bounds__(256) void gemm_small_kernel(const float* __restrict__ A, int64_t lda,
-                                                         const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
-                                                         int64_t ldc, int64_t rows, int k, int c) {
-    __shared__ __attribute__((aligned(16))) float As[32][34];     // [kk][row]
-    __shared__ __attribute__((aligned(16))) float Bs[32][132];    // [kk][col]
+// C (rows x c) = A (rows x k) * B (k x c) in plain fp32 FMAs, k, c <= 128.  A workgroup owns 16 rows;
+// its A rows and all of B go to LDS in one shot (every global load is issued before the first LDS
+// store: one memory round trip), a thread owns 1 row x 8 columns.  The first clear_rows rows of A
+// (may exceed `rows`) are cleared once they have been read, which leaves A ready as the target of
+// an accumulating product.
+constexpr int kGsRows = 16;
+constexpr int kGsPitch = 132;
+
+__global__ __launch_bounds__(256) void gemm_small_kernel(float* __restrict__ A, int64_t lda, const float* __restrict__ B,
+                                                         int64_t ldb, float* __restrict__ C, int64_t ldc, int64_t rows,
+                                                         int k, int c, int64_t clear_rows, int vec_b) {
+    extern __shared__ __align__(16) float gs_sm[];
+    float* As = gs_sm;                          // [16][132]
+    float* Bs = gs_sm + kGsRows * kGsPitch;     // [128][132]
     const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
-    const int64_t r0 = (int64_t)blockIdx.x * 32;
-    const int c0 = blockIdx.y * 128;
-    float acc[2][8];
+    const int64_t r0 = (int64_t)blockIdx.x * kGsRows;
+
+    // A: 16 rows x 128 k = 512 float4, two per thread (k is a multiple of 4 and rows are 16-byte aligned)
+    float4 av[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int u = 0; u < 2; ++u) {
+        const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
+        av[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r0 + r < rows && k4 < k) av[u] = *(const float4*)(A + (r0 + r) * lda + k4);
+    }
+    // B: 128 x 128 = 4096 float4, sixteen per thread
+    float4 bv[16];
+    if (vec_b) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
-    for (int k0 = 0; k0 < k; k0 += 32) {
-        {
-            const int r = tid >> 3, kq = (tid & 7) * 4;
-            const int64_t gr = r0 + r;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int kk = kq + e;
-                As[kk][r] = (gr < rows && k0 + kk < k) ? A[gr * lda + k0 + kk] : 0.f;
-            }
+        for (int u = 0; u < 16; ++u) {
+            const int q = tid + 256 * u, kk = q >> 5, c4 = (q & 31) * 4;
+            bv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (kk < k && c4 < c) bv[u] = *(const float4*)(B + (int64_t)kk * ldb + c4);
         }
-        {
-            const int kk = tid >> 3, cq = (tid & 7) * 16;
+    } else {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int cc = c0 + cq + e;
-                Bs[kk][cq + e] = (k0 + kk < k && cc < c) ? B[(int64_t)(k0 + kk) * ldb + cc] : 0.f;
-            }
+        for (int u = 0; u < 16; ++u) {
+            const int q = tid + 256 * u, kk = q >> 5, c4 = (q & 31) * 4;
+            float t[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (kk < k && c4 + e < c) t[e] = B[(int64_t)kk * ldb + c4 + e];
+            bv[u] = make_float4(t[0], t[1], t[2], t[3]);
         }
-        __syncthreads();
-#pragma unroll 8
-        for (int kk = 0; kk < 32; ++kk) {
-            const float2 av = *(const float2*)&As[kk][2 * ty];
-            const float4 b0 = *(const float4*)&Bs[kk][8 * tx];
-            const float4 b1 = *(const float4*)&Bs[kk][8 * tx + 4];
-            const float a2[2] = {av.x, av.y};
-            const float b8[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[i][j] = fmaf(a2[i], b8[j], acc[i][j]);
-        }
-        __syncthreads();
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int64_t gr = r0 + 2 * ty + i;
-        if (gr >= rows) continue;
+    for (int u = 0; u < 2; ++u) {
+        const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
+        *(float4*)(As + r * kGsPitch + k4) = av[u];
+        if (r0 + r < clear_rows && k4 < k) *(float4*)(A + (r0 + r) * lda + k4) = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int q = tid + 256 * u, kk = q >> 5, c4 = (q & 31) * 4;
+        *(float4*)(Bs + kk * kGsPitch + c4) = bv[u];
+    }
+    __syncthreads();
+
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    const float* arow = As + ty * kGsPitch;
+    const float* bcol = Bs + 8 * tx;
+#pragma unroll 4
+    for (int k4 = 0; k4 < k; k4 += 4) {
+        const float4 a4 = *(const float4*)(arow + k4);
+        const float aa[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float4 b0 = *(const float4*)(bcol + (k4 + e) * kGsPitch);
+            const float4 b1 = *(const float4*)(bcol + (k4 + e) * kGsPitch + 4);
+            acc[0] = fmaf(aa[e], b0.x, acc[0]); acc[1] = fmaf(aa[e], b0.y, acc[1]);
+            acc[2] = fmaf(aa[e], b0.z, acc[2]); acc[3] = fmaf(aa[e], b0.w, acc[3]);
+            acc[4] = fmaf(aa[e], b1.x, acc[4]); acc[5] = fmaf(aa[e], b1.y, acc[5]);
+            acc[6] = fmaf(aa[e], b1.z, acc[6]); acc[7] = fmaf(aa[e], b1.w, acc[7]);
+        }
+    }
+    const int64_t gr = r0 + ty;
+    if (gr < rows) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int cc = c0 + 8 * tx + j;
-            if (cc < c) C[gr * ldc + cc] = acc[i][j];
+            const int cc = 8 * tx + j;
+            if (cc < c) C[gr * ldc + cc] = acc[j];
         }
     }
 }
@@ -192,11 +219,20 @@ int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float*
     return aser_check_launch(ctx, "jacobi");
 }
 
-int aser_gemm_small_f32(aser_ctx* ctx, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
-                        int64_t rows, int k, int c) {
+int aser_gemm_small_f32(aser_ctx* ctx, float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+                        int64_t rows, int k, int c, int64_t clear_rows) {
     if (rows <= 0) return ASER_OK;
-    if (k <= 0 || c <= 0) ASER_FAIL(ctx, ASER_ERR_SHAPE, "gemm_small: k > 0 and c > 0 required");
-    dim3 grid((unsigned)ceil_div64(rows, 32), (unsigned)((c + 127) / 128));
-    hipLaunchKernelGGL(gemm_small_kernel, grid, dim3(256), 0, ctx->stream, A, lda, B, ldb, C, ldc, rows, k, c);
+    if (k <= 0 || c <= 0 || k > 128 || c > 128 || (k & 3)) ASER_FAIL(ctx, ASER_ERR_SHAPE, "gemm_small: need 0 < k, c <= 128, k % 4 == 0");
+    if (((uintptr_t)A & 15) || (lda & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_small: A must be 16-byte aligned with lda % 4 == 0");
+    const int vec_b = (((uintptr_t)B & 15) == 0 && (ldb & 3) == 0 && (c & 3) == 0) ? 1 : 0;
+    static bool attr_set[16] = {false};
+    const size_t lds = (size_t)(kGsRows + 128) * kGsPitch * sizeof(float);
+    if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
+        ASER_HIP(ctx, hipFuncSetAttribute((const void*)gemm_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set[ctx->device] = true;
+    }
+    const int64_t cover = rows > clear_rows ? rows : clear_rows;
+    hipLaunchKernelGGL(gemm_small_kernel, dim3((unsigned)ceil_div64(cover, kGsRows)), dim3(256), lds, ctx->stream, A, lda, B, ldb,
+                       C, ldc, rows, k, c, clear_rows, vec_b);
     return aser_check_launch(ctx, "gemm_small");
 }

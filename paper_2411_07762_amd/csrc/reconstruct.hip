@@ -83,9 +83,10 @@ size_t aser_reconstruct_workspace(int64_t m, int64_t n, int r, const aser_svd_op
 
 namespace {
 
+// C += A^T B with K split over workgroups (fp32 atomics); `clear` zeroes C first.
 int gemm_tn_atomic(aser_ctx* ctx, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
-                   int64_t M, int64_t N, int64_t K, int bm, int bn) {
-    ASER_TRY(aser_fill_f32(ctx, C, M, N, ldc, 0.f));
+                   int64_t M, int64_t N, int64_t K, int bm, int bn, bool clear) {
+    if (clear) ASER_TRY(aser_fill_f32(ctx, C, M, N, ldc, 0.f));
     GemmArgs g{};
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.Ct = nullptr; g.ldct = 0;
     g.M = M; g.N = N; g.K = K; g.alpha = 1.f;
@@ -104,11 +105,14 @@ int gemm_tn_atomic(aser_ctx* ctx, const float* A, int64_t lda, const float* B, i
     return aser_gemm_tn(ctx, g);
 }
 
-// Y (rows x b) <- Y R^-1 with R^T R = Y^T Y (Cholesky-QR).  Returns the new Y in *Y (swapped with *tmp).
-int chol_qr(aser_ctx* ctx, float** Y, float** tmp, int64_t rows, int b, float* Mb, float* Rinv, int32_t* info) {
-    ASER_TRY(gemm_tn_atomic(ctx, *Y, b, *Y, b, Mb, b, b, b, rows, 128, 128));
-    ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rinv, info, 0));
-    ASER_TRY(aser_gemm_small_f32(ctx, *Y, b, Rinv, b, *tmp, b, rows, b, b));
+// Y (rows x b) <- Y R^-1 with R^T R = Y^T Y (Cholesky-QR).  Mb must be zero on entry and is zero again
+// on return.  The new Y is returned in *Y (swapped with *tmp); the old buffer, now *tmp, has been
+// cleared: it is ready as the target of the next accumulating product.
+int chol_qr(aser_ctx* ctx, float** Y, float** tmp, int64_t rows, int64_t clear_rows, int b, float* Mb, float* Rinv,
+            int32_t* info) {
+    ASER_TRY(gemm_tn_atomic(ctx, *Y, b, *Y, b, Mb, b, b, b, rows, 128, 128, false));
+    ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rinv, info, 0, /*clear_d=*/true));
+    ASER_TRY(aser_gemm_small_f32(ctx, *Y, b, Rinv, b, *tmp, b, rows, b, b, clear_rows));
     float* t = *Y; *Y = *tmp; *tmp = t;
     return ASER_OK;
 }
@@ -184,21 +188,28 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         hipLaunchKernelGGL(random_block_kernel, dim3(blocks), dim3(256), 0, ctx->stream, Q, total, p.seed);
         ASER_TRY(aser_check_launch(ctx, "random_block"));
     }
+    // Three tall buffers rotate: after every chol_qr `tp` is all zero, so the next product can
+    // accumulate into it without a separate clearing pass.
     float* Qp = Q;
     float* Zp = Z;
     float* tp = tmp;
-    ASER_TRY(chol_qr(ctx, &Qp, &tp, m, b, Mb, Rinv, info));
+    const int64_t mx = m > n ? m : n;
+    ASER_TRY(aser_fill_f32(ctx, Mb, b, b, b, 0.f));
+    ASER_TRY(chol_qr(ctx, &Qp, &tp, m, mx, b, Mb, Rinv, info));
     const int bmA = 128, bnB = 128;
     for (int it = 0; it < p.iters; ++it) {
-        ASER_TRY(gemm_tn_atomic(ctx, A, n, Qp, b, Zp, b, n, b, m, bmA, bnB));      // Z = A^T Q
-        ASER_TRY(chol_qr(ctx, &Zp, &tp, n, b, Mb, Rinv, info));
-        ASER_TRY(gemm_tn_atomic(ctx, At, m, Zp, b, Qp, b, m, b, n, bmA, bnB));     // Q = A Z
-        ASER_TRY(chol_qr(ctx, &Qp, &tp, m, b, Mb, Rinv, info));
+        ASER_TRY(gemm_tn_atomic(ctx, A, n, Qp, b, tp, b, n, b, m, bmA, bnB, false));    // Z = A^T Q
+        { float* t = Zp; Zp = tp; tp = t; }
+        ASER_TRY(chol_qr(ctx, &Zp, &tp, n, mx, b, Mb, Rinv, info));
+        ASER_TRY(gemm_tn_atomic(ctx, At, m, Zp, b, tp, b, m, b, n, bmA, bnB, false));   // Q = A Z
+        { float* t = Qp; Qp = tp; tp = t; }
+        ASER_TRY(chol_qr(ctx, &Qp, &tp, m, mx, b, Mb, Rinv, info));
     }
-    ASER_TRY(chol_qr(ctx, &Qp, &tp, m, b, Mb, Rinv, info));                        // second pass: orthonormal to fp32
+    ASER_TRY(chol_qr(ctx, &Qp, &tp, m, mx, b, Mb, Rinv, info));                        // second pass: orthonormal to fp32
     // Rayleigh-Ritz: Z = A^T Q, eigen-pairs of Z^T Z = Q^T A A^T Q
-    ASER_TRY(gemm_tn_atomic(ctx, A, n, Qp, b, Zp, b, n, b, m, bmA, bnB));
-    ASER_TRY(gemm_tn_atomic(ctx, Zp, b, Zp, b, Mb, b, b, b, n, 128, 128));
+    ASER_TRY(gemm_tn_atomic(ctx, A, n, Qp, b, tp, b, n, b, m, bmA, bnB, false));
+    { float* t = Zp; Zp = tp; tp = t; }
+    ASER_TRY(gemm_tn_atomic(ctx, Zp, b, Zp, b, Mb, b, b, b, n, 128, 128, false));
     ASER_TRY(aser_tridiag_eig(ctx, Mb, b, lambda, Uhat, refl, tri, cluster));
     ASER_TRY(aser_jacobi_eig(ctx, Mb, b, lambda, Uhat, cluster));      // only runs if eigenvalues cluster
     hipLaunchKernelGGL(ritz_factors_kernel, dim3(16), dim3(256), 0, ctx->stream, (const float*)lambda, (const float*)Uhat, b,
@@ -224,7 +235,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     // L_A = Q (Uhat_r Sigma_r)
     ASER_TRY(aser_gemm_small_f32(ctx, Qp, b, WA, r, L_A, r, m, b, r));
     // L_B^T = (T^T Q) (Uhat_r Sigma_r^-1)  ->  L_B
-    ASER_TRY(gemm_tn_atomic(ctx, T, ldt, Qp, b, Zp, b, n, b, m, bmA, bnB));        // C^T = T^T Q (n x b)
+    ASER_TRY(gemm_tn_atomic(ctx, T, ldt, Qp, b, Zp, b, n, b, m, bmA, bnB, true));  // C^T = T^T Q (n x b)
     ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, WBt, r, tp, r, n, b, r));             // n x r
     ASER_TRY(aser_transpose_f32(ctx, tp, n, r, r, L_B, n));
 
