@@ -95,7 +95,7 @@ int aser_sumsq_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols, in
 // Small dense kernels (one workgroup, matrices in LDS)
 // Upper Cholesky of the b x b block D (ld) in place: upper part <- R (D = R^T R), lower part <- R^T;
 // Rinv (b x b, ld = b) <- R^-1 (upper).  b <= 128.  On a non-positive pivot at column j,
-// atomicMin(info, pivot_base + j + 1) and the pivot is replaced by 1.  clear_d: D is overwritten with
+// atomicMin(info, pivot_base + j + 1) and the factor is meaningless from that column on.  clear_d: D is overwritten with
 // zeros instead of the factor (callers that only need R^-1 and reuse D as an accumulation target).
 int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base,
                     bool clear_d = false);

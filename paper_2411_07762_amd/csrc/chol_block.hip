@@ -15,8 +15,8 @@
 //   3. everyone: trailing update A[right, right] -= R[k, right]^T R[k, right] over the upper
 //      triangle of tiles, and the new block column of the inverse X[above, k] = -X[above, above] Y.
 //
-// A non-positive pivot at column j is reported as atomicMin(info, pivot_base + j + 1) and replaced
-// by 1.  Rows and columns beyond b are padded with the identity.
+// A non-positive pivot at column j is reported as atomicMin(info, pivot_base + j + 1); its row is
+// left unscaled (the factor is meaningless from there on).  Rows and columns beyond b are padded with the identity.
 #include "aser_internal.h"
 
 namespace {
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
     extern __shared__ __align__(16) float sm[];
     float* As = sm;                      // working matrix, upper triangle -> R
     float* Xs = As + kN * kP;            // R^-1 (upper), zero elsewhere
-    float* Ys = Xs + kN * kP;            // 96 x 32 scratch
+    float* Ys = Xs + kN * kP;            // 96 x 32 scratch, then 64 words that take masked-off stores
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nsub = (b + kSub - 1) / kSub;
     const int nb = nsub * kSub;          // padded with the identity up to here
@@ -92,16 +92,16 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
                 a2[e] = (row == col) ? 1.f : 0.f;
             }
             int bad = kSub;
+            // LDS targets of this lane's row / column stores; the half of the lanes that holds another
+            // row in the same register writes to a scratch word instead (no exec-mask changes in the chain)
+            float* const dummy = Ys + 96 * kPY + lane;
 #pragma unroll
             for (int j = 0; j < kSub; ++j) {
                 const int e = 4 * (j / 8) + j % 4, hj = (j / 4) & 1;
-                float piv = lane_bcast(a1[e], 32 * hj + j);
-                if (!(piv > 0.f)) {
-                    if (bad > j) bad = j;
-                    piv = 1.f;
-                    a1[e] = (lane == 32 * hj + j) ? 1.f : a1[e];
-                }
-                const float rs = __builtin_amdgcn_rsqf(piv);      // 1 ulp: as good as the fp32 data it scales
+                const float piv = lane_bcast(a1[e], 32 * hj + j);
+                const bool ok = piv > 0.f;
+                bad = ok ? bad : (bad < j ? bad : j);
+                const float rs = __builtin_amdgcn_rsqf(ok ? piv : 1.f);   // 1 ulp: as good as the fp32 data it scales
                 // The update of the first accumulator is issued before the second one is touched:
                 // the next pivot only waits for the first.
                 const float rv = a1[e] * rs;
@@ -110,10 +110,8 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
                 __builtin_amdgcn_sched_barrier(0);
                 const float lv = a2[e] * rs;
                 if (j + 1 < kSub) a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, lv, a2, 0, 0, 0);
-                if (h == hj) {
-                    As[(o + j) * kP + o + col] = rv;              // row j of R_kk (entries left of the diagonal are dead)
-                    Xs[(o + col) * kP + o + j] = lv;              // X_kk = (L_kk^-1)^T
-                }
+                *((h == hj) ? As + (o + j) * kP + o + col : dummy) = rv;   // row j of R_kk (left of the diagonal: dead)
+                *((h == hj) ? Xs + (o + col) * kP + o + j : dummy) = lv;   // X_kk = (L_kk^-1)^T
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (bad < kSub && lane == 0 && o + bad < b && info) atomicMin(info, pivot_base + o + bad + 1);
@@ -202,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
 int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base, bool clear_d) {
     if (b <= 0 || b > kN) ASER_FAIL(ctx, ASER_ERR_SHAPE, "chol_block: block size out of range");
     static bool attr_set[16] = {false};
-    const size_t lds = (size_t)(2 * kN * kP + 96 * kPY) * sizeof(float);
+    const size_t lds = (size_t)(2 * kN * kP + 96 * kPY + 64) * sizeof(float);
     if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
         ASER_HIP(ctx, hipFuncSetAttribute((const void*)chol_block_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set[ctx->device] = true;
