@@ -75,6 +75,7 @@ struct GemmArgs {
     int in_type, epi, tiles, krange;
     int k_parts;               // split of the K range over blockIdx.y
     int bm, bn;                // tile: 256x256, 128x256, 256x128 or 128x128
+    int upper_only;            // ATOMIC only: skip entries with row > col (C is symmetric, its upper part is used)
 };
 int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g);
 

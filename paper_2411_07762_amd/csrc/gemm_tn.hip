@@ -392,10 +392,13 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t
             if (col >= g.N) continue;
             float* cbase = g.C + rbase * g.ldc + col;
             if (g.epi == GEMM_EPI_ATOMIC) {
+                // upper_only: entries left of the diagonal are never read by the caller; leaving them
+                // out halves the atomic traffic of the small symmetric products
+                const int64_t rmax = g.upper_only ? (col + 1 < g.M ? col + 1 : g.M) : g.M;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int dr = 8 * (e >> 2) + (e & 3);
-                    if (rbase + dr < g.M) unsafeAtomicAdd(cbase + (int64_t)dr * g.ldc, alpha * acc[i][j][e]);
+                    if (rbase + dr < rmax) unsafeAtomicAdd(cbase + (int64_t)dr * g.ldc, alpha * acc[i][j][e]);
                 }
             } else {
 #pragma unroll

@@ -85,13 +85,13 @@ namespace {
 
 // C += A^T B with K split over workgroups (fp32 atomics); `clear` zeroes C first.
 int gemm_tn_atomic(aser_ctx* ctx, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
-                   int64_t M, int64_t N, int64_t K, int bm, int bn, bool clear) {
+                   int64_t M, int64_t N, int64_t K, int bm, int bn, bool clear, bool upper_only = false) {
     if (clear) ASER_TRY(aser_fill_f32(ctx, C, M, N, ldc, 0.f));
     GemmArgs g{};
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.Ct = nullptr; g.ldct = 0;
     g.M = M; g.N = N; g.K = K; g.alpha = 1.f;
     g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_ATOMIC; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
-    g.bm = bm; g.bn = bn;
+    g.bm = bm; g.bn = bn; g.upper_only = upper_only ? 1 : 0;
     // Split K so that about 256 workgroups run.  Every part pays a pipeline fill and an atomic
     // flush of its whole tile, so parts keep at least 8 K steps (4 when the output is tiny and the
     // call is pure latency).
@@ -110,7 +110,7 @@ int gemm_tn_atomic(aser_ctx* ctx, const float* A, int64_t lda, const float* B, i
 // cleared: it is ready as the target of the next accumulating product.
 int chol_qr(aser_ctx* ctx, float** Y, float** tmp, int64_t rows, int64_t clear_rows, int b, float* Mb, float* Rinv,
             int32_t* info) {
-    ASER_TRY(gemm_tn_atomic(ctx, *Y, b, *Y, b, Mb, b, b, b, rows, 128, 128, false));
+    ASER_TRY(gemm_tn_atomic(ctx, *Y, b, *Y, b, Mb, b, b, b, rows, 128, 128, false, /*upper_only=*/true));
     ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rinv, info, 0, /*clear_d=*/true));
     ASER_TRY(aser_gemm_small_f32(ctx, *Y, b, Rinv, b, *tmp, b, rows, b, b, clear_rows));
     float* t = *Y; *Y = *tmp; *tmp = t;
