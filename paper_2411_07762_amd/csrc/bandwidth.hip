@@ -9,6 +9,7 @@ namespace {
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
@@ -161,13 +162,14 @@ __global__ __launch_bounds__(256) void sumsq_kernel(const float* A, int64_t rows
 }
 
 // ------------------------------------------------------------------------------------ weight RTN
-// One workgroup per output row.  A thread owns groups of 8 consecutive columns; the row stays in
+// One workgroup per output row (256 to 1024 threads, two or four groups each, so that wide rows
+// still run at full occupancy).  A thread owns groups of 8 consecutive columns; the row stays in
 // registers between the absmax reduction and the quantization, so W is read from HBM once.  The
 // global loads are issued before the outlier-column bitmask is built in LDS, so that its two
 // barriers overlap the load latency.  Integer decisions (scale, codes) are taken in IEEE fp32 with
 // correctly rounded division and round-half-to-even.
-template <int VPT>   // 8-column groups per thread
-__global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ W, int64_t n, int64_t ldw,
+template <int VPT, int NT>   // 8-column groups per thread, threads per row
+__global__ __launch_bounds__(NT) void rtn_kernel(const float* __restrict__ W, int64_t n, int64_t ldw,
                                                   const int32_t* __restrict__ idx, const float* __restrict__ mdiag, int f,
                                                   float qmax, int layout, uint8_t* __restrict__ codes, int64_t code_pitch,
                                                   float* __restrict__ scales, float* __restrict__ T, int64_t ldt) {
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ W, i
     float v[VPT][8];
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int64_t c = ((int64_t)u * 256 + tid) * 8;
+        const int64_t c = ((int64_t)u * NT + tid) * 8;
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[u][e] = 0.f;
         if (c < n) {
@@ -198,9 +200,9 @@ __global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ W, i
         }
     }
     const int mask_words = (int)((n + 31) / 32);
-    for (int i = tid; i < mask_words; i += 256) mask[i] = 0u;
+    for (int i = tid; i < mask_words; i += NT) mask[i] = 0u;
     __syncthreads();
-    for (int i = tid; i < f; i += 256) {
+    for (int i = tid; i < f; i += NT) {
         const int c = idx[i];
         atomicOr(&mask[c >> 5], 1u << (c & 31));
     }
@@ -210,7 +212,7 @@ __global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ W, i
     float amax = 0.f;
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int64_t c = ((int64_t)u * 256 + tid) * 8;
+        const int64_t c = ((int64_t)u * NT + tid) * 8;
         om[u] = 0u;
         if (c < n) {
             om[u] = (mask[c >> 5] >> (c & 31)) & 0xFFu;   // c is a multiple of 8: one mask word
@@ -228,7 +230,7 @@ __global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ W, i
     const bool c_vec = vec_ok && (((uintptr_t)crow & 7) == 0);
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int64_t c = ((int64_t)u * 256 + tid) * 8;
+        const int64_t c = ((int64_t)u * NT + tid) * 8;
         if (c >= n) continue;
         float t[8];
         int q[8];
@@ -285,48 +287,90 @@ __global__ __launch_bounds__(256) void rtn_kernel(const float* __restrict__ W, i
 }
 
 // ------------------------------------------------------------------------------------ activation RTN
-// One workgroup per token.  X' = X / m with an IEEE fp32 division, per-token absmax scale.
-template <bool BF16, int VPT>   // 4-element groups per thread
-__global__ __launch_bounds__(256) void act_rtn_kernel(const void* __restrict__ X, int64_t n, int64_t ldx,
-                                                      const float* __restrict__ mdiag, float qmax,
-                                                      int8_t* __restrict__ codes, float* __restrict__ scales) {
+// One workgroup per token (256 to 1024 threads).  X' = X / m with an IEEE fp32 division, per-token
+// absmax scale.  A thread owns groups of 8 consecutive channels: one 16-byte load of bf16 (two of
+// fp32), one 8-byte store of codes; the token stays in registers between the absmax reduction
+// and the rounding.
+template <bool BF16, int VPT, int NT>
+__global__ __launch_bounds__(NT) void act_rtn_kernel(const void* __restrict__ X, int64_t n, int64_t ldx,
+                                                     const float* __restrict__ mdiag, float qmax,
+                                                     int8_t* __restrict__ codes, float* __restrict__ scales) {
     __shared__ float red[16];
     const int64_t row = blockIdx.x;
     const int tid = threadIdx.x;
-    float4 v[VPT];
+    const char* xrow = (const char*)X + row * ldx * (BF16 ? 2 : 4);
+    const bool vec_ok = (((uintptr_t)xrow & 15) == 0) && ((n & 7) == 0);
+    const bool m_vec = mdiag && (((uintptr_t)mdiag & 15) == 0);
+    float v[VPT][8];
     float amax = 0.f;
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int64_t c = ((int64_t)u * 256 + tid) * 4;
-        float t[4] = {0.f, 0.f, 0.f, 0.f};
-        if (c < n) {
-            for (int e = 0; e < 4; ++e) {
-                if (c + e < n) {
-                    float x;
-                    if (BF16) x = __uint_as_float((uint32_t)(((const uint16_t*)X)[row * ldx + c + e]) << 16);
-                    else x = ((const float*)X)[row * ldx + c + e];
-                    t[e] = mdiag ? x / mdiag[c + e] : x;
+        const int64_t c = ((int64_t)u * NT + tid) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[u][e] = 0.f;
+        if (c >= n) continue;
+        if (vec_ok) {
+            if (BF16) {
+                const u32x4_t w = __builtin_nontemporal_load((const u32x4_t*)(xrow + c * 2));
+                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[u][2 * e] = __uint_as_float(ww[e] << 16);
+                    v[u][2 * e + 1] = __uint_as_float(ww[e] & 0xFFFF0000u);
                 }
+            } else {
+                const f32x4_t x0 = __builtin_nontemporal_load((const f32x4_t*)(xrow + c * 4));
+                const f32x4_t x1 = __builtin_nontemporal_load((const f32x4_t*)(xrow + c * 4 + 16));
+                v[u][0] = x0.x; v[u][1] = x0.y; v[u][2] = x0.z; v[u][3] = x0.w;
+                v[u][4] = x1.x; v[u][5] = x1.y; v[u][6] = x1.z; v[u][7] = x1.w;
             }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (c + e < n)
+                    v[u][e] = BF16 ? __uint_as_float((uint32_t)(((const uint16_t*)xrow)[c + e]) << 16) : ((const float*)xrow)[c + e];
         }
-        v[u] = make_float4(t[0], t[1], t[2], t[3]);
-        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(t[0]), fabsf(t[1])), fmaxf(fabsf(t[2]), fabsf(t[3]))));
+        if (mdiag) {
+            float mm[8];
+            if (m_vec && c + 8 <= n) {
+                const float4 m0 = *(const float4*)(mdiag + c), m1 = *(const float4*)(mdiag + c + 4);
+                mm[0] = m0.x; mm[1] = m0.y; mm[2] = m0.z; mm[3] = m0.w; mm[4] = m1.x; mm[5] = m1.y; mm[6] = m1.z; mm[7] = m1.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) mm[e] = (c + e < n) ? mdiag[c + e] : 1.f;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[u][e] = v[u][e] / mm[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[u][e]));
     }
     amax = block_max(amax, red);
     const float scale = (amax == 0.f) ? 1.f : amax / qmax;
     if (tid == 0) scales[row] = scale;
     int8_t* crow = codes + row * n;
+    const bool c_vec = (((uintptr_t)crow & 7) == 0) && ((n & 7) == 0);
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
-        const int64_t c = ((int64_t)u * 256 + tid) * 4;
+        const int64_t c = ((int64_t)u * NT + tid) * 8;
         if (c >= n) continue;
-        const float t[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-        for (int e = 0; e < 4; ++e) {
-            if (c + e < n) {
-                float qf = rintf(t[e] / scale);
-                qf = fminf(fmaxf(qf, -qmax), qmax);
-                crow[c + e] = (int8_t)(int)qf;
-            }
+        int q[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float qf = rintf(v[u][e] / scale);
+            qf = fminf(fmaxf(qf, -qmax), qmax);
+            q[e] = (int)qf;
+        }
+        if (c_vec) {
+            const u32x2_t pk = {(uint32_t)(q[0] & 0xFF) | ((uint32_t)(q[1] & 0xFF) << 8) | ((uint32_t)(q[2] & 0xFF) << 16) |
+                                    ((uint32_t)(q[3] & 0xFF) << 24),
+                                (uint32_t)(q[4] & 0xFF) | ((uint32_t)(q[5] & 0xFF) << 8) | ((uint32_t)(q[6] & 0xFF) << 16) |
+                                    ((uint32_t)(q[7] & 0xFF) << 24)};
+            __builtin_nontemporal_store(pk, (u32x2_t*)(crow + c));
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (c + e < n) crow[c + e] = (int8_t)q[e];
         }
     }
 }
@@ -412,13 +456,13 @@ extern "C" int aser_quantize_rtn(aser_ctx* ctx, const float* W, int64_t m, int64
     const size_t lds = (size_t)((n + 31) / 32) * 4 + 64;
     const int64_t groups = ceil_div64(n, 8);
     dim3 grid((unsigned)m);
-#define ASER_RTN_LAUNCH(V)                                                                                     \
-    hipLaunchKernelGGL(rtn_kernel<V>, grid, dim3(256), lds, ctx->stream, W, n, ldw, idx, mdiag, (int)f, qmax, \
+#define ASER_RTN_LAUNCH(V, NT)                                                                                      \
+    hipLaunchKernelGGL((rtn_kernel<V, NT>), grid, dim3(NT), lds, ctx->stream, W, n, ldw, idx, mdiag, (int)f, qmax, \
                        (int)layout, (uint8_t*)codes, pitch, scales, T, ldt)
-    if (groups <= 256 * 2) ASER_RTN_LAUNCH(2);
-    else if (groups <= 256 * 4) ASER_RTN_LAUNCH(4);
-    else if (groups <= 256 * 8) ASER_RTN_LAUNCH(8);
-    else ASER_RTN_LAUNCH(16);
+    if (groups <= 256 * 2) ASER_RTN_LAUNCH(2, 256);
+    else if (groups <= 512 * 2) ASER_RTN_LAUNCH(2, 512);
+    else if (groups <= 1024 * 2) ASER_RTN_LAUNCH(2, 1024);
+    else ASER_RTN_LAUNCH(4, 1024);
 #undef ASER_RTN_LAUNCH
     return aser_check_launch(ctx, "rtn");
 }
@@ -435,19 +479,20 @@ extern "C" int aser_quantize_act_rtn(aser_ctx* ctx, const void* X, int x_dtype, 
     if (rows == 0) return ASER_OK;
     ASER_TRY(aser_prepare_device(ctx));
     const float qmax = (float)((1 << (bits - 1)) - 1);
-    const int64_t groups = ceil_div64(n, 4);
+    const int64_t groups = ceil_div64(n, 8);
     dim3 grid((unsigned)rows);
-#define ASER_ACT_LAUNCH(B, V) \
-    hipLaunchKernelGGL((act_rtn_kernel<B, V>), grid, dim3(256), 0, ctx->stream, X, n, ldx, mdiag, qmax, codes, scales)
-    if (x_dtype == ASER_DTYPE_BF16) {
-        if (groups <= 256 * 4) ASER_ACT_LAUNCH(true, 4);
-        else if (groups <= 256 * 16) ASER_ACT_LAUNCH(true, 16);
-        else ASER_ACT_LAUNCH(true, 32);
-    } else {
-        if (groups <= 256 * 4) ASER_ACT_LAUNCH(false, 4);
-        else if (groups <= 256 * 16) ASER_ACT_LAUNCH(false, 16);
-        else ASER_ACT_LAUNCH(false, 32);
-    }
+#define ASER_ACT_LAUNCH(B, V, NT) \
+    hipLaunchKernelGGL((act_rtn_kernel<B, V, NT>), grid, dim3(NT), 0, ctx->stream, X, n, ldx, mdiag, qmax, codes, scales)
+#define ASER_ACT_PICK(B)                                         \
+    do {                                                         \
+        if (groups <= 256 * 2) ASER_ACT_LAUNCH(B, 2, 256);       \
+        else if (groups <= 512 * 2) ASER_ACT_LAUNCH(B, 2, 512);  \
+        else if (groups <= 1024 * 2) ASER_ACT_LAUNCH(B, 2, 1024);\
+        else ASER_ACT_LAUNCH(B, 4, 1024);                        \
+    } while (0)
+    if (x_dtype == ASER_DTYPE_BF16) ASER_ACT_PICK(true);
+    else ASER_ACT_PICK(false);
+#undef ASER_ACT_PICK
 #undef ASER_ACT_LAUNCH
     return aser_check_launch(ctx, "act_rtn");
 }

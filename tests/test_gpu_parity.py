@@ -355,6 +355,83 @@ def test_headline_layer_full_size():
     run_e2e("c1_full", spec, True)
 
 
+def test_large_mlp_layer_full_size_sampled():
+    """The 4096 x 11008 layer with 65536 tokens of heavy-tailed activations, at full size.  The oracle's
+    SVD of that layer takes minutes, so each stage is checked on samples the oracle computes one by one
+    (Gram entries, statistics, RTN rows) or through identities that hold at any size (S S^T = G',
+    reported error = whitened error recomputed from the returned factors, Eq. 8)."""
+    spec = synth.CONFIGS["c2"]
+    say("c2 full size m=%d n=%d N=%d r=%d f=%d" % (spec.m, spec.n, spec.tokens, spec.r, spec.f))
+    rng = np.random.default_rng(7)
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    ctx = new_ctx()
+    buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, True)
+    aser.calibrate_layer(ctx, torch.from_numpy(W).to(DEV), to_dev_x(spec, x_np), buf)
+    torch.cuda.synchronize()
+    say("c2: device path done, err=%.6g" % buf.err)
+
+    # statistics of all channels (fp64, chunked) and the smoothing decision
+    abs_ref = np.zeros(spec.n)
+    for a in range(0, spec.tokens, 8192):
+        abs_ref += np.abs(synth.bf16_to_f32(x_np[a:a + 8192])).sum(axis=0, dtype=np.float64)
+    assert np.allclose(buf.abs_sum.cpu().numpy(), abs_ref, rtol=1e-12, atol=0)
+    sm = orc.smooth_outliers(W, abs_ref, spec.tokens, spec.f)
+    assert buf.idx.cpu().numpy()[:spec.f].tolist() == sm.idx.tolist()
+    assert np.array_equal(buf.mdiag.cpu().numpy(), sm.mdiag)
+
+    # Gram entries: pairs of channels across tiles, the last tile, planted outliers and the diagonal
+    planted, _ = synth.outlier_channels(spec)
+    cols = np.unique(np.concatenate([rng.integers(0, spec.n, 20), [0, 255, 256, spec.n - 1, spec.n - 256], planted[:4]]))
+    Xs = synth.bf16_to_f32(x_np[:, cols])
+    G_ref, _, _ = orc.gram(Xs)
+    G = buf.G.cpu().numpy()
+    # the lower triangle is authoritative: take entry (max, min)
+    Gs = np.where(cols[:, None] >= cols[None, :], G[np.ix_(cols, cols)], G[np.ix_(cols, cols)].T)
+    d = np.sqrt(np.diag(G_ref))
+    assert np.all(np.abs(Gs - G_ref) <= 2e-5 * np.outer(d, d))
+    del Xs
+
+    # RTN on sampled rows (rows are independent)
+    rows = np.unique(np.concatenate([rng.integers(0, spec.m, 40), [0, spec.m - 1]]))
+    ref_q = orc.quantize_rtn(W[rows], sm.idx, sm.mdiag, spec.bits)
+    codes = unpack_int4(buf.codes.cpu().numpy()[rows])
+    assert np.array_equal(codes, ref_q.codes)
+    assert np.array_equal(buf.scales.cpu().numpy()[rows], ref_q.scales)
+    T = buf.T.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(T[rows] - ref_q.T) <= 2.0 ** -23 * np.abs(ref_q.T) + 1e-30)
+
+    # whitening: lower triangular and S S^T = M^-1 G M^-1 on the sampled entries
+    S = buf.S.cpu().numpy().astype(np.float64)
+    assert not np.triu(S[:512, :512], 1).any() and not np.triu(S[-512:, -512:], 1).any() and not S[:256, -256:].any()
+    SS = S[cols] @ S[cols].T
+    Gp = G_ref / np.outer(sm.mdiag[cols].astype(np.float64), sm.mdiag[cols].astype(np.float64))
+    dp = np.sqrt(np.diag(Gp))
+    assert np.all(np.abs(SS - Gp) <= 3e-5 * np.outer(dp, dp))
+
+    # Eq. 8: the reported error is the whitened error of the returned factors, which stay below the
+    # error of doing nothing, and sigma / the residual split the energy of T S
+    L_A = buf.L_A.cpu().numpy()
+    L_B = buf.L_B.cpu().numpy()
+    sigma = buf.sigma.cpu().numpy().astype(np.float64)
+    e = orc.whitened_error(T, S, L_A, L_B)
+    say("c2: whitened error recomputed %.6g reported %.6g rel %.2e" % (e, buf.err, abs(e - buf.err) / e))
+    assert abs(e - buf.err) / e <= 1e-4
+    A = T @ S
+    e0 = float(np.linalg.norm(A))
+    assert e < e0
+    # the optimum itself, from the spectrum of the smaller Gram matrix: sigma_i^2 = eig_i(A A^T)
+    lam = np.linalg.eigvalsh(A @ A.T)[::-1]
+    e_opt = float(np.sqrt(np.sum(lam[spec.r:])))
+    say("c2: optimal whitened error %.6g, device %.6g, rel %.2e; sigma_r/sigma_r+1 = %.4f" %
+        (e_opt, e, (e - e_opt) / e_opt, np.sqrt(lam[spec.r - 1] / lam[spec.r])))
+    assert 0.0 <= (e - e_opt) / e_opt + 1e-9 and (e - e_opt) / e_opt <= 1e-4
+    assert np.allclose(sigma[:spec.f], np.sqrt(lam[:spec.f]), rtol=1e-3)
+    del A
+    assert abs(e * e + float(np.sum(sigma ** 2)) - e0 * e0) <= 1e-4 * e0 * e0
+    assert np.all(np.diff(sigma) <= 1e-6 * sigma[0])
+
+
 def test_deterministic_integer_outputs():
     spec = synth.mini("d1", 130, 520, 1500, r=16, f=8)
     W = torch.from_numpy(synth.make_weight(spec)).to(DEV)
