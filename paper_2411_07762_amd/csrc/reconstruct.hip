@@ -40,22 +40,35 @@ __global__ void random_block_kernel(float* Q, int64_t total, uint32_t seed) {
     }
 }
 
-// C = alpha A B for upper triangular b x b matrices (ld = b, b <= 128), one workgroup of 1024
-// threads, a 4 x 4 block of C per thread, k restricted to the range where both factors are non-zero.
+// C = alpha A B for upper triangular b x b matrices (ld = b, b <= 128), one workgroup of 16
+// wavefronts, fp32 MFMA: C is cut into 16 x 16 tiles, tile (ti <= tj) needs k in [16 ti, 16 tj + 16)
+// only.  Tiles are dealt to the wavefronts longest first.
 // with_beta: alpha = -beta with beta = (0.9 s^2 / 2)^2, s = min_i 1 / |B[i][i]| (B holds R_z^-1).
-constexpr int kTriPitch = 132;
+typedef float tri_f4v __attribute__((ext_vector_type(4)));
+constexpr int kTriPitch = 133;
 __global__ __launch_bounds__(1024) void tri_mm_kernel(const float* __restrict__ A, const float* __restrict__ B,
                                                       float* __restrict__ C, int b, int with_beta) {
     extern __shared__ __align__(16) float tri_sm[];
-    float* At = tri_sm;                       // At[k][i] = A[i][k]
-    float* Bs = tri_sm + 128 * kTriPitch;     // Bs[k][j]
+    float* As = tri_sm;                       // row-major, zero outside the upper triangle
+    float* Bs = tri_sm + 128 * kTriPitch;
     __shared__ float red[16];
-    const int tid = threadIdx.x;
-    for (int t = tid; t < 128 * 128; t += 1024) {
-        const int i = t >> 7, k = t & 127;
-        const bool in = i < b && k < b;
-        At[k * kTriPitch + i] = in ? A[i * b + k] : 0.f;
-        Bs[i * kTriPitch + k] = in ? B[i * b + k] : 0.f;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    {
+        // all global loads first (upper triangles only), then the LDS stores
+        float va[16], vb[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int t = tid + 1024 * u, i = t >> 7, k = t & 127;
+            const bool in = i < b && k < b && k >= i;
+            va[u] = in ? A[i * b + k] : 0.f;
+            vb[u] = in ? B[i * b + k] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int t = tid + 1024 * u, i = t >> 7, k = t & 127;
+            As[i * kTriPitch + k] = va[u];
+            Bs[i * kTriPitch + k] = vb[u];
+        }
     }
     float alpha = 1.f;
     if (with_beta) {
@@ -63,38 +76,37 @@ __global__ __launch_bounds__(1024) void tri_mm_kernel(const float* __restrict__ 
         if (tid < b) s = 1.0f / fabsf(B[tid * b + tid]);
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) s = fminf(s, __shfl_xor(s, o, 64));
-        if ((tid & 63) == 0) red[tid >> 6] = s;
+        if (lane == 0) red[wave] = s;
         __syncthreads();
         s = fminf(red[0], red[1]);
         const float h = 0.45f * s * s;
         alpha = -h * h;
     }
     __syncthreads();
-    const int ti = tid >> 5, tj = tid & 31;
-    float acc[4][4];
+    // job j = 0..35: diagonal distance d descending (d = 7: 1 tile, d = 6: 2 tiles, ...)
+    const int t_i = lane & 15, t_q = lane >> 4;
+    for (int job = wave; job < 36; job += 16) {
+        int d = 7, first = 0;
+        while (job >= first + (8 - d)) { first += 8 - d; --d; }
+        const int ti = job - first, tj = ti + d;
+        tri_f4v acc = {0.f, 0.f, 0.f, 0.f};
+        const float* pa = As + (16 * ti + t_i) * kTriPitch + 16 * ti + t_q;
+        const float* pb = Bs + (16 * ti + t_q) * kTriPitch + 16 * tj + t_i;
+        const int nk4 = 4 * (d + 1);
+#pragma unroll 4
+        for (int q = 0; q < nk4; ++q)
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(pa[4 * q], pb[4 * q * kTriPitch], acc, 0, 0, 0);
 #pragma unroll
-    for (int p = 0; p < 4; ++p)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) acc[p][q] = 0.f;
-    if (ti <= tj) {
-        const int kend = (4 * tj + 4 < b) ? 4 * tj + 4 : b;
-        for (int k = 4 * ti; k < kend; ++k) {
-            const float4 a4 = *(const float4*)(At + k * kTriPitch + 4 * ti);
-            const float4 b4 = *(const float4*)(Bs + k * kTriPitch + 4 * tj);
-            const float aa[4] = {a4.x, a4.y, a4.z, a4.w}, bv[4] = {b4.x, b4.y, b4.z, b4.w};
-#pragma unroll
-            for (int p = 0; p < 4; ++p)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) acc[p][q] = fmaf(aa[p], bv[q], acc[p][q]);
+        for (int e = 0; e < 4; ++e) {
+            const int i = 16 * ti + 4 * t_q + e, j = 16 * tj + t_i;
+            if (i < b && j < b) C[i * b + j] = alpha * acc[e];
         }
     }
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int i = 4 * ti + p, j = 4 * tj + q;
-            if (i < b && j < b) C[i * b + j] = alpha * acc[p][q];
-        }
+    // the strictly lower tiles of C are zero
+    for (int t = tid; t < b * b; t += 1024) {
+        const int i = t / b, j = t % b;
+        if ((i >> 4) > (j >> 4)) C[t] = 0.f;
+    }
 }
 
 int tri_mm(aser_ctx* ctx, const float* A, const float* B, float* C, int b, bool with_beta) {
