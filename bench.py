@@ -27,8 +27,8 @@ BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch at workload c1 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # 1 GiB copy (x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE); see profiles/gram_rtn_hbm_traffic.txt.
-MEASURED_TRAFFIC_C1 = {"gram": 443120 * 1024 * 2.0 + 143360 * 1024 * 1.0,
-                       "rtn": 32851 * 1024 * 2.0 + 73856 * 1024 * 1.0}
+MEASURED_TRAFFIC_C1 = {"gram": 435600 * 1024 * 2.0 + 132610 * 1024 * 1.0,
+                       "rtn": 32887 * 1024 * 2.0 + 76649 * 1024 * 1.0}
 
 
 def log(*a):
@@ -200,13 +200,13 @@ def main():
         "dtype": "bf16" if spec.x_dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: W %dx%d fp32, X %dx%d %s, W%d per-channel RTN, r=%d, f=%d" %
                                (spec.name, spec.m, spec.n, spec.tokens, spec.n, spec.x_dtype, spec.bits, spec.r, spec.f),
-                   "svd_block": 2 * spec.r if 2 * spec.r <= 128 else 128, "svd_iters": 12},
+                   "svd_block": 2 * spec.r if 2 * spec.r <= 128 else 128, "svd_iters": 10},
         "layers_per_s": 1e3 / ms_per_step,
         "calibration_tokens_per_s": spec.tokens * 1e3 / ms_per_step,
         "stage_ms": {k: round(v, 4) for k, v in zip(stage_names, stage_ms)},
         "gram_mfma_util_pct": 100.0 * gram_tflops / BF16_PEAK_TFLOPS,
         "whitened_error": err,
-        "roofline": {"kernel": "gemm_tn_kernel<bf16,256,256> (Gram update G += X^T X, lower-triangle tiles)",
+        "roofline": {"kernel": "gram_dma_kernel (Gram update G += X^T X, 256x256 lower-triangle tiles, bf16 MFMA)",
                      "bound": "mfma", "achieved": gram_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gram_tflops / BF16_PEAK_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_C1["gram"] if spec.name == "c1" else None,
