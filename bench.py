@@ -194,6 +194,20 @@ def main():
     rtn_bytes = 8.5 * spec.m * spec.n + 4.0 * spec.m
     rtn_gbs = rtn_bytes / (rtn_ms * 1e-3) / 1e9
 
+    # Per-token activation quantizer (a7) on the calibration stream: algorithmic bytes 3 N n + 4 N for bf16 X.
+    act_codes = torch.empty((spec.tokens, spec.n), dtype=torch.int8, device=dev)
+    act_scales = torch.empty(spec.tokens, dtype=torch.float32, device=dev)
+    ctx.check(aser.aser_quantize_act_rtn(ctx, X, buf.mdiag, 8, act_codes, act_scales))
+    e0.record()
+    for i in range(reps):
+        ctx.check(aser.aser_quantize_act_rtn(ctx, X, buf.mdiag, 8, act_codes, act_scales))
+    e1.record()
+    torch.cuda.synchronize()
+    act_ms = e0.elapsed_time(e1) / reps
+    act_bytes = (X.element_size() + 1.0) * spec.tokens * spec.n + 4.0 * spec.tokens
+    act_gbs = act_bytes / (act_ms * 1e-3) / 1e9
+    del act_codes
+
     out = {
         "metric": METRIC, "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
@@ -215,12 +229,15 @@ def main():
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rtn_gbs / HBM_PEAK_GBS,
                          "traffic": MEASURED_TRAFFIC_C1["rtn"] if spec.name == "c1" else None,
                          "algorithmic_bytes_per_launch": rtn_bytes, "avg_launch_ms": rtn_ms},
+        "roofline_act_quant": {"kernel": "act_rtn_kernel (per-token A8 quantizer of X M^-1)", "bound": "hbm",
+                               "achieved": act_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": act_gbs / HBM_PEAK_GBS,
+                               "traffic": None, "algorithmic_bytes_per_launch": act_bytes, "avg_launch_ms": act_ms},
     }
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(spec)
     log("stage ms:", out["stage_ms"], "gram %.3f ms = %.1f TFLOP/s" % (gram_ms, gram_tflops),
-        "rtn %.1f us = %.0f GB/s" % (rtn_ms * 1e3, rtn_gbs))
+        "rtn %.1f us = %.0f GB/s" % (rtn_ms * 1e3, rtn_gbs), "act quant %.1f us = %.0f GB/s" % (act_ms * 1e3, act_gbs))
     print(json.dumps(out))
 
 

@@ -161,6 +161,17 @@ __global__ __launch_bounds__(256) void sumsq_kernel(const float* A, int64_t rows
     if (threadIdx.x == 0) atomicAdd(out, red[0] + red[1] + red[2] + red[3]);
 }
 
+// rint(x / scale) with the result of the IEEE division, at the cost of a multiplication: the
+// quotient is first formed with the hardware reciprocal (relative error below 2e-7, so absolute
+// error below 3e-5 for |x / scale| <= 128); only when that value lies within 1e-4 of a rounding
+// boundary k + 1/2 can the two roundings differ, and then the correctly rounded division decides.
+__device__ __forceinline__ float rint_div(float x, float scale, float rscale) {
+    float q = x * rscale;
+    const float aq = fabsf(q);
+    if (!(aq < 200.f) || fabsf(aq - floorf(aq) - 0.5f) < 1e-4f) q = x / scale;   // also: reciprocal of a denormal scale
+    return rintf(q);
+}
+
 // ------------------------------------------------------------------------------------ weight RTN
 // One workgroup per output row (256 to 1024 threads, two or four groups each, so that wide rows
 // still run at full occupancy).  A thread owns groups of 8 consecutive columns; the row stays in
@@ -222,6 +233,7 @@ __global__ __launch_bounds__(NT) void rtn_kernel(const float* __restrict__ W, in
     }
     amax = block_max(amax, red);
     const float scale = (amax == 0.f) ? 1.f : amax / qmax;
+    const float rscale = __builtin_amdgcn_rcpf(scale);
     if (tid == 0) scales[row] = scale;
 
     uint8_t* crow = codes + row * code_pitch;
@@ -240,7 +252,7 @@ __global__ __launch_bounds__(NT) void rtn_kernel(const float* __restrict__ W, in
                 q[e] = 0;
                 t[e] = (c + e < n) ? v[u][e] * mdiag[c + e] : 0.f;
             } else {
-                float qf = rintf(v[u][e] / scale);
+                float qf = rint_div(v[u][e], scale, rscale);
                 qf = fminf(fmaxf(qf, -qmax), qmax);
                 q[e] = (int)qf;
                 t[e] = __fmaf_rn(-qf, scale, v[u][e]);
@@ -340,13 +352,14 @@ __global__ __launch_bounds__(NT) void act_rtn_kernel(const void* __restrict__ X,
                 for (int e = 0; e < 8; ++e) mm[e] = (c + e < n) ? mdiag[c + e] : 1.f;
             }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[u][e] = v[u][e] / mm[e];
+            for (int e = 0; e < 8; ++e) v[u][e] = (mm[e] == 1.f) ? v[u][e] : v[u][e] / mm[e];   // x / 1 = x exactly
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[u][e]));
     }
     amax = block_max(amax, red);
     const float scale = (amax == 0.f) ? 1.f : amax / qmax;
+    const float rscale = __builtin_amdgcn_rcpf(scale);
     if (tid == 0) scales[row] = scale;
     int8_t* crow = codes + row * n;
     const bool c_vec = (((uintptr_t)crow & 7) == 0) && ((n & 7) == 0);
@@ -357,7 +370,7 @@ __global__ __launch_bounds__(NT) void act_rtn_kernel(const void* __restrict__ X,
         int q[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float qf = rintf(v[u][e] / scale);
+            float qf = rint_div(v[u][e], scale, rscale);
             qf = fminf(fmaxf(qf, -qmax), qmax);
             q[e] = (int)qf;
         }
