@@ -168,7 +168,9 @@ __global__ __launch_bounds__(256) void sumsq_kernel(const float* A, int64_t rows
 __device__ __forceinline__ float rint_div(float x, float scale, float rscale) {
     float q = x * rscale;
     const float aq = fabsf(q);
-    if (!(aq < 200.f) || fabsf(aq - floorf(aq) - 0.5f) < 1e-4f) q = x / scale;   // also: reciprocal of a denormal scale
+    const bool near = !(aq < 200.f) || fabsf(aq - floorf(aq) - 0.5f) < 1e-4f;   // also: reciprocal of a denormal scale
+    // a wave-uniform branch, so that the division is really skipped and not just masked
+    if (__builtin_amdgcn_ballot_w64(near) != 0) q = near ? x / scale : q;
     return rintf(q);
 }
 
@@ -199,8 +201,8 @@ __global__ __launch_bounds__(NT) void rtn_kernel(const float* __restrict__ W, in
         for (int e = 0; e < 8; ++e) v[u][e] = 0.f;
         if (c < n) {
             if (vec_ok) {
-                const f32x4_t x0 = __builtin_nontemporal_load((const f32x4_t*)(wrow + c));
-                const f32x4_t x1 = __builtin_nontemporal_load((const f32x4_t*)(wrow + c + 4));
+                const f32x4_t x0 = *(const f32x4_t*)(wrow + c);
+                const f32x4_t x1 = *(const f32x4_t*)(wrow + c + 4);
                 v[u][0] = x0.x; v[u][1] = x0.y; v[u][2] = x0.z; v[u][3] = x0.w;
                 v[u][4] = x1.x; v[u][5] = x1.y; v[u][6] = x1.z; v[u][7] = x1.w;
             } else {
@@ -352,7 +354,10 @@ __global__ __launch_bounds__(NT) void act_rtn_kernel(const void* __restrict__ X,
                 for (int e = 0; e < 8; ++e) mm[e] = (c + e < n) ? mdiag[c + e] : 1.f;
             }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[u][e] = (mm[e] == 1.f) ? v[u][e] : v[u][e] / mm[e];   // x / 1 = x exactly
+            for (int e = 0; e < 8; ++e) {
+                const bool scaled = mm[e] != 1.f;                                        // x / 1 = x exactly
+                if (__builtin_amdgcn_ballot_w64(scaled) != 0) v[u][e] = scaled ? v[u][e] / mm[e] : v[u][e];
+            }
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[u][e]));
@@ -385,6 +390,81 @@ __global__ __launch_bounds__(NT) void act_rtn_kernel(const void* __restrict__ X,
             for (int e = 0; e < 8; ++e)
                 if (c + e < n) crow[c + e] = (int8_t)q[e];
         }
+    }
+}
+
+// Tokens of at most 4096 channels (16-byte aligned rows, n % 16 == 0): one wavefront per token, 4 groups
+// of 16 channels per lane (32 bytes of bf16 in, 16 bytes of codes out), all loads of a token in
+// flight at once, absmax by lane shuffles: no LDS and no barrier.  Four tokens per workgroup.
+template <bool BF16>
+__global__ __launch_bounds__(256) void act_rtn_wave_kernel(const void* __restrict__ X, int64_t rows, int64_t n, int64_t ldx,
+                                                           const float* __restrict__ mdiag, float qmax,
+                                                           int8_t* __restrict__ codes, float* __restrict__ scales) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const char* xrow = (const char*)X + row * ldx * (BF16 ? 2 : 4);
+    float v[4][16];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t c = ((int64_t)u * 64 + lane) * 16;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) v[u][e] = 0.f;
+        if (c >= n) continue;
+        if (BF16) {
+            const u32x4_t w0 = *(const u32x4_t*)(xrow + c * 2), w1 = *(const u32x4_t*)(xrow + c * 2 + 16);
+            const uint32_t ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                v[u][2 * e] = __uint_as_float(ww[e] << 16);
+                v[u][2 * e + 1] = __uint_as_float(ww[e] & 0xFFFF0000u);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4_t x = *(const f32x4_t*)(xrow + c * 4 + 16 * q);
+                v[u][4 * q] = x.x; v[u][4 * q + 1] = x.y; v[u][4 * q + 2] = x.z; v[u][4 * q + 3] = x.w;
+            }
+        }
+    }
+    float amax = 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t c = ((int64_t)u * 64 + lane) * 16;
+        if (c >= n) continue;
+        if (mdiag) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 m4 = *(const float4*)(mdiag + c + 4 * q);
+                const float mm[4] = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool scaled = mm[e] != 1.f;                                    // x / 1 = x exactly
+                    if (__builtin_amdgcn_ballot_w64(scaled) != 0) v[u][4 * q + e] = scaled ? v[u][4 * q + e] / mm[e] : v[u][4 * q + e];
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) amax = fmaxf(amax, fabsf(v[u][e]));
+    }
+    amax = wave_max(amax);
+    const float scale = (amax == 0.f) ? 1.f : amax / qmax;
+    const float rscale = __builtin_amdgcn_rcpf(scale);
+    if (lane == 0) scales[row] = scale;
+    int8_t* crow = codes + row * n;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t c = ((int64_t)u * 64 + lane) * 16;
+        if (c >= n) continue;
+        uint32_t pk[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            float qf = rint_div(v[u][e], scale, rscale);
+            qf = fminf(fmaxf(qf, -qmax), qmax);
+            pk[e >> 2] |= (uint32_t)((int)qf & 0xFF) << (8 * (e & 3));
+        }
+        const u32x4_t pkv = {pk[0], pk[1], pk[2], pk[3]};
+        __builtin_nontemporal_store(pkv, (u32x4_t*)(crow + c));
     }
 }
 
@@ -503,6 +583,17 @@ extern "C" int aser_quantize_act_rtn(aser_ctx* ctx, const void* X, int x_dtype, 
         else if (groups <= 1024 * 2) ASER_ACT_LAUNCH(B, 2, 1024);\
         else ASER_ACT_LAUNCH(B, 4, 1024);                        \
     } while (0)
+    const int esz = (x_dtype == ASER_DTYPE_BF16) ? 2 : 4;
+    const bool wave_ok = n <= 4096 && (n & 15) == 0 && ((uintptr_t)X & 15) == 0 && ((ldx * esz) & 15) == 0 &&
+                         ((uintptr_t)codes & 15) == 0 && (!mdiag || ((uintptr_t)mdiag & 15) == 0);
+    if (wave_ok) {
+        dim3 wgrid((unsigned)ceil_div64(rows, 4));
+        if (x_dtype == ASER_DTYPE_BF16)
+            hipLaunchKernelGGL(act_rtn_wave_kernel<true>, wgrid, dim3(256), 0, ctx->stream, X, rows, n, ldx, mdiag, qmax, codes, scales);
+        else
+            hipLaunchKernelGGL(act_rtn_wave_kernel<false>, wgrid, dim3(256), 0, ctx->stream, X, rows, n, ldx, mdiag, qmax, codes, scales);
+        return aser_check_launch(ctx, "act_rtn");
+    }
     if (x_dtype == ASER_DTYPE_BF16) ASER_ACT_PICK(true);
     else ASER_ACT_PICK(false);
 #undef ASER_ACT_PICK

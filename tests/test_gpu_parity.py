@@ -174,7 +174,8 @@ def test_quantize_rtn(name, spec, bits, packed):
 
 
 ACT_CASES = [("bf16", synth.mini("a1", 8, 333, 70, f=5)), ("f32", synth.mini("a2", 8, 520, 33, x_dtype="f32", f=3)),
-             ("wide_bf16", synth.mini("a3", 8, 4096, 16, f=8))]
+             ("wide_bf16", synth.mini("a3", 8, 4096, 16, f=8)), ("wave_ragged_bf16", synth.mini("a4", 8, 1000, 37, f=6)),
+             ("wave_f32", synth.mini("a5", 8, 2048, 9, x_dtype="f32", f=4)), ("very_wide_bf16", synth.mini("a6", 8, 14336, 5, f=8))]
 
 
 @pytest.mark.parametrize("name,spec", ACT_CASES, ids=[c[0] for c in ACT_CASES])
