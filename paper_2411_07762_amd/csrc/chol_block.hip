@@ -7,7 +7,8 @@
 //   1. one wavefront factors the 32 x 32 diagonal sub-block A_kk with the sub-block and an identity
 //      next to it held in two 32 x 32 MFMA accumulators.  Pivot j: reciprocal square root of the
 //      diagonal entry, row j scaled (that is row j of R_kk and, in the second accumulator, row j of
-//      L_kk^-1 with R_kk = L_kk^T), then one rank-1 MFMA update per accumulator.  An accumulator
+//      L_kk^-1 with R_kk = L_kk^T), then one rank-1 MFMA update per accumulator (the next row is
+//      updated by plain FMAs on a copy, so the pivot chain does not wait for the MFMAs).  An accumulator
 //      register holds row j in one half of the lanes and row j +- 4 in the other; the MFMA's second
 //      k-slot takes a zero multiplier for that half, so no lane exchange is needed.
 //   2. everyone, 16 x 16 MFMA tiles: row panel R[k, right] = L_kk^-1 A[k, right] and, for the
@@ -95,24 +96,50 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
             // LDS targets of this lane's row / column stores; the half of the lanes that holds another
             // row in the same register writes to a scratch word instead (no exec-mask changes in the chain)
             float* const dummy = Ys + 96 * kPY + lane;
+            // One row of look-ahead keeps the MFMA latency out of the pivot chain: update j leaves row
+            // j + 1 to two plain FMAs on a copy taken from the accumulators before the MFMAs of step j
+            // are issued (their multiplier for that row is zero), so pivot j + 1 depends on pivot j
+            // through a handful of VALU operations only, and the MFMAs run behind.
+            float x1 = a1[0], x2 = a2[0];             // row j of both accumulators, all updates applied
 #pragma unroll
             for (int j = 0; j < kSub; ++j) {
-                const int e = 4 * (j / 8) + j % 4, hj = (j / 4) & 1;
-                const float piv = lane_bcast(a1[e], 32 * hj + j);
+                const int hj = (j / 4) & 1;
+                const int en = 4 * ((j + 1) / 8) + (j + 1) % 4;                    // register of row j + 1
+                float y1 = 0.f, y2 = 0.f;
+                if (j + 1 < kSub) {                                               // updates < j applied
+                    // explicit early copies: read lazily, these elements would keep the old accumulator
+                    // tuples alive and every VALU access to them would wait for the MFMA in flight
+                    asm volatile("v_mov_b32 %0, %1" : "=v"(y1) : "v"(a1[en]));
+                    asm volatile("v_mov_b32 %0, %1" : "=v"(y2) : "v"(a2[en]));
+                }
+                const float piv = lane_bcast(x1, 32 * hj + j);
                 const bool ok = piv > 0.f;
                 bad = ok ? bad : (bad < j ? bad : j);
                 const float rs = __builtin_amdgcn_rsqf(ok ? piv : 1.f);   // 1 ulp: as good as the fp32 data it scales
-                // The update of the first accumulator is issued before the second one is touched:
-                // the next pivot only waits for the first.
-                const float rv = a1[e] * rs;
-                const float mult = (h == hj) ? -rv : 0.f;
-                if (j + 1 < kSub) a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, rv, a1, 0, 0, 0);
+                // Instruction order matters (one wave, in-order issue): the wave stalls at an MFMA
+                // until the pipe accepts it, so the scalar work of the chain is placed behind the first
+                // MFMA of the step and the work on the second accumulator behind the second.
+                const float rv = x1 * rs;
+                const float mult = (h == hj && col != j + 1) ? -rv : 0.f;
+                if (j + 2 < kSub) a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, rv, a1, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                const float lv = a2[e] * rs;
-                if (j + 1 < kSub) a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, lv, a2, 0, 0, 0);
+                float m = 0.f;
+                if (j + 1 < kSub) {
+                    m = lane_bcast(rv, 32 * hj + j + 1);                           // r_j[j + 1]
+                    // row j + 1 sits in the other half of the lanes when j + 1 starts a new group of four
+                    const float rvn = (j % 4 == 3) ? __shfl_xor(rv, 32, 64) : rv;
+                    x1 = fmaf(-m, rvn, y1);
+                }
                 *((h == hj) ? As + (o + j) * kP + o + col : dummy) = rv;   // row j of R_kk (left of the diagonal: dead)
-                *((h == hj) ? Xs + (o + col) * kP + o + j : dummy) = lv;   // X_kk = (L_kk^-1)^T
+                const float lv = x2 * rs;
                 __builtin_amdgcn_sched_barrier(0);
+                if (j + 2 < kSub) a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(mult, lv, a2, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (j + 1 < kSub) {
+                    const float lvn = (j % 4 == 3) ? __shfl_xor(lv, 32, 64) : lv;
+                    x2 = fmaf(-m, lvn, y2);
+                }
+                *((h == hj) ? Xs + (o + col) * kP + o + j : dummy) = lv;   // X_kk = (L_kk^-1)^T
             }
             if (bad < kSub && lane == 0 && o + bad < b && info) atomicMin(info, pivot_base + o + bad + 1);
         }
