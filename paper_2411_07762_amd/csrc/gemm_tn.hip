@@ -290,41 +290,39 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t
     for (int j = 0; j < TN; ++j) offb[j] = (lane >> 5) * BN + swz(wn0 + 32 * j + (lane & 31));
 
     const int64_t steps = (kEnd - kBeg + BK - 1) / BK;
-    // The 256 x 256 tile has no registers left for a second set: one step of loads in flight.
-    constexpr bool TWO_SETS = !(BM == 256 && BN == 256);
+    // Register sets for global loads in flight: the 256 x 256 tile has room for one step only, the
+    // smaller tiles keep two steps in flight (four were measured and change nothing: their calls are
+    // bound by the operand stream, 6 TB/s summed over the workgroups, not by its latency).
+    constexpr int NSETS = (BM == 256 && BN == 256) ? 1 : 2;
+    constexpr bool TWO_SETS = NSETS > 1;
     if (TWO_SETS) {
-        Staged a0, b0, a1, b1;                          // set 0 holds odd steps, set 1 even steps (>= 2)
+        Staged ra[NSETS], rb[NSETS];                    // set u holds steps u + 1, u + 1 + NSETS, ...
         if (steps > 0) {
-            fa.load(a0, kEnd);
-            fb.load(b0, kEnd);
-            fa.store(a0, smem);
-            fb.store(b0, smem + Cfg::A_CHUNKS);
-            if (steps > 1) { fa.load(a0, kEnd); fb.load(b0, kEnd); }
-            if (steps > 2) { fa.load(a1, kEnd); fb.load(b1, kEnd); }
+            fa.load(ra[0], kEnd);
+            fb.load(rb[0], kEnd);
+            fa.store(ra[0], smem);
+            fb.store(rb[0], smem + Cfg::A_CHUNKS);
+#pragma unroll
+            for (int u = 0; u < NSETS; ++u)
+                if (steps > u + 1) { fa.load(ra[u], kEnd); fb.load(rb[u], kEnd); }
         }
         __syncthreads();
-        for (int64_t s = 0; s < steps; s += 2) {
-            {   // even step: next data in set 0
-                const uint4* sa = smem;
-                uint4* da = smem + Cfg::STAGE_CHUNKS;
-                mfma_step<IN, BM, BN>(acc, sa, sa + Cfg::A_CHUNKS, offa, offb);
-                if (s + 1 < steps) {
-                    fa.store(a0, da);
-                    fb.store(b0, da + Cfg::A_CHUNKS);
-                    if (s + 3 < steps) { fa.load(a0, kEnd); fb.load(b0, kEnd); }
+        for (int64_t s0 = 0; s0 < steps; s0 += NSETS) {
+#pragma unroll
+            for (int u = 0; u < NSETS; ++u) {
+                const int64_t s = s0 + u;
+                if (s < steps) {
+                    // NSETS is even, so the LDS stage of step s is u & 1
+                    const uint4* sa = smem + (u & 1) * Cfg::STAGE_CHUNKS;
+                    uint4* da = smem + ((u + 1) & 1) * Cfg::STAGE_CHUNKS;
+                    mfma_step<IN, BM, BN>(acc, sa, sa + Cfg::A_CHUNKS, offa, offb);
+                    if (s + 1 < steps) {
+                        fa.store(ra[u], da);
+                        fb.store(rb[u], da + Cfg::A_CHUNKS);
+                        if (s + 1 + NSETS < steps) { fa.load(ra[u], kEnd); fb.load(rb[u], kEnd); }
+                    }
+                    __syncthreads();
                 }
-                __syncthreads();
-            }
-            if (s + 1 < steps) {   // odd step: next data in set 1
-                const uint4* sa = smem + Cfg::STAGE_CHUNKS;
-                uint4* da = smem;
-                mfma_step<IN, BM, BN>(acc, sa, sa + Cfg::A_CHUNKS, offa, offb);
-                if (s + 2 < steps) {
-                    fa.store(a1, da);
-                    fb.store(b1, da + Cfg::A_CHUNKS);
-                    if (s + 4 < steps) { fa.load(a1, kEnd); fb.load(b1, kEnd); }
-                }
-                __syncthreads();
             }
         }
     } else {
