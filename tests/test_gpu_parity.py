@@ -356,13 +356,17 @@ def test_headline_layer_full_size():
     run_e2e("c1_full", spec, True)
 
 
-def test_large_mlp_layer_full_size_sampled():
-    """The 4096 x 11008 layer with 65536 tokens of heavy-tailed activations, at full size.  The oracle's
-    SVD of that layer takes minutes, so each stage is checked on samples the oracle computes one by one
-    (Gram entries, statistics, RTN rows) or through identities that hold at any size (S S^T = G',
-    reported error = whitened error recomputed from the returned factors, Eq. 8)."""
-    spec = synth.CONFIGS["c2"]
-    say("c2 full size m=%d n=%d N=%d r=%d f=%d" % (spec.m, spec.n, spec.tokens, spec.r, spec.f))
+@pytest.mark.parametrize("cfg", ["c2", "c3.gate", "c3.k"])
+def test_large_layers_full_size_sampled(cfg):
+    """Full-size layers whose oracle SVD takes minutes: the 4096 x 11008 layer with 65536 tokens of
+    heavy-tailed activations, and two layers of the Llama-3-8B-shaped block with 131072 tokens (the
+    tall 14336 x 4096 gate projection and the flat 1024 x 4096 key projection).  Each stage is checked
+    on samples the oracle computes one by one (Gram entries, statistics, RTN rows) or through
+    identities that hold at any size (S S^T = G', reported error = whitened error recomputed from the
+    returned factors, Eq. 8), and the error against the optimum from the spectrum of the smaller Gram
+    matrix of A = T S."""
+    spec = synth.CONFIGS[cfg]
+    say("%s full size m=%d n=%d N=%d r=%d f=%d" % (cfg, spec.m, spec.n, spec.tokens, spec.r, spec.f))
     rng = np.random.default_rng(7)
     W = synth.make_weight(spec)
     x_np = synth.make_activations(spec)
@@ -370,7 +374,7 @@ def test_large_mlp_layer_full_size_sampled():
     buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, True)
     aser.calibrate_layer(ctx, torch.from_numpy(W).to(DEV), to_dev_x(spec, x_np), buf)
     torch.cuda.synchronize()
-    say("c2: device path done, err=%.6g" % buf.err)
+    say("%s: device path done, err=%.6g" % (cfg, buf.err))
 
     # statistics of all channels (fp64, chunked) and the smoothing decision
     abs_ref = np.zeros(spec.n)
@@ -384,6 +388,7 @@ def test_large_mlp_layer_full_size_sampled():
     # Gram entries: pairs of channels across tiles, the last tile, planted outliers and the diagonal
     planted, _ = synth.outlier_channels(spec)
     cols = np.unique(np.concatenate([rng.integers(0, spec.n, 20), [0, 255, 256, spec.n - 1, spec.n - 256], planted[:4]]))
+    cols = cols[(cols >= 0) & (cols < spec.n)]
     Xs = synth.bf16_to_f32(x_np[:, cols])
     G_ref, _, _ = orc.gram(Xs)
     G = buf.G.cpu().numpy()
@@ -416,16 +421,16 @@ def test_large_mlp_layer_full_size_sampled():
     L_B = buf.L_B.cpu().numpy()
     sigma = buf.sigma.cpu().numpy().astype(np.float64)
     e = orc.whitened_error(T, S, L_A, L_B)
-    say("c2: whitened error recomputed %.6g reported %.6g rel %.2e" % (e, buf.err, abs(e - buf.err) / e))
+    say("%s: whitened error recomputed %.6g reported %.6g rel %.2e" % (cfg, e, buf.err, abs(e - buf.err) / e))
     assert abs(e - buf.err) / e <= 1e-4
     A = T @ S
     e0 = float(np.linalg.norm(A))
     assert e < e0
     # the optimum itself, from the spectrum of the smaller Gram matrix: sigma_i^2 = eig_i(A A^T)
-    lam = np.linalg.eigvalsh(A @ A.T)[::-1]
+    lam = np.maximum(np.linalg.eigvalsh(A @ A.T if spec.m <= spec.n else A.T @ A)[::-1], 0.0)
     e_opt = float(np.sqrt(np.sum(lam[spec.r:])))
-    say("c2: optimal whitened error %.6g, device %.6g, rel %.2e; sigma_r/sigma_r+1 = %.4f" %
-        (e_opt, e, (e - e_opt) / e_opt, np.sqrt(lam[spec.r - 1] / lam[spec.r])))
+    say("%s: optimal whitened error %.6g, device %.6g, rel %.2e; sigma_r/sigma_r+1 = %.4f" %
+        (cfg, e_opt, e, (e - e_opt) / e_opt, np.sqrt(lam[spec.r - 1] / lam[spec.r])))
     assert 0.0 <= (e - e_opt) / e_opt + 1e-9 and (e - e_opt) / e_opt <= 1e-4
     assert np.allclose(sigma[:spec.f], np.sqrt(lam[:spec.f]), rtol=1e-3)
     del A
