@@ -356,11 +356,12 @@ def test_headline_layer_full_size():
     run_e2e("c1_full", spec, True)
 
 
-@pytest.mark.parametrize("cfg", ["c2", "c3.gate", "c3.k"])
+@pytest.mark.parametrize("cfg", ["c2", "c3.gate", "c3.k", "c3.down"])
 def test_large_layers_full_size_sampled(cfg):
     """Full-size layers whose oracle SVD takes minutes: the 4096 x 11008 layer with 65536 tokens of
     heavy-tailed activations, and two layers of the Llama-3-8B-shaped block with 131072 tokens (the
-    tall 14336 x 4096 gate projection and the flat 1024 x 4096 key projection).  Each stage is checked
+    tall 14336 x 4096 gate projection, the flat 1024 x 4096 key projection and the 4096 x 14336 down
+    projection).  Each stage is checked
     on samples the oracle computes one by one (Gram entries, statistics, RTN rows) or through
     identities that hold at any size (S S^T = G', reported error = whitened error recomputed from the
     returned factors, Eq. 8), and the error against the optimum from the spectrum of the smaller Gram
