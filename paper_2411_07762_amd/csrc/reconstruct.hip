@@ -137,7 +137,7 @@ __global__ void ritz_factors_kernel(const float* lambda, const float* Uhat, int 
 struct Plan {
     int b, iters;
     uint32_t seed;
-    size_t off_big0, off_big1, off_tall, tall_bytes, off_small, total;
+    size_t off_big0, off_big1, off_big2, off_tall, tall_bytes, off_small, total;
 };
 
 int default_block(int r) {
@@ -155,8 +155,9 @@ int make_plan(int64_t m, int64_t n, int r, const aser_svd_opts* o, Plan* p) {
     p->seed = (o && o->seed) ? o->seed : 1u;
     const int64_t mx = m > n ? m : n;
     size_t off = 0;
-    p->off_big0 = off; off += align_up((size_t)m * n * 4, 256);        // T^T, later A^T
+    p->off_big0 = off; off += align_up((size_t)m * n * 4, 256);        // T^T
     p->off_big1 = off; off += align_up((size_t)m * n * 4, 256);        // A
+    p->off_big2 = off; off += align_up((size_t)m * n * 4, 256);        // A^T
     // five tall blocks (three on the Q side, two on the Z side) that change roles by pointer swap
     p->tall_bytes = align_up((size_t)mx * p->b * 4, 256);
     p->off_tall = off; off += 5 * p->tall_bytes;
@@ -235,8 +236,9 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
 
     char* ws = (char*)ctx->ws;
     const int b = p.b;
-    float* big0 = (float*)(ws + p.off_big0);     // T^T (n x m), later A^T (n x m)
+    float* big0 = (float*)(ws + p.off_big0);     // T^T (n x m)
     float* A = (float*)(ws + p.off_big1);        // m x n
+    float* At = (float*)(ws + p.off_big2);       // A^T (n x m), written by the same product as A
     float* tall[5];
     for (int i = 0; i < 5; ++i) tall[i] = (float*)(ws + p.off_tall + i * p.tall_bytes);   // max(m, n) x b each
     char* sm = ws + p.off_small;
@@ -258,11 +260,11 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     float* WBt = (float*)(sm + 3 * bb + 8192 + b128);
     float* refl = (float*)(sm + 3 * bb + 8192 + 2 * b128);
 
-    // A = T S through T^T (K-major operand), A^T
+    // A = T S through T^T (K-major operand); the product's epilogue also writes A^T
     ASER_TRY(aser_transpose_f32(ctx, T, m, n, ldt, big0, m));
     {
         GemmArgs g{};
-        g.A = big0; g.lda = m; g.B = S; g.ldb = lds; g.C = A; g.ldc = n; g.Ct = nullptr; g.ldct = 0;
+        g.A = big0; g.lda = m; g.B = S; g.ldb = lds; g.C = A; g.ldc = n; g.Ct = At; g.ldct = m;
         g.M = m; g.N = n; g.K = n; g.alpha = 1.f;
         g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_STORE; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_GE_COL;
         g.k_parts = 1;
@@ -271,8 +273,6 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     }
     ASER_TRY(aser_fill_bytes(ctx, normA2, 8));
     ASER_TRY(aser_fill_bytes(ctx, info, 4));
-    ASER_TRY(aser_transpose_f32(ctx, A, m, n, n, big0, m));
-    float* At = big0;
 
     // start block and subspace iteration with momentum
     float *Qcur = tall[0], *Qold = tall[1], *Qacc = tall[2];   // Q_k, Q_{k-1} (or spare), accumulation target
