@@ -128,7 +128,7 @@ constexpr int kGsPitch = 132;
 
 __global__ __launch_bounds__(256) void gemm_small_kernel(float* __restrict__ A, int64_t lda, const float* __restrict__ B,
                                                          int64_t ldb, float* __restrict__ C, int64_t ldc, int64_t rows,
-                                                         int k, int c, int64_t clear_rows, int vec_b) {
+                                                         int k, int c, int64_t clear_rows, int vec_b, int transposed) {
     extern __shared__ __align__(16) float gs_sm[];
     float* As = gs_sm;                          // [16][132]
     float* Bs = gs_sm + kGsRows * kGsPitch;     // [128][132]
@@ -200,7 +200,10 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(float* __restrict__ A, 
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int cc = 8 * tx + j;
-            if (cc < c) C[gr * ldc + cc] = acc[j];
+            if (cc < c) {
+                if (transposed) C[(int64_t)cc * ldc + gr] = acc[j];      // C^T (c x rows, ld = ldc)
+                else C[gr * ldc + cc] = acc[j];
+            }
         }
     }
 }
@@ -220,7 +223,7 @@ int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float*
 }
 
 int aser_gemm_small_f32(aser_ctx* ctx, float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
-                        int64_t rows, int k, int c, int64_t clear_rows) {
+                        int64_t rows, int k, int c, int64_t clear_rows, bool transposed) {
     if (rows <= 0) return ASER_OK;
     if (k <= 0 || c <= 0 || k > 128 || c > 128 || (k & 3)) ASER_FAIL(ctx, ASER_ERR_SHAPE, "gemm_small: need 0 < k, c <= 128, k % 4 == 0");
     if (((uintptr_t)A & 15) || (lda & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_small: A must be 16-byte aligned with lda % 4 == 0");
@@ -233,6 +236,6 @@ int aser_gemm_small_f32(aser_ctx* ctx, float* A, int64_t lda, const float* B, in
     }
     const int64_t cover = rows > clear_rows ? rows : clear_rows;
     hipLaunchKernelGGL(gemm_small_kernel, dim3((unsigned)ceil_div64(cover, kGsRows)), dim3(256), lds, ctx->stream, A, lda, B, ldb,
-                       C, ldc, rows, k, c, clear_rows, vec_b);
+                       C, ldc, rows, k, c, clear_rows, vec_b, transposed ? 1 : 0);
     return aser_check_launch(ctx, "gemm_small");
 }

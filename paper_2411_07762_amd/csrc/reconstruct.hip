@@ -317,13 +317,11 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     // Whitened error of Eq. 8 as an explicit residual: A <- A - U_r (U_r^T A), then ||A||_F.
     // U_r^T A = (Z Uhat_r)^T with Z = A^T Q; the subtraction form avoids the cancellation of
     // ||A||^2 - sum sigma_i^2 when the top singular values carry almost all of the norm.
-    ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, Uhat, b, tp, r, n, b, r));            // V_r Sigma_r  (n x r)
-    ASER_TRY(aser_transpose_f32(ctx, tp, n, r, r, L_B, n));                        // (r x n), parked in L_B
-    ASER_TRY(aser_gemm_small_f32(ctx, Qp, b, Uhat, b, tp, r, m, b, r));            // U_r  (m x r)
-    ASER_TRY(aser_transpose_f32(ctx, tp, m, r, r, Zp, m));                         // U_r^T (r x m)
+    ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, Uhat, b, L_B, n, n, b, r, 0, true));  // (V_r Sigma_r)^T (r x n), parked in L_B
+    ASER_TRY(aser_gemm_small_f32(ctx, Qp, b, Uhat, b, tp, m, m, b, r, 0, true));   // U_r^T (r x m)
     {
         GemmArgs g{};
-        g.A = Zp; g.lda = m; g.B = L_B; g.ldb = n; g.C = A; g.ldc = n; g.Ct = nullptr; g.ldct = 0;
+        g.A = tp; g.lda = m; g.B = L_B; g.ldb = n; g.C = A; g.ldc = n; g.Ct = nullptr; g.ldct = 0;
         g.M = m; g.N = n; g.K = r; g.alpha = -1.f;
         g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_RMW; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
         g.k_parts = 1;
@@ -335,8 +333,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     ASER_TRY(aser_gemm_small_f32(ctx, Qp, b, WA, r, L_A, r, m, b, r));
     // L_B^T = (T^T Q) (Uhat_r Sigma_r^-1)  ->  L_B
     ASER_TRY(gemm_tn_atomic(ctx, T, ldt, Qp, b, Zp, b, n, b, m, bmA, bnB, true));  // C^T = T^T Q (n x b)
-    ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, WBt, r, tp, r, n, b, r));             // n x r
-    ASER_TRY(aser_transpose_f32(ctx, tp, n, r, r, L_B, n));
+    ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, WBt, r, L_B, n, n, b, r, 0, true));   // (n x r)^T = L_B
 
     double h_res2 = 0.0;
     ASER_HIP(ctx, hipMemcpyAsync(&h_res2, normA2, 8, hipMemcpyDeviceToHost, ctx->stream));
