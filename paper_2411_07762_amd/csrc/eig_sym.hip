@@ -1,7 +1,8 @@
 // Symmetric eigen-solver for the Rayleigh-Ritz step of the truncated SVD (Eq. 6): all eigenpairs
 // of a b x b matrix (b <= 128), eigenvalues descending.  Two kernels:
 //
-//   tridiag_kernel   one workgroup, the matrix lives in registers (2 x 8 elements per thread).
+//   tridiag_kernel   one workgroup of 256 threads, the matrix lives in registers (8 x 8 elements per
+//                    thread, rows and columns dealt cyclically).
 //                    Householder tridiagonalisation M = Q T Q^T in fp32: per reflector one
 //                    mat-vec reduced along 16-lane DPP rows, one rank-2 update, two barriers.
 //   ritz_pair_kernel one wavefront per eigenvalue, b wavefronts spread over the chip.  In fp64:
@@ -14,6 +15,8 @@
 // the largest eigenvalue; in fp64 the vectors of distinct eigenvalues come out orthogonal to about
 // 1e-16 / relative gap.  If two eigenvalues are closer than 1e-8 of the spectral radius a flag is
 // raised instead and the caller runs the Jacobi solver, which does not care about clusters.
+#include <type_traits>
+
 #include "aser_internal.h"
 
 namespace {
@@ -41,42 +44,54 @@ __device__ __forceinline__ float wave_sum(float v) {
            (__int_as_float(__builtin_amdgcn_readlane(iv, 32)) + __int_as_float(__builtin_amdgcn_readlane(iv, 48)));
 }
 
-// Thread t holds rows 2 (t >> 4) + {0, 1} and columns 8 (t & 15) + {0..7}: the 16 lanes of a DPP
-// row share their two matrix rows, so the mat-vec reduction never leaves the row.
-__global__ __launch_bounds__(1024) void tridiag_kernel(const float* __restrict__ Mb, int b, float* __restrict__ refl /* [k][128] */,
-                                                       float* __restrict__ tri /* d | e | tau, 128 each */,
-                                                       int* __restrict__ cluster_flag) {
+// 256 threads in a 16 x 16 grid, thread (ti, tj) holds a[s][c] = A[ti + 16 s][tj + 16 c], s, c = 0..7.
+// The 16 lanes of a DPP row share their matrix rows, so the mat-vec reduction never leaves the row,
+// and the cyclic layout lets every thread skip the slots that lie wholly inside the finished part
+// (the work shrinks with the trailing block).  Vectors live in LDS in the same cyclic order
+// (element i at (i % 16) * 8 + i / 16) so that a thread reads its 8 values as two float4.
+__device__ __forceinline__ int cyc(int i) { return (i & 15) * 8 + (i >> 4); }
+
+__global__ __launch_bounds__(256) void tridiag_kernel(const float* __restrict__ Mb, int b, float* __restrict__ refl /* [k][128] */,
+                                                      float* __restrict__ tri /* d | e | tau, 128 each */,
+                                                      int* __restrict__ cluster_flag) {
     // Everything the loop produces stays in LDS until the end: a global store inside the loop
     // would have to drain before each barrier.
     extern __shared__ __align__(16) float sm[];
-    float (*xc)[kB] = (float (*)[kB])sm;        // [2][kB] column k of the current matrix, double-buffered
-    float* pb = sm + 2 * kB;
+    float (*xc)[kB] = (float (*)[kB])sm;        // [2][kB] column k of the current matrix (cyclic order), double-buffered
+    float* pb = sm + 2 * kB;                    // tau * A v (cyclic order)
     float* td = pb + kB;
     float* te = td + kB;
     float* tt = te + kB;
-    float* rs = tt + kB;                        // [b - 2][kB] reflectors
+    float* rs = tt + kB;                        // [b - 2][kB] reflectors (natural order)
     const int tid = threadIdx.x, lane = tid & 63;
-    const int r0 = 2 * (tid >> 4), c0 = 8 * (tid & 15);
+    const int ti = tid >> 4, tj = tid & 15;
 
-    float a[2][8];
+    float a[8][8];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int s = 0; s < 8; ++s)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int r = r0 + i, c = c0 + j;
-            a[i][j] = (r < b && c < b) ? 0.5f * (Mb[r * b + c] + Mb[c * b + r]) : 0.f;
+        for (int c = 0; c < 8; ++c) {
+            // unconditional loads from clamped indices: all 128 of a thread are in flight together
+            const int r = ti + 16 * s, q = tj + 16 * c;
+            const int rc = r < b ? r : b - 1, qc = q < b ? q : b - 1;
+            const float lo = Mb[rc * b + qc], up = Mb[qc * b + rc];
+            a[s][c] = (r < b && q < b) ? 0.5f * (lo + up) : 0.f;
         }
     if (tid == 0) *cluster_flag = 0;
     if (tid < kB) { td[tid] = 0.f; te[tid] = 0.f; tt[tid] = 0.f; }
-    if (c0 == 0) { xc[0][r0] = a[0][0]; xc[0][r0 + 1] = a[1][0]; }
+    if (tj == 0) {
+        *(float4*)(xc[0] + 8 * ti) = make_float4(a[0][0], a[1][0], a[2][0], a[3][0]);
+        *(float4*)(xc[0] + 8 * ti + 4) = make_float4(a[4][0], a[5][0], a[6][0], a[7][0]);
+    }
     __syncthreads();
 
     for (int k = 0; k + 2 < b; ++k) {
         const float* cur = xc[k & 1];
-        // reflector k annihilates A[k+2.., k]
+        // reflector k annihilates A[k+2.., k]; lane l looks at cyclic positions l and l + 64
+        const int i0 = ((lane >> 3) & 15) + 16 * (lane & 7), i1 = i0 + 8;      // natural indices of those positions
         const float x0 = cur[lane], x1 = cur[lane + 64];
-        const float alpha = cur[k + 1];
-        const float sigma = wave_sum(((lane > k + 1) ? x0 * x0 : 0.f) + ((lane + 64 > k + 1) ? x1 * x1 : 0.f));
+        const float alpha = cur[cyc(k + 1)];
+        const float sigma = wave_sum(((i0 > k + 1) ? x0 * x0 : 0.f) + ((i1 > k + 1) ? x1 * x1 : 0.f));
         float beta = alpha, tk = 0.f, scal = 0.f;
         if (sigma > 1e-30f * alpha * alpha && sigma > 0.f) {
             beta = -copysignf(sqrtf(alpha * alpha + sigma), alpha);
@@ -84,75 +99,114 @@ __global__ __launch_bounds__(1024) void tridiag_kernel(const float* __restrict__
             scal = 1.0f / (alpha - beta);
         }
         auto vat = [&](int idx, float x) { return (idx <= k) ? 0.f : ((idx == k + 1) ? 1.f : x * scal); };
-        float vr[2], vc[8];
+        const int smin = (k + 1) >> 4;              // slots below hold only indices <= k
+        float vr[8], vc[8];
         {
-            const float2 xr = *(const float2*)(cur + r0);
-            const float4 xa = *(const float4*)(cur + c0), xb = *(const float4*)(cur + c0 + 4);
-            vr[0] = vat(r0, xr.x); vr[1] = vat(r0 + 1, xr.y);
-            vc[0] = vat(c0 + 0, xa.x); vc[1] = vat(c0 + 1, xa.y); vc[2] = vat(c0 + 2, xa.z); vc[3] = vat(c0 + 3, xa.w);
-            vc[4] = vat(c0 + 4, xb.x); vc[5] = vat(c0 + 5, xb.y); vc[6] = vat(c0 + 6, xb.z); vc[7] = vat(c0 + 7, xb.w);
-        }
-        // p = tau * A v on the trailing block (rows <= k are dead)
-        float s0 = 0.f, s1 = 0.f;
+            const float4 ra = *(const float4*)(cur + 8 * ti), rb = *(const float4*)(cur + 8 * ti + 4);
+            const float4 ca = *(const float4*)(cur + 8 * tj), cb = *(const float4*)(cur + 8 * tj + 4);
+            const float xr[8] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w};
+            const float xq[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { s0 += a[0][j] * vc[j]; s1 += a[1][j] * vc[j]; }
-        s0 = row16_sum(s0);
-        s1 = row16_sum(s1);
-        if (c0 == 0) {
-            pb[r0] = (r0 > k) ? tk * s0 : 0.f;
-            pb[r0 + 1] = (r0 + 1 > k) ? tk * s1 : 0.f;
+            for (int s = 0; s < 8; ++s) { vr[s] = vat(ti + 16 * s, xr[s]); vc[s] = vat(tj + 16 * s, xq[s]); }
         }
-        if (tid < 64) {
-            rs[k * kB + lane] = vat(lane, x0);
-            rs[k * kB + lane + 64] = vat(lane + 64, x1);
+        // p = tau * A v on the trailing block
+        float ps[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) ps[s] = 0.f;
+        // one uniform branch per step picks the body compiled for this number of finished slots
+        auto matvec = [&](auto first) {
+            constexpr int S0 = decltype(first)::value;
+#pragma unroll
+            for (int s = S0; s < 8; ++s) {
+#pragma unroll
+                for (int c = S0; c < 8; ++c) ps[s] += a[s][c] * vc[c];
+                ps[s] = row16_sum(ps[s]);
+                ps[s] = (ti + 16 * s > k) ? tk * ps[s] : 0.f;
+            }
+        };
+        switch (smin) {
+            case 0: matvec(std::integral_constant<int, 0>{}); break;
+            case 1: matvec(std::integral_constant<int, 1>{}); break;
+            case 2: matvec(std::integral_constant<int, 2>{}); break;
+            case 3: matvec(std::integral_constant<int, 3>{}); break;
+            case 4: matvec(std::integral_constant<int, 4>{}); break;
+            case 5: matvec(std::integral_constant<int, 5>{}); break;
+            case 6: matvec(std::integral_constant<int, 6>{}); break;
+            default: matvec(std::integral_constant<int, 7>{}); break;
+        }
+        if (tj == 0) {
+            *(float4*)(pb + 8 * ti) = make_float4(ps[0], ps[1], ps[2], ps[3]);
+            *(float4*)(pb + 8 * ti + 4) = make_float4(ps[4], ps[5], ps[6], ps[7]);
+#pragma unroll
+            for (int s = 0; s < 8; ++s) rs[k * kB + ti + 16 * s] = vr[s];
         }
         if (tid == 0) { te[k] = beta; tt[k] = tk; }
+        if (ti == (k & 15) && tj == (k & 15)) {
+            float dv = a[0][0];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (r0 + i == k && c0 + j == k) td[k] = a[i][j];
+            for (int s = 1; s < 8; ++s)
+                if ((k >> 4) == s) dv = a[s][s];
+            td[k] = dv;
+        }
         __syncthreads();
         // A -= v w^T + w v^T with w = p - (tau/2)(p^T v) v
-        const float kk = wave_sum(pb[lane] * vat(lane, x0) + pb[lane + 64] * vat(lane + 64, x1));
+        const float kk = wave_sum(pb[lane] * vat(i0, x0) + pb[lane + 64] * vat(i1, x1));
         const float a2 = -0.5f * tk * kk;
-        float wr[2], wc[8];
+        float wr[8], wc[8];
         {
-            const float2 pr = *(const float2*)(pb + r0);
-            const float4 pa = *(const float4*)(pb + c0), pc = *(const float4*)(pb + c0 + 4);
-            wr[0] = pr.x + a2 * vr[0]; wr[1] = pr.y + a2 * vr[1];
-            wc[0] = pa.x + a2 * vc[0]; wc[1] = pa.y + a2 * vc[1]; wc[2] = pa.z + a2 * vc[2]; wc[3] = pa.w + a2 * vc[3];
-            wc[4] = pc.x + a2 * vc[4]; wc[5] = pc.y + a2 * vc[5]; wc[6] = pc.z + a2 * vc[6]; wc[7] = pc.w + a2 * vc[7];
+            const float4 ra = *(const float4*)(pb + 8 * ti), rb = *(const float4*)(pb + 8 * ti + 4);
+            const float4 ca = *(const float4*)(pb + 8 * tj), cb = *(const float4*)(pb + 8 * tj + 4);
+            const float pr[8] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w};
+            const float pq[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
+#pragma unroll
+            for (int s = 0; s < 8; ++s) { wr[s] = pr[s] + a2 * vr[s]; wc[s] = pq[s] + a2 * vc[s]; }
         }
+        auto update = [&](auto first) {
+            constexpr int S0 = decltype(first)::value;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int s = S0; s < 8; ++s)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) a[i][j] -= vr[i] * wc[j] + wr[i] * vc[j];
+                for (int c = S0; c < 8; ++c) a[s][c] -= vr[s] * wc[c] + wr[s] * vc[c];
+        };
+        switch (smin) {
+            case 0: update(std::integral_constant<int, 0>{}); break;
+            case 1: update(std::integral_constant<int, 1>{}); break;
+            case 2: update(std::integral_constant<int, 2>{}); break;
+            case 3: update(std::integral_constant<int, 3>{}); break;
+            case 4: update(std::integral_constant<int, 4>{}); break;
+            case 5: update(std::integral_constant<int, 5>{}); break;
+            case 6: update(std::integral_constant<int, 6>{}); break;
+            default: update(std::integral_constant<int, 7>{}); break;
+        }
         // next column to the other buffer
-        if (c0 == ((k + 1) & ~7)) {
-            const int jj = (k + 1) & 7;
-            float y0 = a[0][0], y1 = a[1][0];
+        if (tj == ((k + 1) & 15)) {
+            const int cs = (k + 1) >> 4;
+            float y[8];
 #pragma unroll
-            for (int j = 1; j < 8; ++j)
-                if (jj == j) { y0 = a[0][j]; y1 = a[1][j]; }
+            for (int s = 0; s < 8; ++s) {
+                y[s] = a[s][0];
+#pragma unroll
+                for (int c = 1; c < 8; ++c)
+                    if (cs == c) y[s] = a[s][c];
+            }
             float* nxt = xc[(k + 1) & 1];
-            nxt[r0] = y0;
-            nxt[r0 + 1] = y1;
+            *(float4*)(nxt + 8 * ti) = make_float4(y[0], y[1], y[2], y[3]);
+            *(float4*)(nxt + 8 * ti + 4) = make_float4(y[4], y[5], y[6], y[7]);
         }
         __syncthreads();
     }
     // the last 2 x 2 block
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int s = 0; s < 8; ++s)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int r = r0 + i, c = c0 + j;
-            if (r == c && (r == b - 1 || r == b - 2)) td[r] = a[i][j];
-            if (r == b - 1 && c == b - 2) te[b - 2] = a[i][j];
+        for (int c = 0; c < 8; ++c) {
+            const int r = ti + 16 * s, q = tj + 16 * c;
+            if (r == q && (r == b - 1 || r == b - 2)) td[r] = a[s][c];
+            if (r == b - 1 && q == b - 2) te[b - 2] = a[s][c];
         }
     __syncthreads();
-    for (int t = tid; t < (b - 2) * kB; t += 1024) refl[t] = rs[t];
-    if (tid < 3 * kB) tri[tid] = td[tid];
+    for (int t = tid; t < (b - 2) * kB; t += 256) refl[t] = rs[t];
+    for (int t = tid; t < 3 * kB; t += 256) tri[t] = td[t];
 }
 
 __device__ __forceinline__ double fast_rcp(double q) {
@@ -327,7 +381,7 @@ int aser_tridiag_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float
         ASER_HIP(ctx, hipFuncSetAttribute((const void*)ritz_pair_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_r));
         attr_set[ctx->device] = true;
     }
-    hipLaunchKernelGGL(tridiag_kernel, dim3(1), dim3(1024), lds, ctx->stream, Mb, b, refl, tri, cluster_flag);
+    hipLaunchKernelGGL(tridiag_kernel, dim3(1), dim3(256), lds, ctx->stream, Mb, b, refl, tri, cluster_flag);
     hipLaunchKernelGGL(ritz_pair_kernel, dim3(b), dim3(64), lds_r, ctx->stream, (const float*)tri, (const float*)refl, b, lambda, V,
                        cluster_flag);
     return aser_check_launch(ctx, "tridiag_eig");
