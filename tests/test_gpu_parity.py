@@ -40,6 +40,9 @@ GRAM_CASES = [
     ("multi_tile_bf16", synth.mini("g5", 8, 1300, 4500), 1, 0),
     ("persistent_schedule_bf16", synth.mini("g7", 8, 2100, 8300), 1, 0),
     ("persistent_schedule_f32", synth.mini("g8", 8, 2100, 4200, x_dtype="f32"), 1, 4),
+    # the LDS-direct kernel (aligned bf16): channel count not a multiple of the tile, token counts not a multiple of the step
+    ("lds_direct_ragged_bf16", synth.mini("g9", 8, 2104, 8227), 1, 0),
+    ("lds_direct_ragged_chunks_pad_bf16", synth.mini("g10", 8, 2312, 17001), 2, 8),
 ]
 
 
