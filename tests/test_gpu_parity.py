@@ -141,6 +141,7 @@ RTN_CASES = [
     ("wide_int8", synth.mini("q3", 20, 9000, 64, f=32, n_outliers=8), 8, False),
     ("very_wide_int4", synth.mini("q4", 6, 28672, 32, f=64, n_outliers=8), 4, True),
     ("no_outliers", synth.mini("q5", 33, 256, 128, f=0), 4, True),
+    ("mid_width_int4", synth.mini("q6", 12, 6000, 64, f=16, n_outliers=8), 4, True),
 ]
 
 
