@@ -6,8 +6,7 @@
 
 namespace {
 
-constexpr int kSelThreads = 1024;
-constexpr int kSelPerThread = 32;           // supports n <= 32768
+constexpr int kSelMaxN = 32768;
 
 struct Cand {
     double s;
@@ -31,15 +30,13 @@ __global__ __launch_bounds__(256) void score_kernel(const double* abs_sum, const
 // One workgroup.  Every thread keeps its scores (channels tid, tid + 1024, ...) in registers with
 // its current local best; each of the f rounds is a workgroup arg-max, after which only the
 // winner's owner rescans its registers.  Then the smoothing diagonal of Eq. 11 is written.
+template <int kSelThreads, int kSelPerThread>   // kSelThreads * kSelPerThread >= n
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const double* __restrict__ score,
                                                              const double* __restrict__ abs_sum,
                                                              const int64_t* __restrict__ count, int n, int f,
                                                              int32_t* __restrict__ idx, float* __restrict__ mdiag) {
-    __shared__ double red_s[kSelThreads / 64];
-    __shared__ int red_i[kSelThreads / 64];
-    __shared__ double win_s;
-    __shared__ int win_i;
-    __shared__ double xmin_sh;
+    __shared__ double red_s[2][kSelThreads / 64];
+    __shared__ int red_i[2][kSelThreads / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     for (int i = tid; i < n; i += kSelThreads) mdiag[i] = 1.0f;
@@ -67,19 +64,18 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const double* __res
             const int i2 = __shfl_xor(i, o, 64);
             if (beats(s2, i2, s, i)) { s = s2; i = i2; }
         }
-        if (lane == 0) { red_s[wave] = s; red_i[wave] = i; }
+        // per-wave winners go to the buffer of this round's parity; every thread then finds the
+        // overall winner itself, so one barrier per round is enough
+        double* rs = red_s[round & 1];
+        int* ri = red_i[round & 1];
+        if (lane == 0) { rs[wave] = s; ri[wave] = i; }
         __syncthreads();
-        if (tid == 0) {
-            double ws = red_s[0];
-            int wi = red_i[0];
-            for (int w = 1; w < kSelThreads / 64; ++w)
-                if (beats(red_s[w], red_i[w], ws, wi)) { ws = red_s[w]; wi = red_i[w]; }
-            win_s = ws;
-            win_i = wi;
-            idx[round] = wi;
-        }
-        __syncthreads();
-        const int wi = win_i;
+        double ws = rs[0];
+        int wi = ri[0];
+#pragma unroll
+        for (int w = 1; w < kSelThreads / 64; ++w)
+            if (beats(rs[w], ri[w], ws, wi)) { ws = rs[w]; wi = ri[w]; }
+        if (tid == 0) idx[round] = wi;
         if ((wi % kSelThreads) == tid) {             // owner: retire the winner, rescan
             best_s = -1.0;
             best_i = 0x7FFFFFFF;
@@ -93,20 +89,27 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const double* __res
     }
     __syncthreads();
     if (f > 0) {
-        if (tid == 0) {
-            const double cnt = (double)(*count);
-            double xmin = abs_sum[idx[0]] / cnt;
-            for (int k = 1; k < f; ++k) {
-                const double x = abs_sum[idx[k]] / cnt;
-                xmin = x < xmin ? x : xmin;
-            }
-            xmin_sh = xmin;
-        }
-        __syncthreads();
+        // X_min over the selected channels (Eq. 11): one channel per thread (idx was written by thread 0
+        // before the barrier above), then a workgroup minimum
         const double cnt = (double)(*count);
+        double xmin = 1.0e300;
+        for (int k = tid; k < f; k += kSelThreads) {
+            const double x = abs_sum[idx[k]] / cnt;
+            xmin = x < xmin ? x : xmin;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double x2 = __shfl_xor(xmin, o, 64);
+            xmin = x2 < xmin ? x2 : xmin;
+        }
+        if (lane == 0) red_s[0][wave] = xmin;
+        __syncthreads();
+        xmin = red_s[0][0];
+#pragma unroll
+        for (int w = 1; w < kSelThreads / 64; ++w) xmin = red_s[0][w] < xmin ? red_s[0][w] : xmin;
         for (int k = tid; k < f; k += kSelThreads) {
             const int c = idx[k];
-            mdiag[c] = (float)((abs_sum[c] / cnt) / xmin_sh);
+            mdiag[c] = (float)((abs_sum[c] / cnt) / xmin);
         }
     }
 }
@@ -133,7 +136,7 @@ extern "C" int aser_smooth_outliers(aser_ctx* ctx, const float* W, int64_t m, in
     if (m <= 0 || n <= 0 || ldw < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: bad shape");
     if (f < 0 || f > n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: f must be in [0, n]");
     if (f > 0 && !idx) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: idx is null");
-    if (n > kSelThreads * kSelPerThread) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: n > 32768 is not supported");
+    if (n > kSelMaxN) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: n > 32768 is not supported");
     if (((uintptr_t)abs_sum & 7) || ((uintptr_t)count & 7) || (score && ((uintptr_t)score & 7)))
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: misaligned fp64/int64 pointer");
     const size_t need = align_up((size_t)n * 8, 256) * 2;
@@ -147,8 +150,17 @@ extern "C" int aser_smooth_outliers(aser_ctx* ctx, const float* W, int64_t m, in
     hipLaunchKernelGGL(score_kernel, dim3((unsigned)ceil_div64(n, 256)), dim3(256), 0, ctx->stream, abs_sum, count,
                        (const double*)wsum, m, n, sc);
     ASER_TRY(aser_check_launch(ctx, "score"));
-    hipLaunchKernelGGL(select_kernel, dim3(1), dim3(kSelThreads), 0, ctx->stream, (const double*)sc, abs_sum, count,
-                       (int)n, (int)f, idx, mdiag);
+    // few threads for few channels: a round costs instructions per wavefront, and every wavefront
+    // of the single workgroup repeats the same reduction
+    if (n <= 4096)
+        hipLaunchKernelGGL((select_kernel<256, 16>), dim3(1), dim3(256), 0, ctx->stream, (const double*)sc, abs_sum, count,
+                           (int)n, (int)f, idx, mdiag);
+    else if (n <= 16384)
+        hipLaunchKernelGGL((select_kernel<512, 32>), dim3(1), dim3(512), 0, ctx->stream, (const double*)sc, abs_sum, count,
+                           (int)n, (int)f, idx, mdiag);
+    else
+        hipLaunchKernelGGL((select_kernel<1024, 32>), dim3(1), dim3(1024), 0, ctx->stream, (const double*)sc, abs_sum, count,
+                           (int)n, (int)f, idx, mdiag);
     ASER_TRY(aser_check_launch(ctx, "select"));
     if (W_o && f > 0) {
         const int64_t total = m * f;
