@@ -98,8 +98,10 @@ int aser_sumsq_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols, in
 // Rinv (b x b, ld = b) <- R^-1 (upper).  b <= 128.  On a non-positive pivot at column j,
 // atomicMin(info, pivot_base + j + 1) and the factor is meaningless from that column on.  clear_d: D is overwritten with
 // zeros instead of the factor (callers that only need R^-1 and reuse D as an accumulation target).
+// Lmul / Cmul (both may be null): Cmul = alpha Lmul R^-1 for an upper triangular b x b Lmul (ld = b);
+// alpha = 1, or with_beta: alpha = -(0.9 s^2 / 2)^2 with s the smallest diagonal entry of R.
 int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base,
-                    bool clear_d = false);
+                    bool clear_d = false, const float* Lmul = nullptr, float* Cmul = nullptr, bool with_beta = false);
 // Symmetric eigen-decomposition of the b x b matrix Mb (ld = b) by cyclic Jacobi: eigenvalues
 // descending into lambda (b), eigenvectors as columns of V (b x b, ld = b).  b <= 128, b even.
 // `gate` (device, may be null): the kernel returns at once when *gate == 0.

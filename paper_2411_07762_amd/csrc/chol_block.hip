@@ -48,7 +48,8 @@ __device__ __forceinline__ f4v mma16(f4v acc, const float* pa, int sak, const fl
 }
 
 __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t ld, int b, float* Rinv, int32_t* info,
-                                                              int32_t pivot_base, int clear_d) {
+                                                              int32_t pivot_base, int clear_d, const float* Lmul,
+                                                              float* Cmul, int with_beta) {
     extern __shared__ __align__(16) float sm[];
     float* As = sm;                      // working matrix, upper triangle -> R
     float* Xs = As + kN * kP;            // R^-1 (upper), zero elsewhere
@@ -220,11 +221,62 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
             Rinv[i * b + k] = (k >= i) ? Xs[i * kP + k] : 0.f;
         }
     }
+    if (!Lmul) return;
+
+    // ---- optional: Cmul = alpha Lmul R^-1 for an upper triangular b x b Lmul (ld = b), with R^-1 still
+    // in LDS.  with_beta: alpha = -(0.9 s^2 / 2)^2, s = the smallest diagonal entry of R (the momentum
+    // coefficient of the subspace iteration); else alpha = 1.
+    __syncthreads();                                      // everyone has read R out of As
+    {
+        constexpr int kPer = kN * kN / kThreads;
+        float v[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int t = tid + u * kThreads, i = t >> 7, k = t & 127;
+            v[u] = (k >= i && k < b) ? Lmul[i * b + k] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int t = tid + u * kThreads, i = t >> 7, k = t & 127;
+            As[i * kP + k] = v[u];
+        }
+    }
+    float alpha = 1.f;
+    if (with_beta) {
+        float sdiag = 3.0e38f;
+        if (tid < b) sdiag = 1.0f / fabsf(Xs[tid * kP + tid]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sdiag = fminf(sdiag, __shfl_xor(sdiag, o, 64));
+        if (lane == 0) Ys[wave] = sdiag;
+        __syncthreads();
+        sdiag = fminf(Ys[0], Ys[1]);
+        const float hbeta = 0.45f * sdiag * sdiag;
+        alpha = -hbeta * hbeta;
+    }
+    __syncthreads();
+    // 36 upper tiles of 16 x 16, longest k range first: tile (ti, tj) needs k in [16 ti, 16 tj + 16)
+    for (int job = wave; job < 36; job += kWaves) {
+        int d = 7, first = 0;
+        while (job >= first + (8 - d)) { first += 8 - d; --d; }
+        const int ti = job - first, tj = ti + d;
+        f4v acc = {0.f, 0.f, 0.f, 0.f};
+        acc = mma16(acc, As + (16 * ti + t_i) * kP + 16 * ti + t_q, 1, Xs + (16 * ti + t_q) * kP + 16 * tj + t_i, kP, 4 * (d + 1), alpha);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = 16 * ti + 4 * t_q + e, j = 16 * tj + t_i;
+            if (i < b && j < b) Cmul[i * b + j] = acc[e];
+        }
+    }
+    for (int t = tid; t < b * b; t += kThreads) {
+        const int i = t / b, j = t % b;
+        if ((i >> 4) > (j >> 4)) Cmul[t] = 0.f;
+    }
 }
 
 }  // namespace
 
-int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base, bool clear_d) {
+int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base, bool clear_d,
+                    const float* Lmul, float* Cmul, bool with_beta) {
     if (b <= 0 || b > kN) ASER_FAIL(ctx, ASER_ERR_SHAPE, "chol_block: block size out of range");
     static bool attr_set[16] = {false};
     const size_t lds = (size_t)(2 * kN * kP + 96 * kPY + 64) * sizeof(float);
@@ -233,6 +285,6 @@ int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int
         attr_set[ctx->device] = true;
     }
     hipLaunchKernelGGL(chol_block_kernel, dim3(1), dim3(kThreads), lds, ctx->stream, D, ld, b, Rinv, info, pivot_base,
-                       clear_d ? 1 : 0);
+                       clear_d ? 1 : 0, Lmul, Cmul, with_beta ? 1 : 0);
     return aser_check_launch(ctx, "chol_block");
 }

@@ -15,8 +15,9 @@
 // In terms of the orthonormal blocks and the triangular factors of the two Cholesky-QR steps of
 // iteration k (A^T Q_k = Z R_z, then Y = Q_{k+1} R_q):
 //     Y = A Z - beta Q_{k-1} P_k R_z^-1,      P_{k+1} = R_z^-1 R_q^-1,
-// so the extra work is two products of b x b triangular matrices and one tall-times-small
-// product, which also replaces the clearing of the accumulation target.  beta = (0.9 s^2 / 2)^2
+// so the extra work is two products of b x b triangular matrices (done by the factorisation
+// kernel while R^-1 is still in LDS) and one tall-times-small product, which also replaces the
+// clearing of the accumulation target.  beta = (0.9 s^2 / 2)^2
 // with s the smallest diagonal entry of R_z: s^2 stays below the b-th eigenvalue of A A^T, which
 // keeps every wanted direction (eigenvalue above 2 sqrt(beta)) in the amplified regime.  On the
 // bulk of a quantisation-error spectrum this reaches in 10 iterations what the plain iteration
@@ -38,86 +39,6 @@ __global__ void random_block_kernel(float* Q, int64_t total, uint32_t seed) {
         const uint32_t h = mix32((uint32_t)i * 0x9E3779B9U + mix32(seed + (uint32_t)(i >> 32)));
         Q[i] = (float)(h >> 8) * (1.0f / 8388608.0f) - 1.0f;
     }
-}
-
-// C = alpha A B for upper triangular b x b matrices (ld = b, b <= 128), one workgroup of 16
-// wavefronts, fp32 MFMA: C is cut into 16 x 16 tiles, tile (ti <= tj) needs k in [16 ti, 16 tj + 16)
-// only.  Tiles are dealt to the wavefronts longest first.
-// with_beta: alpha = -beta with beta = (0.9 s^2 / 2)^2, s = min_i 1 / |B[i][i]| (B holds R_z^-1).
-typedef float tri_f4v __attribute__((ext_vector_type(4)));
-constexpr int kTriPitch = 133;
-__global__ __launch_bounds__(1024) void tri_mm_kernel(const float* __restrict__ A, const float* __restrict__ B,
-                                                      float* __restrict__ C, int b, int with_beta) {
-    extern __shared__ __align__(16) float tri_sm[];
-    float* As = tri_sm;                       // row-major, zero outside the upper triangle
-    float* Bs = tri_sm + 128 * kTriPitch;
-    __shared__ float red[16];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    {
-        // all global loads first (upper triangles only), then the LDS stores
-        float va[16], vb[16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const int t = tid + 1024 * u, i = t >> 7, k = t & 127;
-            const bool in = i < b && k < b && k >= i;
-            va[u] = in ? A[i * b + k] : 0.f;
-            vb[u] = in ? B[i * b + k] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const int t = tid + 1024 * u, i = t >> 7, k = t & 127;
-            As[i * kTriPitch + k] = va[u];
-            Bs[i * kTriPitch + k] = vb[u];
-        }
-    }
-    float alpha = 1.f;
-    if (with_beta) {
-        float s = 3.0e38f;
-        if (tid < b) s = 1.0f / fabsf(B[tid * b + tid]);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) s = fminf(s, __shfl_xor(s, o, 64));
-        if (lane == 0) red[wave] = s;
-        __syncthreads();
-        s = fminf(red[0], red[1]);
-        const float h = 0.45f * s * s;
-        alpha = -h * h;
-    }
-    __syncthreads();
-    // job j = 0..35: diagonal distance d descending (d = 7: 1 tile, d = 6: 2 tiles, ...)
-    const int t_i = lane & 15, t_q = lane >> 4;
-    for (int job = wave; job < 36; job += 16) {
-        int d = 7, first = 0;
-        while (job >= first + (8 - d)) { first += 8 - d; --d; }
-        const int ti = job - first, tj = ti + d;
-        tri_f4v acc = {0.f, 0.f, 0.f, 0.f};
-        const float* pa = As + (16 * ti + t_i) * kTriPitch + 16 * ti + t_q;
-        const float* pb = Bs + (16 * ti + t_q) * kTriPitch + 16 * tj + t_i;
-        const int nk4 = 4 * (d + 1);
-#pragma unroll 4
-        for (int q = 0; q < nk4; ++q)
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(pa[4 * q], pb[4 * q * kTriPitch], acc, 0, 0, 0);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int i = 16 * ti + 4 * t_q + e, j = 16 * tj + t_i;
-            if (i < b && j < b) C[i * b + j] = alpha * acc[e];
-        }
-    }
-    // the strictly lower tiles of C are zero
-    for (int t = tid; t < b * b; t += 1024) {
-        const int i = t / b, j = t % b;
-        if ((i >> 4) > (j >> 4)) C[t] = 0.f;
-    }
-}
-
-int tri_mm(aser_ctx* ctx, const float* A, const float* B, float* C, int b, bool with_beta) {
-    static bool attr_set[16] = {false};
-    const size_t lds = (size_t)2 * 128 * kTriPitch * sizeof(float);
-    if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
-        ASER_HIP(ctx, hipFuncSetAttribute((const void*)tri_mm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set[ctx->device] = true;
-    }
-    hipLaunchKernelGGL(tri_mm_kernel, dim3(1), dim3(1024), lds, ctx->stream, A, B, C, b, with_beta ? 1 : 0);
-    return aser_check_launch(ctx, "tri_mm");
 }
 
 // From the Ritz pairs (lambda descending, Uhat b x b): sigma_i = sqrt(lambda_i),
@@ -200,11 +121,12 @@ int gemm_tn_atomic(aser_ctx* ctx, const float* A, int64_t lda, const float* B, i
 
 // out (rows x b) = Y R^-1 with R^T R = Y^T Y (Cholesky-QR); R^-1 is left in Rinv.  Mb must be zero on
 // entry and is zero again on return.  The first clear_rows rows of Y are cleared after they have
-// been read (0: Y is left alone).
+// been read (0: Y is left alone).  Lmul / Cmul / with_beta: the factorisation kernel also leaves
+// Cmul = alpha Lmul R^-1 (see aser_chol_block); both null: nothing.
 int chol_qr(aser_ctx* ctx, float* Y, float* out, int64_t rows, int64_t clear_rows, int b, float* Mb, float* Rinv,
-            int32_t* info) {
+            int32_t* info, const float* Lmul = nullptr, float* Cmul = nullptr, bool with_beta = false) {
     ASER_TRY(gemm_tn_atomic(ctx, Y, b, Y, b, Mb, b, b, b, rows, 128, 128, false, /*upper_only=*/true));
-    ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rinv, info, 0, /*clear_d=*/true));
+    ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rinv, info, 0, /*clear_d=*/true, Lmul, Cmul, with_beta));
     return aser_gemm_small_f32(ctx, Y, b, Rinv, b, out, b, rows, b, b, clear_rows);
 }
 
@@ -290,16 +212,13 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     const int bmA = 128, bnB = 128;
     for (int it = 0; it < p.iters; ++it) {
         ASER_TRY(gemm_tn_atomic(ctx, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // A^T Q_k
-        ASER_TRY(chol_qr(ctx, Zt, Zs, n, mx, b, Mb, Rz_inv, info));                       // = Z R_z; Zt is zero again
-        if (it == 0) {
-            ASER_TRY(aser_fill_f32(ctx, Qacc, mx, b, b, 0.f));
-        } else {
-            ASER_TRY(tri_mm(ctx, Pm, Rz_inv, Bm, b, true));                               // -beta P_k R_z^-1
-            ASER_TRY(aser_gemm_small_f32(ctx, Qold, b, Bm, b, Qacc, b, m, b, b));         // momentum term
-        }
+        // = Z R_z (Zt is zero again); from the second iteration on also Bm = -beta P_k R_z^-1
+        ASER_TRY(chol_qr(ctx, Zt, Zs, n, mx, b, Mb, Rz_inv, info, it ? Pm : nullptr, it ? Bm : nullptr, true));
+        if (it == 0) ASER_TRY(aser_fill_f32(ctx, Qacc, mx, b, b, 0.f));
+        else ASER_TRY(aser_gemm_small_f32(ctx, Qold, b, Bm, b, Qacc, b, m, b, b));        // momentum term
         ASER_TRY(gemm_tn_atomic(ctx, At, m, Zs, b, Qacc, b, m, b, n, bmA, bnB, false));   // + A Z
-        ASER_TRY(chol_qr(ctx, Qacc, Qold, m, 0, b, Mb, Rq_inv, info));                    // = Q_{k+1} R_q, into the old block
-        ASER_TRY(tri_mm(ctx, Rz_inv, Rq_inv, Pm, b, false));                              // P_{k+1}
+        // = Q_{k+1} R_q, into the old block; also P_{k+1} = R_z^-1 R_q^-1
+        ASER_TRY(chol_qr(ctx, Qacc, Qold, m, 0, b, Mb, Rq_inv, info, Rz_inv, Pm, false));
         { float* t = Qold; Qold = Qcur; Qcur = t; }
     }
     ASER_TRY(chol_qr(ctx, Qcur, Qacc, m, 0, b, Mb, Rq_inv, info));                 // second pass: orthonormal to fp32
