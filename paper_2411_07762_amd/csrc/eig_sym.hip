@@ -250,7 +250,20 @@ __global__ __launch_bounds__(64) void ritz_pair_kernel(const float* __restrict__
     extern __shared__ __align__(16) float rl[];     // [b - 2][kB] reflectors, read once up front
     const int lane = threadIdx.x;
     const int m = blockIdx.x;
-    for (int t = lane; t < (b - 2) * (kB / 4); t += 64) ((float4*)rl)[t] = ((const float4*)refl)[t];
+    // the reflectors, 16 float4 per lane in flight at a time
+    for (int t0 = 0; t0 < (b - 2) * (kB / 4); t0 += 64 * 16) {
+        float4 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int t = t0 + u * 64 + lane;
+            v[u] = (t < (b - 2) * (kB / 4)) ? ((const float4*)refl)[t] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int t = t0 + u * 64 + lane;
+            if (t < (b - 2) * (kB / 4)) ((float4*)rl)[t] = v[u];
+        }
+    }
 
     double glo = 1e300, ghi = -1e300;
     for (int i = lane; i < kB; i += 64) {
