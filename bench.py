@@ -27,8 +27,8 @@ BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch at workload c1 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # 1 GiB copy (x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE); see profiles/gram_rtn_hbm_traffic.txt.
-MEASURED_TRAFFIC_C1 = {"gram": 435560 * 1024 * 2.0 + 132610 * 1024 * 1.0,
-                       "rtn": 32897 * 1024 * 2.0 + 79198 * 1024 * 1.0}
+MEASURED_TRAFFIC_C1 = {"gram": 435579 * 1024 * 2.0 + 132608 * 1024 * 1.0,
+                       "rtn": 32862 * 1024 * 2.0 + 79958 * 1024 * 1.0}
 
 
 def log(*a):
@@ -229,7 +229,7 @@ def main():
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rtn_gbs / HBM_PEAK_GBS,
                          "traffic": MEASURED_TRAFFIC_C1["rtn"] if spec.name == "c1" else None,
                          "algorithmic_bytes_per_launch": rtn_bytes, "avg_launch_ms": rtn_ms},
-        "roofline_act_quant": {"kernel": "act_rtn_kernel (per-token A8 quantizer of X M^-1)", "bound": "hbm",
+        "roofline_act_quant": {"kernel": "act_rtn_wave_kernel (per-token A8 quantizer of X M^-1)", "bound": "hbm",
                                "achieved": act_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": act_gbs / HBM_PEAK_GBS,
                                "traffic": None, "algorithmic_bytes_per_launch": act_bytes, "avg_launch_ms": act_ms},
     }
