@@ -140,24 +140,33 @@ def _x_chunk_f32(spec: LayerSpec, c: int, rows: int) -> np.ndarray:
     return x
 
 
-def make_activations(spec: LayerSpec, start: int = 0, stop: int | None = None) -> np.ndarray:
+def make_activations(spec: LayerSpec, start: int = 0, stop: int | None = None, workers: int = 1) -> np.ndarray:
     """Rows [start, stop) of X (tokens x n, row-major).
 
     Returns uint16 bf16 bit patterns when spec.x_dtype == "bf16", else fp32.
-    A chunk is always generated whole, so a row's values never depend on the range asked for.
+    A chunk is always generated whole, so a row's values never depend on the range asked for,
+    nor on `workers` (threads that draw different chunks at the same time).
     """
     stop = spec.tokens if stop is None else stop
     if not (0 <= start <= stop <= spec.tokens):
         raise ValueError("token range out of bounds")
     out = np.empty((stop - start, spec.n), dtype=np.uint16 if spec.x_dtype == "bf16" else np.float32)
-    c = start // CHUNK
-    while c * CHUNK < stop:
+
+    def fill(c):
         lo, hi = c * CHUNK, min((c + 1) * CHUNK, spec.tokens)
         x = _x_chunk_f32(spec, c, hi - lo)
         a, b = max(lo, start), min(hi, stop)
         part = x[a - lo:b - lo]
         out[a - start:b - start] = f32_to_bf16_bits(part) if spec.x_dtype == "bf16" else part
-        c += 1
+
+    chunks = range(start // CHUNK, (stop + CHUNK - 1) // CHUNK) if stop > start else range(0)
+    if workers > 1 and len(chunks) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(workers) as pool:
+            list(pool.map(fill, chunks))
+    else:
+        for c in chunks:
+            fill(c)
     return out
 
 

@@ -102,7 +102,7 @@ def main():
     W_np = synth.make_weight(spec)
     n_rot = 4                                   # rotate weight buffers so the 256 MB cache does not flatter RTN
     Ws = [torch.from_numpy(W_np).to(dev) for _ in range(n_rot)]
-    x_np = synth.make_activations(spec)
+    x_np = synth.make_activations(spec, workers=8)
     if spec.x_dtype == "bf16":
         X = torch.from_numpy(x_np.view(np.int16)).to(dev).view(torch.bfloat16)
     else:
@@ -214,7 +214,7 @@ def main():
         "dtype": "bf16" if spec.x_dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: W %dx%d fp32, X %dx%d %s, W%d per-channel RTN, r=%d, f=%d" %
                                (spec.name, spec.m, spec.n, spec.tokens, spec.n, spec.x_dtype, spec.bits, spec.r, spec.f),
-                   "svd_block": 2 * spec.r if 2 * spec.r <= 128 else 128, "svd_iters": 12 if max(spec.m, spec.n) > 8192 else 10},
+                   "svd_block": 2 * spec.r if 2 * spec.r <= 128 else 128, "svd_iters": 24 if spec.r > 64 else (12 if max(spec.m, spec.n) > 8192 else 10)},
         "layers_per_s": 1e3 / ms_per_step,
         "calibration_tokens_per_s": spec.tokens * 1e3 / ms_per_step,
         "stage_ms": {k: round(v, 4) for k, v in zip(stage_names, stage_ms)},

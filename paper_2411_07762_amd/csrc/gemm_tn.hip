@@ -578,10 +578,12 @@ int launch_gram_persistent2(aser_ctx* ctx, const GemmArgs& g) {
 // bytes.  global_load_lds_dwordx4 copies it straight into LDS: a wavefront instruction moves
 // 64 x 16 bytes to 1 KB of consecutive LDS (two slab rows), and each lane chooses which 16-byte
 // chunk of the row it fetches, which is how the layout gets its XOR swizzle: chunk c of slab row
-// k sits at chunk slot c ^ 2 (k & 3).  The MFMA operands (8 consecutive tokens of one channel
+// k sits at chunk slot c ^ 4 (k & 3).  The MFMA operands (8 consecutive tokens of one channel
 // per lane) come out of that token-major layout through ds_read_b64_tr_b16: 16 lanes read a
 // 4 token x 16 channel block (4 lanes per row, 8 bytes each) and each lane receives the 4 tokens
-// of its channel; with the swizzle the 4 rows of a block fall into different bank groups.  So
+// of its channel; with the swizzle the 4 rows of a block lie 64 bytes apart in the bank map, which is
+// what this read needs to run without bank conflicts (the conflict counter reads zero; with rows 32
+// bytes apart every read took twice as long).  So
 // there is no transpose in registers, no LDS store instruction and no staging VGPRs; a ring of
 // four 32 KB stages keeps three steps of loads in flight.  Rows past the token range and
 // channels past n are fetched from a block of zeros.
@@ -628,7 +630,7 @@ __device__ __forceinline__ void gram_tile_dma(const GemmArgs& g, int64_t I0, int
     int64_t tok_next = kBeg + row0;                      // token of gp[.][0]
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
-        const int chunk = slot ^ (2 * ((2 * par + drow) & 3));
+        const int chunk = slot ^ (4 * ((2 * par + drow) & 3));
         const int64_t ca = I0 + 8 * chunk, cb = J0 + 8 * chunk;
         gstep[0][par] = (ca < g.M) ? kDmaBK * ld_bytes : 0;
         gstep[1][par] = (cb < g.N) ? kDmaBK * ld_bytes : 0;
@@ -664,7 +666,7 @@ __device__ __forceinline__ void gram_tile_dma(const GemmArgs& g, int64_t I0, int
     int offa[4], offb[4];
     {
         const int krow = 8 * (lane >> 5) + ((lane & 15) >> 2);
-        const int xr = 2 * ((lane & 15) >> 2);
+        const int xr = 4 * ((lane & 15) >> 2);
         const int msub = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {

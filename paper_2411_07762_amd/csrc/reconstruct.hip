@@ -71,8 +71,10 @@ int default_block(int r) {
 
 int make_plan(int64_t m, int64_t n, int r, const aser_svd_opts* o, Plan* p) {
     p->b = (o && o->block > 0) ? o->block : default_block(r);
-    // default: 10 iterations, 12 for wide layers (the bulk of the spectrum gets denser with the size)
-    p->iters = (o && o->max_iter > 0) ? o->max_iter : (((m > n ? m : n) > 8192) ? 12 : 10);
+    // default: 10 iterations, 12 for wide layers (the bulk of the spectrum gets denser with the size),
+    // 24 when the block has fewer than r oversampling columns (r > 64: the wanted directions at the
+    // edge of the bulk then converge at the rate of the gap to the next singular value alone)
+    p->iters = (o && o->max_iter > 0) ? o->max_iter : (p->b < 2 * r ? 24 : (((m > n ? m : n) > 8192) ? 12 : 10));
     p->seed = (o && o->seed) ? o->seed : 1u;
     const int64_t mx = m > n ? m : n;
     size_t off = 0;

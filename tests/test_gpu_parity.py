@@ -319,6 +319,8 @@ E2E_CASES = [
     ("ragged", synth.mini("e1", 130, 333, 1500, r=24, f=6), False),
     ("c1_shape_small", synth.CONFIGS["c1"].with_(m=512, n=768, tokens=3072, r=32, f=16), True),
     ("c2_shape_small", synth.CONFIGS["c2"].with_(m=384, n=1032, tokens=4096, r=32, f=16, n_outliers=8), True),
+    # r = 128 fills the widest subspace block: no oversampling columns, the longer default iteration
+    ("c4_shape_small", synth.CONFIGS["c4"].with_(m=1024, n=3584, tokens=8192), True),
 ]
 
 
@@ -360,12 +362,13 @@ def test_headline_layer_full_size():
     run_e2e("c1_full", spec, True)
 
 
-@pytest.mark.parametrize("cfg", ["c2", "c3.gate", "c3.k", "c3.down"])
+@pytest.mark.parametrize("cfg", ["c2", "c3.gate", "c3.k", "c3.down", "c4"])
 def test_large_layers_full_size_sampled(cfg):
     """Full-size layers whose oracle SVD takes minutes: the 4096 x 11008 layer with 65536 tokens of
     heavy-tailed activations, and two layers of the Llama-3-8B-shaped block with 131072 tokens (the
     tall 14336 x 4096 gate projection, the flat 1024 x 4096 key projection and the 4096 x 14336 down
-    projection).  Each stage is checked
+    projection), and the 8192 x 28672 layer with 262144 tokens and r = 128 (15 GB of activations, a
+    3.3 GB Gram matrix, no oversampling columns in the subspace block).  Each stage is checked
     on samples the oracle computes one by one (Gram entries, statistics, RTN rows) or through
     identities that hold at any size (S S^T = G', reported error = whitened error recomputed from the
     returned factors, Eq. 8), and the error against the optimum from the spectrum of the smaller Gram
@@ -374,7 +377,8 @@ def test_large_layers_full_size_sampled(cfg):
     say("%s full size m=%d n=%d N=%d r=%d f=%d" % (cfg, spec.m, spec.n, spec.tokens, spec.r, spec.f))
     rng = np.random.default_rng(7)
     W = synth.make_weight(spec)
-    x_np = synth.make_activations(spec)
+    x_np = synth.make_activations(spec, workers=12)
+    say("%s: inputs drawn" % cfg)
     ctx = new_ctx()
     buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, True)
     aser.calibrate_layer(ctx, torch.from_numpy(W).to(DEV), to_dev_x(spec, x_np), buf)
