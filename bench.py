@@ -1,6 +1,6 @@
 """Benchmark of the ASER per-layer calibration path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c1|c2|c4|c3.<layer>|c3]
 
 One step = one pass of the whole hot path over one synthetic layer whose inputs already sit in
 HBM: reset statistics, Gram accumulation (+ channel |x| sums), outlier selection / smoothing
@@ -8,7 +8,8 @@ diagonal, per-channel RTN and target T, Cholesky whitening, rank-r truncated SVD
 The default workload is the 4096 x 4096 Llama-7B-shaped projection (N = 32768 bf16 tokens, W4,
 r = 64, f = 32).  Prints ONE JSON line.  The "roofline" object prices the dominant kernel (the
 bf16 MFMA Gram update) by its algorithmic flops N n (n + 1); "cpu_baseline" times the CPU
-oracle on a bounded sample on this host.
+oracle on a bounded sample on this host.  `--config c3` times the whole Llama-3-8B-shaped block
+(seven layers on four input streams, plus the per-token A8 quantizer) and reports per-layer times.
 """
 from __future__ import annotations
 
@@ -72,6 +73,102 @@ def cpu_baseline(spec):
             "stages_s_measured": {k: round(v, 3) for k, v in timings.items()}}
 
 
+def _gpu_present():
+    import torch
+    return torch.cuda.is_available()
+
+
+def run_block(args):
+    """--config c3: the Llama-3-8B-shaped block, layer by layer: one Gram per input stream (q, k, v share
+    one, gate and up another), then smoothing, RTN, whitening, reconstruction and the per-token A8
+    quantizer of the layer's smoothed input for each of the seven layers."""
+    import torch
+    import aser_synth as synth
+    import paper_2411_07762_amd as aser
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    ctx = aser.Context(0)
+    specs = [synth.CONFIGS[k] for k in synth.C3_LAYERS]
+    streams, layers = {}, []
+    for spec in specs:
+        if spec.stream_id not in streams:
+            log("generating stream %d: X %dx%d bf16" % (spec.stream_id, spec.tokens, spec.n))
+            x_np = synth.make_activations(spec, workers=8)
+            X = torch.from_numpy(x_np.view("int16")).to(dev).view(torch.bfloat16)
+            del x_np
+            streams[spec.stream_id] = {"X": X, "owner": None,
+                                       "codes": torch.empty((spec.tokens, spec.n), dtype=torch.int8, device=dev),
+                                       "scales": torch.empty(spec.tokens, dtype=torch.float32, device=dev)}
+        st = streams[spec.stream_id]
+        buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed=True)
+        if st["owner"] is None:
+            st["owner"] = buf
+        else:                                    # layers of one input share its statistics
+            buf.G, buf.abs_sum, buf.count = st["owner"].G, st["owner"].abs_sum, st["owner"].count
+        W = torch.from_numpy(synth.make_weight(spec)).to(dev)
+        layers.append((spec, st, buf, W))
+        ctx.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, spec.r))
+
+    def block(ev=None):
+        errs = []
+        for i, (spec, st, buf, W) in enumerate(layers):
+            if ev is not None:
+                ev[i].record()
+            first = st["owner"] is buf
+            if first:
+                buf.reset_statistics()
+            aser.calibrate_layer(ctx, W, st["X"], buf, accumulate=first)
+            ctx.check(aser.aser_quantize_act_rtn(ctx, st["X"], buf.mdiag, 8, st["codes"], st["scales"]))
+            errs.append(buf.err)
+        if ev is not None:
+            ev[len(layers)].record()
+        return errs
+
+    for _ in range(args.warmup):
+        block()
+    torch.cuda.synchronize()
+    layer_ms = [0.0] * len(layers)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(layers) + 1)]
+        errs = block(ev)
+        torch.cuda.synchronize()
+        for i in range(len(layers)):
+            layer_ms[i] += ev[i].elapsed_time(ev[i + 1]) / args.steps
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # the Gram kernel of the widest stream alone, for the roofline object
+    spec, st, buf, _ = layers[-1]
+    G2 = torch.zeros_like(buf.G)
+    ctx.check(aser.aser_gram_accumulate(ctx, st["X"], G2))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(3, args.steps)
+    e0.record()
+    for _ in range(reps):
+        ctx.check(aser.aser_gram_accumulate(ctx, st["X"], G2))
+    e1.record()
+    torch.cuda.synchronize()
+    gram_ms = e0.elapsed_time(e1) / reps
+    gram_flops = float(spec.tokens) * spec.n * (spec.n + 1)
+    gram_tflops = gram_flops / (gram_ms * 1e-3) / 1e12
+    out = {
+        "metric": "ASER calibration ms, Llama-3-8B-shaped block (7 layers, 4 Grams, W4A8)", "value": wall_ms, "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_ms, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c3: q 4096x4096, k/v 1024x4096, o 4096x4096, gate/up 14336x4096, down 4096x14336; "
+                               "131072 bf16 tokens per input stream; W4 per-channel RTN, A8 per-token, r=64, f=32"},
+        "layer_ms": {sp.name: round(ms, 3) for (sp, _, _, _), ms in zip(layers, layer_ms)},
+        "whitened_error": {sp.name: e for (sp, _, _, _), e in zip(layers, errs)},
+        "roofline": {"kernel": "gram_dma_kernel (Gram update of the 14336-channel stream)", "bound": "mfma",
+                     "achieved": gram_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gram_tflops / BF16_PEAK_TFLOPS, "traffic": None,
+                     "algorithmic_flops_per_launch": gram_flops, "avg_launch_ms": gram_ms},
+    }
+    log("layer ms:", out["layer_ms"], "block %.2f ms" % wall_ms)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -86,6 +183,12 @@ def main():
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
               file=sys.stderr)
         sys.exit(2)
+
+    if args.config == "c3":
+        if not _gpu_present():
+            print("bench.py needs a GPU", file=sys.stderr)
+            sys.exit(2)
+        return run_block(args)
 
     import numpy as np
     import torch
