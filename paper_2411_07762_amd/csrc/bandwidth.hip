@@ -47,7 +47,9 @@ __global__ void fill_zero_kernel(uint32_t* p, int64_t words) {
 // ------------------------------------------------------------------------------------ column |.| sums
 // A workgroup is 64 column groups (16 bytes each) x 4 row lanes over a strip of rows.  Each thread
 // sums its rows in fp64; the four row lanes are combined through LDS and one fp64 atomic per
-// column and strip goes to abs_sum.
+// column and strip goes to abs_sum.  The strips are long (about one workgroup per compute unit):
+// the atomics on the few thousand shared addresses, not the reads, set the time of short strips
+// (32768 x 4096 bf16: 85 us with 256-row strips, 49 us with 1024-row strips, 43 us without atomics).
 template <bool BF16>
 __global__ __launch_bounds__(256) void col_abs_sum_kernel(const void* X, int64_t rows, int64_t n, int64_t ld,
                                                           int64_t rows_per_block, double* out, int64_t* count,
@@ -70,12 +72,12 @@ __global__ __launch_bounds__(256) void col_abs_sum_kernel(const void* X, int64_t
     for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
     if (vec_ok) {
         int64_t r = r0 + rl;
-        for (; r + 12 < r1; r += 16) {
-            uint4 v[4];
+        for (; r + 28 < r1; r += 32) {
+            uint4 v[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = *(const uint4*)(base + (r + 4 * u) * ld * ESZ);
+            for (int u = 0; u < 8; ++u) v[u] = *(const uint4*)(base + (r + 4 * u) * ld * ESZ);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 8; ++u) {
                 const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
@@ -235,7 +237,9 @@ __global__ __launch_bounds__(NT) void rtn_kernel(const float* __restrict__ W, in
     }
     amax = block_max(amax, red);
     const float scale = (amax == 0.f) ? 1.f : amax / qmax;
-    const float rscale = __builtin_amdgcn_rcpf(scale);
+    // the reciprocal of a denormal scale is not finite: such a row takes true divisions throughout
+    const bool plain = __builtin_amdgcn_readfirstlane(scale > 1e-30f ? 1 : 0) != 0;
+    const float rscale = plain ? __builtin_amdgcn_rcpf(scale) : 0.f;
     if (tid == 0) scales[row] = scale;
 
     uint8_t* crow = codes + row * code_pitch;
@@ -248,16 +252,43 @@ __global__ __launch_bounds__(NT) void rtn_kernel(const float* __restrict__ W, in
         if (c >= n) continue;
         float t[8];
         int q[8];
+        if (plain && __builtin_amdgcn_ballot_w64(om[u] != 0u) == 0) {
+            // no outlier column in this wavefront's groups: rint(w / scale) from the reciprocal multiply
+            // (error below 4e-5), one test per group for a quotient within 1e-4 of a rounding boundary
+            // k + 1/2, where the correctly rounded division decides
+            float r[8], dist[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            if ((om[u] >> e) & 1u) {
-                q[e] = 0;
-                t[e] = (c + e < n) ? v[u][e] * mdiag[c + e] : 0.f;
-            } else {
-                float qf = rint_div(v[u][e], scale, rscale);
-                qf = fminf(fmaxf(qf, -qmax), qmax);
-                q[e] = (int)qf;
-                t[e] = __fmaf_rn(-qf, scale, v[u][e]);
+            for (int e = 0; e < 8; ++e) {
+                const float tq = v[u][e] * rscale;
+                r[e] = rintf(tq);
+                dist[e] = fabsf(tq - r[e]);
+            }
+            const float far = fmaxf(fmaxf(fmaxf(dist[0], dist[1]), fmaxf(dist[2], dist[3])),
+                                    fmaxf(fmaxf(dist[4], dist[5]), fmaxf(dist[6], dist[7])));
+            if (__builtin_amdgcn_ballot_w64(far > 0.4999f) != 0) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if (dist[e] > 0.4999f) r[e] = rintf(v[u][e] / scale);
+                    asm volatile("" : "+v"(r[e]));        // keeps the division behind its branch
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                q[e] = (int)r[e];
+                t[e] = __fmaf_rn(-r[e], scale, v[u][e]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if ((om[u] >> e) & 1u) {
+                    q[e] = 0;
+                    t[e] = (c + e < n) ? v[u][e] * mdiag[c + e] : 0.f;
+                } else {
+                    float qf = plain ? rint_div(v[u][e], scale, rscale) : rintf(v[u][e] / scale);
+                    qf = fminf(fmaxf(qf, -qmax), qmax);
+                    q[e] = (int)qf;
+                    t[e] = __fmaf_rn(-qf, scale, v[u][e]);
+                }
             }
         }
         if (layout == ASER_CODES_INT8) {
@@ -395,76 +426,124 @@ __global__ __launch_bounds__(NT) void act_rtn_kernel(const void* __restrict__ X,
 
 // Tokens of at most 4096 channels (16-byte aligned rows, n % 16 == 0): one wavefront per token, 4 groups
 // of 16 channels per lane (32 bytes of bf16 in, 16 bytes of codes out), all loads of a token in
-// flight at once, absmax by lane shuffles: no LDS and no barrier.  Four tokens per workgroup.
+// flight at once, absmax by lane shuffles: no LDS and no barrier.  The arithmetic, not the memory
+// system, bounds this kernel, so everything that depends on M alone is done once per wavefront,
+// which then walks several tokens: its 64 entries of M stay in registers, and a 64-bit scalar mask
+// says in which of the 64 register slots any lane holds a scaled channel at all; the IEEE division
+// x / m runs only in those slots (x / 1 = x exactly, so the other lanes of such a slot are not
+// touched by it), behind scalar branches.  The next token's loads are issued before the current
+// token is reduced.
+template <bool BF16>
+__device__ __forceinline__ void act_load_token(const char* xrow, int64_t n, int lane, u32x4_t (&raw)[BF16 ? 8 : 16]) {
+    constexpr int PER = BF16 ? 2 : 4;                    // 16-byte loads per group of 16 channels
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t c = ((int64_t)u * 64 + lane) * 16;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            raw[u * PER + q] = u32x4_t{0u, 0u, 0u, 0u};
+            if (c < n) raw[u * PER + q] = *(const u32x4_t*)(xrow + c * (BF16 ? 2 : 4) + 16 * q);
+        }
+    }
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(256) void act_rtn_wave_kernel(const void* __restrict__ X, int64_t rows, int64_t n, int64_t ldx,
                                                            const float* __restrict__ mdiag, float qmax,
-                                                           int8_t* __restrict__ codes, float* __restrict__ scales) {
+                                                           int8_t* __restrict__ codes, float* __restrict__ scales,
+                                                           int tokens_per_wave) {
     const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= rows) return;
-    const char* xrow = (const char*)X + row * ldx * (BF16 ? 2 : 4);
-    float v[4][16];
+    const int64_t row0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * tokens_per_wave;
+    if (row0 >= rows) return;
+    const int64_t row1 = (row0 + tokens_per_wave < rows) ? row0 + tokens_per_wave : rows;
+    const int64_t row_bytes = ldx * (BF16 ? 2 : 4);
+
+    float m[4][16];
+    uint64_t slots = 0;                                  // bit 16 u + e: some lane's channel of that slot has m != 1
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int64_t c = ((int64_t)u * 64 + lane) * 16;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) v[u][e] = 0.f;
-        if (c >= n) continue;
-        if (BF16) {
-            const u32x4_t w0 = *(const u32x4_t*)(xrow + c * 2), w1 = *(const u32x4_t*)(xrow + c * 2 + 16);
-            const uint32_t ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+        for (int q = 0; q < 4; ++q) {
+            float4 m4 = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (mdiag && c < n) m4 = *(const float4*)(mdiag + c + 4 * q);
+            m[u][4 * q] = m4.x; m[u][4 * q + 1] = m4.y; m[u][4 * q + 2] = m4.z; m[u][4 * q + 3] = m4.w;
+        }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                v[u][2 * e] = __uint_as_float(ww[e] << 16);
-                v[u][2 * e + 1] = __uint_as_float(ww[e] & 0xFFFF0000u);
-            }
-        } else {
+        for (int e = 0; e < 16; ++e)
+            if (__builtin_amdgcn_ballot_w64(m[u][e] != 1.f) != 0) slots |= 1ull << (16 * u + e);
+    }
+
+    u32x4_t raw[BF16 ? 8 : 16];
+    act_load_token<BF16>((const char*)X + row0 * row_bytes, n, lane, raw);
+    for (int64_t row = row0; row < row1; ++row) {
+        float v[4][16];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x4_t x = *(const f32x4_t*)(xrow + c * 4 + 16 * q);
-                v[u][4 * q] = x.x; v[u][4 * q + 1] = x.y; v[u][4 * q + 2] = x.z; v[u][4 * q + 3] = x.w;
+        for (int u = 0; u < 4; ++u) {
+            if (BF16) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t w = raw[2 * u + (e >> 2)][e & 3];
+                    v[u][2 * e] = __uint_as_float(w << 16);
+                    v[u][2 * e + 1] = __uint_as_float(w & 0xFFFF0000u);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) v[u][e] = __uint_as_float(raw[4 * u + (e >> 2)][e & 3]);
             }
         }
-    }
-    float amax = 0.f;
+        if (row + 1 < row1) act_load_token<BF16>((const char*)X + (row + 1) * row_bytes, n, lane, raw);
+        float amax = 0.f;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int64_t c = ((int64_t)u * 64 + lane) * 16;
-        if (c >= n) continue;
-        if (mdiag) {
+        for (int u = 0; u < 4; ++u) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 m4 = *(const float4*)(mdiag + c + 4 * q);
-                const float mm[4] = {m4.x, m4.y, m4.z, m4.w};
+            for (int e = 0; e < 16; ++e) {
+                if ((slots >> (16 * u + e)) & 1) {
+                    v[u][e] = v[u][e] / m[u][e];
+                    asm volatile("" : "+v"(v[u][e]));     // keeps the division behind its branch
+                }
+                amax = fmaxf(amax, fabsf(v[u][e]));
+            }
+        }
+        amax = wave_max(amax);
+        const float scale = (amax == 0.f) ? 1.f : amax / qmax;
+        // the reciprocal of a denormal scale is not finite: then every quotient is a true division
+        const bool plain = __builtin_amdgcn_readfirstlane(scale > 1e-30f ? 1 : 0) != 0;
+        const float rscale = plain ? __builtin_amdgcn_rcpf(scale) : 0.f;
+        if (lane == 0) scales[row] = scale;
+        int8_t* crow = codes + row * n;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t c = ((int64_t)u * 64 + lane) * 16;
+            u32x4_t pkv;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                // rint(x / scale) from a reciprocal multiply (error below 4e-5 for |quotient| <= 128); only
+                // within 1e-4 of a rounding boundary k + 1/2 does the correctly rounded division decide.
+                // One test per four channels: the largest distance to the nearest integer among them.
+                float t[4], r[4], dist[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const bool scaled = mm[e] != 1.f;                                    // x / 1 = x exactly
-                    if (__builtin_amdgcn_ballot_w64(scaled) != 0) v[u][4 * q + e] = scaled ? v[u][4 * q + e] / mm[e] : v[u][4 * q + e];
+                    t[e] = v[u][4 * d + e] * rscale;
+                    r[e] = rintf(t[e]);
+                    dist[e] = fabsf(t[e] - r[e]);
                 }
+                const float far = fmaxf(fmaxf(dist[0], dist[1]), fmaxf(dist[2], dist[3]));
+                if (!plain || __builtin_amdgcn_ballot_w64(far > 0.4999f) != 0) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (!plain || dist[e] > 0.4999f) r[e] = rintf(v[u][4 * d + e] / scale);
+                        asm volatile("" : "+v"(r[e]));
+                    }
+                }
+                int qi[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) qi[e] = (int)r[e];
+                pkv[d] = __builtin_amdgcn_perm((uint32_t)qi[1], (uint32_t)qi[0], 0x0c0c0400u) |
+                         __builtin_amdgcn_perm((uint32_t)qi[3], (uint32_t)qi[2], 0x04000c0cu);
             }
+            if (c < n) __builtin_nontemporal_store(pkv, (u32x4_t*)(crow + c));
         }
-#pragma unroll
-        for (int e = 0; e < 16; ++e) amax = fmaxf(amax, fabsf(v[u][e]));
-    }
-    amax = wave_max(amax);
-    const float scale = (amax == 0.f) ? 1.f : amax / qmax;
-    const float rscale = __builtin_amdgcn_rcpf(scale);
-    if (lane == 0) scales[row] = scale;
-    int8_t* crow = codes + row * n;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int64_t c = ((int64_t)u * 64 + lane) * 16;
-        if (c >= n) continue;
-        uint32_t pk[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            float qf = rint_div(v[u][e], scale, rscale);
-            qf = fminf(fmaxf(qf, -qmax), qmax);
-            pk[e >> 2] |= (uint32_t)((int)qf & 0xFF) << (8 * (e & 3));
-        }
-        const u32x4_t pkv = {pk[0], pk[1], pk[2], pk[3]};
-        __builtin_nontemporal_store(pkv, (u32x4_t*)(crow + c));
     }
 }
 
@@ -488,12 +567,20 @@ int aser_fill_bytes(aser_ctx* ctx, void* p, size_t bytes) {
     return aser_check_launch(ctx, "fill_zero");
 }
 
+// Rows per strip of the column-sum kernels: the largest power of two that still leaves about one
+// workgroup per compute unit, between 256 and 8192 (and few enough strips for the grid's y range).
+static int64_t strip_rows(int64_t rows, int64_t col_groups) {
+    int64_t rpb = 256;
+    while (rpb < 8192 && rpb * 2 * 256 <= rows * col_groups) rpb *= 2;
+    while (ceil_div64(rows, rpb) > 65535) rpb *= 2;
+    return rpb;
+}
+
 int aser_col_abs_sum_x(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int64_t n, int64_t ldx,
                        double* abs_sum, int64_t* count) {
     const int vec = (x_dtype == ASER_DTYPE_BF16) ? 8 : 4;
     const int64_t gx = ceil_div64(ceil_div64(n, vec), 64);
-    int64_t rpb = 256;
-    while (ceil_div64(rows, rpb) > 65535) rpb *= 2;
+    const int64_t rpb = strip_rows(rows, gx);
     const int64_t gy = ceil_div64(rows, rpb);
     dim3 grid((unsigned)gx, (unsigned)gy);
     if (x_dtype == ASER_DTYPE_BF16)
@@ -505,8 +592,7 @@ int aser_col_abs_sum_x(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, 
 
 int aser_col_abs_sum_w(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw, double* wsum) {
     const int64_t gx = ceil_div64(ceil_div64(n, 4), 64);
-    int64_t rpb = 128;
-    while (ceil_div64(m, rpb) > 65535) rpb *= 2;
+    const int64_t rpb = strip_rows(m, gx);
     dim3 grid((unsigned)gx, (unsigned)ceil_div64(m, rpb));
     hipLaunchKernelGGL(col_abs_sum_kernel<false>, grid, dim3(256), 0, ctx->stream, (const void*)W, m, n, ldw, rpb, wsum,
                        (int64_t*)nullptr, (int64_t)0);
@@ -587,11 +673,14 @@ extern "C" int aser_quantize_act_rtn(aser_ctx* ctx, const void* X, int x_dtype, 
     const bool wave_ok = n <= 4096 && (n & 15) == 0 && ((uintptr_t)X & 15) == 0 && ((ldx * esz) & 15) == 0 &&
                          ((uintptr_t)codes & 15) == 0 && (!mdiag || ((uintptr_t)mdiag & 15) == 0);
     if (wave_ok) {
-        dim3 wgrid((unsigned)ceil_div64(rows, 4));
+        // several tokens per wavefront once there are enough tokens for four workgroups per compute unit
+        int tpw = (int)(rows / 4096);
+        tpw = tpw < 1 ? 1 : (tpw > 8 ? 8 : tpw);
+        dim3 wgrid((unsigned)ceil_div64(rows, 4 * (int64_t)tpw));
         if (x_dtype == ASER_DTYPE_BF16)
-            hipLaunchKernelGGL(act_rtn_wave_kernel<true>, wgrid, dim3(256), 0, ctx->stream, X, rows, n, ldx, mdiag, qmax, codes, scales);
+            hipLaunchKernelGGL(act_rtn_wave_kernel<true>, wgrid, dim3(256), 0, ctx->stream, X, rows, n, ldx, mdiag, qmax, codes, scales, tpw);
         else
-            hipLaunchKernelGGL(act_rtn_wave_kernel<false>, wgrid, dim3(256), 0, ctx->stream, X, rows, n, ldx, mdiag, qmax, codes, scales);
+            hipLaunchKernelGGL(act_rtn_wave_kernel<false>, wgrid, dim3(256), 0, ctx->stream, X, rows, n, ldx, mdiag, qmax, codes, scales, tpw);
         return aser_check_launch(ctx, "act_rtn");
     }
     if (x_dtype == ASER_DTYPE_BF16) ASER_ACT_PICK(true);

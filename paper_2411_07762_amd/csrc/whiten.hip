@@ -116,7 +116,7 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
             u.C = D; u.ldc = lds; u.Ct = nullptr; u.ldct = 0;
             u.M = b; u.N = n - k0; u.K = k0; u.alpha = -1.f;
             u.in_type = GEMM_IN_F32X3; u.epi = GEMM_EPI_ATOMIC; u.tiles = GEMM_TILES_ALL; u.krange = GEMM_K_FULL;
-            u.bm = 128; u.bn = 128; u.upper_only = 1;
+            u.bm = 128; u.bn = (u.N >= 4096) ? 256 : 128; u.upper_only = 1;
             const int64_t tiles = ceil_div64(u.N, u.bn), ksteps = ceil_div64(k0, 32);
             int64_t parts = ceil_div64(256, tiles);
             const int64_t max_parts = ksteps / 4 > 0 ? ksteps / 4 : 1;
