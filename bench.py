@@ -272,7 +272,7 @@ def main():
     stage_ms = [s / args.steps for s in stage_ms]
 
     # Dominant kernel alone: the Gram MFMA kernel (no statistics pass), HIP events on the launch stream.
-    reps = max(5, args.steps)
+    reps = max(10, args.steps)
     G2 = torch.zeros_like(buf.G)
     ctx.check(aser.aser_gram_accumulate(ctx, X, G2))
     torch.cuda.synchronize()
@@ -287,6 +287,9 @@ def main():
     gram_tflops = gram_flops / (gram_ms * 1e-3) / 1e12
 
     # Bandwidth kernel: RTN + target (algorithmic bytes 8.5 m n + 4 m), rotating weight buffers.
+    for i in range(4):                           # untimed: the first launches after another kernel run slower
+        ctx.check(aser.aser_quantize_rtn(ctx, Ws[i % n_rot], buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes,
+                                         buf.scales, buf.T))
     e0.record()
     for i in range(reps):
         ctx.check(aser.aser_quantize_rtn(ctx, Ws[i % n_rot], buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes,

@@ -53,7 +53,8 @@ enum GemmIn { GEMM_IN_BF16 = 0, GEMM_IN_F32X3 = 1 };
 enum GemmEpi {
     GEMM_EPI_STORE = 0,    // C = alpha * acc            (needs k_parts == 1)
     GEMM_EPI_ATOMIC = 1,   // atomicAdd(C, alpha * acc)  (any k_parts)
-    GEMM_EPI_RMW = 2       // C += alpha * acc           (needs k_parts == 1, disjoint tiles)
+    GEMM_EPI_RMW = 2,      // C += alpha * acc           (needs k_parts == 1, disjoint tiles)
+    GEMM_EPI_RESID = 3     // *sumsq += ||C + alpha * acc||_F^2, C only read (needs k_parts == 1)
 };
 enum GemmTiles {
     GEMM_TILES_ALL = 0,    // every BM x BN tile of C
@@ -76,6 +77,7 @@ struct GemmArgs {
     int k_parts;               // split of the K range over blockIdx.y
     int bm, bn;                // tile: 256x256, 128x256, 256x128 or 128x128
     int upper_only;            // ATOMIC only: skip entries with row > col (C is symmetric, its upper part is used)
+    double* sumsq;             // RESID only: device scalar that receives the sum of squares (accumulates)
 };
 int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g);
 

@@ -47,6 +47,19 @@ __device__ __forceinline__ f4v mma16(f4v acc, const float* pa, int sak, const fl
     return acc;
 }
 
+// Trailing update of one 16 x 16 tile behind the sub-block at offset o: A[i][c] -= sum_k P[k][i] P[k][c]
+// with the row panel P in rows o .. o + 31, tile (ti <= tc) counted from column o + 32.
+__device__ __forceinline__ void trailing_tile(float* As, int o, int ti, int tc, int t_i, int t_q) {
+    const float* prow = As + o * kP + o + kSub;
+    float* out = As + (o + kSub + 16 * ti + 4 * t_q) * kP + o + kSub + 16 * tc + t_i;
+    f4v c;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) c[e] = out[e * kP];
+    c = mma16(c, prow + t_q * kP + 16 * ti + t_i, kP, prow + t_q * kP + 16 * tc + t_i, kP, 8, -1.f);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) out[e * kP] = c[e];
+}
+
 __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t ld, int b, float* Rinv, int32_t* info,
                                                               int32_t pivot_base, int clear_d, const float* Lmul,
                                                               float* Cmul, int with_beta) {
@@ -79,12 +92,17 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
     }
     __syncthreads();
 
-    for (int kb = 0; kb < nsub; ++kb) {
+    // Round kb factors diagonal sub-block kb (one wavefront), forms its row panel and the Y block, and
+    // updates what lies behind it.  The pivot chain is the long part and keeps a single wavefront busy,
+    // so it runs beside the bulk of the previous round's updates: once the three 16 x 16 tiles of the
+    // next diagonal sub-block are updated, wavefront 0 starts on it while the other fifteen finish the
+    // rest of the trailing update and the new block column of the inverse.
+    for (int kb = 0; kb <= nsub; ++kb) {
         const int o = kb * kSub;
         const int ncb = nsub - 1 - kb;             // 32-column blocks to the right
 
         // ---- 1. diagonal sub-block: accumulator register e of lane l holds row 8 (e / 4) + 4 (l / 32) + e % 4, column l % 32
-        if (wave == 0) {
+        if (wave == 0 && kb < nsub) {
             const int h = lane >> 5, col = lane & 31;
             f16v a1, a2;
 #pragma unroll
@@ -144,7 +162,38 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
             }
             if (bad < kSub && lane == 0 && o + bad < b && info) atomicMin(info, pivot_base + o + bad + 1);
         }
+        if (kb > 0 && (wave > 0 || kb == nsub)) {
+            // ---- rest of round kb - 1: new block column of the inverse (long jobs first), then the trailing
+            // update without the tiles of diagonal sub-block kb (done before the last barrier)
+            const int op = o - kSub;
+            const int w0 = (kb < nsub) ? 1 : 0;
+            const int nx = (op / 16) * 2;
+            const int nt = 2 * (ncb + 1), ntri = nt * (nt + 1) / 2;
+            for (int job = wave - w0; job < nx + ntri; job += kWaves - w0) {
+                if (job < nx) {
+                    // X[i][op + c] = -sum_{t >= i} X[i][t] Y[t][c]
+                    const int it = job >> 1, cj = job & 1;
+                    const float* pa = Xs + (16 * it + t_i) * kP + 16 * it + t_q;
+                    const float* pb = Ys + (16 * it + t_q) * kPY + 16 * cj + t_i;
+                    f4v x = {0.f, 0.f, 0.f, 0.f};
+                    x = mma16(x, pa, 1, pb, kPY, (op - 16 * it) / 4, -1.f);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) Xs[(16 * it + 4 * t_q + e) * kP + op + 16 * cj + t_i] = x[e];
+                } else {
+                    // A[i][c] -= sum_k P[k][i] P[k][c] on tile (ti <= tc): rows ar and nt-1-ar of the
+                    // triangle together hold nt + 1 tiles
+                    const int idx = job - nx;
+                    const int ar = idx / (nt + 1), cc = idx - ar * (nt + 1);
+                    int ti, tc;
+                    if (cc < nt - ar) { ti = ar; tc = ar + cc; }
+                    else { ti = nt - 1 - ar; tc = ti + (cc - (nt - ar)); }
+                    if (tc < 2) continue;                            // diagonal sub-block kb: already updated
+                    trailing_tile(As, op, ti, tc, t_i, t_q);
+                }
+            }
+        }
         __syncthreads();
+        if (kb == nsub) break;
 
         // ---- 2. panel (one job per 16-column tile, both row halves) and Y (one job per 16 x 16 tile)
         {
@@ -177,40 +226,11 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
         }
         __syncthreads();
 
-        // ---- 3. new block column of the inverse (long jobs first), then the trailing update
-        {
-            const int nx = (o / 16) * 2;
-            const int nt = 2 * ncb, ntri = nt * (nt + 1) / 2;
-            for (int job = wave; job < nx + ntri; job += kWaves) {
-                if (job < nx) {
-                    // X[i][o + c] = -sum_{t >= i} X[i][t] Y[t][c]
-                    const int it = job >> 1, cj = job & 1;
-                    const float* pa = Xs + (16 * it + t_i) * kP + 16 * it + t_q;
-                    const float* pb = Ys + (16 * it + t_q) * kPY + 16 * cj + t_i;
-                    f4v x = {0.f, 0.f, 0.f, 0.f};
-                    x = mma16(x, pa, 1, pb, kPY, (o - 16 * it) / 4, -1.f);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) Xs[(16 * it + 4 * t_q + e) * kP + o + 16 * cj + t_i] = x[e];
-                } else {
-                    // A[i][c] -= sum_k P[k][i] P[k][c] on tile (ti <= tc): rows ar and nt-1-ar of the
-                    // triangle together hold nt + 1 tiles
-                    const int idx = job - nx;
-                    const int ar = idx / (nt + 1), cc = idx - ar * (nt + 1);
-                    int ti, tc;
-                    if (cc < nt - ar) { ti = ar; tc = ar + cc; }
-                    else { ti = nt - 1 - ar; tc = ti + (cc - (nt - ar)); }
-                    const float* prow = As + o * kP + o + kSub;
-                    float* out = As + (o + kSub + 16 * ti + 4 * t_q) * kP + o + kSub + 16 * tc + t_i;
-                    f4v c;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) c[e] = out[e * kP];
-                    c = mma16(c, prow + t_q * kP + 16 * ti + t_i, kP, prow + t_q * kP + 16 * tc + t_i, kP, 8, -1.f);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) out[e * kP] = c[e];
-                }
-            }
+        // ---- 3. the three tiles of the next diagonal sub-block
+        if (ncb > 0) {
+            if (wave < 3) trailing_tile(As, o, wave == 2 ? 1 : 0, wave == 0 ? 0 : 1, t_i, t_q);
+            __syncthreads();
         }
-        __syncthreads();
     }
 
     // write out: R above the diagonal, R^T below it (or zeros over the input when clear_d), and R^-1

@@ -351,6 +351,42 @@ __device__ __forceinline__ void tile_body(const GemmArgs& g, int64_t I0, int64_t
     // Epilogue.  acc[i][j][e] is C(row, col) with row = 32 i + 8 (e / 4) + 4 (lane / 32) + e % 4,
     // col = 32 j + lane % 32 inside the wave's sub-tile.
     const float alpha = g.alpha;
+    if (BM == 128 && BN == 128 && g.epi == GEMM_EPI_RESID) {   // (the large tiles have no registers to spare for it)
+        // squared Frobenius norm of C + alpha acc, nothing stored: the loads of one row of 32 x 32
+        // blocks are in flight together, squares are summed in fp64, one atomic per wavefront
+        double sum = 0.0;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t rbase = I0 + wm0 + 32 * i + 4 * (lane >> 5);
+            float old[TN][16];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t col = J0 + wn0 + 32 * j + (lane & 31);
+                const float* cbase = g.C + rbase * g.ldc + col;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int dr = 8 * (e >> 2) + (e & 3);
+                    const bool in = col < g.N && rbase + dr < g.M;
+                    old[j][e] = in ? cbase[(int64_t)dr * g.ldc] : 0.f;
+                    if (!in) acc[i][j][e] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                float part = 0.f;                          // 16 squares of comparable size in fp32, then fp64
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float d = old[j][e] + alpha * acc[i][j][e];
+                    part = fmaf(d, d, part);
+                }
+                sum += (double)part;
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        if (lane == 0) atomicAdd(g.sumsq, sum);
+        return;
+    }
     if (g.epi == GEMM_EPI_RMW) {
         // read-modify-write: one row of 32 x 32 blocks (up to 64 values per lane) is loaded before
         // anything is stored, so that the loads overlap instead of forming a chain
@@ -827,6 +863,8 @@ int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g) {
     if (g.tiles != GEMM_TILES_ALL && (g.M != g.N || g.bm != g.bn))
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: triangular tiling needs a square problem and tile");
     if (g.Ct && g.epi != GEMM_EPI_STORE) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: Ct needs the store epilogue");
+    if (g.epi == GEMM_EPI_RESID && (!g.sumsq || g.k_parts != 1 || g.bm != 128 || g.bn != 128))
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: the residual epilogue needs sumsq, k_parts == 1 and 128 x 128 tiles");
     if (g.in_type == GEMM_IN_BF16) return dispatch_tile<GEMM_IN_BF16>(ctx, g);
     if (g.in_type == GEMM_IN_F32X3) return dispatch_tile<GEMM_IN_F32X3>(ctx, g);
     ASER_FAIL(ctx, ASER_ERR_DTYPE, "gemm_tn: unknown input type");

@@ -235,7 +235,8 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     hipLaunchKernelGGL(ritz_factors_kernel, dim3(16), dim3(256), 0, ctx->stream, (const float*)lambda, (const float*)Uhat, b,
                        (int)r, sigma, WA, WBt);
     ASER_TRY(aser_check_launch(ctx, "ritz_factors"));
-    // Whitened error of Eq. 8 as an explicit residual: A <- A - U_r (U_r^T A), then ||A||_F.
+    // Whitened error of Eq. 8 as an explicit residual: ||A - U_r (U_r^T A)||_F, formed tile by tile in
+    // the product's epilogue (A is read once and nothing is written).
     // U_r^T A = (Z Uhat_r)^T with Z = A^T Q; the subtraction form avoids the cancellation of
     // ||A||^2 - sum sigma_i^2 when the top singular values carry almost all of the norm.
     ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, Uhat, b, L_B, n, n, b, r, 0, true));  // (V_r Sigma_r)^T (r x n), parked in L_B
@@ -243,13 +244,12 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     {
         GemmArgs g{};
         g.A = tp; g.lda = m; g.B = L_B; g.ldb = n; g.C = A; g.ldc = n; g.Ct = nullptr; g.ldct = 0;
-        g.M = m; g.N = n; g.K = r; g.alpha = -1.f;
-        g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_RMW; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
+        g.M = m; g.N = n; g.K = r; g.alpha = -1.f; g.sumsq = normA2;
+        g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_RESID; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
         g.k_parts = 1;
-        g.bm = (m > 1024) ? 256 : 128; g.bn = (n > 1024) ? 256 : 128;
+        g.bm = 128; g.bn = 128;                           // short K: many small workgroups hide the latency of reading A
         ASER_TRY(aser_gemm_tn(ctx, g));
     }
-    ASER_TRY(aser_sumsq_f32(ctx, A, m, n, n, normA2));
     // L_A = Q (Uhat_r Sigma_r)
     ASER_TRY(aser_gemm_small_f32(ctx, Qp, b, WA, r, L_A, r, m, b, r));
     // L_B^T = (T^T Q) (Uhat_r Sigma_r^-1)  ->  L_B
