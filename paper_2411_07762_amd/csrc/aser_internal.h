@@ -77,6 +77,8 @@ struct GemmArgs {
     int k_parts;               // split of the K range over blockIdx.y
     int bm, bn;                // tile: 256x256, 128x256, 256x128 or 128x128
     int upper_only;            // ATOMIC only: skip entries with row > col (C is symmetric, its upper part is used)
+    int pair_cols;             // TILES_ALL, k_parts == 1, 256 x 128 tiles: a workgroup takes tile columns j and tn - 1 - j of its tile row
+                               // (equal work per workgroup when K shrinks linearly with the column, K_GE_COL)
     double* sumsq;             // RESID only: device scalar that receives the sum of squares (accumulates)
 };
 int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g);

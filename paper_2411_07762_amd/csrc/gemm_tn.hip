@@ -492,6 +492,25 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     tile_body<IN, BM, BN, FAST>(g, I0, J0, kBeg, kEnd, smem);
 }
 
+// 256 x 128 tiles, tile columns j and tn - 1 - j of one tile row per workgroup, one after the other:
+// equal work per workgroup when the K range shrinks linearly with the column (B lower triangular).
+template <int IN, bool FAST>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_tn_pair_kernel(GemmArgs g) {
+    extern __shared__ uint4 smem[];
+    constexpr int BK = InTraits<IN>::BK, BM = 256, BN = 128;
+    const int64_t tn = (g.N + BN - 1) / BN, half = (tn + 1) / 2;
+    const int64_t ti = blockIdx.x / half, j0 = blockIdx.x % half;
+#pragma nounroll
+    for (int rep = 0; rep < 2; ++rep) {
+        const int64_t tj = rep ? tn - 1 - j0 : j0;
+        if (rep && tj == j0) break;
+        const int64_t J0 = tj * BN;
+        const int64_t k0 = (g.krange == GEMM_K_GE_COL) ? (J0 / BK) * BK : 0;
+        if (rep) __syncthreads();                        // the first tile's readers are done with the LDS stages
+        tile_body<IN, BM, BN, FAST>(g, ti * BM, J0, k0, g.K, smem);
+    }
+}
+
 // True when both operands allow the branch-free 16-byte fetch path.
 template <int IN>
 bool operands_fast(const GemmArgs& g) {
@@ -517,7 +536,22 @@ int launch_plain(aser_ctx* ctx, const GemmArgs& g) {
 }
 
 template <int IN, bool FAST>
+int launch_pair(aser_ctx* ctx, const GemmArgs& g) {
+    using Cfg = TileCfg<IN, 256, 128>;
+    static bool attr_set[16] = {false};
+    auto kern = gemm_tn_pair_kernel<IN, FAST>;
+    if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
+        ASER_HIP(ctx, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::LDS_BYTES));
+        attr_set[ctx->device] = true;
+    }
+    const int64_t tm = ceil_div64(g.M, 256), tn = ceil_div64(g.N, 128);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tm * ((tn + 1) / 2))), dim3(kThreads), Cfg::LDS_BYTES, ctx->stream, g);
+    return aser_check_launch(ctx, "gemm_tn_pair");
+}
+
+template <int IN, bool FAST>
 int dispatch_tile2(aser_ctx* ctx, const GemmArgs& g) {
+    if (g.pair_cols) return launch_pair<IN, FAST>(ctx, g);
     if (g.bm == 256 && g.bn == 256) return launch_plain<IN, 256, 256, FAST>(ctx, g);
     if (g.bm == 128 && g.bn == 256) return launch_plain<IN, 128, 256, FAST>(ctx, g);
     if (g.bm == 256 && g.bn == 128) return launch_plain<IN, 256, 128, FAST>(ctx, g);
@@ -863,6 +897,8 @@ int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g) {
     if (g.tiles != GEMM_TILES_ALL && (g.M != g.N || g.bm != g.bn))
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: triangular tiling needs a square problem and tile");
     if (g.Ct && g.epi != GEMM_EPI_STORE) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: Ct needs the store epilogue");
+    if (g.pair_cols && (g.tiles != GEMM_TILES_ALL || g.k_parts != 1 || g.bm != 256 || g.bn != 128))
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: paired tile columns need all tiles, k_parts == 1 and 256 x 128 tiles");
     if (g.epi == GEMM_EPI_RESID && (!g.sumsq || g.k_parts != 1 || g.bm != 128 || g.bn != 128))
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: the residual epilogue needs sumsq, k_parts == 1 and 128 x 128 tiles");
     if (g.in_type == GEMM_IN_BF16) return dispatch_tile<GEMM_IN_BF16>(ctx, g);

@@ -192,7 +192,10 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         g.M = m; g.N = n; g.K = n; g.alpha = 1.f;
         g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_STORE; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_GE_COL;
         g.k_parts = 1;
-        g.bm = (m > 1024) ? 256 : 128; g.bn = (n > 1024) ? 256 : 128;
+        // S is lower triangular, so the K range of a tile shrinks with its column: pairing column j with
+        // column tn - 1 - j gives every workgroup the same work
+        g.pair_cols = (m > 1024 && n > 1024) ? 1 : 0;
+        g.bm = g.pair_cols ? 256 : 128; g.bn = 128;
         ASER_TRY(aser_gemm_tn(ctx, g));
     }
     ASER_TRY(aser_fill_bytes(ctx, normA2, 8));
