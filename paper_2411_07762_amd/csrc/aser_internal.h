@@ -118,5 +118,10 @@ int aser_tridiag_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float
 // C (rows x c) = A (rows x k) * B (k x c), plain fp32 FMA; k, c <= 128, k % 4 == 0, A 16-byte aligned with
 // lda % 4 == 0.  C may not alias A.  The first clear_rows rows of A (k columns each; may exceed `rows`) are
 // set to zero after they have been read.  transposed: the result is stored as C^T (c x rows, leading dimension ldc).
+// C (rows x b) = A1 B1 + A2 B2 (A2 null: one term); tall blocks and b x b factors, all with leading
+// dimension b <= 128 (b % 4 == 0), 16-byte aligned.  Afterwards the rows of A1 and the first zrows rows
+// of Zclr (may be null) are zero.
+int aser_combine_f32(aser_ctx* ctx, float* A1, const float* B1, const float* A2, const float* B2, float* C, int64_t rows,
+                     int b, float* Zclr, int64_t zrows);
 int aser_gemm_small_f32(aser_ctx* ctx, float* A, int64_t lda, const float* B, int64_t ldb,
                         float* C, int64_t ldc, int64_t rows, int k, int c, int64_t clear_rows = 0, bool transposed = false);

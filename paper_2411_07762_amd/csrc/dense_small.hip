@@ -208,6 +208,81 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(float* __restrict__ A, 
     }
 }
 
+// C (rows x b) = A1 B1 + A2 B2 for two tall blocks and two b x b factors (A2 null: one term), b a
+// multiple of 4 up to 128, all leading dimensions b.  After they have been read, the rows of A1 and
+// the first zrows rows of Zclr (may be null) are cleared: both are accumulation targets of the
+// products that follow.  Same staging as gemm_small_kernel, one term after the other.
+__global__ __launch_bounds__(256) void combine_kernel(float* __restrict__ A1, const float* __restrict__ B1,
+                                                      const float* __restrict__ A2, const float* __restrict__ B2,
+                                                      float* __restrict__ C, int64_t rows, int b,
+                                                      float* __restrict__ Zclr, int64_t zrows) {
+    extern __shared__ __align__(16) float gs_sm[];
+    float* As = gs_sm;                          // [16][132]
+    float* Bs = gs_sm + kGsRows * kGsPitch;     // [128][132]
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    const int64_t r0 = (int64_t)blockIdx.x * kGsRows;
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    for (int term = 0; term < 2; ++term) {
+        const float* A = term ? A2 : A1;
+        const float* B = term ? B2 : B1;
+        if (!A) break;
+        float4 av[2], bv[16];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
+            av[u] = zero4;
+            if (r0 + r < rows && k4 < b) av[u] = *(const float4*)(A + (r0 + r) * b + k4);
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int q = tid + 256 * u, kk = q >> 5, c4 = (q & 31) * 4;
+            bv[u] = zero4;
+            if (kk < b && c4 < b) bv[u] = *(const float4*)(B + (int64_t)kk * b + c4);
+        }
+        if (term) __syncthreads();                      // the first term's readers are done with the stages
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
+            *(float4*)(As + r * kGsPitch + k4) = av[u];
+            if (!term && r0 + r < rows && k4 < b) *(float4*)(A1 + (r0 + r) * b + k4) = zero4;
+            if (!term && Zclr && r0 + r < zrows && k4 < b) *(float4*)(Zclr + (r0 + r) * b + k4) = zero4;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int q = tid + 256 * u, kk = q >> 5, c4 = (q & 31) * 4;
+            *(float4*)(Bs + kk * kGsPitch + c4) = bv[u];
+        }
+        __syncthreads();
+        const float* arow = As + ty * kGsPitch;
+        const float* bcol = Bs + 8 * tx;
+#pragma unroll 4
+        for (int k4 = 0; k4 < b; k4 += 4) {
+            const float4 a4 = *(const float4*)(arow + k4);
+            const float aa[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float4 b0 = *(const float4*)(bcol + (k4 + e) * kGsPitch);
+                const float4 b1 = *(const float4*)(bcol + (k4 + e) * kGsPitch + 4);
+                acc[0] = fmaf(aa[e], b0.x, acc[0]); acc[1] = fmaf(aa[e], b0.y, acc[1]);
+                acc[2] = fmaf(aa[e], b0.z, acc[2]); acc[3] = fmaf(aa[e], b0.w, acc[3]);
+                acc[4] = fmaf(aa[e], b1.x, acc[4]); acc[5] = fmaf(aa[e], b1.y, acc[5]);
+                acc[6] = fmaf(aa[e], b1.z, acc[6]); acc[7] = fmaf(aa[e], b1.w, acc[7]);
+            }
+        }
+    }
+    const int64_t gr = r0 + ty;
+    if (gr < rows) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int cc = 8 * tx + j;
+            if (cc < b) C[gr * b + cc] = acc[j];
+        }
+    }
+}
+
 }  // namespace
 
 int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float* V, const int* gate) {
@@ -238,4 +313,23 @@ int aser_gemm_small_f32(aser_ctx* ctx, float* A, int64_t lda, const float* B, in
     hipLaunchKernelGGL(gemm_small_kernel, dim3((unsigned)ceil_div64(cover, kGsRows)), dim3(256), lds, ctx->stream, A, lda, B, ldb,
                        C, ldc, rows, k, c, clear_rows, vec_b, transposed ? 1 : 0);
     return aser_check_launch(ctx, "gemm_small");
+}
+
+int aser_combine_f32(aser_ctx* ctx, float* A1, const float* B1, const float* A2, const float* B2, float* C, int64_t rows,
+                     int b, float* Zclr, int64_t zrows) {
+    if (rows <= 0) return ASER_OK;
+    if (b <= 0 || b > 128 || (b & 3)) ASER_FAIL(ctx, ASER_ERR_SHAPE, "combine: need 0 < b <= 128, b % 4 == 0");
+    if (((uintptr_t)A1 & 15) || ((uintptr_t)B1 & 15) || ((uintptr_t)A2 & 15) || ((uintptr_t)B2 & 15) || ((uintptr_t)C & 15) ||
+        ((uintptr_t)Zclr & 15))
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "combine: operands must be 16-byte aligned");
+    static bool attr_set[16] = {false};
+    const size_t lds = (size_t)(kGsRows + 128) * kGsPitch * sizeof(float);
+    if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
+        ASER_HIP(ctx, hipFuncSetAttribute((const void*)combine_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set[ctx->device] = true;
+    }
+    const int64_t cover = (Zclr && zrows > rows) ? zrows : rows;
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)ceil_div64(cover, kGsRows)), dim3(256), lds, ctx->stream, A1, B1, A2, B2,
+                       C, rows, b, Zclr, zrows);
+    return aser_check_launch(ctx, "combine");
 }

@@ -5,7 +5,7 @@
 // Every large product is arranged in the K-major "A^T B" form of the MFMA kernel:
 //     A   = (T^T)^T S            A^T from a transpose pass
 //     Z   = A^T Q   (n x b)      K = m, operands A and Q
-//     Q   = A Z     (m x b)      K = n, operands A^T and Z
+//     A Zt          (m x b)      K = n, operands A^T and Zt = A^T Q = Z R_z (Z itself is never formed)
 //     Z^T Z, Q^T Q  (b x b)      Gram matrices of the Cholesky-QR orthogonalisation
 //     C^T = T^T Q   (n x b)      for L_B
 // The b x b work (Cholesky, inverse, symmetric eigen-solver) runs in one workgroup in LDS.
@@ -16,8 +16,9 @@
 // iteration k (A^T Q_k = Z R_z, then Y = Q_{k+1} R_q):
 //     Y = A Z - beta Q_{k-1} P_k R_z^-1,      P_{k+1} = R_z^-1 R_q^-1,
 // so the extra work is two products of b x b triangular matrices (done by the factorisation
-// kernel while R^-1 is still in LDS) and one tall-times-small product, which also replaces the
-// clearing of the accumulation target.  beta = (0.9 s^2 / 2)^2
+// kernel while R^-1 is still in LDS) and a second term in the tall-times-small product that applies
+// R_z^-1: Y = (A Zt) R_z^-1 + Q_{k-1} (-beta P_k R_z^-1) in one kernel, which also clears the two
+// accumulation targets it has read.  beta = (0.9 s^2 / 2)^2
 // with s the smallest diagonal entry of R_z: s^2 stays below the b-th eigenvalue of A A^T, which
 // keeps every wanted direction (eigenvalue above 2 sqrt(beta)) in the amplified regime.  On the
 // bulk of a quantisation-error spectrum this reaches in 10 iterations what the plain iteration
@@ -203,7 +204,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
 
     // start block and subspace iteration with momentum
     float *Qcur = tall[0], *Qold = tall[1], *Qacc = tall[2];   // Q_k, Q_{k-1} (or spare), accumulation target
-    float *Zt = tall[3], *Zs = tall[4];                        // Z accumulation target (kept zero), Z orthonormal
+    float *Zt = tall[3], *Qraw = tall[4];                      // accumulation targets of A^T Q and A Zt (kept zero)
     const int64_t mx = m > n ? m : n;
     {
         const int64_t total = m * (int64_t)b;
@@ -215,13 +216,15 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     ASER_TRY(aser_fill_f32(ctx, Zt, mx, b, b, 0.f));
     ASER_TRY(chol_qr(ctx, Qacc, Qcur, m, 0, b, Mb, Rq_inv, info));                 // Q_0
     const int bmA = 128, bnB = 128;
+    ASER_TRY(aser_fill_f32(ctx, Qraw, mx, b, b, 0.f));
     for (int it = 0; it < p.iters; ++it) {
-        ASER_TRY(gemm_tn_atomic(ctx, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // A^T Q_k
-        // = Z R_z (Zt is zero again); from the second iteration on also Bm = -beta P_k R_z^-1
-        ASER_TRY(chol_qr(ctx, Zt, Zs, n, mx, b, Mb, Rz_inv, info, it ? Pm : nullptr, it ? Bm : nullptr, true));
-        if (it == 0) ASER_TRY(aser_fill_f32(ctx, Qacc, mx, b, b, 0.f));
-        else ASER_TRY(aser_gemm_small_f32(ctx, Qold, b, Bm, b, Qacc, b, m, b, b));        // momentum term
-        ASER_TRY(gemm_tn_atomic(ctx, At, m, Zs, b, Qacc, b, m, b, n, bmA, bnB, false));   // + A Z
+        ASER_TRY(gemm_tn_atomic(ctx, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // Zt = A^T Q_k = Z R_z
+        // R_z^-1 (Z itself is never formed); from the second iteration on also Bm = -beta P_k R_z^-1
+        ASER_TRY(gemm_tn_atomic(ctx, Zt, b, Zt, b, Mb, b, b, b, n, 128, 128, false, /*upper_only=*/true));
+        ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rz_inv, info, 0, /*clear_d=*/true, it ? Pm : nullptr, it ? Bm : nullptr, true));
+        ASER_TRY(gemm_tn_atomic(ctx, At, m, Zt, b, Qraw, b, m, b, n, bmA, bnB, false));   // A Zt
+        // A Z + momentum term = (A Zt) R_z^-1 + Q_{k-1} Bm; Qraw and Zt are zero again afterwards
+        ASER_TRY(aser_combine_f32(ctx, Qraw, Rz_inv, it ? Qold : nullptr, Bm, Qacc, m, b, Zt, n));
         // = Q_{k+1} R_q, into the old block; also P_{k+1} = R_z^-1 R_q^-1
         ASER_TRY(chol_qr(ctx, Qacc, Qold, m, 0, b, Mb, Rq_inv, info, Rz_inv, Pm, false));
         { float* t = Qold; Qold = Qcur; Qcur = t; }
@@ -231,7 +234,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     // Rayleigh-Ritz: Z = A^T Q, eigen-pairs of Z^T Z = Q^T A A^T Q
     ASER_TRY(gemm_tn_atomic(ctx, A, n, Qp, b, Zt, b, n, b, m, bmA, bnB, false));
     float* Zp = Zt;
-    float* tp = Zs;
+    float* tp = Qraw;
     ASER_TRY(gemm_tn_atomic(ctx, Zp, b, Zp, b, Mb, b, b, b, n, 128, 128, false));
     ASER_TRY(aser_tridiag_eig(ctx, Mb, b, lambda, Uhat, refl, tri, cluster));
     ASER_TRY(aser_jacobi_eig(ctx, Mb, b, lambda, Uhat, cluster));      // only runs if eigenvalues cluster
