@@ -18,6 +18,37 @@ __device__ __forceinline__ bool beats(double sa, int ia, double sb, int ib) {
     return (sa > sb) || (sa == sb && ia < ib);
 }
 
+// The better of a lane's candidate and that of the lane a DPP pattern pairs it with.
+template <int CTRL>
+__device__ __forceinline__ void dpp_best(double& s, int& i) {
+    const int lo = __double2loint(s), hi = __double2hiint(s);
+    const int lo2 = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xF, 0xF, false);
+    const int hi2 = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xF, 0xF, false);
+    const int i2 = __builtin_amdgcn_update_dpp(i, i, CTRL, 0xF, 0xF, false);
+    const double s2 = __hiloint2double(hi2, lo2);
+    if (beats(s2, i2, s, i)) { s = s2; i = i2; }
+}
+
+// Best candidate of the wavefront, in every lane: four DPP steps inside each row of 16 lanes
+// (lane ^ 1, lane ^ 2, rotations by 4 and 8), then the four row results through scalar registers.
+__device__ __forceinline__ void wave_best(double& s, int& i) {
+    dpp_best<0xB1>(s, i);      // quad_perm [1, 0, 3, 2]
+    dpp_best<0x4E>(s, i);      // quad_perm [2, 3, 0, 1]
+    dpp_best<0x124>(s, i);     // row_ror 4
+    dpp_best<0x128>(s, i);     // row_ror 8
+    const int lo = __double2loint(s), hi = __double2hiint(s);
+    double bs = __hiloint2double(__builtin_amdgcn_readlane(hi, 0), __builtin_amdgcn_readlane(lo, 0));
+    int bi = __builtin_amdgcn_readlane(i, 0);
+#pragma unroll
+    for (int r = 16; r < 64; r += 16) {
+        const double rs = __hiloint2double(__builtin_amdgcn_readlane(hi, r), __builtin_amdgcn_readlane(lo, r));
+        const int ri = __builtin_amdgcn_readlane(i, r);
+        if (beats(rs, ri, bs, bi)) { bs = rs; bi = ri; }
+    }
+    s = bs;
+    i = bi;
+}
+
 __global__ __launch_bounds__(256) void score_kernel(const double* abs_sum, const int64_t* count, const double* wsum,
                                                     int64_t m, int64_t n, double* score) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -58,12 +89,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const double* __res
     for (int round = 0; round < f; ++round) {
         double s = best_s;
         int i = best_i;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const double s2 = __shfl_xor(s, o, 64);
-            const int i2 = __shfl_xor(i, o, 64);
-            if (beats(s2, i2, s, i)) { s = s2; i = i2; }
-        }
+        wave_best(s, i);
         // per-wave winners go to the buffer of this round's parity; every thread then finds the
         // overall winner itself, so one barrier per round is enough
         double* rs = red_s[round & 1];
