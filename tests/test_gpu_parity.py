@@ -447,6 +447,44 @@ def test_large_layers_full_size_sampled(cfg):
     assert np.all(np.diff(sigma) <= 1e-6 * sigma[0])
 
 
+def test_quantizers_with_denormal_scales():
+    """Rows whose absmax / qmax is a denormal or tiny fp32 number: the reciprocal of such a scale is not
+    finite, so the kernels must take true divisions there; codes and scales stay bit-exact."""
+    spec = synth.mini("qd", 12, 512, 64, f=4)
+    W = synth.make_weight(spec)
+    W[2, :] *= np.float32(1e-37)                                 # scale ~ 1e-39 (int4) / 5e-41 (int8): denormal
+    W[5, :] *= np.float32(1e-30)                                 # tiny but normal
+    x_np = synth.make_activations(spec)
+    _, abs_ref, cnt = orc.gram(synth.activations_as_f32(spec, x_np))
+    sm = orc.smooth_outliers(W, abs_ref, cnt, spec.f)
+    idx = torch.from_numpy(sm.idx).to(DEV)
+    mdiag = torch.from_numpy(sm.mdiag).to(DEV)
+    for bits, packed in ((4, True), (8, False)):
+        ref = orc.quantize_rtn(W, sm.idx, sm.mdiag, bits)
+        ctx = new_ctx()
+        codes = torch.zeros((spec.m, spec.n // 2 if packed else spec.n), dtype=torch.uint8 if packed else torch.int8, device=DEV)
+        scales = torch.empty(spec.m, dtype=torch.float32, device=DEV)
+        T = torch.empty((spec.m, spec.n), dtype=torch.float32, device=DEV)
+        layout = aser.ASER_CODES_INT4_PACKED if packed else aser.ASER_CODES_INT8
+        ctx.check(aser.aser_quantize_rtn(ctx, torch.from_numpy(W).to(DEV), idx, mdiag, spec.f, bits, layout, codes, scales, T))
+        torch.cuda.synchronize()
+        got = codes.cpu().numpy()
+        assert np.array_equal(unpack_int4(got) if packed else got, ref.codes)
+        assert np.array_equal(scales.cpu().numpy(), ref.scales)
+    X = synth.activations_as_f32(spec, x_np).copy()
+    X[3, :] *= np.float32(1e-37)
+    X[9, :] = 0.0
+    X[9, 5] = np.float32(1e-41)                                  # a single denormal entry: scale 7.8e-44
+    ref_codes, ref_scales = orc.quantize_act_rtn(X, sm.mdiag, 8)
+    ctx = new_ctx()
+    codes = torch.empty((X.shape[0], spec.n), dtype=torch.int8, device=DEV)
+    scales = torch.empty(X.shape[0], dtype=torch.float32, device=DEV)
+    ctx.check(aser.aser_quantize_act_rtn(ctx, torch.from_numpy(X).to(DEV), mdiag, 8, codes, scales))
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), ref_codes)
+    assert np.array_equal(scales.cpu().numpy(), ref_scales)
+
+
 def test_deterministic_integer_outputs():
     spec = synth.mini("d1", 130, 520, 1500, r=16, f=8)
     W = torch.from_numpy(synth.make_weight(spec)).to(DEV)
