@@ -107,22 +107,35 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
     // contribution of all finished rows above it in one product with a long K (split over
     // workgroups, fp32 atomics), then its diagonal block is factored and the row is multiplied by
     // the inverse of that factor.  Every entry of the matrix is updated once, by one launch.
+    // Wide matrices take the long-K update for two block rows at a time (256 x 256 tiles convert each
+    // fp32 operand element once per 256 instead of 128 result columns or rows); the second block row of
+    // a pair then still lacks the contribution of the first, a K = 128 update of its own.
+    const bool pairs = n >= 12288;   // measured: 11008 columns are still faster one block row at a time
+    auto update = [&](int64_t row0, int64_t rows, int64_t kfrom, int64_t klen, int bm, int bn) -> int {
+        GemmArgs u{};
+        u.A = S + kfrom * lds + row0; u.lda = lds; u.B = S + kfrom * lds + row0; u.ldb = lds;
+        u.C = S + row0 * lds + row0; u.ldc = lds; u.Ct = nullptr; u.ldct = 0;
+        u.M = rows; u.N = n - row0; u.K = klen; u.alpha = -1.f;
+        u.in_type = GEMM_IN_F32X3; u.epi = GEMM_EPI_ATOMIC; u.tiles = GEMM_TILES_ALL; u.krange = GEMM_K_FULL;
+        u.bm = bm; u.bn = bn; u.upper_only = 1;
+        const int64_t tiles = ceil_div64(u.M, u.bm) * ceil_div64(u.N, u.bn), ksteps = ceil_div64(klen, 32);
+        int64_t parts = ceil_div64(256, tiles);
+        const int64_t max_parts = ksteps / 4 > 0 ? ksteps / 4 : 1;
+        if (parts > max_parts) parts = max_parts;
+        u.k_parts = (int)parts;
+        return aser_gemm_tn(ctx, u);
+    };
     for (int64_t k0 = 0; k0 < n; k0 += kNb) {
         const int b = (int)((n - k0 < kNb) ? n - k0 : kNb);
         float* D = S + k0 * lds + k0;
-        if (k0 > 0) {
-            GemmArgs u{};
-            u.A = S + k0; u.lda = lds; u.B = S + k0; u.ldb = lds;
-            u.C = D; u.ldc = lds; u.Ct = nullptr; u.ldct = 0;
-            u.M = b; u.N = n - k0; u.K = k0; u.alpha = -1.f;
-            u.in_type = GEMM_IN_F32X3; u.epi = GEMM_EPI_ATOMIC; u.tiles = GEMM_TILES_ALL; u.krange = GEMM_K_FULL;
-            u.bm = 128; u.bn = (u.N >= 4096) ? 256 : 128; u.upper_only = 1;
-            const int64_t tiles = ceil_div64(u.N, u.bn), ksteps = ceil_div64(k0, 32);
-            int64_t parts = ceil_div64(256, tiles);
-            const int64_t max_parts = ksteps / 4 > 0 ? ksteps / 4 : 1;
-            if (parts > max_parts) parts = max_parts;
-            u.k_parts = (int)parts;
-            ASER_TRY(aser_gemm_tn(ctx, u));
+        if (pairs) {
+            if (k0 % (2 * kNb) == 0) {
+                if (k0 > 0) ASER_TRY(update(k0, (n - k0 < 2 * kNb) ? n - k0 : 2 * kNb, 0, k0, 256, 256));
+            } else {
+                ASER_TRY(update(k0, b, k0 - kNb, kNb, 128, 256));
+            }
+        } else if (k0 > 0) {
+            ASER_TRY(update(k0, b, 0, k0, 128, (n - k0 >= 4096) ? 256 : 128));
         }
         ASER_TRY(aser_chol_block(ctx, D, lds, b, Rinv, info_dev, (int32_t)k0));
         const int64_t rem = n - k0 - b;
