@@ -458,7 +458,10 @@ __global__ __launch_bounds__(256) void act_rtn_wave_kernel(const void* __restric
     const int64_t row1 = (row0 + tokens_per_wave < rows) ? row0 + tokens_per_wave : rows;
     const int64_t row_bytes = ldx * (BF16 ? 2 : 4);
 
-    float m[4][16];
+    // The lane's 64 entries of M go to LDS ([slot][lane]; the four wavefronts of a workgroup hold the
+    // same channels, so each writes the same values): the division slots read them back, and the
+    // registers stay free for a third and fourth wavefront per SIMD.
+    __shared__ float m_lds[64 * 64];
     uint64_t slots = 0;                                  // bit 16 u + e: some lane's channel of that slot has m != 1
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -467,12 +470,15 @@ __global__ __launch_bounds__(256) void act_rtn_wave_kernel(const void* __restric
         for (int q = 0; q < 4; ++q) {
             float4 m4 = make_float4(1.f, 1.f, 1.f, 1.f);
             if (mdiag && c < n) m4 = *(const float4*)(mdiag + c + 4 * q);
-            m[u][4 * q] = m4.x; m[u][4 * q + 1] = m4.y; m[u][4 * q + 2] = m4.z; m[u][4 * q + 3] = m4.w;
-        }
+            const float mm[4] = {m4.x, m4.y, m4.z, m4.w};
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-            if (__builtin_amdgcn_ballot_w64(m[u][e] != 1.f) != 0) slots |= 1ull << (16 * u + e);
+            for (int e = 0; e < 4; ++e) {
+                m_lds[(16 * u + 4 * q + e) * 64 + lane] = mm[e];
+                if (__builtin_amdgcn_ballot_w64(mm[e] != 1.f) != 0) slots |= 1ull << (16 * u + 4 * q + e);
+            }
+        }
     }
+    // no barrier: a wavefront reads only what it wrote itself (the other wavefronts write the same values)
 
     u32x4_t raw[BF16 ? 8 : 16];
     act_load_token<BF16>((const char*)X + row0 * row_bytes, n, lane, raw);
@@ -499,7 +505,7 @@ __global__ __launch_bounds__(256) void act_rtn_wave_kernel(const void* __restric
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 if ((slots >> (16 * u + e)) & 1) {
-                    v[u][e] = v[u][e] / m[u][e];
+                    v[u][e] = v[u][e] / m_lds[(16 * u + e) * 64 + lane];
                     asm volatile("" : "+v"(v[u][e]));     // keeps the division behind its branch
                 }
                 amax = fmaxf(amax, fabsf(v[u][e]));
@@ -675,7 +681,7 @@ extern "C" int aser_quantize_act_rtn(aser_ctx* ctx, const void* X, int x_dtype, 
     if (wave_ok) {
         // several tokens per wavefront once there are enough tokens for four workgroups per compute unit
         int tpw = (int)(rows / 4096);
-        tpw = tpw < 1 ? 1 : (tpw > 8 ? 8 : tpw);
+        tpw = tpw < 1 ? 1 : (tpw > 4 ? 4 : tpw);                 // 2 to 8 measure alike, 16 is slower
         dim3 wgrid((unsigned)ceil_div64(rows, 4 * (int64_t)tpw));
         if (x_dtype == ASER_DTYPE_BF16)
             hipLaunchKernelGGL(act_rtn_wave_kernel<true>, wgrid, dim3(256), 0, ctx->stream, X, rows, n, ldx, mdiag, qmax, codes, scales, tpw);
