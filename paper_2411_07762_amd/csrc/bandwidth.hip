@@ -395,7 +395,9 @@ __global__ __launch_bounds__(NT) void act_rtn_kernel(const void* __restrict__ X,
     }
     amax = block_max(amax, red);
     const float scale = (amax == 0.f) ? 1.f : amax / qmax;
-    const float rscale = __builtin_amdgcn_rcpf(scale);
+    // the reciprocal of a denormal scale is not finite: such a token takes true divisions throughout
+    const bool plain = __builtin_amdgcn_readfirstlane(scale > 1e-30f ? 1 : 0) != 0;
+    const float rscale = plain ? __builtin_amdgcn_rcpf(scale) : 0.f;
     if (tid == 0) scales[row] = scale;
     int8_t* crow = codes + row * n;
     const bool c_vec = (((uintptr_t)crow & 7) == 0) && ((n & 7) == 0);
@@ -403,18 +405,32 @@ __global__ __launch_bounds__(NT) void act_rtn_kernel(const void* __restrict__ X,
     for (int u = 0; u < VPT; ++u) {
         const int64_t c = ((int64_t)u * NT + tid) * 8;
         if (c >= n) continue;
-        int q[8];
+        // rint(x / scale) from the reciprocal multiply (error below 4e-5 for |quotient| <= 128); one test
+        // per group for a quotient within 1e-4 of a rounding boundary k + 1/2, where the division decides
+        float r[8], dist[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float qf = rint_div(v[u][e], scale, rscale);
-            qf = fminf(fmaxf(qf, -qmax), qmax);
-            q[e] = (int)qf;
+            const float tq = v[u][e] * rscale;
+            r[e] = rintf(tq);
+            dist[e] = fabsf(tq - r[e]);
         }
+        const float far = fmaxf(fmaxf(fmaxf(dist[0], dist[1]), fmaxf(dist[2], dist[3])),
+                                fmaxf(fmaxf(dist[4], dist[5]), fmaxf(dist[6], dist[7])));
+        if (!plain || __builtin_amdgcn_ballot_w64(far > 0.4999f) != 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (!plain || dist[e] > 0.4999f) r[e] = rintf(v[u][e] / scale);
+                asm volatile("" : "+v"(r[e]));                // keeps the division behind its branch
+            }
+        }
+        int q[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) q[e] = (int)r[e];
         if (c_vec) {
-            const u32x2_t pk = {(uint32_t)(q[0] & 0xFF) | ((uint32_t)(q[1] & 0xFF) << 8) | ((uint32_t)(q[2] & 0xFF) << 16) |
-                                    ((uint32_t)(q[3] & 0xFF) << 24),
-                                (uint32_t)(q[4] & 0xFF) | ((uint32_t)(q[5] & 0xFF) << 8) | ((uint32_t)(q[6] & 0xFF) << 16) |
-                                    ((uint32_t)(q[7] & 0xFF) << 24)};
+            const u32x2_t pk = {__builtin_amdgcn_perm((uint32_t)q[1], (uint32_t)q[0], 0x0c0c0400u) |
+                                    __builtin_amdgcn_perm((uint32_t)q[3], (uint32_t)q[2], 0x04000c0cu),
+                                __builtin_amdgcn_perm((uint32_t)q[5], (uint32_t)q[4], 0x0c0c0400u) |
+                                    __builtin_amdgcn_perm((uint32_t)q[7], (uint32_t)q[6], 0x04000c0cu)};
             __builtin_nontemporal_store(pk, (u32x2_t*)(crow + c));
         } else {
 #pragma unroll
