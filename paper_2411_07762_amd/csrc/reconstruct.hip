@@ -199,24 +199,22 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         g.bm = g.pair_cols ? 256 : 128; g.bn = 128;
         ASER_TRY(aser_gemm_tn(ctx, g));
     }
-    ASER_TRY(aser_fill_bytes(ctx, normA2, 8));
-    ASER_TRY(aser_fill_bytes(ctx, info, 4));
+    // two clearing passes for everything that must start at zero: the scalars (lambda .. cluster share
+    // 4 KB) and, contiguous in the workspace, the two accumulation targets and Mb
+    ASER_TRY(aser_fill_bytes(ctx, lambda, 4096));
+    ASER_TRY(aser_fill_bytes(ctx, tall[3], 2 * p.tall_bytes + bb));
 
     // start block and subspace iteration with momentum
     float *Qcur = tall[0], *Qold = tall[1], *Qacc = tall[2];   // Q_k, Q_{k-1} (or spare), accumulation target
     float *Zt = tall[3], *Qraw = tall[4];                      // accumulation targets of A^T Q and A Zt (kept zero)
-    const int64_t mx = m > n ? m : n;
     {
         const int64_t total = m * (int64_t)b;
         const int blocks = (int)(ceil_div64(total, 256) < 2048 ? ceil_div64(total, 256) : 2048);
         hipLaunchKernelGGL(random_block_kernel, dim3(blocks), dim3(256), 0, ctx->stream, Qacc, total, p.seed);
         ASER_TRY(aser_check_launch(ctx, "random_block"));
     }
-    ASER_TRY(aser_fill_f32(ctx, Mb, b, b, b, 0.f));
-    ASER_TRY(aser_fill_f32(ctx, Zt, mx, b, b, 0.f));
     ASER_TRY(chol_qr(ctx, Qacc, Qcur, m, 0, b, Mb, Rq_inv, info));                 // Q_0
     const int bmA = 128, bnB = 128;
-    ASER_TRY(aser_fill_f32(ctx, Qraw, mx, b, b, 0.f));
     for (int it = 0; it < p.iters; ++it) {
         ASER_TRY(gemm_tn_atomic(ctx, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // Zt = A^T Q_k = Z R_z
         // R_z^-1 (Z itself is never formed); from the second iteration on also Bm = -beta P_k R_z^-1
