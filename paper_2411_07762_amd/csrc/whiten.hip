@@ -69,10 +69,23 @@ __global__ __launch_bounds__(256) void diag_scaled_sum_kernel(const float* G, in
 
 __global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
 
+// 16 rows x 1024 columns per workgroup, 16-byte stores where a whole group of four lies right of the diagonal
 __global__ __launch_bounds__(256) void zero_strict_upper_kernel(float* S, int64_t n, int64_t lds) {
-    const int64_t r = blockIdx.y;
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (c < n && c > r) S[r * lds + c] = 0.f;
+    const int64_t c = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c >= n) return;
+    const int64_t r0 = (int64_t)blockIdx.y * 16;
+    if (c + 3 <= r0) return;                              // left of the diagonal for every row of the strip
+#pragma unroll 4
+    for (int64_t r = r0; r < r0 + 16 && r < n; ++r) {
+        float* p = S + r * lds + c;
+        if (c > r && c + 3 < n && ((((uintptr_t)p) & 15) == 0)) {
+            *(float4*)p = make_float4(0.f, 0.f, 0.f, 0.f);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (c + e < n && c + e > r) p[e] = 0.f;
+        }
+    }
 }
 
 }  // namespace
@@ -149,8 +162,8 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
         p.k_parts = 1; p.bm = 128; p.bn = (rem > 128) ? 256 : 128;
         ASER_TRY(aser_gemm_tn(ctx, p));
     }
-    hipLaunchKernelGGL(zero_strict_upper_kernel, dim3((unsigned)ceil_div64(n, 256), (unsigned)n), dim3(256), 0, ctx->stream,
-                       S, n, lds);
+    hipLaunchKernelGGL(zero_strict_upper_kernel, dim3((unsigned)ceil_div64(n, 1024), (unsigned)ceil_div64(n, 16)), dim3(256), 0,
+                       ctx->stream, S, n, lds);
     ASER_TRY(aser_check_launch(ctx, "zero_upper"));
 
     int32_t h_info = 0;
