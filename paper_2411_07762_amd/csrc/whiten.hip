@@ -5,8 +5,8 @@
 //   update           G'[k:k+b, k:] -= R[:k, k:k+b]^T R[:k, k:]   (A, B = the finished rows above; K = k)
 //   diagonal block   R11 = chol(D), R11^-1                       (one workgroup, LDS)
 //   row panel        R12 = (R11^-1)^T * G'[k, k+b:]              (A = R11^-1, B = the panel, in place)
-// The panel kernel also writes R12^T below the diagonal, so the lower triangle fills up with
-// S = R^T as the factorisation proceeds; a final pass clears the strict upper triangle.
+// A final pass moves R to the lower triangle (S = R^T) and clears the strict upper triangle; writing
+// R12^T from the panel kernel instead cost 4 us per panel in scattered 16-byte stores.
 #include <limits.h>
 
 #include "aser_internal.h"
@@ -69,22 +69,30 @@ __global__ __launch_bounds__(256) void diag_scaled_sum_kernel(const float* G, in
 
 __global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
 
-// 16 rows x 1024 columns per workgroup, 16-byte stores where a whole group of four lies right of the diagonal
-__global__ __launch_bounds__(256) void zero_strict_upper_kernel(float* S, int64_t n, int64_t lds) {
-    const int64_t c = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (c >= n) return;
-    const int64_t r0 = (int64_t)blockIdx.y * 16;
-    if (c + 3 <= r0) return;                              // left of the diagonal for every row of the strip
-#pragma unroll 4
-    for (int64_t r = r0; r < r0 + 16 && r < n; ++r) {
-        float* p = S + r * lds + c;
-        if (c > r && c + 3 < n && ((((uintptr_t)p) & 15) == 0)) {
-            *(float4*)p = make_float4(0.f, 0.f, 0.f, 0.f);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (c + e < n && c + e > r) p[e] = 0.f;
+// The factor was built as R = S^T in the upper triangle.  One pass over pairs of 64 x 64 tiles moves it
+// to the lower triangle (through LDS, both sides coalesced) and clears the strict upper triangle.
+__global__ __launch_bounds__(256) void upper_to_lower_kernel(float* S, int64_t n, int64_t lds) {
+    __shared__ float tile[64][65];
+    const int64_t t = blockIdx.x;
+    int64_t bi = (int64_t)((sqrt(8.0 * (double)t + 1.0) - 1.0) * 0.5);
+    while (bi * (bi + 1) / 2 > t) --bi;
+    while ((bi + 1) * (bi + 2) / 2 <= t) ++bi;
+    const int64_t bj = t - bi * (bi + 1) / 2;          // bi >= bj: upper tile (bj, bi) -> lower tile (bi, bj)
+    const int64_t u0 = bj * 64, v0 = bi * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int i = ty; i < 64; i += 4) {
+        const int64_t r = u0 + i, c = v0 + tx;
+        float v = 0.f;
+        if (r < n && c < n) {
+            v = S[r * lds + c];
+            if (c > r) S[r * lds + c] = 0.f;
         }
+        tile[i][tx] = v;
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        const int64_t r = v0 + i, c = u0 + tx;          // lower entry (r, c) = upper entry (c, r)
+        if (r < n && c < n && r > c) S[r * lds + c] = tile[tx][i];
     }
 }
 
@@ -156,15 +164,14 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
         float* S12 = S + k0 * lds + (k0 + b);
         GemmArgs p{};
         p.A = Rinv; p.lda = b; p.B = S12; p.ldb = lds; p.C = S12; p.ldc = lds;
-        p.Ct = S + (k0 + b) * lds + k0; p.ldct = lds;
+        p.Ct = nullptr; p.ldct = 0;
         p.M = b; p.N = rem; p.K = b; p.alpha = 1.f;
         p.in_type = GEMM_IN_F32X3; p.epi = GEMM_EPI_STORE; p.tiles = GEMM_TILES_ALL; p.krange = GEMM_K_FULL;
         p.k_parts = 1; p.bm = 128; p.bn = (rem > 128) ? 256 : 128;
         ASER_TRY(aser_gemm_tn(ctx, p));
     }
-    hipLaunchKernelGGL(zero_strict_upper_kernel, dim3((unsigned)ceil_div64(n, 1024), (unsigned)ceil_div64(n, 16)), dim3(256), 0,
-                       ctx->stream, S, n, lds);
-    ASER_TRY(aser_check_launch(ctx, "zero_upper"));
+    hipLaunchKernelGGL(upper_to_lower_kernel, dim3((unsigned)(t64 * (t64 + 1) / 2)), dim3(256), 0, ctx->stream, S, n, lds);
+    ASER_TRY(aser_check_launch(ctx, "upper_to_lower"));
 
     int32_t h_info = 0;
     ASER_HIP(ctx, hipMemcpyAsync(&h_info, info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
