@@ -40,11 +40,12 @@ __global__ __launch_bounds__(256) void whiten_prep_kernel(const float* G, int64_
         tile[i][tx] = v;
     }
     __syncthreads();
-    for (int i = ty; i < 64; i += 4) {
-        const int64_t r = r0 + i, c = c0 + tx;
-        if (r < n && c < n) S[r * lds + c] = tile[i][tx];
-    }
-    if (bi != bj) {
+    if (bi == bj) {                                      // only the upper triangle is worked on from here
+        for (int i = ty; i < 64; i += 4) {
+            const int64_t r = r0 + i, c = c0 + tx;
+            if (r < n && c < n) S[r * lds + c] = tile[i][tx];
+        }
+    } else {
         for (int i = ty; i < 64; i += 4) {
             const int64_t r = c0 + i, c = r0 + tx;      // transposed tile
             if (r < n && c < n) S[r * lds + c] = tile[tx][i];
