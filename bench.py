@@ -320,7 +320,7 @@ def main():
         "dtype": "bf16" if spec.x_dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: W %dx%d fp32, X %dx%d %s, W%d per-channel RTN, r=%d, f=%d" %
                                (spec.name, spec.m, spec.n, spec.tokens, spec.n, spec.x_dtype, spec.bits, spec.r, spec.f),
-                   "svd_block": 2 * spec.r if 2 * spec.r <= 128 else 128, "svd_iters": 24 if spec.r > 64 else (12 if max(spec.m, spec.n) > 8192 else 10)},
+                   "svd_block": 2 * spec.r if 2 * spec.r <= 128 else 128, "svd_iters": 24 if spec.r > 64 else (12 if max(spec.m, spec.n) > 8192 else 9)},
         "layers_per_s": 1e3 / ms_per_step,
         "calibration_tokens_per_s": spec.tokens * 1e3 / ms_per_step,
         "stage_ms": {k: round(v, 4) for k, v in zip(stage_names, stage_ms)},

@@ -65,7 +65,7 @@ typedef enum aser_code_layout {
 typedef struct aser_svd_opts {
     int32_t block;      /* subspace width b (multiple of 32, r <= b <= 128); default: the
                            smallest multiple of 32 that is >= min(2 r, 128) and >= r        */
-    int32_t max_iter;   /* number of subspace iterations (A A^T applications); default 10, 12 when max(m, n) > 8192,
+    int32_t max_iter;   /* number of subspace iterations (A A^T applications); default 9, 12 when max(m, n) > 8192,
                            24 when block < 2 r */
     uint32_t seed;      /* seed of the random start block; default 1                       */
     int32_t reserved;
