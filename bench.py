@@ -234,7 +234,7 @@ def main():
         mark(3)
         ctx.check(aser.aser_quantize_rtn(ctx, W, buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes, buf.scales, buf.T))
         mark(4)
-        st, info = aser.aser_whiten(ctx, buf.G, buf.mdiag, 0.0, buf.S)
+        st, info = aser.aser_whiten(ctx, buf.G, buf.mdiag, 0.0, buf.S, want_info=False)   # pivot check at the layer's one sync
         ctx.check(st)
         mark(5)
         st, err, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma)

@@ -130,9 +130,11 @@ int aser_quantize_rtn(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64
  *     S = lower Cholesky factor, S S^T = G'
  * Reads the lower triangle of G (n x n, ldg); writes S (n x n, lds) with zeros above the
  * diagonal.  S may alias G (in place).  mdiag may be NULL (M = I).  damp >= 0, normally 0.
- * *info (host, may be NULL): 0, or the 1-based index of the first non-positive pivot, in
- * which case ASER_ERR_NOT_SPD is returned and S is unspecified.  Synchronises the stream.
- * Needs workspace. */
+ * *info (host): 0, or the 1-based index of the first non-positive pivot, in which case
+ * ASER_ERR_NOT_SPD is returned and S is unspecified; the call then synchronises the stream.
+ * info == NULL: the call stays asynchronous; a non-positive pivot is then reported (as
+ * ASER_ERR_NOT_SPD) by the next aser_error_reconstruct or aser_set_workspace on this context,
+ * whose result is unspecified in that case.  Needs workspace. */
 int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n, const float* mdiag, float damp,
                 float* S, int64_t lds, int32_t* info);
 

@@ -149,9 +149,12 @@ class Context:
         except Exception:
             pass
 
+    def last_error(self) -> str:
+        return self._lib.aser_last_error(self.handle).decode()
+
     def check(self, status: int):
         if status != ASER_OK:
-            raise AserError(status, self._lib.aser_last_error(self.handle).decode())
+            raise AserError(status, self.last_error())
 
     def ensure_workspace(self, nbytes: int):
         """Allocates (with torch) and binds a workspace of at least nbytes."""
@@ -197,13 +200,14 @@ def aser_quantize_rtn(ctx: Context, W, idx, mdiag, f: int, bits: int, layout: in
                                       (_ld(T, n) if T is not None else n) if ldt is None else ldt)
 
 
-def aser_whiten(ctx: Context, G, mdiag, damp: float, S, *, n=None, ldg=None, lds=None):
-    """Returns (status, info)."""
+def aser_whiten(ctx: Context, G, mdiag, damp: float, S, *, n=None, ldg=None, lds=None, want_info: bool = True):
+    """Returns (status, info).  want_info=False passes info = NULL: no synchronisation, a non-positive
+    pivot is reported by the next aser_error_reconstruct on this context (info is returned as None)."""
     n = G.shape[0] if n is None else n
     info = ctypes.c_int32(0)
     st = ctx._lib.aser_whiten(ctx.handle, _ptr(G), _ld(G, n) if ldg is None else ldg, n, _ptr(mdiag), float(damp),
-                              _ptr(S), _ld(S, n) if lds is None else lds, ctypes.byref(info))
-    return st, info.value
+                              _ptr(S), _ld(S, n) if lds is None else lds, ctypes.byref(info) if want_info else None)
+    return st, (info.value if want_info else None)
 
 
 def aser_error_reconstruct(ctx: Context, T, S, r: int, L_A, L_B, sigma, opts: Optional[aser_svd_opts] = None, *,
@@ -269,7 +273,7 @@ def calibrate_layer(ctx: Context, W, X, buf: LayerBuffers, opts: Optional[aser_s
         ctx.check(aser_gram_accumulate(ctx, X, buf.G, buf.abs_sum, buf.count))
     ctx.check(aser_smooth_outliers(ctx, W, buf.abs_sum, buf.count, buf.f, buf.idx, buf.mdiag))
     ctx.check(aser_quantize_rtn(ctx, W, buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes, buf.scales, buf.T))
-    st, info = aser_whiten(ctx, buf.G, buf.mdiag, damp, buf.S)
+    st, _ = aser_whiten(ctx, buf.G, buf.mdiag, damp, buf.S, want_info=False)   # pivot check at the layer's one sync
     ctx.check(st)
     st, err, _ = aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, opts)
     ctx.check(st)

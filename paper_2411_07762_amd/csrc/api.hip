@@ -1,4 +1,5 @@
 // Context management and stage 1 (Gram accumulation, Eq. 5) of the C ABI.
+#include <limits.h>
 #include <new>
 
 #include "aser_internal.h"
@@ -26,6 +27,7 @@ extern "C" int aser_create(aser_ctx** out, int device, void* hip_stream) {
     c->ws = nullptr;
     c->ws_bytes = 0;
     c->device_ready = false;
+    c->pending_info_dev = nullptr;
     c->err[0] = 0;
     *out = c;
     return ASER_OK;
@@ -43,6 +45,14 @@ extern "C" int aser_set_workspace(aser_ctx* ctx, void* dev_ptr, size_t bytes) {
     if (!ctx) return ASER_ERR_INVALID_ARG;
     if (dev_ptr && ((uintptr_t)dev_ptr & 255)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "set_workspace: pointer must be 256-byte aligned");
     if (!dev_ptr && bytes) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "set_workspace: null pointer with non-zero size");
+    if (ctx->pending_info_dev) {
+        // a deferred pivot flag lives in the old workspace: fetch it before that memory goes away
+        int32_t h = INT_MAX;
+        ASER_HIP(ctx, hipMemcpyAsync(&h, ctx->pending_info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+        ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        ctx->pending_info_dev = nullptr;
+        if (h != INT_MAX && h != 0) ASER_FAIL(ctx, ASER_ERR_NOT_SPD, "whiten: non-positive pivot at index %d", h);
+    }
     ctx->ws = dev_ptr;
     ctx->ws_bytes = dev_ptr ? bytes : 0;
     return ASER_OK;
@@ -51,13 +61,13 @@ extern "C" int aser_set_workspace(aser_ctx* ctx, void* dev_ptr, size_t bytes) {
 extern "C" size_t aser_workspace_bytes(int64_t m, int64_t n, int32_t r, const aser_svd_opts* opts) {
     if (m <= 0 || n <= 0) return 0;
     size_t need = align_up((size_t)n * 8, 256) * 2;             // smoothing: column sums of |W|, scores
-    const size_t chol = (size_t)128 * 128 * 4 + 512;            // whitening: inverse of a diagonal block, info
+    const size_t chol = (size_t)128 * 128 * 4 + 512;            // whitening: inverse of a diagonal block, damping sum
     if (chol > need) need = chol;
     if (r > 0) {
         const size_t rec = aser_reconstruct_workspace(m, n, r, opts);
         if (rec > need) need = rec;
     }
-    return need;
+    return need + kAserWsTail;                                  // the whitening's pivot flag sits behind everything
 }
 
 int aser_prepare_device(aser_ctx* ctx) {

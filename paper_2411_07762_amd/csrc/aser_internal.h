@@ -14,8 +14,14 @@ struct aser_ctx {
     void* ws;
     size_t ws_bytes;
     bool device_ready;
+    // aser_whiten without a host `info` leaves its pivot flag on the device (last 256 bytes of the
+    // workspace) and does not synchronise; the next synchronising call reads it.
+    int32_t* pending_info_dev;
     char err[256];
 };
+
+// Bytes at the end of the bound workspace that hold the whitening's pivot flag.
+static const size_t kAserWsTail = 256;
 
 #define ASER_FAIL(ctx, code, ...)                                   \
     do {                                                            \

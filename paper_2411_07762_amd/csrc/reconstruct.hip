@@ -23,6 +23,7 @@
 // keeps every wanted direction (eigenvalue above 2 sqrt(beta)) in the amplified regime.  On the
 // bulk of a quantisation-error spectrum this reaches in 10 iterations what the plain iteration
 // needs about 16 for; the excess over the optimal whitened error halves with every iteration.
+#include <limits.h>
 #include <math.h>
 
 #include "aser_internal.h"
@@ -156,7 +157,8 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         make_plan(m, n, r, &o2, &p);
     }
     if (((uintptr_t)T & 3) || ((uintptr_t)S & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "error_reconstruct: misaligned pointer");
-    if (!ctx->ws || ctx->ws_bytes < p.total) ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "error_reconstruct: workspace too small (%zu needed)", p.total);
+    if (!ctx->ws || ctx->ws_bytes < p.total + kAserWsTail)
+        ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "error_reconstruct: workspace too small (%zu needed)", p.total + kAserWsTail);
     ASER_TRY(aser_prepare_device(ctx));
 
     char* ws = (char*)ctx->ws;
@@ -261,8 +263,14 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, WBt, r, L_B, n, n, b, r, 0, true));   // (n x r)^T = L_B
 
     double h_res2 = 0.0;
+    int32_t h_pivot = INT_MAX;
     ASER_HIP(ctx, hipMemcpyAsync(&h_res2, normA2, 8, hipMemcpyDeviceToHost, ctx->stream));
+    if (ctx->pending_info_dev)                           // pivot flag of a whitening that did not synchronise
+        ASER_HIP(ctx, hipMemcpyAsync(&h_pivot, ctx->pending_info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->pending_info_dev = nullptr;
+    if (h_pivot != INT_MAX && h_pivot != 0)
+        ASER_FAIL(ctx, ASER_ERR_NOT_SPD, "whiten: non-positive pivot at index %d (reported by error_reconstruct)", h_pivot);
     if (err) *err = sqrt(h_res2 > 0.0 ? h_res2 : 0.0);
     if (n_iter) *n_iter = p.iters;
     return ASER_OK;

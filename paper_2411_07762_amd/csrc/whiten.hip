@@ -106,12 +106,12 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
     if (n <= 0 || ldg < n || lds < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "whiten: bad shape");
     if (!(damp >= 0.f)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "whiten: damp must be >= 0");
     if (((uintptr_t)G & 3) || ((uintptr_t)S & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "whiten: misaligned pointer");
-    const size_t need = (size_t)kNb * kNb * 4 + 512;
+    const size_t need = (size_t)kNb * kNb * 4 + 512 + kAserWsTail;
     if (!ctx->ws || ctx->ws_bytes < need) ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "whiten: workspace too small");
     ASER_TRY(aser_prepare_device(ctx));
 
     float* Rinv = (float*)ctx->ws;
-    int32_t* info_dev = (int32_t*)((char*)ctx->ws + (size_t)kNb * kNb * 4);
+    int32_t* info_dev = (int32_t*)((char*)ctx->ws + ctx->ws_bytes - kAserWsTail);
     double* diag_sum = (double*)((char*)ctx->ws + (size_t)kNb * kNb * 4 + 256);
 
     hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, info_dev, (int32_t)INT_MAX);
@@ -174,11 +174,16 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
     hipLaunchKernelGGL(upper_to_lower_kernel, dim3((unsigned)(t64 * (t64 + 1) / 2)), dim3(256), 0, ctx->stream, S, n, lds);
     ASER_TRY(aser_check_launch(ctx, "upper_to_lower"));
 
+    if (!info) {                                         // asynchronous: the flag is read by the next synchronising call
+        ctx->pending_info_dev = info_dev;
+        return ASER_OK;
+    }
+    ctx->pending_info_dev = nullptr;
     int32_t h_info = 0;
     ASER_HIP(ctx, hipMemcpyAsync(&h_info, info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
     const int32_t res = (h_info == INT_MAX) ? 0 : h_info;
-    if (info) *info = res;
+    *info = res;
     if (res != 0) ASER_FAIL(ctx, ASER_ERR_NOT_SPD, "whiten: non-positive pivot at index %d", res);
     return ASER_OK;
 }

@@ -259,6 +259,20 @@ def test_whiten_reports_non_spd():
     assert st == aser.ASER_ERR_NOT_SPD and info == 151
     st, info = aser.aser_whiten(ctx, Gd, None, 0.01, S)            # damping repairs it
     assert st == aser.ASER_OK and info == 0
+    # without a host `info` the call does not synchronise; the pivot is reported by the next
+    # aser_error_reconstruct on the context, and only once
+    ctx.ensure_workspace(aser.aser_workspace_bytes(64, n, 4))
+    st, info = aser.aser_whiten(ctx, Gd, None, 0.0, S, want_info=False)
+    assert st == aser.ASER_OK and info is None
+    T = torch.from_numpy(rng.standard_normal((64, n)).astype(np.float32)).to(DEV)
+    Sok = torch.eye(n, dtype=torch.float32, device=DEV)
+    L_A = torch.empty((64, 4), dtype=torch.float32, device=DEV)
+    L_B = torch.empty((4, n), dtype=torch.float32, device=DEV)
+    sigma = torch.empty(4, dtype=torch.float32, device=DEV)
+    st, _, _ = aser.aser_error_reconstruct(ctx, T, Sok, 4, L_A, L_B, sigma)
+    assert st == aser.ASER_ERR_NOT_SPD and "151" in ctx.last_error()
+    st, err, _ = aser.aser_error_reconstruct(ctx, T, Sok, 4, L_A, L_B, sigma)
+    assert st == aser.ASER_OK and np.isfinite(err)
 
 
 def check_reconstruction(spec, ref, L_A, L_B, sigma, err_gpu, label):
