@@ -241,9 +241,13 @@ class LayerBuffers:
         import torch
         dev = "cuda:%d" % device
         self.m, self.n, self.r, self.f, self.bits, self.packed = m, n, r, f, bits, packed
-        self.G = torch.zeros((n, n), dtype=torch.float32, device=dev)
-        self.abs_sum = torch.zeros(n, dtype=torch.float64, device=dev)
-        self.count = torch.zeros(1, dtype=torch.int64, device=dev)
+        # the three statistics share one allocation, so that clearing them is one launch
+        g_bytes = (n * n * 4 + 255) // 256 * 256
+        a_bytes = (n * 8 + 255) // 256 * 256
+        self._stats = torch.zeros(g_bytes + a_bytes + 256, dtype=torch.uint8, device=dev)
+        self.G = self._stats[:n * n * 4].view(torch.float32).view(n, n)
+        self.abs_sum = self._stats[g_bytes:g_bytes + n * 8].view(torch.float64)
+        self.count = self._stats[g_bytes + a_bytes:g_bytes + a_bytes + 8].view(torch.int64)
         self.idx = torch.zeros(max(f, 1), dtype=torch.int32, device=dev)
         self.mdiag = torch.empty(n, dtype=torch.float32, device=dev)
         self.codes = torch.empty((m, n // 2 if packed else n), dtype=torch.uint8 if packed else torch.int8, device=dev)
@@ -256,9 +260,7 @@ class LayerBuffers:
         self.err = float("nan")
 
     def reset_statistics(self):
-        self.G.zero_()
-        self.abs_sum.zero_()
-        self.count.zero_()
+        self._stats.zero_()
 
 
 def calibrate_layer(ctx: Context, W, X, buf: LayerBuffers, opts: Optional[aser_svd_opts] = None, damp: float = 0.0,
