@@ -48,7 +48,7 @@ typedef enum aser_status {
     ASER_ERR_SHAPE = 2,         /* non-positive size, ld < cols, f > n, r > min(m, n) ... */
     ASER_ERR_DTYPE = 3,         /* unsupported dtype / bit width                          */
     ASER_ERR_NOT_SPD = 4,       /* Cholesky met a non-positive pivot                      */
-    ASER_ERR_NO_CONVERGE = 5,   /* reserved                                               */
+    ASER_ERR_NO_CONVERGE = 5,   /* the subspace iteration's orthogonalisation broke down  */
     ASER_ERR_WORKSPACE = 6,     /* workspace missing or too small                         */
     ASER_ERR_HIP = 7            /* a HIP runtime call failed                              */
 } aser_status;

@@ -123,6 +123,10 @@ int gemm_tn_atomic(aser_ctx* ctx, const float* A, int64_t lda, const float* B, i
     return aser_gemm_tn(ctx, g);
 }
 
+// The factorisation kernel reports a non-positive pivot with atomicMin(info, base + column + 1); the
+// flag of this file starts at zero, so a negative base makes any failed pivot show as a negative flag.
+constexpr int32_t kPivotBase = -1000;
+
 // out (rows x b) = Y R^-1 with R^T R = Y^T Y (Cholesky-QR); R^-1 is left in Rinv.  Mb must be zero on
 // entry and is zero again on return.  The first clear_rows rows of Y are cleared after they have
 // been read (0: Y is left alone).  Lmul / Cmul / with_beta: the factorisation kernel also leaves
@@ -130,7 +134,7 @@ int gemm_tn_atomic(aser_ctx* ctx, const float* A, int64_t lda, const float* B, i
 int chol_qr(aser_ctx* ctx, float* Y, float* out, int64_t rows, int64_t clear_rows, int b, float* Mb, float* Rinv,
             int32_t* info, const float* Lmul = nullptr, float* Cmul = nullptr, bool with_beta = false) {
     ASER_TRY(gemm_tn_atomic(ctx, Y, b, Y, b, Mb, b, b, b, rows, 128, 128, false, /*upper_only=*/true));
-    ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rinv, info, 0, /*clear_d=*/true, Lmul, Cmul, with_beta));
+    ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rinv, info, kPivotBase, /*clear_d=*/true, Lmul, Cmul, with_beta));
     return aser_gemm_small_f32(ctx, Y, b, Rinv, b, out, b, rows, b, b, clear_rows);
 }
 
@@ -221,7 +225,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         ASER_TRY(gemm_tn_atomic(ctx, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // Zt = A^T Q_k = Z R_z
         // R_z^-1 (Z itself is never formed); from the second iteration on also Bm = -beta P_k R_z^-1
         ASER_TRY(gemm_tn_atomic(ctx, Zt, b, Zt, b, Mb, b, b, b, n, 128, 128, false, /*upper_only=*/true));
-        ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rz_inv, info, 0, /*clear_d=*/true, it ? Pm : nullptr, it ? Bm : nullptr, true));
+        ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rz_inv, info, kPivotBase, /*clear_d=*/true, it ? Pm : nullptr, it ? Bm : nullptr, true));
         ASER_TRY(gemm_tn_atomic(ctx, At, m, Zt, b, Qraw, b, m, b, n, bmA, bnB, false));   // A Zt
         // A Z + momentum term = (A Zt) R_z^-1 + Q_{k-1} Bm; Qraw and Zt are zero again afterwards
         ASER_TRY(aser_combine_f32(ctx, Qraw, Rz_inv, it ? Qold : nullptr, Bm, Qacc, m, b, Zt, n));
@@ -263,14 +267,20 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, WBt, r, L_B, n, n, b, r, 0, true));   // (n x r)^T = L_B
 
     double h_res2 = 0.0;
-    int32_t h_pivot = INT_MAX;
+    int32_t h_pivot = INT_MAX, h_qr = 0;
     ASER_HIP(ctx, hipMemcpyAsync(&h_res2, normA2, 8, hipMemcpyDeviceToHost, ctx->stream));
+    ASER_HIP(ctx, hipMemcpyAsync(&h_qr, info, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     if (ctx->pending_info_dev)                           // pivot flag of a whitening that did not synchronise
         ASER_HIP(ctx, hipMemcpyAsync(&h_pivot, ctx->pending_info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
     ctx->pending_info_dev = nullptr;
     if (h_pivot != INT_MAX && h_pivot != 0)
         ASER_FAIL(ctx, ASER_ERR_NOT_SPD, "whiten: non-positive pivot at index %d (reported by error_reconstruct)", h_pivot);
+    if (h_qr < 0 || !(h_res2 >= 0.0) || h_res2 > 1e300)
+        ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE,
+                  "error_reconstruct: the Cholesky-QR orthogonalisation broke down (pivot %d of a block Gram matrix is not "
+                  "positive): the singular values of the subspace span more than the products resolve",
+                  h_qr < 0 ? h_qr - kPivotBase : 0);
     if (err) *err = sqrt(h_res2 > 0.0 ? h_res2 : 0.0);
     if (n_iter) *n_iter = p.iters;
     return ASER_OK;

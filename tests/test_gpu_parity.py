@@ -499,6 +499,24 @@ def test_quantizers_with_denormal_scales():
     assert np.array_equal(scales.cpu().numpy(), ref_scales)
 
 
+def test_ill_conditioned_block_is_reported():
+    """W8 with smoothed outlier columns: the unquantized outlier part of T is thousands of times larger
+    than the int8 rounding error (sigma_1 / sigma_b = 4400 here), more than the fp32-class products and
+    the Cholesky-QR orthogonalisation resolve.  The call must say so (ASER_ERR_NO_CONVERGE) instead of
+    returning numbers; all kernels run to completion."""
+    spec = synth.mini("fz21", 145, 410, 1105, x_dtype="bf16", x_dist="gauss", n_outliers=3, r=31, f=3, bits=8, seed_id=721)
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    ctx = new_ctx()
+    buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, False)
+    with pytest.raises(aser.AserError) as e:
+        aser.calibrate_layer(ctx, torch.from_numpy(W).to(DEV), to_dev_x(spec, x_np), buf)
+    assert e.value.status == aser.ASER_ERR_NO_CONVERGE
+    # the same layer at W4 is within range
+    spec4 = spec.with_(bits=4)
+    run_e2e("fz21_w4", spec4, False)
+
+
 def test_deterministic_integer_outputs():
     spec = synth.mini("d1", 130, 520, 1500, r=16, f=8)
     W = torch.from_numpy(synth.make_weight(spec)).to(DEV)
