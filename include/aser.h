@@ -68,7 +68,14 @@ typedef struct aser_svd_opts {
     int32_t max_iter;   /* number of subspace iterations (A A^T applications); default 9, 12 when max(m, n) > 8192,
                            24 when block < 2 r */
     uint32_t seed;      /* seed of the random start block; default 1                       */
-    int32_t reserved;
+    int32_t n_lead;     /* number of entries of lead_cols (0: none)                         */
+    const int32_t* lead_cols; /* DEVICE pointer, may be NULL: columns of T that are far larger than the
+                           rest (the unquantized outlier columns I_f of Eq. 12).  They become the
+                           first columns of the start block, ahead of the random ones, so that the
+                           orthogonalisation sees a graded block instead of columns that all mix the
+                           largest and the smallest wanted singular directions; without the hint
+                           sigma_1 / sigma_b beyond a few hundred ends in ASER_ERR_NO_CONVERGE.
+                           The result does not depend on the hint otherwise.                  */
 } aser_svd_opts;
 
 const char* aser_status_string(int status);

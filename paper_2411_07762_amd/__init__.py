@@ -37,7 +37,7 @@ EXPORTS = (
 
 class aser_svd_opts(ctypes.Structure):
     _fields_ = [("block", ctypes.c_int32), ("max_iter", ctypes.c_int32), ("seed", ctypes.c_uint32),
-                ("reserved", ctypes.c_int32)]
+                ("n_lead", ctypes.c_int32), ("lead_cols", ctypes.c_void_p)]
 
 
 class AserError(RuntimeError):
@@ -277,7 +277,12 @@ def calibrate_layer(ctx: Context, W, X, buf: LayerBuffers, opts: Optional[aser_s
     ctx.check(aser_quantize_rtn(ctx, W, buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes, buf.scales, buf.T))
     st, _ = aser_whiten(ctx, buf.G, buf.mdiag, damp, buf.S, want_info=False)   # pivot check at the layer's one sync
     ctx.check(st)
-    st, err, _ = aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, opts)
+    o = aser_svd_opts()
+    if opts is not None:
+        o.block, o.max_iter, o.seed = opts.block, opts.max_iter, opts.seed
+    if buf.f > 0:                                # graded start block: the unquantized outlier columns of T lead
+        o.n_lead, o.lead_cols = buf.f, _ptr(buf.idx)
+    st, err, _ = aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, o)
     ctx.check(st)
     buf.err = err
     return buf

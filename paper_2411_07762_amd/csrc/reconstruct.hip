@@ -35,6 +35,18 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
     return x;
 }
 
+// Leading columns of the start block: Q[i][c] = T[i][cols[c]] for c < k (row-major m x b block).
+__global__ void lead_columns_kernel(const float* __restrict__ T, int64_t m, int64_t ldt, const int32_t* __restrict__ cols,
+                                    int k, int64_t n, float* __restrict__ Q, int b) {
+    const int64_t total = m * k;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t i = t / k;
+        const int c = (int)(t % k);
+        const int64_t col = cols[c];
+        if (col >= 0 && col < n) Q[i * b + c] = T[i * ldt + col];
+    }
+}
+
 // Start block: uniform values in [-1, 1) from a counter-based hash of (seed, index).
 __global__ void random_block_kernel(float* Q, int64_t total, uint32_t seed) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
@@ -218,6 +230,15 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         const int blocks = (int)(ceil_div64(total, 256) < 2048 ? ceil_div64(total, 256) : 2048);
         hipLaunchKernelGGL(random_block_kernel, dim3(blocks), dim3(256), 0, ctx->stream, Qacc, total, p.seed);
         ASER_TRY(aser_check_launch(ctx, "random_block"));
+        if (opts && opts->lead_cols && opts->n_lead > 0) {
+            // graded start: the dominant columns of T first (their span holds the largest left singular
+            // directions of T S), the random columns behind them
+            const int k = opts->n_lead < b ? opts->n_lead : b;
+            const int64_t tot = m * (int64_t)k;
+            const int blk = (int)(ceil_div64(tot, 256) < 1024 ? ceil_div64(tot, 256) : 1024);
+            hipLaunchKernelGGL(lead_columns_kernel, dim3(blk), dim3(256), 0, ctx->stream, T, m, ldt, opts->lead_cols, k, n, Qacc, b);
+            ASER_TRY(aser_check_launch(ctx, "lead_columns"));
+        }
     }
     ASER_TRY(chol_qr(ctx, Qacc, Qcur, m, 0, b, Mb, Rq_inv, info));                 // Q_0
     const int bmA = 128, bnB = 128;

@@ -335,6 +335,15 @@ E2E_CASES = [
     ("c2_shape_small", synth.CONFIGS["c2"].with_(m=384, n=1032, tokens=4096, r=32, f=16, n_outliers=8), True),
     # r = 128 fills the widest subspace block: no oversampling columns, the longer default iteration
     ("c4_shape_small", synth.CONFIGS["c4"].with_(m=1024, n=3584, tokens=8192), True),
+    # W8 with smoothed outliers: the unquantized columns of T dwarf the int8 rounding error
+    # (sigma_1 / sigma_b in the thousands); needs the graded start block (outlier columns first)
+    ("w8_outliers", synth.mini("fz1", 613, 404, 1038, n_outliers=6, r=20, f=25, bits=8, seed_id=701), False),
+    ("w8_outliers_silu_f32", synth.mini("fz8", 181, 548, 1501, x_dtype="f32", x_dist="silu_prod", n_outliers=6, r=40, f=23,
+                                        bits=8, seed_id=708), False),
+    ("w8_few_outliers", synth.mini("fz21", 145, 410, 1105, n_outliers=3, r=31, f=3, bits=8, seed_id=721), False),
+    # the subspace block is nearly as wide as the matrix (b = 64 of n = 74): the end of the spectrum is in it
+    ("block_as_wide_as_matrix", synth.mini("fz7", 322, 74, 333, x_dtype="f32", x_dist="silu_prod", n_outliers=6, r=23, f=6,
+                                           bits=4, seed_id=707), True),
 ]
 
 
@@ -501,20 +510,28 @@ def test_quantizers_with_denormal_scales():
 
 def test_ill_conditioned_block_is_reported():
     """W8 with smoothed outlier columns: the unquantized outlier part of T is thousands of times larger
-    than the int8 rounding error (sigma_1 / sigma_b = 4400 here), more than the fp32-class products and
-    the Cholesky-QR orthogonalisation resolve.  The call must say so (ASER_ERR_NO_CONVERGE) instead of
-    returning numbers; all kernels run to completion."""
+    than the int8 rounding error (sigma_1 / sigma_b = 4400 here).  With a purely random start block every
+    column mixes both, which is more than the fp32-class products and the Cholesky-QR orthogonalisation
+    resolve: without the lead_cols hint the call must say so (ASER_ERR_NO_CONVERGE) instead of returning
+    numbers; all kernels run to completion.  With the hint the same layer passes the parity bars
+    (test_end_to_end_layer[w8_few_outliers])."""
     spec = synth.mini("fz21", 145, 410, 1105, x_dtype="bf16", x_dist="gauss", n_outliers=3, r=31, f=3, bits=8, seed_id=721)
-    W = synth.make_weight(spec)
-    x_np = synth.make_activations(spec)
+    W = torch.from_numpy(synth.make_weight(spec)).to(DEV)
+    X = to_dev_x(spec, synth.make_activations(spec))
     ctx = new_ctx()
     buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, False)
-    with pytest.raises(aser.AserError) as e:
-        aser.calibrate_layer(ctx, torch.from_numpy(W).to(DEV), to_dev_x(spec, x_np), buf)
-    assert e.value.status == aser.ASER_ERR_NO_CONVERGE
-    # the same layer at W4 is within range
-    spec4 = spec.with_(bits=4)
-    run_e2e("fz21_w4", spec4, False)
+    ctx.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, spec.r))
+    ctx.check(aser.aser_gram_accumulate(ctx, X, buf.G, buf.abs_sum, buf.count))
+    ctx.check(aser.aser_smooth_outliers(ctx, W, buf.abs_sum, buf.count, buf.f, buf.idx, buf.mdiag))
+    ctx.check(aser.aser_quantize_rtn(ctx, W, buf.idx, buf.mdiag, buf.f, buf.bits, aser.ASER_CODES_INT8, buf.codes, buf.scales, buf.T))
+    st, info = aser.aser_whiten(ctx, buf.G, buf.mdiag, 0.0, buf.S)
+    assert st == aser.ASER_OK and info == 0
+    st, _, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma)
+    assert st == aser.ASER_ERR_NO_CONVERGE
+    hint = aser.aser_svd_opts()
+    hint.n_lead, hint.lead_cols = spec.f, buf.idx.data_ptr()
+    st, err, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, hint)
+    assert st == aser.ASER_OK and np.isfinite(err)
 
 
 def test_deterministic_integer_outputs():
