@@ -28,8 +28,8 @@ BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch at workload c1 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # 1 GiB copy (x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE); see profiles/gram_rtn_hbm_traffic.txt.
-MEASURED_TRAFFIC_C1 = {"gram": 435579 * 1024 * 2.0 + 132608 * 1024 * 1.0,
-                       "rtn": 32888 * 1024 * 2.0 + 77272 * 1024 * 1.0}
+MEASURED_TRAFFIC_C1 = {"gram": 435532 * 1024 * 2.0 + 132608 * 1024 * 1.0,
+                       "rtn": 32888 * 1024 * 2.0 + 77731 * 1024 * 1.0}
 
 
 def log(*a):
