@@ -681,8 +681,8 @@ __device__ __forceinline__ bf16x8_t lds_tr_frag(const char* p, int off_lo, int o
 // Step s multiplies stage s % 4 in two 16-token slices of 16 MFMAs each.  One wave per SIMD means
 // nothing but instruction order hides latencies, so the order is pinned by hand: the operand reads
 // of slice 1 are interleaved with the MFMAs of slice 0; the wait for the next stage, the barrier,
-// the operand reads of the next step's slice 0 and the loads of stage s + 3 are interleaved, in
-// that order, with the MFMAs of slice 1.
+// the loads of stage s + 3 and the operand reads of the next step's slice 0 are interleaved with
+// the MFMAs of slice 1.
 __device__ __forceinline__ void gram_tile_dma(const GemmArgs& g, int64_t I0, int64_t J0, int64_t kBeg, int64_t kEnd,
                                               char* smem) {
     const int tid = threadIdx.x, lane = tid & 63;
@@ -786,9 +786,8 @@ __device__ __forceinline__ void gram_tile_dma(const GemmArgs& g, int64_t I0, int
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        // slice 1: the first two MFMAs cover the wait and the barrier, the next eight the reads of the
-        // next step's slice 0 (as early as the barrier allows: the first MFMA of that step needs them),
-        // the four after those the eight loads of stage s + 3
+        // slice 1: row 0 of MFMAs covers the wait and the barrier, rows 1 and 2 the eight loads of
+        // stage s + 3, rows 2 and 3 the reads of the next step's slice 0
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -800,12 +799,13 @@ __device__ __forceinline__ void gram_tile_dma(const GemmArgs& g, int64_t I0, int
                     else __builtin_amdgcn_s_waitcnt(0x0F70);                             // vmcnt(0)
                     __syncthreads();                      // everyone's share landed; stage s - 1 is free
                 }
-                {
-                    const int q = 4 * i + j;             // position in the slice
-                    if (more && q >= 2 && q < 6) a0[q - 2] = lds_tr_frag(sn + offa[q - 2], 0, 4 * 512);
-                    if (more && q >= 6 && q < 10) b0[q - 6] = lds_tr_frag(sn + offb[q - 6], 0, 4 * 512);
-                    if (fetch && q >= 10 && q < 14) { issue_one(s + kDmaStages - 1, (q - 10) >> 1, 2 * ((q - 10) & 1), tail); issue_one(s + kDmaStages - 1, (q - 10) >> 1, 2 * ((q - 10) & 1) + 1, tail); }
+                if (fetch && i == 1) { issue_one(s + kDmaStages - 1, 0, j, tail); }
+                if (fetch && i == 2 && j < 2) { issue_one(s + kDmaStages - 1, 1, 2 * j, tail); issue_one(s + kDmaStages - 1, 1, 2 * j + 1, tail); }
+                if (more && i == 2 && j >= 2) {
+                    a0[2 * (j - 2)] = lds_tr_frag(sn + offa[2 * (j - 2)], 0, 4 * 512);
+                    a0[2 * (j - 2) + 1] = lds_tr_frag(sn + offa[2 * (j - 2) + 1], 0, 4 * 512);
                 }
+                if (more && i == 3) b0[j] = lds_tr_frag(sn + offb[j], 0, 4 * 512);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
