@@ -155,7 +155,9 @@ int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n, const flo
  *             whitened layer-output error ||(T - L_A L_B) S||_F of Eq. 8
  *     *n_iter (host, may be NULL) = subspace iterations performed
  * T: m x n fp32 (ldt); S: n x n fp32 lower triangular with zeros above the diagonal (lds).
- * 0 < r <= min(m, n, 128).  Synchronises the stream.  Needs workspace. */
+ * 0 < r <= min(m, n, 128), and a multiple of 32 must lie in [r, min(m, n, 128)] (the subspace
+ * width; e.g. r = 40 needs min(m, n) >= 64), else ASER_ERR_SHAPE.  Synchronises the stream.
+ * Needs workspace. */
 int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt,
                            const float* S, int64_t lds, int32_t r, const aser_svd_opts* opts,
                            float* L_A, float* L_B, float* sigma, double* err, int32_t* n_iter);

@@ -110,8 +110,10 @@ def test_whiten_and_reconstruct_validation(ctx):
     assert r(ctx, P, P, 65, P, P, P, m=64, n=256)[0] == aser.ASER_ERR_SHAPE             # r > min(m, n)
     assert r(ctx, P, P, 129, P, P, P, m=512, n=512)[0] == aser.ASER_ERR_SHAPE
     assert r(ctx, P, P, 8, None, P, P, m=64, n=64)[0] == aser.ASER_ERR_INVALID_ARG
-    o = aser.aser_svd_opts(block=48, max_iter=0, seed=0, reserved=0)
+    o = aser.aser_svd_opts(block=48, max_iter=0, seed=0, n_lead=0, lead_cols=None)
     assert r(ctx, P, P, 8, P, P, P, o, m=64, n=64)[0] == aser.ASER_ERR_SHAPE             # block not multiple of 32
+    assert r(ctx, P, P, 40, P, P, P, m=695, n=44)[0] == aser.ASER_ERR_SHAPE              # no multiple of 32 in [40, 44]
+    assert "block width" in ctx._lib.aser_last_error(ctx.handle).decode()
 
 
 def test_act_rtn_validation(ctx):
