@@ -101,7 +101,6 @@ int aser_col_abs_sum_x(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, 
                        double* abs_sum, int64_t* count);
 int aser_col_abs_sum_w(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw, double* wsum);
 int aser_transpose_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols, int64_t lda, float* At, int64_t ldat);
-int aser_sumsq_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols, int64_t lda, double* out /*device, accumulates*/);
 
 // Small dense kernels (one workgroup, matrices in LDS)
 // Upper Cholesky of the b x b block D (ld) in place: upper part <- R (D = R^T R), lower part <- R^T;

@@ -147,22 +147,6 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float* A, int64_t 
     }
 }
 
-// ------------------------------------------------------------------------------------ sum of squares
-__global__ __launch_bounds__(256) void sumsq_kernel(const float* A, int64_t rows, int64_t cols, int64_t lda, double* out) {
-    __shared__ double red[4];
-    double acc = 0.0;
-    const int64_t total = rows * cols;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-        const float v = A[(i / cols) * lda + (i % cols)];
-        acc += (double)v * (double)v;
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) atomicAdd(out, red[0] + red[1] + red[2] + red[3]);
-}
-
 // rint(x / scale) with the result of the IEEE division, at the cost of a multiplication: the
 // quotient is first formed with the hardware reciprocal (relative error below 2e-7, so absolute
 // error below 3e-5 for |x / scale| <= 128); only when that value lies within 1e-4 of a rounding
@@ -625,13 +609,6 @@ int aser_transpose_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols
     dim3 grid((unsigned)ceil_div64(cols, 64), (unsigned)ceil_div64(rows, 64));
     hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, ctx->stream, A, rows, cols, lda, At, ldat);
     return aser_check_launch(ctx, "transpose");
-}
-
-int aser_sumsq_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols, int64_t lda, double* out) {
-    const int64_t total = rows * cols;
-    const int blocks = (int)((total + 4095) / 4096 < 2048 ? (total + 4095) / 4096 : 2048);
-    hipLaunchKernelGGL(sumsq_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, ctx->stream, A, rows, cols, lda, out);
-    return aser_check_launch(ctx, "sumsq");
 }
 
 // ---------------------------------------------------------------------------------------- ABI: stage 3
