@@ -142,14 +142,18 @@ def run_block(args):
     spec, st, buf, _ = layers[-1]
     G2 = torch.zeros_like(buf.G)
     ctx.check(aser.aser_gram_accumulate(ctx, st["X"], G2))
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = max(3, args.steps)
-    e0.record()
-    for _ in range(reps):
-        ctx.check(aser.aser_gram_accumulate(ctx, st["X"], G2))
-    e1.record()
     torch.cuda.synchronize()
-    gram_ms = e0.elapsed_time(e1) / reps
+    reps = max(3, args.steps)
+    pairs = []
+    for _ in range(reps):                       # one event pair per launch, the block between two launches
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ctx.check(aser.aser_gram_accumulate(ctx, st["X"], G2))
+        e1.record()
+        pairs.append((e0, e1))
+        block()
+    torch.cuda.synchronize()
+    gram_ms = sum(a.elapsed_time(b) for a, b in pairs) / reps
     gram_flops = float(spec.tokens) * spec.n * (spec.n + 1)
     gram_tflops = gram_flops / (gram_ms * 1e-3) / 1e12
     out = {
@@ -275,18 +279,29 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     stage_ms = [s / args.steps for s in stage_ms]
 
-    # Dominant kernel alone: the Gram MFMA kernel (no statistics pass), HIP events on the launch stream.
+    # Dominant kernel alone: the Gram MFMA kernel (no statistics pass), HIP events on the launch stream, one
+    # pair around every launch, and a whole layer step between two launches as in the pipeline.  (Launched
+    # back to back the kernel heats the chip and the clock drops within milliseconds: ten such launches
+    # climb from 490 to 590 us at c1, a rate no calibration run sees.)
     reps = max(10, args.steps)
     G2 = torch.zeros_like(buf.G)
     ctx.check(aser.aser_gram_accumulate(ctx, X, G2))
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
+    pairs = []
+    for i in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        # a streaming kernel in front, as the statistics pass is in the pipeline: the step before ended with
+        # a host synchronisation, and the Gram launch is not meant to start on an idle device
+        ctx.check(aser.aser_quantize_rtn(ctx, Ws[i % n_rot], buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes,
+                                         buf.scales, buf.T))
+        e0.record()
         ctx.check(aser.aser_gram_accumulate(ctx, X, G2))
-    e1.record()
+        e1.record()
+        step(i)
+        pairs.append((e0, e1))
     torch.cuda.synchronize()
-    gram_ms = e0.elapsed_time(e1) / reps
+    gram_ms = sum(a.elapsed_time(b) for a, b in pairs) / reps
+    e0, e1 = pairs[0]
     gram_flops = float(spec.tokens) * spec.n * (spec.n + 1)
     gram_tflops = gram_flops / (gram_ms * 1e-3) / 1e12
 
