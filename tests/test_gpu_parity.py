@@ -547,3 +547,38 @@ def test_deterministic_integer_outputs():
         outs.append((buf.idx.cpu().numpy().copy(), buf.codes.cpu().numpy().copy(), buf.scales.cpu().numpy().copy()))
     for a, b in zip(outs[0], outs[1]):
         assert np.array_equal(a, b)
+
+
+def test_c0_against_stored_oracle_results():
+    """The HIP path on layer c0 against tests/golden/c0_oracle.json (written from the oracle alone):
+    indices, factors, scales and codes exactly, singular values and the whitened error (Eq. 8) to 1e-4."""
+    import hashlib
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "c0_oracle.json")) as fh:
+        gold = json.load(fh)
+    spec = synth.CONFIGS["c0"]
+    say("golden c0")
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    ctx = new_ctx()
+    buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, False)
+    Xd = to_dev_x(spec, x_np)
+    aser.calibrate_layer(ctx, torch.from_numpy(W).to(DEV), Xd, buf)
+    torch.cuda.synchronize()
+    idx = buf.idx.cpu().numpy()[:spec.f].tolist()
+    assert idx == gold["idx"]
+    md = buf.mdiag.cpu().numpy()
+    assert [float(md[i]) for i in idx] == gold["mdiag_on_idx"]
+    assert [float(s) for s in buf.scales.cpu().numpy()[:8]] == gold["rtn_scales_first8"]
+    codes = np.ascontiguousarray(buf.codes.cpu().numpy(), dtype=np.int8)
+    assert hashlib.sha256(codes.tobytes()).hexdigest() == gold["rtn_codes_sha256"]
+    sig = buf.sigma.cpu().numpy()[:spec.r].astype(np.float64)
+    assert np.allclose(sig, gold["sigma_first"][:spec.r], rtol=1e-4)
+    assert abs(buf.err - gold["whitened_error"]) <= 1e-4 * gold["whitened_error"]
+    act_codes = torch.empty((spec.tokens, spec.n), dtype=torch.int8, device=DEV)
+    act_scales = torch.empty(spec.tokens, dtype=torch.float32, device=DEV)
+    ctx.check(aser.aser_quantize_act_rtn(ctx, Xd, buf.mdiag, 8, act_codes, act_scales))
+    torch.cuda.synchronize()
+    assert [float(s) for s in act_scales.cpu().numpy()[:8]] == gold["act_scales_first8"]
+    assert hashlib.sha256(np.ascontiguousarray(act_codes.cpu().numpy()).tobytes()).hexdigest() == gold["act_codes_sha256"]

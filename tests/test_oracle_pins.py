@@ -301,3 +301,30 @@ def test_synth_is_chunk_addressable_and_bf16_exact():
     assert np.array_equal(synth.f32_to_bf16_bits(f), full)                 # round trip is exact
     x = np.array([1.0, 1.00390625, 1.01171875, -3.0e-39], dtype=np.float32)  # ties go to even
     assert synth.f32_to_bf16_bits(x)[:3].tolist() == [0x3F80, 0x3F80, 0x3F82]
+
+
+# ---------------------------------------------------------------- stored oracle results (tests/golden)
+def test_golden_c0_fixture_is_what_the_oracle_computes():
+    """tests/golden/c0_oracle.json was written by tests/golden/make_golden.py from the oracle alone; the
+    oracle must still reproduce it (integers and hashes exactly, floats to 1e-9: LAPACK builds differ in
+    the last bits).  A deliberate change of the oracle regenerates the fixture in the same commit."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.compute()
+    with open(os.path.join(here, "c0_oracle.json")) as fh:
+        stored = json.load(fh)
+    assert set(now) == set(stored)
+    for key, val in stored.items():
+        if isinstance(val, float):
+            assert now[key] == pytest.approx(val, rel=1e-9), key
+        elif isinstance(val, list) and val and isinstance(val[0], float):
+            assert now[key] == pytest.approx(val, rel=1e-9), key
+        else:
+            assert now[key] == val, key
+    # the planted channels of c0 are in the stored outlier set, largest first
+    assert set(stored["idx"][:3]) == {3, 77, 190}
