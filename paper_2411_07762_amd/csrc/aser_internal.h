@@ -89,6 +89,24 @@ struct GemmArgs {
 };
 int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g);
 
+// Number of K parts for a split-K update with atomic accumulation, from a cost model fitted to kernel
+// traces (microseconds; u = tile area in units of 128 x 128): one workgroup per CU, so the workgroups run
+// in ceil(tiles * parts / 256) rounds; a round costs 4 us of prologue and flush plus 0.75 u per 32-deep K
+// step; every workgroup adds 0.06 u of atomic traffic that the others wait behind.  More parts shorten
+// the K loop but multiply the atomics, and one workgroup more than 256 doubles the rounds.
+// A part keeps at least min_steps K steps.
+static inline int aser_split_k_parts(int64_t tiles, int64_t ksteps, int64_t min_steps, double u) {
+    const int64_t max_parts = ksteps / min_steps > 0 ? ksteps / min_steps : 1;
+    int best = 1;
+    double best_cost = 0.0;
+    for (int64_t p = 1; p <= max_parts && p <= 64; ++p) {
+        const int64_t wgs = tiles * p, rounds = ceil_div64(wgs, 256), steps = ceil_div64(ksteps, p);
+        const double cost = (double)rounds * (0.75 * u * (double)steps + 4.0) + 0.06 * u * (double)wgs;
+        if (p == 1 || cost < best_cost) { best_cost = cost; best = (int)p; }
+    }
+    return best;
+}
+
 // Gram update G(lower) += X^T X with the XCD-aware persistent schedule (bf16 or fp32 X).
 int aser_syrk_gram(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int64_t n, int64_t ldx,
                    float* G, int64_t ldg);

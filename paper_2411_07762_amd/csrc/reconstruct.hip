@@ -122,16 +122,12 @@ int gemm_tn_atomic(aser_ctx* ctx, const float* A, int64_t lda, const float* B, i
     g.M = M; g.N = N; g.K = K; g.alpha = 1.f;
     g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_ATOMIC; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
     g.bm = bm; g.bn = bn; g.upper_only = upper_only ? 1 : 0;
-    // Split K so that about 256 workgroups run.  Every part pays a pipeline fill and an atomic
+    // Split K by the cost model of aser_split_k_parts.  Every part pays a pipeline fill and an atomic
     // flush of its whole tile, so parts keep at least 8 K steps (4 when the output is tiny and the
     // call is pure latency).
     const int64_t tiles = ceil_div64(M, bm) * ceil_div64(N, bn);
-    int64_t parts = ceil_div64(256, tiles);
     const int64_t ksteps = ceil_div64(K, 32);
-    const int64_t min_steps = tiles <= 4 ? 4 : 8;
-    const int64_t max_parts = ksteps / min_steps > 0 ? ksteps / min_steps : 1;
-    if (parts > max_parts) parts = max_parts;
-    g.k_parts = (int)(parts < 1 ? 1 : parts);
+    g.k_parts = aser_split_k_parts(tiles, ksteps, tiles <= 4 ? 4 : 8, (double)(bm * bn) / (128.0 * 128.0));
     return aser_gemm_tn(ctx, g);
 }
 

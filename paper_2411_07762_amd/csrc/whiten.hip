@@ -141,10 +141,7 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
         u.in_type = GEMM_IN_F32X3; u.epi = GEMM_EPI_ATOMIC; u.tiles = GEMM_TILES_ALL; u.krange = GEMM_K_FULL;
         u.bm = bm; u.bn = bn; u.upper_only = 1;
         const int64_t tiles = ceil_div64(u.M, u.bm) * ceil_div64(u.N, u.bn), ksteps = ceil_div64(klen, 32);
-        int64_t parts = ceil_div64(256, tiles);
-        const int64_t max_parts = ksteps / 4 > 0 ? ksteps / 4 : 1;
-        if (parts > max_parts) parts = max_parts;
-        u.k_parts = (int)parts;
+        u.k_parts = aser_split_k_parts(tiles, ksteps, 4, (double)(bm * bn) / (128.0 * 128.0));
         return aser_gemm_tn(ctx, u);
     };
     for (int64_t k0 = 0; k0 < n; k0 += kNb) {
