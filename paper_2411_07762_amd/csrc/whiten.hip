@@ -165,7 +165,7 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
         p.Ct = nullptr; p.ldct = 0;
         p.M = b; p.N = rem; p.K = b; p.alpha = 1.f;
         p.in_type = GEMM_IN_F32X3; p.epi = GEMM_EPI_STORE; p.tiles = GEMM_TILES_ALL; p.krange = GEMM_K_FULL;
-        p.k_parts = 1; p.bm = 128; p.bn = (rem > 128) ? 256 : 128;
+        p.k_parts = 1; p.bm = 128; p.bn = 128;           // K = 128 only: twice the workgroups beat the wider tile (16.6 -> 12 us at c1)
         ASER_TRY(aser_gemm_tn(ctx, p));
     }
     hipLaunchKernelGGL(upper_to_lower_kernel, dim3((unsigned)(t64 * (t64 + 1) / 2)), dim3(256), 0, ctx->stream, S, n, lds);
