@@ -151,7 +151,7 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
             if (k0 % (2 * kNb) == 0) {
                 if (k0 > 0) ASER_TRY(update(k0, (n - k0 < 2 * kNb) ? n - k0 : 2 * kNb, 0, k0, 256, 256));
             } else {
-                ASER_TRY(update(k0, b, k0 - kNb, kNb, 128, 256));
+                ASER_TRY(update(k0, b, k0 - kNb, kNb, 128, 128));   // K = 128 only, as the row panel: many small tiles
             }
         } else if (k0 > 0) {
             ASER_TRY(update(k0, b, 0, k0, 128, (n - k0 >= 4096) ? 256 : 128));
