@@ -222,10 +222,6 @@ def main():
     layout = aser.ASER_CODES_INT4_PACKED
     stage_names = ["reset", "gram", "smooth", "rtn", "whiten", "reconstruct"]
 
-    svd_opts = aser.aser_svd_opts()                 # defaults, with the outlier columns leading the start block
-    if buf.f > 0:
-        svd_opts.n_lead, svd_opts.lead_cols = buf.f, buf.idx.data_ptr()
-
     def step(i, ev=None):
         W = Ws[i % n_rot]
 
@@ -245,7 +241,7 @@ def main():
         st, info = aser.aser_whiten(ctx, buf.G, buf.mdiag, 0.0, buf.S, want_info=False)   # pivot check at the layer's one sync
         ctx.check(st)
         mark(5)
-        st, err, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, svd_opts)
+        st, err, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, idx=buf.idx, f=buf.f)
         ctx.check(st)
         mark(6)
         return err

@@ -31,13 +31,12 @@ ASER_CODES_INT4_PACKED = 1
 EXPORTS = (
     "aser_status_string", "aser_create", "aser_destroy", "aser_last_error", "aser_set_workspace",
     "aser_workspace_bytes", "aser_gram_accumulate", "aser_smooth_outliers", "aser_quantize_rtn",
-    "aser_whiten", "aser_error_reconstruct", "aser_quantize_act_rtn",
+    "aser_whiten", "aser_error_reconstruct", "aser_svd_plan", "aser_quantize_act_rtn",
 )
 
 
 class aser_svd_opts(ctypes.Structure):
-    _fields_ = [("block", ctypes.c_int32), ("max_iter", ctypes.c_int32), ("seed", ctypes.c_uint32),
-                ("n_lead", ctypes.c_int32), ("lead_cols", ctypes.c_void_p)]
+    _fields_ = [("block", ctypes.c_int32), ("max_iter", ctypes.c_int32), ("seed", ctypes.c_uint32)]
 
 
 class AserError(RuntimeError):
@@ -80,9 +79,12 @@ def load_library() -> ctypes.CDLL:
     lib.aser_whiten.restype = ctypes.c_int
     lib.aser_whiten.argtypes = [vp, vp, i64, i64, vp, f32, vp, i64, ctypes.POINTER(ctypes.c_int32)]
     lib.aser_error_reconstruct.restype = ctypes.c_int
-    lib.aser_error_reconstruct.argtypes = [vp, vp, i64, i64, i64, vp, i64, i32, ctypes.POINTER(aser_svd_opts),
+    lib.aser_error_reconstruct.argtypes = [vp, vp, i64, i64, i64, vp, i64, i32, vp, i32, ctypes.POINTER(aser_svd_opts),
                                            vp, vp, vp, ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int32)]
+    lib.aser_svd_plan.restype = ctypes.c_int
+    lib.aser_svd_plan.argtypes = [i64, i64, i32, ctypes.POINTER(aser_svd_opts), ctypes.POINTER(ctypes.c_int32),
+                                  ctypes.POINTER(ctypes.c_int32)]
     lib.aser_quantize_act_rtn.restype = ctypes.c_int
     lib.aser_quantize_act_rtn.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, vp, i32, vp, vp]
     _lib = lib
@@ -137,6 +139,7 @@ class Context:
         self.handle = h
         self.device = device
         self._ws = None
+        self._ws_bytes = 0
 
     def close(self):
         if self.handle:
@@ -159,11 +162,15 @@ class Context:
     def ensure_workspace(self, nbytes: int):
         """Allocates (with torch) and binds a workspace of at least nbytes."""
         import torch
-        if self._ws is None or self._ws.numel() < nbytes:
-            self._ws = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device="cuda:%d" % self.device)
-            base = self._ws.data_ptr()
+        nbytes = (int(nbytes) + 255) // 256 * 256
+        if self._ws is None or self._ws_bytes < nbytes:
+            new = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda:%d" % self.device)
+            base = new.data_ptr()
             off = (-base) % 256
-            self.check(self._lib.aser_set_workspace(self.handle, ctypes.c_void_p(base + off), int(nbytes)))
+            # the old tensor stays alive until the library has read what it left pending in it
+            st = self._lib.aser_set_workspace(self.handle, ctypes.c_void_p(base + off), nbytes)
+            self._ws, self._ws_bytes = new, nbytes
+            self.check(st)
 
 
 def aser_workspace_bytes(m: int, n: int, r: int, opts: Optional[aser_svd_opts] = None) -> int:
@@ -211,17 +218,25 @@ def aser_whiten(ctx: Context, G, mdiag, damp: float, S, *, n=None, ldg=None, lds
 
 
 def aser_error_reconstruct(ctx: Context, T, S, r: int, L_A, L_B, sigma, opts: Optional[aser_svd_opts] = None, *,
-                           m=None, n=None, ldt=None, lds=None):
-    """Returns (status, err, n_iter)."""
+                           idx=None, f: int = 0, m=None, n=None, ldt=None, lds=None):
+    """Returns (status, err, n_iter).  idx, f: the outlier set of aser_smooth_outliers (f = 0: none)."""
     m = T.shape[0] if m is None else m
     n = T.shape[1] if n is None else n
     err = ctypes.c_double(0.0)
     nit = ctypes.c_int32(0)
     st = ctx._lib.aser_error_reconstruct(ctx.handle, _ptr(T), m, n, _ld(T, n) if ldt is None else ldt, _ptr(S),
-                                         _ld(S, n) if lds is None else lds, r,
+                                         _ld(S, n) if lds is None else lds, r, _ptr(idx) if f > 0 else None, f,
                                          ctypes.byref(opts) if opts is not None else None, _ptr(L_A), _ptr(L_B),
                                          _ptr(sigma), ctypes.byref(err), ctypes.byref(nit))
     return st, err.value, nit.value
+
+
+def aser_svd_plan(m: int, n: int, r: int, opts: Optional[aser_svd_opts] = None):
+    """Returns (status, block, iters): what aser_error_reconstruct will use for this shape."""
+    b, it = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = load_library().aser_svd_plan(m, n, r, ctypes.byref(opts) if opts is not None else None, ctypes.byref(b),
+                                      ctypes.byref(it))
+    return st, b.value, it.value
 
 
 def aser_quantize_act_rtn(ctx: Context, X, mdiag, bits: int, codes, scales, *, rows=None, n=None, ldx=None,
@@ -277,12 +292,8 @@ def calibrate_layer(ctx: Context, W, X, buf: LayerBuffers, opts: Optional[aser_s
     ctx.check(aser_quantize_rtn(ctx, W, buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes, buf.scales, buf.T))
     st, _ = aser_whiten(ctx, buf.G, buf.mdiag, damp, buf.S, want_info=False)   # pivot check at the layer's one sync
     ctx.check(st)
-    o = aser_svd_opts()
-    if opts is not None:
-        o.block, o.max_iter, o.seed = opts.block, opts.max_iter, opts.seed
-    if buf.f > 0:                                # graded start block: the unquantized outlier columns of T lead
-        o.n_lead, o.lead_cols = buf.f, _ptr(buf.idx)
-    st, err, _ = aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, o)
+    st, err, _ = aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, opts,
+                                        idx=buf.idx, f=buf.f)
     ctx.check(st)
     buf.err = err
     return buf

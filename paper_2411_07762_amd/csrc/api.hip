@@ -28,6 +28,7 @@ extern "C" int aser_create(aser_ctx** out, int device, void* hip_stream) {
     c->ws_bytes = 0;
     c->device_ready = false;
     c->pending_info_dev = nullptr;
+    c->pending_sel_dev = nullptr;
     c->err[0] = 0;
     *out = c;
     return ASER_OK;
@@ -45,17 +46,17 @@ extern "C" int aser_set_workspace(aser_ctx* ctx, void* dev_ptr, size_t bytes) {
     if (!ctx) return ASER_ERR_INVALID_ARG;
     if (dev_ptr && ((uintptr_t)dev_ptr & 255)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "set_workspace: pointer must be 256-byte aligned");
     if (!dev_ptr && bytes) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "set_workspace: null pointer with non-zero size");
-    if (ctx->pending_info_dev) {
-        // a deferred pivot flag lives in the old workspace: fetch it before that memory goes away
-        int32_t h = INT_MAX;
-        ASER_HIP(ctx, hipMemcpyAsync(&h, ctx->pending_info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    int pending_status = ASER_OK;
+    if (ctx->pending_info_dev || ctx->pending_sel_dev) {
+        // deferred status words live in the old workspace: fetch them before that memory goes away
+        AserPending pend;
+        ASER_TRY(aser_fetch_pending(ctx, &pend));
         ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        ctx->pending_info_dev = nullptr;
-        if (h != INT_MAX && h != 0) ASER_FAIL(ctx, ASER_ERR_NOT_SPD, "whiten: non-positive pivot at index %d", h);
+        pending_status = aser_report_pending(ctx, pend, "set_workspace");
     }
     ctx->ws = dev_ptr;
-    ctx->ws_bytes = dev_ptr ? bytes : 0;
-    return ASER_OK;
+    ctx->ws_bytes = dev_ptr ? (bytes & ~(size_t)255) : 0;   // whole 256-byte units: the status words sit at the end
+    return pending_status;
 }
 
 extern "C" size_t aser_workspace_bytes(int64_t m, int64_t n, int32_t r, const aser_svd_opts* opts) {
@@ -79,6 +80,28 @@ int aser_prepare_device(aser_ctx* ctx) {
         ASER_HIP(ctx, hipGetDevice(&cur));
         if (cur != ctx->device) ASER_HIP(ctx, hipSetDevice(ctx->device));
     }
+    return ASER_OK;
+}
+
+int aser_fetch_pending(aser_ctx* ctx, AserPending* p) {
+    p->pivot = INT_MAX;
+    p->sel = 0;
+    if (ctx->pending_info_dev)
+        ASER_HIP(ctx, hipMemcpyAsync(&p->pivot, ctx->pending_info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    if (ctx->pending_sel_dev)
+        ASER_HIP(ctx, hipMemcpyAsync(&p->sel, ctx->pending_sel_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    return ASER_OK;
+}
+
+int aser_report_pending(aser_ctx* ctx, const AserPending& p, const char* who) {
+    ctx->pending_info_dev = nullptr;
+    ctx->pending_sel_dev = nullptr;
+    if (p.sel != 0)
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG,
+                  "smooth_outliers: fewer than f channels have a finite score (no tokens accumulated, or NaN/Inf in the "
+                  "statistics or in W); reported by %s", who);
+    if (p.pivot != INT_MAX && p.pivot != 0)
+        ASER_FAIL(ctx, ASER_ERR_NOT_SPD, "whiten: non-positive pivot at index %d (reported by %s)", p.pivot, who);
     return ASER_OK;
 }
 

@@ -17,11 +17,26 @@ struct aser_ctx {
     // aser_whiten without a host `info` leaves its pivot flag on the device (last 256 bytes of the
     // workspace) and does not synchronise; the next synchronising call reads it.
     int32_t* pending_info_dev;
+    // aser_smooth_outliers never synchronises; when fewer than f channels have a usable score its
+    // selection kernel raises the word behind the pivot flag, which the next synchronising call reads.
+    int32_t* pending_sel_dev;
     char err[256];
 };
 
-// Bytes at the end of the bound workspace that hold the whitening's pivot flag.
+// Bytes at the end of the bound workspace that hold the deferred status words: the whitening's pivot
+// flag (word 0) and the outlier selection's "no usable candidate" flag (word 1).
 static const size_t kAserWsTail = 256;
+
+// Host copies of the deferred status words; INT_MAX / 0 mean "nothing pending or nothing wrong".
+struct AserPending {
+    int32_t pivot;
+    int32_t sel;
+};
+// Enqueues the copies of whatever is pending into *p (the caller synchronises the stream, then calls
+// aser_report_pending, which clears the pending state and turns a raised word into a status).
+int aser_fetch_pending(aser_ctx* ctx, AserPending* p);
+int aser_report_pending(aser_ctx* ctx, const AserPending& p, const char* who);
+int aser_set_i32(aser_ctx* ctx, int32_t* p, int32_t v);
 
 #define ASER_FAIL(ctx, code, ...)                                   \
     do {                                                            \

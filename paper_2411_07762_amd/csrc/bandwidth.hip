@@ -39,6 +39,8 @@ __global__ void fill_f32_kernel(float* p, int64_t rows, int64_t cols, int64_t ld
         p[(i / cols) * ld + (i % cols)] = v;
 }
 
+__global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
+
 __global__ void fill_zero_kernel(uint32_t* p, int64_t words) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (int64_t)gridDim.x * blockDim.x)
         p[i] = 0u;
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(NT) void rtn_kernel(const float* __restrict__ W, in
     __syncthreads();
     for (int i = tid; i < f; i += NT) {
         const int c = idx[i];
-        atomicOr(&mask[c >> 5], 1u << (c & 31));
+        if (c >= 0 && c < n) atomicOr(&mask[c >> 5], 1u << (c & 31));   // entries outside [0, n) are ignored
     }
     __syncthreads();
 
@@ -562,6 +564,11 @@ int aser_fill_f32(aser_ctx* ctx, float* p, int64_t rows, int64_t cols, int64_t l
     const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
     hipLaunchKernelGGL(fill_f32_kernel, dim3(blocks), dim3(256), 0, ctx->stream, p, rows, cols, ld, v);
     return aser_check_launch(ctx, "fill_f32");
+}
+
+int aser_set_i32(aser_ctx* ctx, int32_t* p, int32_t v) {
+    hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, p, v);
+    return aser_check_launch(ctx, "set_i32");
 }
 
 int aser_fill_bytes(aser_ctx* ctx, void* p, size_t bytes) {

@@ -146,27 +146,51 @@ int chol_qr(aser_ctx* ctx, float* Y, float* out, int64_t rows, int64_t clear_row
     return aser_gemm_small_f32(ctx, Y, b, Rinv, b, out, b, rows, b, b, clear_rows);
 }
 
+// The plan with the block width made legal for the shape: ASER_OK, or ASER_ERR_SHAPE with a text in *why.
+int legal_plan(int64_t m, int64_t n, int r, const aser_svd_opts* opts, Plan* p, const char** why) {
+    if (m <= 0 || n <= 0) { *why = "bad shape"; return ASER_ERR_SHAPE; }
+    if (r <= 0 || r > m || r > n || r > 128) { *why = "need 0 < r <= min(m, n, 128)"; return ASER_ERR_SHAPE; }
+    make_plan(m, n, r, opts, p);
+    if (p->b < r || p->b > 128 || (p->b % 32) != 0 || p->b > m || p->b > n) {
+        // a block wider than the matrix makes no sense; shrink to the largest legal width
+        int b = p->b;
+        if (opts && opts->block > 0) { *why = "block must be a multiple of 32 in [r, min(128, m, n)]"; return ASER_ERR_SHAPE; }
+        const int64_t lim = (m < n ? m : n);
+        while (b > lim) b -= 32;
+        if (b < r) { *why = "no legal block width for this r and shape"; return ASER_ERR_SHAPE; }
+        aser_svd_opts o2 = opts ? *opts : aser_svd_opts{0, 0, 0};
+        o2.block = b;
+        make_plan(m, n, r, &o2, p);
+    }
+    return ASER_OK;
+}
+
 }  // namespace
 
+extern "C" int aser_svd_plan(int64_t m, int64_t n, int32_t r, const aser_svd_opts* opts, int32_t* block, int32_t* iters) {
+    Plan p;
+    const char* why = "";
+    const int st = legal_plan(m, n, r, opts, &p, &why);
+    if (st != ASER_OK) return st;
+    if (block) *block = p.b;
+    if (iters) *iters = p.iters;
+    return ASER_OK;
+}
+
 extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt,
-                                      const float* S, int64_t lds, int32_t r, const aser_svd_opts* opts,
+                                      const float* S, int64_t lds, int32_t r, const int32_t* idx, int32_t f,
+                                      const aser_svd_opts* opts,
                                       float* L_A, float* L_B, float* sigma, double* err, int32_t* n_iter) {
     if (!ctx) return ASER_ERR_INVALID_ARG;
     if (!T || !S || !L_A || !L_B || !sigma) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "error_reconstruct: null pointer");
     if (m <= 0 || n <= 0 || ldt < n || lds < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: bad shape");
-    if (r <= 0 || r > m || r > n || r > 128) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: need 0 < r <= min(m, n, 128)");
+    if (f < 0 || f > n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: f must be in [0, n]");
+    if (f > 0 && !idx) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "error_reconstruct: idx is null with f > 0");
     Plan p;
-    make_plan(m, n, r, opts, &p);
-    if (p.b < r || p.b > 128 || (p.b % 32) != 0 || p.b > m || p.b > n) {
-        // a block wider than the matrix makes no sense; shrink to the largest legal width
-        int b = p.b;
-        if (opts && opts->block > 0) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: block must be a multiple of 32 in [r, min(128, m, n)]");
-        const int64_t lim = (m < n ? m : n);
-        while (b > lim) b -= 32;
-        if (b < r) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: no legal block width for this r and shape");
-        aser_svd_opts o2 = opts ? *opts : aser_svd_opts{0, 0, 0, 0};
-        o2.block = b;
-        make_plan(m, n, r, &o2, &p);
+    {
+        const char* why = "";
+        const int st = legal_plan(m, n, r, opts, &p, &why);
+        if (st != ASER_OK) ASER_FAIL(ctx, st, "error_reconstruct: %s", why);
     }
     if (((uintptr_t)T & 3) || ((uintptr_t)S & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "error_reconstruct: misaligned pointer");
     if (!ctx->ws || ctx->ws_bytes < p.total + kAserWsTail)
@@ -226,13 +250,13 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         const int blocks = (int)(ceil_div64(total, 256) < 2048 ? ceil_div64(total, 256) : 2048);
         hipLaunchKernelGGL(random_block_kernel, dim3(blocks), dim3(256), 0, ctx->stream, Qacc, total, p.seed);
         ASER_TRY(aser_check_launch(ctx, "random_block"));
-        if (opts && opts->lead_cols && opts->n_lead > 0) {
-            // graded start: the dominant columns of T first (their span holds the largest left singular
-            // directions of T S), the random columns behind them
-            const int k = opts->n_lead < b ? opts->n_lead : b;
+        if (f > 0) {
+            // graded start: the unquantized outlier columns of T first (their span holds the largest left
+            // singular directions of T S), the random columns behind them
+            const int k = f < b ? f : b;
             const int64_t tot = m * (int64_t)k;
             const int blk = (int)(ceil_div64(tot, 256) < 1024 ? ceil_div64(tot, 256) : 1024);
-            hipLaunchKernelGGL(lead_columns_kernel, dim3(blk), dim3(256), 0, ctx->stream, T, m, ldt, opts->lead_cols, k, n, Qacc, b);
+            hipLaunchKernelGGL(lead_columns_kernel, dim3(blk), dim3(256), 0, ctx->stream, T, m, ldt, idx, k, n, Qacc, b);
             ASER_TRY(aser_check_launch(ctx, "lead_columns"));
         }
     }
@@ -284,15 +308,13 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, WBt, r, L_B, n, n, b, r, 0, true));   // (n x r)^T = L_B
 
     double h_res2 = 0.0;
-    int32_t h_pivot = INT_MAX, h_qr = 0;
+    int32_t h_qr = 0;
+    AserPending pend;                                    // status words of calls that did not synchronise
     ASER_HIP(ctx, hipMemcpyAsync(&h_res2, normA2, 8, hipMemcpyDeviceToHost, ctx->stream));
     ASER_HIP(ctx, hipMemcpyAsync(&h_qr, info, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
-    if (ctx->pending_info_dev)                           // pivot flag of a whitening that did not synchronise
-        ASER_HIP(ctx, hipMemcpyAsync(&h_pivot, ctx->pending_info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    ASER_TRY(aser_fetch_pending(ctx, &pend));
     ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    ctx->pending_info_dev = nullptr;
-    if (h_pivot != INT_MAX && h_pivot != 0)
-        ASER_FAIL(ctx, ASER_ERR_NOT_SPD, "whiten: non-positive pivot at index %d (reported by error_reconstruct)", h_pivot);
+    ASER_TRY(aser_report_pending(ctx, pend, "error_reconstruct"));
     if (h_qr < 0 || !(h_res2 >= 0.0) || h_res2 > 1e300)
         ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE,
                   "error_reconstruct: the Cholesky-QR orthogonalisation broke down (pivot %d of a block Gram matrix is not "

@@ -65,7 +65,8 @@ template <int kSelThreads, int kSelPerThread>   // kSelThreads * kSelPerThread >
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const double* __restrict__ score,
                                                              const double* __restrict__ abs_sum,
                                                              const int64_t* __restrict__ count, int n, int f,
-                                                             int32_t* __restrict__ idx, float* __restrict__ mdiag) {
+                                                             int32_t* __restrict__ idx, float* __restrict__ mdiag,
+                                                             int32_t* __restrict__ no_candidate) {
     __shared__ double red_s[2][kSelThreads / 64];
     __shared__ int red_i[2][kSelThreads / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -77,6 +78,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const double* __res
     for (int u = 0; u < kSelPerThread; ++u) {
         const int c = u * kSelThreads + tid;
         sc[u] = (c < n) ? score[c] : -1.0;          // scores are >= 0; -1 marks "absent / taken"
+        if (!(sc[u] <= 1.7e308)) sc[u] = -1.0;      // NaN or +Inf (no tokens, or non-finite statistics): never a candidate
     }
     double best_s = -1.0;
     int best_i = 0x7FFFFFFF;
@@ -101,8 +103,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const double* __res
 #pragma unroll
         for (int w = 1; w < kSelThreads / 64; ++w)
             if (beats(rs[w], ri[w], ws, wi)) { ws = rs[w]; wi = ri[w]; }
-        if (tid == 0) idx[round] = wi;
-        if ((wi % kSelThreads) == tid) {             // owner: retire the winner, rescan
+        // No candidate left (fewer than f channels with a finite score): the slot gets -1, which every
+        // consumer of idx skips, and the flag makes the next synchronising call fail with a status.
+        const bool none = wi < 0 || wi >= n;
+        if (tid == 0) {
+            idx[round] = none ? -1 : wi;
+            if (none) *no_candidate = 1;
+        }
+        if (!none && (wi % kSelThreads) == tid) {    // owner: retire the winner, rescan
             best_s = -1.0;
             best_i = 0x7FFFFFFF;
 #pragma unroll
@@ -120,7 +128,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const double* __res
         const double cnt = (double)(*count);
         double xmin = 1.0e300;
         for (int k = tid; k < f; k += kSelThreads) {
-            const double x = abs_sum[idx[k]] / cnt;
+            const int c = idx[k];
+            if (c < 0) continue;
+            const double x = abs_sum[c] / cnt;
             xmin = x < xmin ? x : xmin;
         }
 #pragma unroll
@@ -135,12 +145,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const double* __res
         for (int w = 1; w < kSelThreads / 64; ++w) xmin = red_s[0][w] < xmin ? red_s[0][w] : xmin;
         for (int k = tid; k < f; k += kSelThreads) {
             const int c = idx[k];
-            mdiag[c] = (float)((abs_sum[c] / cnt) / xmin);
+            if (c >= 0) mdiag[c] = (float)((abs_sum[c] / cnt) / xmin);
         }
     }
 }
 
-__global__ __launch_bounds__(256) void gather_wo_kernel(const float* __restrict__ W, int64_t m, int64_t ldw,
+__global__ __launch_bounds__(256) void gather_wo_kernel(const float* __restrict__ W, int64_t m, int64_t n, int64_t ldw,
                                                         const int32_t* __restrict__ idx, const float* __restrict__ mdiag,
                                                         int f, float* __restrict__ W_o) {
     const int64_t total = m * f;
@@ -148,29 +158,20 @@ __global__ __launch_bounds__(256) void gather_wo_kernel(const float* __restrict_
         const int64_t o = t / f;
         const int k = (int)(t % f);
         const int c = idx[k];
-        W_o[t] = W[o * ldw + c] * mdiag[c];
+        W_o[t] = (c >= 0 && c < n) ? W[o * ldw + c] * mdiag[c] : 0.f;
     }
 }
 
 }  // namespace
 
-extern "C" int aser_smooth_outliers(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
-                                    const double* abs_sum, const int64_t* count, int32_t f,
-                                    int32_t* idx, float* mdiag, float* W_o, double* score) {
-    if (!ctx) return ASER_ERR_INVALID_ARG;
-    if (!W || !abs_sum || !count || !mdiag) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: null pointer");
-    if (m <= 0 || n <= 0 || ldw < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: bad shape");
-    if (f < 0 || f > n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: f must be in [0, n]");
-    if (f > 0 && !idx) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: idx is null");
-    if (n > kSelMaxN) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: n > 32768 is not supported");
-    if (((uintptr_t)abs_sum & 7) || ((uintptr_t)count & 7) || (score && ((uintptr_t)score & 7)))
-        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: misaligned fp64/int64 pointer");
-    const size_t need = align_up((size_t)n * 8, 256) * 2;
-    if (!ctx->ws || ctx->ws_bytes < need) ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "smooth_outliers: workspace too small");
-    ASER_TRY(aser_prepare_device(ctx));
-
-    double* wsum = (double*)ctx->ws;
-    double* sc = score ? score : (double*)((char*)ctx->ws + align_up((size_t)n * 8, 256));
+// The two fp64 arrays of n entries (column sums of |W|, scores) and the selection's status word, wherever
+// they live: in the bound workspace (aser_smooth_outliers) or in this file's static array.
+static int smooth_run(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw, const double* abs_sum,
+                      const int64_t* count, int32_t f, int32_t* idx, float* mdiag, float* W_o, double* score,
+                      double* wsum, double* sc_scratch, int32_t* sel_flag) {
+    if (ctx->pending_sel_dev != sel_flag) ASER_TRY(aser_set_i32(ctx, sel_flag, 0));
+    ctx->pending_sel_dev = sel_flag;
+    double* sc = score ? score : sc_scratch;
     ASER_TRY(aser_fill_bytes(ctx, wsum, (size_t)n * 8));
     ASER_TRY(aser_col_abs_sum_w(ctx, W, m, n, ldw, wsum));
     hipLaunchKernelGGL(score_kernel, dim3((unsigned)ceil_div64(n, 256)), dim3(256), 0, ctx->stream, abs_sum, count,
@@ -180,20 +181,46 @@ extern "C" int aser_smooth_outliers(aser_ctx* ctx, const float* W, int64_t m, in
     // of the single workgroup repeats the same reduction
     if (n <= 4096)
         hipLaunchKernelGGL((select_kernel<256, 16>), dim3(1), dim3(256), 0, ctx->stream, (const double*)sc, abs_sum, count,
-                           (int)n, (int)f, idx, mdiag);
+                           (int)n, (int)f, idx, mdiag, sel_flag);
     else if (n <= 16384)
         hipLaunchKernelGGL((select_kernel<512, 32>), dim3(1), dim3(512), 0, ctx->stream, (const double*)sc, abs_sum, count,
-                           (int)n, (int)f, idx, mdiag);
+                           (int)n, (int)f, idx, mdiag, sel_flag);
     else
         hipLaunchKernelGGL((select_kernel<1024, 32>), dim3(1), dim3(1024), 0, ctx->stream, (const double*)sc, abs_sum, count,
-                           (int)n, (int)f, idx, mdiag);
+                           (int)n, (int)f, idx, mdiag, sel_flag);
     ASER_TRY(aser_check_launch(ctx, "select"));
     if (W_o && f > 0) {
         const int64_t total = m * f;
         const int blocks = (int)(ceil_div64(total, 256) < 2048 ? ceil_div64(total, 256) : 2048);
-        hipLaunchKernelGGL(gather_wo_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, m, ldw, (const int32_t*)idx,
+        hipLaunchKernelGGL(gather_wo_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, m, n, ldw, (const int32_t*)idx,
                            (const float*)mdiag, (int)f, W_o);
         ASER_TRY(aser_check_launch(ctx, "gather_wo"));
     }
     return ASER_OK;
+}
+
+static int smooth_validate(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw, const double* abs_sum,
+                           const int64_t* count, int32_t f, const int32_t* idx, const float* mdiag, const double* score) {
+    if (!W || !abs_sum || !count || !mdiag) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: null pointer");
+    if (m <= 0 || n <= 0 || ldw < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: bad shape");
+    if (f < 0 || f > n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: f must be in [0, n]");
+    if (f > 0 && !idx) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: idx is null");
+    if (n > kSelMaxN) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers: n > 32768 is not supported");
+    if (((uintptr_t)abs_sum & 7) || ((uintptr_t)count & 7) || (score && ((uintptr_t)score & 7)))
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers: misaligned fp64/int64 pointer");
+    return ASER_OK;
+}
+
+extern "C" int aser_smooth_outliers(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                                    const double* abs_sum, const int64_t* count, int32_t f,
+                                    int32_t* idx, float* mdiag, float* W_o, double* score) {
+    if (!ctx) return ASER_ERR_INVALID_ARG;
+    ASER_TRY(smooth_validate(ctx, W, m, n, ldw, abs_sum, count, f, idx, mdiag, score));
+    const size_t need = align_up((size_t)n * 8, 256) * 2 + kAserWsTail;
+    if (!ctx->ws || ctx->ws_bytes < need) ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "smooth_outliers: workspace too small");
+    ASER_TRY(aser_prepare_device(ctx));
+    // word 1 of the workspace tail: raised by the selection when it runs out of usable channels
+    int32_t* sel_flag = (int32_t*)((char*)ctx->ws + ctx->ws_bytes - kAserWsTail) + 1;
+    return smooth_run(ctx, W, m, n, ldw, abs_sum, count, f, idx, mdiag, W_o, score, (double*)ctx->ws,
+                      (double*)((char*)ctx->ws + align_up((size_t)n * 8, 256)), sel_flag);
 }

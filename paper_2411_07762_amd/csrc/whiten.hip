@@ -68,8 +68,6 @@ __global__ __launch_bounds__(256) void diag_scaled_sum_kernel(const float* G, in
     if (threadIdx.x == 0) *out = red[0] + red[1] + red[2] + red[3];
 }
 
-__global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
-
 // The factor was built as R = S^T in the upper triangle.  One pass over pairs of 64 x 64 tiles moves it
 // to the lower triangle (through LDS, both sides coalesced) and clears the strict upper triangle.
 __global__ __launch_bounds__(256) void upper_to_lower_kernel(float* S, int64_t n, int64_t lds) {
@@ -114,8 +112,9 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
     int32_t* info_dev = (int32_t*)((char*)ctx->ws + ctx->ws_bytes - kAserWsTail);
     double* diag_sum = (double*)((char*)ctx->ws + (size_t)kNb * kNb * 4 + 256);
 
-    hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, ctx->stream, info_dev, (int32_t)INT_MAX);
-    ASER_TRY(aser_check_launch(ctx, "set_info"));
+    // A flag still pending from an earlier asynchronous call is kept (the factorisation lowers it with
+    // atomicMin): that call's failed pivot is then still reported, by whichever call synchronises next.
+    if (ctx->pending_info_dev != info_dev) ASER_TRY(aser_set_i32(ctx, info_dev, (int32_t)INT_MAX));
     if (damp > 0.f) {
         hipLaunchKernelGGL(diag_scaled_sum_kernel, dim3(1), dim3(256), 0, ctx->stream, G, ldg, n, mdiag, diag_sum);
         ASER_TRY(aser_check_launch(ctx, "diag_sum"));
@@ -175,12 +174,10 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
         ctx->pending_info_dev = info_dev;
         return ASER_OK;
     }
-    ctx->pending_info_dev = nullptr;
-    int32_t h_info = 0;
-    ASER_HIP(ctx, hipMemcpyAsync(&h_info, info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    ctx->pending_info_dev = info_dev;
+    AserPending pend;
+    ASER_TRY(aser_fetch_pending(ctx, &pend));
     ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    const int32_t res = (h_info == INT_MAX) ? 0 : h_info;
-    *info = res;
-    if (res != 0) ASER_FAIL(ctx, ASER_ERR_NOT_SPD, "whiten: non-positive pivot at index %d", res);
-    return ASER_OK;
+    *info = (pend.pivot == INT_MAX) ? 0 : pend.pivot;
+    return aser_report_pending(ctx, pend, "whiten");
 }

@@ -6,7 +6,9 @@ the oracle's; the product L_A L_B within 1e-3 relative Frobenius when the oracle
 sigma_r / sigma_{r+1} exceeds 1.05.  Tolerances of the fp32 intermediates are derived in the
 design notes (Gram: fp32 accumulation over N tokens; fp32 inputs: bf16 hi/lo split, 2^-16 per product).
 """
+import os
 import sys
+import time
 
 import numpy as np
 import pytest
@@ -21,9 +23,19 @@ from gpu_util import DEV, lower, new_ctx, padded, run_gram, to_dev_x, unpack_int
 pytestmark = pytest.mark.gpu
 
 
+_PROGRESS = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "test_progress.log")
+
+
 def say(msg):
+    """Names the case before each GPU step: on stdout (shown on failure or with -s) and, because pytest
+    holds stdout back, appended to a progress file that a watcher of a long run can see grow."""
     print(msg, flush=True)
-    sys.stdout.flush()
+    try:
+        os.makedirs(os.path.dirname(_PROGRESS), exist_ok=True)
+        with open(_PROGRESS, "a") as fh:
+            fh.write("%s %s\n" % (time.strftime("%H:%M:%S"), msg))
+    except OSError:
+        pass
 
 
 def oracle_layer(spec, W, x_np, r=None, f=None):
@@ -133,6 +145,46 @@ def test_smooth_tie_break_lower_index():
     assert np.array_equal(mdiag.cpu().numpy(), ref.mdiag)
 
 
+def test_smooth_without_usable_scores_is_reported_not_faulted():
+    """No tokens accumulated (count = 0), and a NaN in the statistics: the selection finds fewer than f
+    channels with a finite score.  idx gets -1 there, every kernel that consumes idx skips such entries,
+    and the next synchronising call returns ASER_ERR_INVALID_ARG instead of numbers."""
+    spec = synth.mini("sg", 24, 96, 64, f=5)
+    W = torch.from_numpy(synth.make_weight(spec)).to(DEV)
+    n, m, f = spec.n, spec.m, spec.f
+    for case in ("count_zero", "nan_statistics"):
+        say("smooth guard case %s" % case)
+        ctx = new_ctx()
+        ctx.ensure_workspace(aser.aser_workspace_bytes(m, n, 4))
+        abs_sum = torch.zeros(n, dtype=torch.float64, device=DEV)
+        count = torch.zeros(1, dtype=torch.int64, device=DEV)
+        if case == "nan_statistics":
+            abs_sum += float("nan")
+            abs_sum[:3] = torch.tensor([5.0, 9.0, 7.0], dtype=torch.float64)   # only three usable channels for f = 5
+            count += 10
+        idx = torch.full((f,), 77, dtype=torch.int32, device=DEV)
+        mdiag = torch.empty(n, dtype=torch.float32, device=DEV)
+        W_o = torch.empty((m, f), dtype=torch.float32, device=DEV)
+        ctx.check(aser.aser_smooth_outliers(ctx, W, abs_sum, count, f, idx, mdiag, W_o))
+        codes = torch.empty((m, n), dtype=torch.int8, device=DEV)
+        scales = torch.empty(m, dtype=torch.float32, device=DEV)
+        T = torch.empty((m, n), dtype=torch.float32, device=DEV)
+        ctx.check(aser.aser_quantize_rtn(ctx, W, idx, mdiag, f, 4, aser.ASER_CODES_INT8, codes, scales, T))
+        torch.cuda.synchronize()
+        got = idx.cpu().numpy().tolist()
+        if case == "count_zero":
+            assert got == [-1] * f
+        else:
+            assert sorted(got[:3]) == [0, 1, 2] and got[3:] == [-1, -1]
+            assert np.isfinite(mdiag.cpu().numpy()).all()
+        G = torch.eye(n, dtype=torch.float32, device=DEV)
+        S = torch.empty_like(G)
+        st, info = aser.aser_whiten(ctx, G, None, 0.0, S)          # the next synchronising call carries the report
+        assert st == aser.ASER_ERR_INVALID_ARG and "smooth_outliers" in ctx.last_error()
+        st, info = aser.aser_whiten(ctx, G, None, 0.0, S)          # reported once
+        assert st == aser.ASER_OK and info == 0
+
+
 RTN_CASES = [
     ("c0_int4_packed", synth.CONFIGS["c0"], 4, True),
     ("c0_int8", synth.CONFIGS["c0"], 8, False),
@@ -205,6 +257,43 @@ def test_quantize_act_rtn(name, spec):
     assert np.array_equal(codes.cpu().numpy(), ref_codes)
     assert np.array_equal(scales.cpu().numpy(), ref_scales)
     assert ref_scales[1] == 1.0
+
+
+# The wavefront-per-token kernel walks 2 to 4 tokens per wavefront once there are 8192 tokens or more (the
+# shape of every activation stream of the bench): token counts that leave the last wavefront with fewer
+# tokens than the others, a channel count below 4096 (lanes without channels), both input types.
+ACT_MANY_TOKENS = [("bf16_8195x4096", 8195, 4096, "bf16"), ("bf16_16387x4096", 16387, 4096, "bf16"),
+                   ("bf16_12290x2064", 12290, 2064, "bf16"), ("f32_8197x4096", 8197, 4096, "f32"),
+                   ("f32_16386x1008", 16386, 1008, "f32")]
+
+
+@pytest.mark.parametrize("name,tokens,n,dt", ACT_MANY_TOKENS, ids=[c[0] for c in ACT_MANY_TOKENS])
+def test_quantize_act_rtn_many_tokens_per_wavefront(name, tokens, n, dt):
+    say("act rtn case %s" % name)
+    spec = synth.mini("am_" + name, 8, n, tokens, x_dtype=dt, f=32, n_outliers=16, seed_id=930)
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    X = synth.activations_as_f32(spec, x_np).copy()
+    X[5, :] = 0.0                                                # an all-zero token: scale 1
+    X[tokens - 1, :] *= np.float32(3.0)                          # the last token, alone in its wavefront's tail
+    x_np = synth.f32_to_bf16_bits(X) if dt == "bf16" else X
+    X = synth.activations_as_f32(spec, x_np)
+    _, abs_ref, cnt = orc.gram(X)
+    sm = orc.smooth_outliers(W, abs_ref, cnt, spec.f)
+    assert (sm.mdiag != 1.0).sum() >= spec.f - 1
+    ctx = new_ctx()
+    xd = to_dev_x(spec, x_np)
+    for bits in (8, 6):
+        ref_codes, ref_scales = orc.quantize_act_rtn(X, sm.mdiag, bits)
+        codes = torch.zeros((tokens, n), dtype=torch.int8, device=DEV)
+        scales = torch.empty(tokens, dtype=torch.float32, device=DEV)
+        ctx.check(aser.aser_quantize_act_rtn(ctx, xd, torch.from_numpy(sm.mdiag).to(DEV), bits, codes, scales))
+        torch.cuda.synchronize()
+        assert np.array_equal(scales.cpu().numpy(), ref_scales)
+        got = codes.cpu().numpy()
+        bad = np.argwhere(got != ref_codes)
+        assert bad.size == 0, "first mismatch at token %d channel %d" % (bad[0][0], bad[0][1])
+        assert ref_scales[5] == 1.0
 
 
 WHITEN_CASES = [
@@ -285,7 +374,11 @@ def check_reconstruction(spec, ref, L_A, L_B, sigma, err_gpu, label):
         (label, r, rec.gap, rec.err, e, rel, abs(err_gpu - rec.err) / rec.err))
     assert rel <= 1e-4
     assert abs(err_gpu - rec.err) / rec.err <= 1e-4
-    assert np.allclose(sigma[:min(r, spec.f)], rec.sigma[:min(r, spec.f)], rtol=1e-3)
+    # singular values: those of the planted outlier directions are isolated and must agree closely; the rest
+    # sit in a near-continuous bulk where a Ritz value is a weighted mean of its neighbours
+    k_iso = min(r, spec.n_outliers)
+    assert np.allclose(sigma[:k_iso], rec.sigma[:k_iso], rtol=1e-3)
+    assert np.allclose(sigma[:min(r, spec.f)], rec.sigma[:min(r, spec.f)], rtol=5e-3)
     assert np.all(np.diff(sigma) <= 1e-6 * sigma[0])
     if rec.gap > 1.05:
         P = L_A.astype(np.float64) @ L_B.astype(np.float64)
@@ -385,17 +478,31 @@ def test_headline_layer_full_size():
     run_e2e("c1_full", spec, True)
 
 
-@pytest.mark.parametrize("cfg", ["c2", "c3.gate", "c3.k", "c3.down", "c4"])
-def test_large_layers_full_size_sampled(cfg):
+def test_headline_layer_full_size_rank_at_the_spectral_gap():
+    """The same layer with r = 16, the number of planted outlier channels: their columns of T stand far
+    above everything else (sigma_16 / sigma_17 = 6.7; the other 16 of the f = 32 extracted channels are
+    ordinary ones, so r = f = 32 sits in the bulk with a gap of 1.001), the product L_A L_B is determined
+    and the 1e-3 bar on it runs at full size (Sec. 4.1 definitions of L_A, L_B)."""
+    spec = synth.CONFIGS["c1"].with_(r=16)
+    say("e2e case c1 full size with r = 16")
+    _, ref = run_e2e("c1_full_r16", spec, True)
+    assert ref.rec.gap > 1.05
+
+
+@pytest.mark.parametrize("cfg", ["c2", "c3.q", "c3.k", "c3.v", "c3.o", "c3.gate", "c3.up", "c3.down", "c4"])
+def test_large_layers_full_size(cfg):
     """Full-size layers whose oracle SVD takes minutes: the 4096 x 11008 layer with 65536 tokens of
-    heavy-tailed activations, and two layers of the Llama-3-8B-shaped block with 131072 tokens (the
-    tall 14336 x 4096 gate projection, the flat 1024 x 4096 key projection and the 4096 x 14336 down
-    projection), and the 8192 x 28672 layer with 262144 tokens and r = 128 (15 GB of activations, a
-    3.3 GB Gram matrix, no oversampling columns in the subspace block).  Each stage is checked
-    on samples the oracle computes one by one (Gram entries, statistics, RTN rows) or through
-    identities that hold at any size (S S^T = G', reported error = whitened error recomputed from the
-    returned factors, Eq. 8), and the error against the optimum from the spectrum of the smaller Gram
-    matrix of A = T S."""
+    heavy-tailed activations, the seven layers of the Llama-3-8B-shaped block with 131072 tokens per
+    input stream, and the 8192 x 28672 layer with 262144 tokens and r = 128 (15 GB of activations, a
+    3.3 GB Gram matrix, no oversampling columns in the subspace block).  Nothing is sampled:
+      * statistics, outlier set, smoothing diagonal, RTN codes, scales and T: every entry against the oracle;
+      * Gram matrix: G V against X^T (X V) in fp64 for random sign vectors V (every entry of the lower
+        triangle enters), plus exact entries on a set of channel pairs;
+      * whitening factor: strictly upper triangle zero everywhere, S (S^T V) against M^-1 X^T (X M^-1 V)
+        (Eq. 5 with the smoothed activations of Algorithm 1), both sides from fp64 host arithmetic on X;
+      * factors: the whitened error of Eq. 8 recomputed in fp64 from L_A, L_B with T and S as the oracle
+        defines them from this layer's statistics (T from the oracle's RTN; S enters only through
+        S S^T = G', checked above), against the optimum from LAPACK's symmetric eigen-solver."""
     spec = synth.CONFIGS[cfg]
     say("%s full size m=%d n=%d N=%d r=%d f=%d" % (cfg, spec.m, spec.n, spec.tokens, spec.r, spec.f))
     rng = np.random.default_rng(7)
@@ -407,48 +514,77 @@ def test_large_layers_full_size_sampled(cfg):
     aser.calibrate_layer(ctx, torch.from_numpy(W).to(DEV), to_dev_x(spec, x_np), buf)
     torch.cuda.synchronize()
     say("%s: device path done, err=%.6g" % (cfg, buf.err))
+    n, m = spec.n, spec.m
 
-    # statistics of all channels (fp64, chunked) and the smoothing decision
-    abs_ref = np.zeros(spec.n)
+    # one fp64 pass over X on the host: |x| sums, X^T (X V) and X^T (X M^-1 V) for random sign vectors
+    nv = 3
+    V = rng.choice([-1.0, 1.0], size=(n, nv))
+    abs_ref = np.zeros(n)
     for a in range(0, spec.tokens, 8192):
         abs_ref += np.abs(synth.bf16_to_f32(x_np[a:a + 8192])).sum(axis=0, dtype=np.float64)
     assert np.allclose(buf.abs_sum.cpu().numpy(), abs_ref, rtol=1e-12, atol=0)
     sm = orc.smooth_outliers(W, abs_ref, spec.tokens, spec.f)
     assert buf.idx.cpu().numpy()[:spec.f].tolist() == sm.idx.tolist()
     assert np.array_equal(buf.mdiag.cpu().numpy(), sm.mdiag)
+    minv = 1.0 / sm.mdiag.astype(np.float64)
+    V2 = np.concatenate([V, minv[:, None] * V], axis=1)
+    XtXV = np.zeros((n, 2 * nv))
+    gdiag = np.zeros(n)
+    for a in range(0, spec.tokens, 4096):
+        xc = synth.bf16_to_f32(x_np[a:a + 4096]).astype(np.float64)
+        XtXV += xc.T @ (xc @ V2)
+        gdiag += np.einsum("ij,ij->j", xc, xc)
+    del xc
+    say("%s: host pass over X done" % cfg)
 
-    # Gram entries: pairs of channels across tiles, the last tile, planted outliers and the diagonal
+    # Gram matrix: every entry of the lower triangle through G V
+    G = buf.G.cpu().numpy()
+    GV = np.zeros((n, nv))
+    for a in range(0, n, 2048):
+        blk = np.tril(G[a:a + 2048].astype(np.float64), k=a)          # rows a.., columns <= row
+        GV[a:a + 2048] += blk @ V
+        blk[:, a:a + 2048] -= np.diag(np.diag(blk[:, a:a + 2048]))    # strictly lower part, transposed contribution
+        GV += blk.T @ V[a:a + 2048]
+    d = np.sqrt(gdiag)
+    # entry errors are bounded by 2e-5 sqrt(G_ii G_jj) and have random signs: their sum over a row of n
+    # entries against sign vectors stays within a fifth of that bound times sqrt(sum_j G_jj)
+    tol = 4e-6 * d[:, None] * np.sqrt((gdiag[:, None] * V * V).sum(axis=0))[None, :]
+    worst = float((np.abs(GV - XtXV[:, :nv]) / tol).max())
+    say("%s: G V against X^T (X V): worst entry at %.2f of its tolerance" % (cfg, worst))
+    assert worst <= 1.0
+    assert np.allclose(np.diag(G), gdiag, rtol=2e-5)
+    # exact entries on channel pairs across tiles, the last tile and planted outliers
     planted, _ = synth.outlier_channels(spec)
-    cols = np.unique(np.concatenate([rng.integers(0, spec.n, 20), [0, 255, 256, spec.n - 1, spec.n - 256], planted[:4]]))
-    cols = cols[(cols >= 0) & (cols < spec.n)]
+    cols = np.unique(np.concatenate([rng.integers(0, n, 20), [0, 255, 256, n - 1, n - 256], planted[:4]]))
     Xs = synth.bf16_to_f32(x_np[:, cols])
     G_ref, _, _ = orc.gram(Xs)
-    G = buf.G.cpu().numpy()
-    # the lower triangle is authoritative: take entry (max, min)
     Gs = np.where(cols[:, None] >= cols[None, :], G[np.ix_(cols, cols)], G[np.ix_(cols, cols)].T)
-    d = np.sqrt(np.diag(G_ref))
-    assert np.all(np.abs(Gs - G_ref) <= 2e-5 * np.outer(d, d))
-    del Xs
+    dc = np.sqrt(np.diag(G_ref))
+    assert np.all(np.abs(Gs - G_ref) <= 2e-5 * np.outer(dc, dc))
+    del Xs, G
 
-    # RTN on sampled rows (rows are independent)
-    rows = np.unique(np.concatenate([rng.integers(0, spec.m, 40), [0, spec.m - 1]]))
-    ref_q = orc.quantize_rtn(W[rows], sm.idx, sm.mdiag, spec.bits)
-    codes = unpack_int4(buf.codes.cpu().numpy()[rows])
-    assert np.array_equal(codes, ref_q.codes)
-    assert np.array_equal(buf.scales.cpu().numpy()[rows], ref_q.scales)
-    T = buf.T.cpu().numpy().astype(np.float64)
-    assert np.all(np.abs(T[rows] - ref_q.T) <= 2.0 ** -23 * np.abs(ref_q.T) + 1e-30)
+    # RTN: every row
+    ref_q = orc.quantize_rtn(W, sm.idx, sm.mdiag, spec.bits)
+    assert np.array_equal(unpack_int4(buf.codes.cpu().numpy()), ref_q.codes)
+    assert np.array_equal(buf.scales.cpu().numpy(), ref_q.scales)
+    assert np.all(np.abs(buf.T.cpu().numpy() - ref_q.T) <= 2.0 ** -23 * np.abs(ref_q.T) + 1e-30)
+    T = ref_q.T                                                   # the oracle's target, fp64
+    say("%s: RTN compared on every row" % cfg)
 
-    # whitening: lower triangular and S S^T = M^-1 G M^-1 on the sampled entries
+    # whitening factor: lower triangular everywhere, and S S^T V = G' V with G' = M^-1 X^T X M^-1 from the host pass
+    assert int(torch.count_nonzero(torch.triu(buf.S, 1)).item()) == 0
     S = buf.S.cpu().numpy().astype(np.float64)
-    assert not np.triu(S[:512, :512], 1).any() and not np.triu(S[-512:, -512:], 1).any() and not S[:256, -256:].any()
-    SS = S[cols] @ S[cols].T
-    Gp = G_ref / np.outer(sm.mdiag[cols].astype(np.float64), sm.mdiag[cols].astype(np.float64))
-    dp = np.sqrt(np.diag(Gp))
-    assert np.all(np.abs(SS - Gp) <= 3e-5 * np.outer(dp, dp))
+    assert np.all(np.diag(S) > 0)
+    GpV = minv[:, None] * XtXV[:, nv:]
+    SSV = S @ (S.T @ V)
+    gp = gdiag * minv * minv
+    tol = 6e-6 * np.sqrt(gp)[:, None] * np.sqrt((gp[:, None] * V * V).sum(axis=0))[None, :]
+    worst = float((np.abs(SSV - GpV) / tol).max())
+    say("%s: S S^T V against G' V: worst entry at %.2f of its tolerance" % (cfg, worst))
+    assert worst <= 1.0
 
-    # Eq. 8: the reported error is the whitened error of the returned factors, which stay below the
-    # error of doing nothing, and sigma / the residual split the energy of T S
+    # Eq. 8: the whitened error of the returned factors (oracle T, S as checked above), against the
+    # reported scalar and against the optimum; sigma and the residual split the energy of T S
     L_A = buf.L_A.cpu().numpy()
     L_B = buf.L_B.cpu().numpy()
     sigma = buf.sigma.cpu().numpy().astype(np.float64)
@@ -458,8 +594,7 @@ def test_large_layers_full_size_sampled(cfg):
     A = T @ S
     e0 = float(np.linalg.norm(A))
     assert e < e0
-    # the optimum itself, from the spectrum of the smaller Gram matrix: sigma_i^2 = eig_i(A A^T)
-    lam = np.maximum(np.linalg.eigvalsh(A @ A.T if spec.m <= spec.n else A.T @ A)[::-1], 0.0)
+    lam = np.maximum(np.linalg.eigvalsh(A @ A.T if m <= n else A.T @ A)[::-1], 0.0)
     e_opt = float(np.sqrt(np.sum(lam[spec.r:])))
     say("%s: optimal whitened error %.6g, device %.6g, rel %.2e; sigma_r/sigma_r+1 = %.4f" %
         (cfg, e_opt, e, (e - e_opt) / e_opt, np.sqrt(lam[spec.r - 1] / lam[spec.r])))
@@ -512,8 +647,8 @@ def test_ill_conditioned_block_is_reported():
     """W8 with smoothed outlier columns: the unquantized outlier part of T is thousands of times larger
     than the int8 rounding error (sigma_1 / sigma_b = 4400 here).  With a purely random start block every
     column mixes both, which is more than the fp32-class products and the Cholesky-QR orthogonalisation
-    resolve: without the lead_cols hint the call must say so (ASER_ERR_NO_CONVERGE) instead of returning
-    numbers; all kernels run to completion.  With the hint the same layer passes the parity bars
+    resolve: without the outlier set (f = 0) the call must say so (ASER_ERR_NO_CONVERGE) instead of returning
+    numbers; all kernels run to completion.  With the outlier set the same layer passes the parity bars
     (test_end_to_end_layer[w8_few_outliers])."""
     spec = synth.mini("fz21", 145, 410, 1105, x_dtype="bf16", x_dist="gauss", n_outliers=3, r=31, f=3, bits=8, seed_id=721)
     W = torch.from_numpy(synth.make_weight(spec)).to(DEV)
@@ -528,9 +663,7 @@ def test_ill_conditioned_block_is_reported():
     assert st == aser.ASER_OK and info == 0
     st, _, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma)
     assert st == aser.ASER_ERR_NO_CONVERGE
-    hint = aser.aser_svd_opts()
-    hint.n_lead, hint.lead_cols = spec.f, buf.idx.data_ptr()
-    st, err, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, hint)
+    st, err, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, idx=buf.idx, f=spec.f)
     assert st == aser.ASER_OK and np.isfinite(err)
 
 

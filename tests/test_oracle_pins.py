@@ -133,6 +133,23 @@ def test_act_rtn_hand_example():
     assert scales.tolist() == [1.0, 1.0]
 
 
+def test_act_rtn_ties_round_half_to_even():
+    """Quotients exactly half way between two codes go to the even one: 0.5 -> 0, 2.5 -> 2, -3.5 -> -4,
+    -0.5 -> 0, 6.5 -> 6 (half away from zero would give 1, 3, -4, -1, 7; truncation 0, 2, -3, 0, 6).
+    Token 1 has a scale that is not 1 (absmax 63.5 at 6 bits: scale 63.5 / 31 is inexact, so its ties
+    are made with scale 2: absmax 62), token 2 reaches its ties through the division by M."""
+    X = np.array([[127.0, 0.5, 2.5, -3.5, -0.5, 6.5],
+                  [62.0, 1.0, 5.0, -7.0, -1.0, 13.0],
+                  [254.0, 1.0, 5.0, -7.0, 3.0, 39.0]], dtype=np.float32)
+    codes, scales = orc.quantize_act_rtn(X[:1], np.ones(6, np.float32), 8)
+    assert scales.tolist() == [1.0] and codes.tolist() == [[127, 0, 2, -4, 0, 6]]
+    codes, scales = orc.quantize_act_rtn(X[1:2], np.ones(6, np.float32), 6)       # qmax 31, scale 2
+    assert scales.tolist() == [2.0] and codes.tolist() == [[31, 0, 2, -4, 0, 6]]
+    mdiag = np.array([2, 2, 2, 2, 2, 6], dtype=np.float32)                        # X' = [127, .5, 2.5, -3.5, 1.5, 6.5]
+    codes, scales = orc.quantize_act_rtn(X[2:], mdiag, 8)
+    assert scales.tolist() == [1.0] and codes.tolist() == [[127, 0, 2, -4, 2, 6]]
+
+
 # ---------------------------------------------------------------- whitening (Eq. 5)
 def test_whitening_identity_and_uniqueness():
     W, X, bits, f, r = _small_layer(7)
