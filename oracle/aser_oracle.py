@@ -27,10 +27,18 @@ Readings of points the paper leaves open (each is also listed in the design note
   * S is the lower Cholesky factor of (M^-1 X)(M^-1 X)^T = M^-1 G M^-1 (Algorithm 1).
   * No damping unless asked for; damp adds damp * mean(diag G') to the diagonal of G'.
 
+  * Eq. 9 is read with a strict "<" and r >= 1; eps of Eq. 4 is 1e-12 (not given in the paper).
+  * The compensated layer reads the same per-token quantized activations in both branches
+    (W_q X_q + L_A L_B X_q), which is what the error ||W X - W~ X_q||_F of Sec. 5.3 measures.
+
 Pins (tests/test_oracle_pins.py): Eckart-Young brute force on tiny matrices, the Eq. 8
 identity with an explicit X, monotone error in r, zero error at full rank, invariance to the
 square root of G, the S-free closed form U_r U_r^T T, the G = I reduction to a plain SVD,
-exactness of W X = (W M)(M^-1 X), RTN invariants, and hand-computed RTN / smoothing examples.
+exactness of W X = (W M)(M^-1 X), RTN invariants, and hand-computed RTN / smoothing examples;
+effective rank in closed form (equal values, rank one, a two-value entropy), the full spectrum
+against the eigenvalues of the Gram matrix, the overhead ratios of the paper's rank table, the
+compensated output by element-wise loops, and the output error without activation quantization
+against the whitened error of Eq. 8 on the calibration set itself.
 Parity unpinned (the paper prints no worked example): which rounding/clipping convention
 Q(.) uses and the tie-break of the outlier selection follow the readings above.
 """
@@ -205,6 +213,78 @@ def quantize_act_rtn(X: np.ndarray, mdiag: np.ndarray, bits: int = 8):
     scales[amax == 0] = np.float32(1.0)
     q = np.clip(np.rint(Xp / scales[:, None]), -qmax, qmax)
     return q.astype(np.int8), scales
+
+
+# ------------------------------------------------------------------ full spectrum, rank threshold, effective rank
+def singular_values(T: np.ndarray, S: Optional[np.ndarray] = None) -> np.ndarray:
+    """All min(m, n) singular values of T S (of T itself when S is None), descending (Eq. 6).
+
+    With S the whitening factor this is the spectrum that Eq. 9 sums and that Sec. 3.2 plots for
+    E_q X (E_q S and E_q X share their singular values because S S^T = X X^T); with S = None it is
+    the spectrum of the weight error E_q alone.
+    """
+    A = np.asarray(T, dtype=np.float64)
+    if S is not None:
+        A = A @ np.asarray(S, dtype=np.float64)
+    return np.linalg.svd(A, compute_uv=False)
+
+
+def effective_rank(sigma: np.ndarray, eps: float = 1e-12) -> float:
+    """exp(-sum_k p_k ln p_k) with p_k = sigma_k / sum_i sigma_i + eps (Eq. 3, Eq. 4).
+
+    The paper does not give eps; 1e-12 only keeps ln p_k finite for zero singular values.
+    """
+    sg = np.asarray(sigma, dtype=np.float64)
+    p = sg / sg.sum() + eps
+    return float(np.exp(-(p * np.log(p)).sum()))
+
+
+def normalized_profile(sigma: np.ndarray, k: int = 128) -> np.ndarray:
+    """The k largest singular values divided by the largest one (the curves of Sec. 3.2's first figure;
+    the paper says "normalized for comparison" without naming the divisor)."""
+    sg = np.sort(np.asarray(sigma, dtype=np.float64))[::-1][:k]
+    return sg / sg[0]
+
+
+def overhead_flops_ratio(r: float, d: int) -> float:
+    """Extra inference FLOPs of the L_A, L_B branch relative to the layer itself: (s d^2 + 2 s r d) / (s d^2) - 1
+    = 2 r / d (overhead analysis of Sec. 5.3; s cancels)."""
+    return 2.0 * float(r) / float(d)
+
+
+# ------------------------------------------------------------------ compensated layer and its output error
+def compensated_weight(codes: np.ndarray, scales: np.ndarray, L_A: Optional[np.ndarray],
+                       L_B: Optional[np.ndarray]) -> np.ndarray:
+    """W~ = deq(Q(W_s)) + L_A L_B, the weight the compensated layer applies to the smoothed input
+    M^-1 X (end of Sec. 4.2: inference is W_q X + L_A L_B X).  L_A = None: the RTN baseline W_q."""
+    Wt = dequantize(codes, scales)
+    if L_A is not None:
+        Wt = Wt + np.asarray(L_A, dtype=np.float64) @ np.asarray(L_B, dtype=np.float64)
+    return Wt
+
+
+def compensated_forward(X: np.ndarray, mdiag: np.ndarray, codes: np.ndarray, scales: np.ndarray,
+                        L_A: Optional[np.ndarray], L_B: Optional[np.ndarray], act_bits: Optional[int]):
+    """Output of the quantized, compensated layer for the tokens in X (tokens x n), as tokens x m:
+    Y~ = X'_q W~^T with X' = X M^-1 and X'_q its per-token RTN image dequantized (Sec. 5.1; the remaining
+    error that Sec. 5.3's figure plots is ||W X - W~ X_q||_F).  act_bits = None: X'_q = X' (weights only).
+    Both branches read the same quantized activations."""
+    md = np.asarray(mdiag, dtype=np.float32)
+    if act_bits is None:
+        Xq = np.asarray(X, dtype=np.float64) / md.astype(np.float64)[None, :]
+    else:
+        q, s = quantize_act_rtn(X, md, act_bits)
+        Xq = q.astype(np.float64) * s.astype(np.float64)[:, None]
+    return Xq @ compensated_weight(codes, scales, L_A, L_B).T
+
+
+def layer_output_error(W: np.ndarray, X: np.ndarray, mdiag: np.ndarray, codes: np.ndarray, scales: np.ndarray,
+                       L_A: Optional[np.ndarray], L_B: Optional[np.ndarray], act_bits: Optional[int]):
+    """||X W^T - X'_q W~^T||_F over the tokens in X and the norm of the exact output ||X W^T||_F
+    (the paper's ||W X - W~ X_q||_F in tokens x channels orientation; caption of Sec. 5.3's error figure)."""
+    Y = np.asarray(X, dtype=np.float64) @ np.asarray(W, dtype=np.float64).T
+    Yq = compensated_forward(X, mdiag, codes, scales, L_A, L_B, act_bits)
+    return float(np.linalg.norm(Y - Yq)), float(np.linalg.norm(Y))
 
 
 # ------------------------------------------------------------------ the whole layer (Algorithm 1, loop body)

@@ -308,6 +308,108 @@ def test_rank_from_alpha_hand_example():
     assert orc.rank_from_alpha(sig, 0.95) == 3
 
 
+def test_rank_from_alpha_follows_the_cumulative_ratio_by_brute_force():
+    rng = np.random.default_rng(11)
+    for _ in range(20):
+        sig = np.sort(rng.gamma(0.7, size=rng.integers(3, 40)))[::-1]
+        alpha = float(rng.uniform(0.05, 0.999))
+        want = 0
+        for r in range(1, len(sig) + 1):                 # Eq. 9 read literally: the largest r whose ratio stays below alpha
+            if sum(sig[:r]) / sum(sig) < alpha:
+                want = r
+        assert orc.rank_from_alpha(sig, alpha) == max(1, want)
+
+
+# ---------------------------------------------------------------- spectrum and effective rank (Eq. 3, Eq. 4)
+def test_singular_values_against_the_gram_eigenvalues_and_eq6():
+    W, X, bits, f, r = _small_layer(21, m=18, n=12, N=60)
+    res = orc.calibrate_layer(W, X, bits, f, r)
+    sig = orc.singular_values(res.quant.T, res.S)
+    assert sig.shape == (12,) and np.all(np.diff(sig) <= 0)
+    # sigma_i^2 are the eigenvalues of (T S)(T S)^T = T G' T^T: no S, no SVD on this side
+    minv = 1.0 / res.smooth.mdiag.astype(np.float64)
+    Gp = res.G * minv[:, None] * minv[None, :]
+    lam = np.sort(np.linalg.eigvalsh(res.quant.T @ Gp @ res.quant.T.T))[::-1][:12]
+    assert np.allclose(sig ** 2, lam, rtol=1e-9, atol=1e-12 * lam[0])
+    assert np.allclose(sig, res.rec.sigma, rtol=1e-12)
+    # without S: the spectrum of the weight error alone; a diagonal matrix returns its entries
+    assert np.allclose(orc.singular_values(np.diag([3.0, -5.0, 1.0])), [5.0, 3.0, 1.0])
+    assert np.isclose(np.linalg.norm(res.quant.T), np.sqrt((orc.singular_values(res.quant.T) ** 2).sum()))
+
+
+def test_effective_rank_closed_forms():
+    # k equal singular values: entropy ln k, effective rank k; rank one: 1
+    assert orc.effective_rank(np.full(7, 2.5), eps=0.0) == pytest.approx(7.0, rel=1e-12)
+    assert orc.effective_rank(np.array([4.0]), eps=0.0) == pytest.approx(1.0, rel=1e-12)
+    assert orc.effective_rank(np.array([4.0, 0.0, 0.0])) == pytest.approx(1.0, abs=1e-9)     # eps keeps ln finite
+    # two values 3 : 1 -> p = (3/4, 1/4), entropy 2 ln 2 - (3/4) ln 3, exp of it = 4 / 3^(3/4)
+    assert orc.effective_rank(np.array([3.0, 1.0]), eps=0.0) == pytest.approx(4.0 / 3.0 ** 0.75, rel=1e-12)
+    sig = np.array([9.0, 4.0, 2.0, 1.0, 0.5])
+    assert orc.effective_rank(sig) == pytest.approx(orc.effective_rank(17.0 * sig[::-1]), rel=1e-10)   # scale, order
+    assert 1.0 < orc.effective_rank(sig) < 5.0
+    # the printed definition adds eps to every p_k (no renormalisation): with a large eps it shows
+    p = sig / sig.sum() + 0.01
+    assert orc.effective_rank(sig, eps=0.01) == pytest.approx(float(np.exp(-(p * np.log(p)).sum())), rel=1e-12)
+    # whitening concentrates the spectrum of a layer with outlier channels (Sec. 3.2: E_q X is more low-rank than E_q)
+    W, X, bits, f, r = _small_layer(22, m=40, n=32, N=200, f=0)
+    res = orc.calibrate_layer(W, X, bits, 0, 4)
+    assert orc.effective_rank(orc.singular_values(res.quant.T, res.S)) < orc.effective_rank(orc.singular_values(res.quant.T))
+    prof = orc.normalized_profile(orc.singular_values(res.quant.T, res.S), 8)
+    assert prof[0] == 1.0 and prof.shape == (8,) and np.all(np.diff(prof) <= 0)
+
+
+def test_overhead_ratio_reproduces_the_papers_rank_table():
+    """tests/golden/paper_rank_overhead.txt holds the rows the paper prints (Sec. 5.3, rank selection
+    table: alpha, mean rank, extra FLOPs for d = 4096); the extra FLOPs are 2 r / d."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_rank_overhead.txt")
+    rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 5
+    for alpha, rbar, pct in rows:
+        assert round(100.0 * orc.overhead_flops_ratio(float(rbar), 4096), 2) == float(pct), (alpha, rbar, pct)
+    s, d, r = 2048, 4096, 64
+    assert orc.overhead_flops_ratio(r, d) == pytest.approx((s * d * d + 2 * s * r * d) / (s * d * d) - 1.0)
+
+
+# ---------------------------------------------------------------- compensated layer (end of Sec. 4.2, Sec. 5.3)
+def test_compensated_forward_by_loops_and_error_identities():
+    W, X, bits, f, r = _small_layer(23, m=10, n=8, N=30, f=2, r=3)
+    res = orc.calibrate_layer(W, X, bits, f, r)
+    md = res.smooth.mdiag
+    q, s = orc.quantize_act_rtn(X[:5], md, 8)
+    Y = orc.compensated_forward(X[:5], md, res.quant.codes, res.quant.scales, res.rec.L_A, res.rec.L_B, 8)
+    ref = np.zeros((5, 10))
+    for t in range(5):
+        for o in range(10):
+            acc = 0.0
+            for i in range(8):
+                w = float(res.quant.codes[o, i]) * float(res.quant.scales[o])
+                for k in range(3):
+                    w += res.rec.L_A[o, k] * res.rec.L_B[k, i]
+                acc += float(q[t, i]) * float(s[t]) * w
+            ref[t, o] = acc
+    assert np.allclose(Y, ref, rtol=1e-12, atol=1e-14)
+    # without activation quantization, over the calibration set itself, the output error is the whitened
+    # error of Eq. 8 (X'^T X' = S S^T), and without compensation it is ||T S||_F
+    e, ynorm = orc.layer_output_error(W, X, md, res.quant.codes, res.quant.scales, res.rec.L_A, res.rec.L_B, None)
+    assert e == pytest.approx(res.rec.err, rel=1e-9)
+    assert ynorm == pytest.approx(np.linalg.norm(X.astype(np.float64) @ W.astype(np.float64).T), rel=1e-12)
+    e0, _ = orc.layer_output_error(W, X, md, res.quant.codes, res.quant.scales, None, None, None)
+    assert e0 == pytest.approx(res.rec.err0, rel=1e-9) and e < e0
+    # with activation quantization the error moves by at most ||dX W~^T||_F, dX the rounding of X' (|dX| <= s_t / 2)
+    e8, _ = orc.layer_output_error(W, X, md, res.quant.codes, res.quant.scales, res.rec.L_A, res.rec.L_B, 8)
+    q, s = orc.quantize_act_rtn(X, md, 8)
+    Wt = orc.compensated_weight(res.quant.codes, res.quant.scales, res.rec.L_A, res.rec.L_B)
+    bound = np.sqrt((X.shape[1] * (s.astype(np.float64) / 2) ** 2).sum()) * np.linalg.norm(Wt, 2)
+    assert abs(e8 - e) <= bound and e8 != e
+    e4, _ = orc.layer_output_error(W, X, md, res.quant.codes, res.quant.scales, res.rec.L_A, res.rec.L_B, 4)
+    assert e4 > e8                                             # coarser activations, larger error
+    # the smoothing diagonal belongs to the forward pass: dropping it changes the output
+    Yw = orc.compensated_forward(X[:5], np.ones_like(md), res.quant.codes, res.quant.scales, res.rec.L_A, res.rec.L_B, None)
+    Yr = orc.compensated_forward(X[:5], md, res.quant.codes, res.quant.scales, res.rec.L_A, res.rec.L_B, None)
+    assert np.linalg.norm(Yw - Yr) > 1e-3 * np.linalg.norm(Yr)
+
+
 # ---------------------------------------------------------------- generators
 def test_synth_is_chunk_addressable_and_bf16_exact():
     spec = synth.mini("t", 8, 32, 3 * synth.CHUNK + 100)
