@@ -119,6 +119,18 @@ int aser_smooth_outliers(aser_ctx* ctx, const float* W, int64_t m, int64_t n, in
                          const double* abs_sum, const int64_t* count, int32_t f,
                          int32_t* idx, float* mdiag, float* W_o, double* score);
 
+/* aser_smooth_outliers for callers that cannot allocate device memory and so have no workspace to bind:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same results, same deferred report; the scratch (two fp64 arrays of n entries and a status word) lives
+ * in a static device array of 512.25 KiB that each GPU the library runs on holds until the process ends.
+ * n <= 32768, else ASER_ERR_SHAPE; the context's device index must be below 16.  Makes no hipMalloc,
+ * hipFree or other allocating call; memory is cleared by kernels, not by memset nodes.  All calls on one
+ * GPU share that GPU's array: calls that overlap on one GPU (two streams, two contexts) race; calls in
+ * stream order on one stream do not. */
+int aser_smooth_outliers_noalloc(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                                 const double* abs_sum, const int64_t* count, int32_t f,
+                                 int32_t* idx, float* mdiag, float* W_o, double* score);
+
 /* Stage 3 (Sec. 3.1 E_q = W - W_q; Eq. 12; per-channel RTN, Sec. 5.1).
  * W_s = W with the idx columns set to zero.  Per output row o, in IEEE fp32:
  *     scale_o = max_j |W_s[o][j]| / qmax,  qmax = 2^(bits-1) - 1   (1 if the row is zero)

@@ -30,7 +30,8 @@ ASER_CODES_INT4_PACKED = 1
 
 EXPORTS = (
     "aser_status_string", "aser_create", "aser_destroy", "aser_last_error", "aser_set_workspace",
-    "aser_workspace_bytes", "aser_gram_accumulate", "aser_smooth_outliers", "aser_quantize_rtn",
+    "aser_workspace_bytes", "aser_gram_accumulate", "aser_smooth_outliers", "aser_smooth_outliers_noalloc",
+    "aser_quantize_rtn",
     "aser_whiten", "aser_error_reconstruct", "aser_svd_plan", "aser_quantize_act_rtn",
 )
 
@@ -74,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.aser_gram_accumulate.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, vp, i64, vp, vp]
     lib.aser_smooth_outliers.restype = ctypes.c_int
     lib.aser_smooth_outliers.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, vp, vp, vp, vp]
+    lib.aser_smooth_outliers_noalloc.restype = ctypes.c_int
+    lib.aser_smooth_outliers_noalloc.argtypes = lib.aser_smooth_outliers.argtypes
     lib.aser_quantize_rtn.restype = ctypes.c_int
     lib.aser_quantize_rtn.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, i32, i32, vp, vp, vp, i64]
     lib.aser_whiten.restype = ctypes.c_int
@@ -196,6 +199,15 @@ def aser_smooth_outliers(ctx: Context, W, abs_sum, count, f: int, idx, mdiag, W_
     n = W.shape[1] if n is None else n
     return ctx._lib.aser_smooth_outliers(ctx.handle, _ptr(W), m, n, _ld(W, n) if ldw is None else ldw, _ptr(abs_sum),
                                          _ptr(count), f, _ptr(idx), _ptr(mdiag), _ptr(W_o), _ptr(score))
+
+
+def aser_smooth_outliers_noalloc(ctx: Context, W, abs_sum, count, f: int, idx, mdiag, W_o=None, score=None, *, m=None,
+                                 n=None, ldw=None) -> int:
+    m = W.shape[0] if m is None else m
+    n = W.shape[1] if n is None else n
+    return ctx._lib.aser_smooth_outliers_noalloc(ctx.handle, _ptr(W), m, n, _ld(W, n) if ldw is None else ldw,
+                                                 _ptr(abs_sum), _ptr(count), f, _ptr(idx), _ptr(mdiag), _ptr(W_o),
+                                                 _ptr(score))
 
 
 def aser_quantize_rtn(ctx: Context, W, idx, mdiag, f: int, bits: int, layout: int, codes, scales, T=None, *, m=None,

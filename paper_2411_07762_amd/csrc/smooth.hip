@@ -224,3 +224,41 @@ extern "C" int aser_smooth_outliers(aser_ctx* ctx, const float* W, int64_t m, in
     return smooth_run(ctx, W, m, n, ldw, abs_sum, count, f, idx, mdiag, W_o, score, (double*)ctx->ws,
                       (double*)((char*)ctx->ws + align_up((size_t)n * 8, 256)), sel_flag);
 }
+
+// ---------------------------------------------------------------------------------------------
+// The same stage for callers that cannot allocate and therefore have no workspace to bind (code under
+// HIP graph capture, serving loops, harnesses that forbid hipMalloc): the two fp64 arrays and the status
+// word live in a static device array of fixed size instead.  Every device holds its own copy of the
+// array at its own address, looked up once per device.
+constexpr size_t kScratchColBytes = (size_t)kSelMaxN * 8;             // one fp64 per channel, n <= 32768
+constexpr size_t kScratchBytes = 2 * kScratchColBytes + 256;          // |W| column sums, scores, status word
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+static void* g_scratch_ptr[16] = {nullptr};
+
+extern "C" int aser_smooth_outliers_noalloc(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                                            const double* abs_sum, const int64_t* count, int32_t f,
+                                            int32_t* idx, float* mdiag, float* W_o, double* score) {
+    if (!ctx) return ASER_ERR_INVALID_ARG;
+    ASER_TRY(smooth_validate(ctx, W, m, n, ldw, abs_sum, count, f, idx, mdiag, score));
+    if ((size_t)n * 8 > kScratchColBytes)
+        ASER_FAIL(ctx, ASER_ERR_SHAPE, "smooth_outliers_noalloc: n = %lld exceeds the static scratch (%d channels)",
+                  (long long)n, kSelMaxN);
+    if (ctx->device < 0 || ctx->device >= 16)
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smooth_outliers_noalloc: device index %d is outside [0, 16)", ctx->device);
+    ASER_TRY(aser_prepare_device(ctx));
+    if (!g_scratch_ptr[ctx->device]) {
+        // the array's name is only a host-side handle: its device address comes from the runtime, with
+        // the context's device current (aser_prepare_device has just made it so)
+        void* p = nullptr;
+        ASER_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) ASER_FAIL(ctx, ASER_ERR_HIP, "smooth_outliers_noalloc: no device address for the static scratch");
+        g_scratch_ptr[ctx->device] = p;
+    }
+    char* base = (char*)g_scratch_ptr[ctx->device];
+    // every call on this device shares the array and finds the last call's contents in it: the column
+    // sums are cleared by smooth_run, the scores are overwritten, the status word is reset unless it is
+    // still pending on this context
+    return smooth_run(ctx, W, m, n, ldw, abs_sum, count, f, idx, mdiag, W_o, score, (double*)base,
+                      (double*)(base + kScratchColBytes), (int32_t*)(base + 2 * kScratchColBytes));
+}
