@@ -191,6 +191,32 @@ int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, 
  * options (either pointer may be NULL).  ASER_ERR_SHAPE where aser_error_reconstruct would refuse. */
 int aser_svd_plan(int64_t m, int64_t n, int32_t r, const aser_svd_opts* opts, int32_t* block, int32_t* iters);
 
+/* All min(m, n) singular values of T S, descending, as fp64 (S == NULL: of T itself): the spectrum that
+ * Eq. 9 sums over, that Eq. 3-4 take the entropy of and whose largest values Sec. 3.2 plots for the
+ * weight error (S == NULL) and for the activation-weight error (S the whitening factor; E_q S and E_q X
+ * have the same singular values because S S^T = X X^T).
+ * T: m x n fp32 (ldt); S: n x n fp32 lower triangular (lds) or NULL; sigma: DEVICE, min(m, n) doubles.
+ * The product T S carries about 2^-16 relative error per term; behind it everything is fp64 (Gram matrix
+ * of the shorter side, Householder tridiagonalisation, bisection), so a singular value is off by at most
+ * about 1e-5 of the mean singular value plus 1e-7 of the largest.  min(m, n) <= 16384.
+ * Asynchronous.  Needs aser_spectrum_workspace_bytes(m, n, S != NULL) bytes of workspace. */
+size_t aser_spectrum_workspace_bytes(int64_t m, int64_t n, int32_t with_s);
+int aser_singular_values(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt,
+                         const float* S, int64_t lds, double* sigma);
+
+/* Rank from the threshold alpha (Eq. 9; Algorithm 1 "r <- ..." line): the largest r with
+ * (sigma_1 + ... + sigma_r) / (sigma_1 + ... + sigma_k) < alpha, strictly, and at least 1.
+ * sigma: DEVICE, k doubles, descending (aser_singular_values).  0 < alpha < 1.
+ * *r (host) receives the rank; stats (host, 3 doubles, may be NULL) receives the sum of all singular
+ * values and the cumulative shares at r and at r + 1, between which alpha lies (how far the decision is
+ * from flipping).  Synchronises the stream.  Needs a bound workspace (any size). */
+int aser_select_rank(aser_ctx* ctx, const double* sigma, int64_t k, double alpha, int32_t* r, double* stats);
+
+/* Effective rank (Eq. 3, Eq. 4): exp(-sum_k p_k ln p_k) with p_k = sigma_k / sum_i sigma_i + eps.
+ * sigma: DEVICE, k doubles; eps >= 0 (the paper does not give its value; 1e-12 keeps ln finite for
+ * zero singular values); *erank: host.  Synchronises the stream.  Needs a bound workspace (any size). */
+int aser_effective_rank(aser_ctx* ctx, const double* sigma, int64_t k, double eps, double* erank);
+
 /* Per-token activation quantizer of the W4A8 setting (Sec. 5.1 "per-token for activations").
  * It does not feed L_A / L_B; it serves the layer-output error under activation quantization.
  *     X'[t][i] = X[t][i] / mdiag[i]  (IEEE fp32),  s_t = max_i |X'[t][i]| / qmax  (1 if zero)

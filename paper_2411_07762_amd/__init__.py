@@ -33,6 +33,7 @@ EXPORTS = (
     "aser_workspace_bytes", "aser_gram_accumulate", "aser_smooth_outliers", "aser_smooth_outliers_noalloc",
     "aser_quantize_rtn",
     "aser_whiten", "aser_error_reconstruct", "aser_svd_plan", "aser_quantize_act_rtn",
+    "aser_spectrum_workspace_bytes", "aser_singular_values", "aser_select_rank", "aser_effective_rank",
 )
 
 
@@ -88,6 +89,15 @@ def load_library() -> ctypes.CDLL:
     lib.aser_svd_plan.restype = ctypes.c_int
     lib.aser_svd_plan.argtypes = [i64, i64, i32, ctypes.POINTER(aser_svd_opts), ctypes.POINTER(ctypes.c_int32),
                                   ctypes.POINTER(ctypes.c_int32)]
+    lib.aser_spectrum_workspace_bytes.restype = ctypes.c_size_t
+    lib.aser_spectrum_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.aser_singular_values.restype = ctypes.c_int
+    lib.aser_singular_values.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
+    lib.aser_select_rank.restype = ctypes.c_int
+    lib.aser_select_rank.argtypes = [vp, vp, i64, ctypes.c_double, ctypes.POINTER(ctypes.c_int32),
+                                     ctypes.POINTER(ctypes.c_double)]
+    lib.aser_effective_rank.restype = ctypes.c_int
+    lib.aser_effective_rank.argtypes = [vp, vp, i64, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
     lib.aser_quantize_act_rtn.restype = ctypes.c_int
     lib.aser_quantize_act_rtn.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, vp, i32, vp, vp]
     _lib = lib
@@ -258,6 +268,34 @@ def aser_quantize_act_rtn(ctx: Context, X, mdiag, bits: int, codes, scales, *, r
     return ctx._lib.aser_quantize_act_rtn(ctx.handle, _ptr(X), _dtype_code(X) if x_dtype is None else x_dtype, rows, n,
                                           _ld(X, n) if ldx is None else ldx, _ptr(mdiag), bits, _ptr(codes),
                                           _ptr(scales))
+
+
+def aser_spectrum_workspace_bytes(m: int, n: int, with_s: bool) -> int:
+    return int(load_library().aser_spectrum_workspace_bytes(m, n, 1 if with_s else 0))
+
+
+def aser_singular_values(ctx: Context, T, S, sigma, *, m=None, n=None, ldt=None, lds=None) -> int:
+    m = T.shape[0] if m is None else m
+    n = T.shape[1] if n is None else n
+    return ctx._lib.aser_singular_values(ctx.handle, _ptr(T), m, n, _ld(T, n) if ldt is None else ldt, _ptr(S),
+                                         (_ld(S, n) if S is not None else n) if lds is None else lds, _ptr(sigma))
+
+
+def aser_select_rank(ctx: Context, sigma, alpha: float, *, k=None):
+    """Returns (status, r, (sum, share_at_r, share_at_r_plus_1))."""
+    k = sigma.shape[0] if k is None else k
+    r = ctypes.c_int32(0)
+    st3 = (ctypes.c_double * 3)()
+    st = ctx._lib.aser_select_rank(ctx.handle, _ptr(sigma), k, float(alpha), ctypes.byref(r), st3)
+    return st, r.value, (st3[0], st3[1], st3[2])
+
+
+def aser_effective_rank(ctx: Context, sigma, eps: float = 1e-12, *, k=None):
+    """Returns (status, effective_rank)."""
+    k = sigma.shape[0] if k is None else k
+    out = ctypes.c_double(0.0)
+    st = ctx._lib.aser_effective_rank(ctx.handle, _ptr(sigma), k, float(eps), ctypes.byref(out))
+    return st, out.value
 
 
 # ----------------------------------------------------------------------------------- one layer, end to end

@@ -24,7 +24,8 @@ struct aser_ctx {
 };
 
 // Bytes at the end of the bound workspace that hold the deferred status words: the whitening's pivot
-// flag (word 0) and the outlier selection's "no usable candidate" flag (word 1).
+// flag (word 0) and the outlier selection's "no usable candidate" flag (word 1); bytes 64 .. 135 carry
+// the scalar results of aser_select_rank and aser_effective_rank to the host.
 static const size_t kAserWsTail = 256;
 
 // Host copies of the deferred status words; INT_MAX / 0 mean "nothing pending or nothing wrong".

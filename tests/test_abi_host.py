@@ -138,6 +138,22 @@ def test_act_rtn_validation(ctx):
     assert a(ctx, P, None, 8, P, P, rows=0, n=8, ldx=8, x_dtype=0) == aser.ASER_OK
 
 
+def test_spectrum_validation(ctx):
+    sv = aser.aser_singular_values
+    assert sv(ctx, P, None, None, m=8, n=8) == aser.ASER_ERR_INVALID_ARG                 # sigma missing
+    assert sv(ctx, P, None, P, m=8, n=8, ldt=4) == aser.ASER_ERR_SHAPE
+    assert sv(ctx, P, None, P, m=20000, n=20000) == aser.ASER_ERR_SHAPE                  # min(m, n) > 16384
+    assert sv(ctx, P, P, P, m=64, n=64) == aser.ASER_ERR_WORKSPACE
+    assert aser.aser_spectrum_workspace_bytes(4096, 4096, True) >= 3 * 4096 * 4096 * 4 + 4096 * 4096 * 8
+    assert aser.aser_spectrum_workspace_bytes(4096, 1024, False) < aser.aser_spectrum_workspace_bytes(4096, 1024, True)
+    assert aser.aser_select_rank(ctx, P, 0.0, k=8)[0] == aser.ASER_ERR_INVALID_ARG       # alpha outside (0, 1)
+    assert aser.aser_select_rank(ctx, P, 1.0, k=8)[0] == aser.ASER_ERR_INVALID_ARG
+    assert aser.aser_select_rank(ctx, P, 0.5, k=0)[0] == aser.ASER_ERR_SHAPE
+    assert aser.aser_select_rank(ctx, P, 0.5, k=8)[0] == aser.ASER_ERR_WORKSPACE
+    assert aser.aser_effective_rank(ctx, P, -1.0, k=8)[0] == aser.ASER_ERR_INVALID_ARG
+    assert aser.aser_effective_rank(ctx, P + 4, 0.0, k=8)[0] == aser.ASER_ERR_INVALID_ARG
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2411_07762_amd")
     for dirpath, _, files in os.walk(pkg):
