@@ -225,6 +225,25 @@ int aser_effective_rank(aser_ctx* ctx, const double* sigma, int64_t k, double ep
 int aser_quantize_act_rtn(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int64_t n, int64_t ldx,
                           const float* mdiag, int32_t bits, int8_t* codes, float* scales);
 
+/* Remaining layer-output error of the quantized, compensated layer on a sample of tokens (the metric
+ * of the paper's per-layer error figure, Sec. 5.3: ||W X - W~ X_q||_F; Sec. 5.1 for the quantizers):
+ *     *err      = || X W^T - X'_q W~^T ||_F,   *ref_norm (may be NULL) = || X W^T ||_F
+ * with X' = X M^-1 (Eq. 10), X'_q the per-token RTN image of X' at act_bits bits, dequantized
+ * (act_bits == 0: X'_q = X', weights only), and W~ = deq(codes, scales) + L_A L_B (end of Sec. 4.2;
+ * r == 0: the RTN baseline without compensation, L_A and L_B may then be NULL).  Both branches of the
+ * compensated layer read the same quantized activations.
+ * W: m x n fp32 (ldw); X: rows x n, bf16 or fp32 (ldx); mdiag: n fp32 or NULL; codes / layout / scales as
+ * written by aser_quantize_rtn; L_A: m x r (ld r), L_B: r x n (ld n); act_bits: 0 or 2..8.  All DEVICE
+ * pointers; err, ref_norm: host.  fp32-class products (about 2^-16 relative per term, random signs):
+ * *err is resolved to about 1e-5 ||X W^T||_F.  Synchronises the stream.
+ * Needs aser_output_error_workspace_bytes(m, n, rows, r) bytes of workspace. */
+size_t aser_output_error_workspace_bytes(int64_t m, int64_t n, int64_t rows, int32_t r);
+int aser_layer_output_error(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                            const void* X, int x_dtype, int64_t rows, int64_t ldx, const float* mdiag,
+                            const void* codes, int32_t layout, const float* scales,
+                            const float* L_A, const float* L_B, int32_t r, int32_t act_bits,
+                            double* err, double* ref_norm);
+
 #ifdef __cplusplus
 }
 #endif

@@ -34,6 +34,7 @@ EXPORTS = (
     "aser_quantize_rtn",
     "aser_whiten", "aser_error_reconstruct", "aser_svd_plan", "aser_quantize_act_rtn",
     "aser_spectrum_workspace_bytes", "aser_singular_values", "aser_select_rank", "aser_effective_rank",
+    "aser_output_error_workspace_bytes", "aser_layer_output_error",
 )
 
 
@@ -98,6 +99,11 @@ def load_library() -> ctypes.CDLL:
                                      ctypes.POINTER(ctypes.c_double)]
     lib.aser_effective_rank.restype = ctypes.c_int
     lib.aser_effective_rank.argtypes = [vp, vp, i64, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
+    lib.aser_output_error_workspace_bytes.restype = ctypes.c_size_t
+    lib.aser_output_error_workspace_bytes.argtypes = [i64, i64, i64, i32]
+    lib.aser_layer_output_error.restype = ctypes.c_int
+    lib.aser_layer_output_error.argtypes = [vp, vp, i64, i64, i64, vp, ctypes.c_int, i64, i64, vp, vp, i32, vp, vp, vp, i32,
+                                            i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.aser_quantize_act_rtn.restype = ctypes.c_int
     lib.aser_quantize_act_rtn.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, vp, i32, vp, vp]
     _lib = lib
@@ -296,6 +302,25 @@ def aser_effective_rank(ctx: Context, sigma, eps: float = 1e-12, *, k=None):
     out = ctypes.c_double(0.0)
     st = ctx._lib.aser_effective_rank(ctx.handle, _ptr(sigma), k, float(eps), ctypes.byref(out))
     return st, out.value
+
+
+def aser_output_error_workspace_bytes(m: int, n: int, rows: int, r: int) -> int:
+    return int(load_library().aser_output_error_workspace_bytes(m, n, rows, r))
+
+
+def aser_layer_output_error(ctx: Context, W, X, mdiag, codes, layout: int, scales, L_A, L_B, r: int, act_bits: int, *,
+                            m=None, n=None, ldw=None, rows=None, ldx=None, x_dtype=None):
+    """Returns (status, err, ref_norm)."""
+    m = W.shape[0] if m is None else m
+    n = W.shape[1] if n is None else n
+    rows = X.shape[0] if rows is None else rows
+    err, ref = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    st = ctx._lib.aser_layer_output_error(ctx.handle, _ptr(W), m, n, _ld(W, n) if ldw is None else ldw, _ptr(X),
+                                          _dtype_code(X) if x_dtype is None else x_dtype, rows,
+                                          _ld(X, n) if ldx is None else ldx, _ptr(mdiag), _ptr(codes), layout,
+                                          _ptr(scales), _ptr(L_A), _ptr(L_B), r, act_bits, ctypes.byref(err),
+                                          ctypes.byref(ref))
+    return st, err.value, ref.value
 
 
 # ----------------------------------------------------------------------------------- one layer, end to end

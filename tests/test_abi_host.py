@@ -154,6 +154,20 @@ def test_spectrum_validation(ctx):
     assert aser.aser_effective_rank(ctx, P + 4, 0.0, k=8)[0] == aser.ASER_ERR_INVALID_ARG
 
 
+def test_output_error_validation(ctx):
+    e = aser.aser_layer_output_error
+    kw = dict(m=8, n=16, ldw=16, rows=4, ldx=16, x_dtype=0)
+    assert e(ctx, P, P, None, P, 0, P, None, None, 0, 8, **kw)[0] == aser.ASER_ERR_WORKSPACE
+    assert e(ctx, P, P, None, P, 0, P, None, None, 3, 8, **kw)[0] == aser.ASER_ERR_INVALID_ARG     # r > 0 without factors
+    assert e(ctx, P, P, None, P, 0, P, None, None, 0, 9, **kw)[0] == aser.ASER_ERR_DTYPE
+    assert e(ctx, P, P, None, P, 0, P, None, None, 0, 1, **kw)[0] == aser.ASER_ERR_DTYPE
+    assert e(ctx, P, P, None, P, 5, P, None, None, 0, 8, **kw)[0] == aser.ASER_ERR_INVALID_ARG     # layout
+    assert e(ctx, P, P, None, P, 1, P, None, None, 0, 8, m=8, n=15, ldw=15, rows=4, ldx=15, x_dtype=0)[0] == aser.ASER_ERR_SHAPE
+    assert e(ctx, P, P, None, None, 0, P, None, None, 0, 8, **kw)[0] == aser.ASER_ERR_INVALID_ARG
+    assert e(ctx, P, P, None, P, 0, P, None, None, 0, 8, m=8, n=16, ldw=8, rows=4, ldx=16, x_dtype=0)[0] == aser.ASER_ERR_SHAPE
+    assert aser.aser_output_error_workspace_bytes(4096, 4096, 4096, 64) >= 5 * 4096 * 4096 * 4
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2411_07762_amd")
     for dirpath, _, files in os.walk(pkg):
