@@ -244,6 +244,23 @@ int aser_layer_output_error(aser_ctx* ctx, const float* W, int64_t m, int64_t n,
                             const float* L_A, const float* L_B, int32_t r, int32_t act_bits,
                             double* err, double* ref_norm);
 
+/* The compensated layer at inference (end of Sec. 4.2: W_q X + L_A L_B X; Sec. 5.3 overhead analysis),
+ * tokens x channels orientation, integer MFMA for the quantized product:
+ *     Y[t][o] = s_t c_o sum_i xq[t][i] wq[o][i] + sum_k P[t][k] L_A[o][k],   P[t][k] = s_t sum_i xq[t][i] L_B[k][i]
+ * x_codes (rows x n int8, pitch n) and x_scales (rows): per-token codes of X M^-1 from aser_quantize_act_rtn;
+ * w_codes / layout / w_scales (m): from aser_quantize_rtn (int8 pitch n, or packed int4 pitch n / 2);
+ * L_A: m x r (ld r), L_B: r x n (ld n), fp32; r == 0: no compensation (L_A, L_B may be NULL);
+ * Y: rows x m fp32 (ldy).  All DEVICE pointers; codes 16-byte aligned.  n % 32 == 0, r <= 128.
+ * The integer sums are exact.  lowrank_split != 0: the rank-r branch runs at fp32-class accuracy (bf16
+ * hi + lo terms, about 2^-16 relative per product); 0: its factors are rounded to bf16 once, as an
+ * inference kernel that stores them in 16 bits would (about 2^-9 relative per factor).
+ * Asynchronous.  Needs aser_forward_workspace_bytes(rows, n, m, r) bytes of workspace when r > 0. */
+size_t aser_forward_workspace_bytes(int64_t rows, int64_t n, int64_t m, int32_t r);
+int aser_compensated_forward(aser_ctx* ctx, const int8_t* x_codes, const float* x_scales, int64_t rows, int64_t n,
+                             const void* w_codes, int32_t layout, const float* w_scales, int64_t m,
+                             const float* L_A, const float* L_B, int32_t r, int32_t lowrank_split,
+                             float* Y, int64_t ldy);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,6 +35,7 @@ EXPORTS = (
     "aser_whiten", "aser_error_reconstruct", "aser_svd_plan", "aser_quantize_act_rtn",
     "aser_spectrum_workspace_bytes", "aser_singular_values", "aser_select_rank", "aser_effective_rank",
     "aser_output_error_workspace_bytes", "aser_layer_output_error",
+    "aser_forward_workspace_bytes", "aser_compensated_forward",
 )
 
 
@@ -104,6 +105,10 @@ def load_library() -> ctypes.CDLL:
     lib.aser_layer_output_error.restype = ctypes.c_int
     lib.aser_layer_output_error.argtypes = [vp, vp, i64, i64, i64, vp, ctypes.c_int, i64, i64, vp, vp, i32, vp, vp, vp, i32,
                                             i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.aser_forward_workspace_bytes.restype = ctypes.c_size_t
+    lib.aser_forward_workspace_bytes.argtypes = [i64, i64, i64, i32]
+    lib.aser_compensated_forward.restype = ctypes.c_int
+    lib.aser_compensated_forward.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i64, vp, vp, i32, i32, vp, i64]
     lib.aser_quantize_act_rtn.restype = ctypes.c_int
     lib.aser_quantize_act_rtn.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, vp, i32, vp, vp]
     _lib = lib
@@ -321,6 +326,20 @@ def aser_layer_output_error(ctx: Context, W, X, mdiag, codes, layout: int, scale
                                           _ptr(scales), _ptr(L_A), _ptr(L_B), r, act_bits, ctypes.byref(err),
                                           ctypes.byref(ref))
     return st, err.value, ref.value
+
+
+def aser_forward_workspace_bytes(rows: int, n: int, m: int, r: int) -> int:
+    return int(load_library().aser_forward_workspace_bytes(rows, n, m, r))
+
+
+def aser_compensated_forward(ctx: Context, x_codes, x_scales, w_codes, layout: int, w_scales, L_A, L_B, r: int,
+                             lowrank_split: bool, Y, *, rows=None, n=None, m=None, ldy=None) -> int:
+    rows = x_codes.shape[0] if rows is None else rows
+    n = x_codes.shape[1] if n is None else n
+    m = w_scales.shape[0] if m is None else m
+    return ctx._lib.aser_compensated_forward(ctx.handle, _ptr(x_codes), _ptr(x_scales), rows, n, _ptr(w_codes), layout,
+                                             _ptr(w_scales), m, _ptr(L_A), _ptr(L_B), r, 1 if lowrank_split else 0,
+                                             _ptr(Y), _ld(Y, m) if ldy is None else ldy)
 
 
 # ----------------------------------------------------------------------------------- one layer, end to end

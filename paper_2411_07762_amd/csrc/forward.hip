@@ -1,0 +1,494 @@
+// The compensated layer at inference (end of Sec. 4.2: W_q X + L_A L_B X; overhead analysis of
+// Sec. 5.3: s d^2 -> s d^2 + 2 s r d operations), in this library's tokens x channels orientation:
+//     Y[t][o] = s_t c_o sum_i xq[t][i] wq[o][i]  +  sum_k P[t][k] L_A[o][k],
+//     P[t][k] = s_t sum_i xq[t][i] L_B[k][i]
+// with xq, s_t the per-token activation codes and scales (aser_quantize_act_rtn of X M^-1), wq, c_o
+// the per-channel weight codes and scales (aser_quantize_rtn), both branches reading the same
+// quantized activations.
+//
+// Every operand is contiguous along the contraction dimension (a token's channels, an output's
+// channels, a row of L_B, a row of L_A), which is how MFMA operands want them: a lane holds 16
+// consecutive int8 (v_mfma_i32_32x32x32_i8) or 8 consecutive bf16 (v_mfma_f32_32x32x16_bf16) of its
+// row.  No transposes anywhere.
+//
+// Main kernel: a workgroup (4 waves, 2 x 2) owns 128 tokens x 256 outputs; per step 64 channels of
+// both operands go through registers into LDS (16-byte chunks, XOR-swizzled so that the 16-byte operand
+// reads of 32 consecutive rows hit distinct banks), double buffered, one barrier per step.  int4 codes
+// are widened while staged: the low nibbles of a dword become the bytes (w << 4) & 0xF0F0F0F0 and the
+// high nibbles w & 0xF0F0F0F0, i.e. 16 q as a signed byte, no borrow between bytes; the factor 16 goes
+// into the scale.  That puts the even channels of a group of 32 into one 16-byte chunk and the odd ones
+// into the next, so the activation bytes are put into the same order with two byte permutes per 8.
+// The int32 sums are exact.  Epilogue: scale, then the rank-r branch as r / 16 further bf16 MFMA steps
+// on the same accumulators (P from the small kernel below, L_A pre-split into bf16 planes), then store.
+//
+// Rank-r branch precision: L_A, L_B and P are fp32; a bf16 MFMA sees hi = bf16(x) and, in the split
+// mode, also lo = bf16(x - hi) (three products hi hi + hi lo + lo hi per fp32 product; the activation
+// codes are exact in bf16, so P needs two).  The plain mode uses hi alone, as an inference kernel that
+// keeps the factors in 16-bit would.
+#include "aser_internal.h"
+
+namespace {
+
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef int v16i_t __attribute__((ext_vector_type(16)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+constexpr int kFwdTM = 128, kFwdTN = 256, kFwdBK = 64;
+
+__device__ __forceinline__ uint32_t bf16_hi_pair(float a, float b) {       // truncation-free: callers pass bf16-exact values or accept RNE below
+    return (__float_as_uint(a) >> 16) | (__float_as_uint(b) & 0xFFFF0000u);
+}
+__device__ __forceinline__ uint32_t bf16_rne(float x) {
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// hi[i][j] = bf16(src[i][j]), lo[i][j] = bf16(src[i][j] - hi) for j < cols, 0 for cols <= j < cols_pad.
+__global__ __launch_bounds__(256) void split_bf16_kernel(const float* __restrict__ src, int64_t rows, int64_t cols, int64_t ld,
+                                                         int64_t cols_pad, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo) {
+    const int64_t total = rows * cols_pad;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+        const int64_t i = t / cols_pad, j = t % cols_pad;
+        const float x = j < cols ? src[i * ld + j] : 0.f;
+        const uint32_t h = bf16_rne(x);
+        hi[t] = (uint16_t)h;
+        lo[t] = (uint16_t)bf16_rne(x - __uint_as_float(h << 16));
+    }
+}
+
+// byte offset of 16-byte chunk c (0..3) of row r inside a [rows][64 bytes] LDS tile
+__device__ __forceinline__ int chunk_off(int r, int c) { return r * 64 + ((c ^ ((r >> 2) & 3)) << 4); }
+
+// Stages 64 channels of `nrows` (128 or 256) code rows: thread t handles row t / 2 (+ 128 per repeat),
+// half t % 2 = channels [32 half, 32 half + 32) of the step.
+//   PLAIN  : int8 codes, 32 bytes copied as two chunks
+//   PERMUTE: int8 codes reordered to (even channels, odd channels) per group of 32
+//   NIBBLES: packed int4 codes (16 bytes) widened to 16 q bytes, even channels first
+enum StageKind { STAGE_PLAIN = 0, STAGE_PERMUTE = 1, STAGE_NIBBLES = 2 };
+
+template <int KIND, int REPS>
+struct CodeStage {
+    uint4 r[REPS][2];
+    const char* p[REPS];
+    bool ok[REPS];
+
+    __device__ __forceinline__ void init(const void* base, int64_t row0, int64_t nrows_total, int64_t pitch_bytes, int tid) {
+        const int half = tid & 1;
+#pragma unroll
+        for (int u = 0; u < REPS; ++u) {
+            const int64_t row = row0 + (tid >> 1) + 128 * u;
+            ok[u] = row < nrows_total;
+            p[u] = (const char*)base + (ok[u] ? row : 0) * pitch_bytes + (KIND == STAGE_NIBBLES ? 16 : 32) * half;
+        }
+    }
+    // loads channels [k0 + 32 half, +32) of the thread's rows; k0 + 64 may exceed n (n % 32 == 0)
+    __device__ __forceinline__ void load(int64_t k0, int64_t n, int tid) {
+        const bool in = k0 + 32 * (tid & 1) < n;
+#pragma unroll
+        for (int u = 0; u < REPS; ++u) {
+            r[u][0] = make_uint4(0u, 0u, 0u, 0u);
+            r[u][1] = make_uint4(0u, 0u, 0u, 0u);
+            if (ok[u] && in) {
+                if (KIND == STAGE_NIBBLES) {
+                    r[u][0] = *(const uint4*)(p[u] + k0 / 2);
+                } else {
+                    r[u][0] = *(const uint4*)(p[u] + k0);
+                    r[u][1] = *(const uint4*)(p[u] + k0 + 16);
+                }
+            }
+        }
+    }
+    __device__ __forceinline__ void store(char* tile, int tid) const {
+        const int half = tid & 1;
+#pragma unroll
+        for (int u = 0; u < REPS; ++u) {
+            const int row = (tid >> 1) + 128 * u;
+            uint4 c0, c1;
+            if (KIND == STAGE_PLAIN) {
+                c0 = r[u][0];
+                c1 = r[u][1];
+            } else if (KIND == STAGE_PERMUTE) {
+                const uint4 a = r[u][0], b = r[u][1];
+                c0 = make_uint4(__builtin_amdgcn_perm(a.y, a.x, 0x06040200u), __builtin_amdgcn_perm(a.w, a.z, 0x06040200u),
+                                __builtin_amdgcn_perm(b.y, b.x, 0x06040200u), __builtin_amdgcn_perm(b.w, b.z, 0x06040200u));
+                c1 = make_uint4(__builtin_amdgcn_perm(a.y, a.x, 0x07050301u), __builtin_amdgcn_perm(a.w, a.z, 0x07050301u),
+                                __builtin_amdgcn_perm(b.y, b.x, 0x07050301u), __builtin_amdgcn_perm(b.w, b.z, 0x07050301u));
+            } else {
+                const uint4 w = r[u][0];
+                c0 = make_uint4((w.x << 4) & 0xF0F0F0F0u, (w.y << 4) & 0xF0F0F0F0u, (w.z << 4) & 0xF0F0F0F0u, (w.w << 4) & 0xF0F0F0F0u);
+                c1 = make_uint4(w.x & 0xF0F0F0F0u, w.y & 0xF0F0F0F0u, w.z & 0xF0F0F0F0u, w.w & 0xF0F0F0F0u);
+            }
+            *(uint4*)(tile + chunk_off(row, 2 * half)) = c0;
+            *(uint4*)(tile + chunk_off(row, 2 * half + 1)) = c1;
+        }
+    }
+};
+
+struct FwdArgs {
+    const int8_t* xq; const float* xs; int64_t rows, n;
+    const void* wq; const float* ws; int64_t m;
+    const float* P; int64_t ldp;                 // rows x r_pad fp32 (null: no rank-r branch)
+    const uint16_t* la_hi; const uint16_t* la_lo; int r_pad;   // m x r_pad bf16 planes
+    float* Y; int64_t ldy;
+};
+
+template <bool W4, bool SPLIT>
+__global__ __launch_bounds__(256) void cf_main_kernel(FwdArgs g) {
+    extern __shared__ __align__(16) char smem[];
+    constexpr int A_BYTES = kFwdTM * 64, B_BYTES = kFwdTN * 64, STAGE = A_BYTES + B_BYTES;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t T0 = (int64_t)blockIdx.y * kFwdTM, O0 = (int64_t)blockIdx.x * kFwdTN;
+
+    CodeStage<W4 ? STAGE_PERMUTE : STAGE_PLAIN, 1> sa;
+    CodeStage<W4 ? STAGE_NIBBLES : STAGE_PLAIN, 2> sb;
+    sa.init(g.xq, T0, g.rows, g.n, tid);
+    sb.init(g.wq, O0, g.m, W4 ? g.n / 2 : g.n, tid);
+
+    v16i_t acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+    // operand read offsets: row of the lane inside the tile, chunk = 2 slice + lane / 32
+    int offa[2][2], offb[2][4];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int c = 2 * s + (lane >> 5);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) offa[s][i] = chunk_off(wm * 64 + 32 * i + (lane & 31), c);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) offb[s][j] = A_BYTES + chunk_off(wn * 128 + 32 * j + (lane & 31), c);
+    }
+
+    const int64_t steps = (g.n + kFwdBK - 1) / kFwdBK;
+    sa.load(0, g.n, tid);
+    sb.load(0, g.n, tid);
+    sa.store(smem, tid);
+    sb.store(smem + A_BYTES, tid);
+    __syncthreads();
+    for (int64_t s = 0; s < steps; ++s) {
+        const char* cur = smem + (s & 1) * STAGE;
+        char* nxt = smem + ((s + 1) & 1) * STAGE;
+        const bool more = s + 1 < steps;
+        if (more) {
+            sa.load((s + 1) * kFwdBK, g.n, tid);
+            sb.load((s + 1) * kFwdBK, g.n, tid);
+        }
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) {
+            v4i_t a[2], b[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = *(const v4i_t*)(cur + offa[sl][i]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = *(const v4i_t*)(cur + offb[sl][j]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            sa.store(nxt, tid);
+            sb.store(nxt + A_BYTES, tid);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: acc[i][j][e] is (token, output) = (32 i + 8 (e / 4) + 4 (lane / 32) + e % 4, 32 j + lane % 32) of the wave's sub-tile
+    const float wfix = W4 ? (1.0f / 16.0f) : 1.0f;
+    f32x16_t y[2][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t col = O0 + wn * 128 + 32 * j + (lane & 31);
+        const float cw = (col < g.m) ? g.ws[col] * wfix : 0.f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int64_t row = T0 + wm * 64 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const float sx = (row < g.rows) ? g.xs[row] : 0.f;
+                y[i][j][e] = (float)acc[i][j][e] * (sx * cw);
+            }
+    }
+    if (g.P) {
+        for (int kk = 0; kk < g.r_pad; kk += 16) {
+            const int kq = kk + 8 * (lane >> 5);
+            bf16x8_t ph[2], pl[2], lh[4], ll[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int64_t row = T0 + wm * 64 + 32 * i + (lane & 31);
+                f32x4_t p0 = {0.f, 0.f, 0.f, 0.f}, p1 = {0.f, 0.f, 0.f, 0.f};
+                if (row < g.rows) {
+                    p0 = *(const f32x4_t*)(g.P + row * g.ldp + kq);
+                    p1 = *(const f32x4_t*)(g.P + row * g.ldp + kq + 4);
+                }
+                const float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                uint32_t h[4], l[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t h0 = bf16_rne(pv[2 * q]), h1 = bf16_rne(pv[2 * q + 1]);
+                    h[q] = h0 | (h1 << 16);
+                    l[q] = bf16_rne(pv[2 * q] - __uint_as_float(h0 << 16)) | (bf16_rne(pv[2 * q + 1] - __uint_as_float(h1 << 16)) << 16);
+                }
+                ph[i] = __builtin_bit_cast(bf16x8_t, make_uint4(h[0], h[1], h[2], h[3]));
+                pl[i] = __builtin_bit_cast(bf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t col = O0 + wn * 128 + 32 * j + (lane & 31);
+                uint4 vh = make_uint4(0u, 0u, 0u, 0u), vl = make_uint4(0u, 0u, 0u, 0u);
+                if (col < g.m) {
+                    vh = *(const uint4*)(g.la_hi + col * g.r_pad + kq);
+                    if (SPLIT) vl = *(const uint4*)(g.la_lo + col * g.r_pad + kq);
+                }
+                lh[j] = __builtin_bit_cast(bf16x8_t, vh);
+                ll[j] = __builtin_bit_cast(bf16x8_t, vl);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (SPLIT) {
+                        y[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl[i], lh[j], y[i][j], 0, 0, 0);
+                        y[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph[i], ll[j], y[i][j], 0, 0, 0);
+                    }
+                    y[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph[i], lh[j], y[i][j], 0, 0, 0);
+                }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t col = O0 + wn * 128 + 32 * j + (lane & 31);
+            if (col >= g.m) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int64_t row = T0 + wm * 64 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                if (row < g.rows) g.Y[row * g.ldy + col] = y[i][j][e];
+            }
+        }
+}
+
+// P[t][k] = s_t sum_i xq[t][i] L_B[k][i] for 128 tokens per workgroup (32 per wave) and all r_pad
+// columns (RB blocks of 32).  L_B comes as bf16 planes [r_pad][n] (hi, lo).  Per step 64 channels: the
+// code tile as in the main kernel (no reordering), the L_B tiles as 16-byte chunks of 8 bf16 with an
+// XOR swizzle; codes become bf16 exactly (|q| <= 128) on their way into the MFMA.
+template <int RB, bool SPLIT>
+__global__ __launch_bounds__(256) void cf_down_kernel(const int8_t* __restrict__ xq, const float* __restrict__ xs, int64_t rows,
+                                                      int64_t n, const uint16_t* __restrict__ lb_hi,
+                                                      const uint16_t* __restrict__ lb_lo, float* __restrict__ P, int64_t ldp) {
+    extern __shared__ __align__(16) char smem[];
+    constexpr int RP = 32 * RB;                              // r_pad
+    constexpr int A_BYTES = 128 * 64, B_BYTES = RP * 128;    // 64 bf16 per row
+    constexpr int BCH = RP * 8 / 256;                        // 16-byte chunks of a B plane per thread
+    char* sA = smem;
+    char* sBh = smem + A_BYTES;
+    char* sBl = sBh + B_BYTES;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t T0 = (int64_t)blockIdx.x * 128;
+    CodeStage<STAGE_PLAIN, 1> sa;
+    sa.init(xq, T0, rows, n, tid);
+    f32x16_t acc[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    uint4 bh[BCH], bl[BCH];
+    auto load_b = [&](int64_t k0) {
+#pragma unroll
+        for (int u = 0; u < BCH; ++u) {
+            const int q = tid + 256 * u, row = q >> 3, c = q & 7;
+            const int64_t k = k0 + 8 * c;
+            bh[u] = make_uint4(0u, 0u, 0u, 0u);
+            bl[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (k < n) {                                     // n % 32 == 0: a chunk of 8 is whole or absent
+                bh[u] = *(const uint4*)(lb_hi + (int64_t)row * n + k);
+                if (SPLIT) bl[u] = *(const uint4*)(lb_lo + (int64_t)row * n + k);
+            }
+        }
+    };
+    auto store_b = [&]() {
+#pragma unroll
+        for (int u = 0; u < BCH; ++u) {
+            const int q = tid + 256 * u, row = q >> 3, c = q & 7;
+            const int off = row * 128 + ((c ^ ((row >> 1) & 7)) << 4);
+            *(uint4*)(sBh + off) = bh[u];
+            if (SPLIT) *(uint4*)(sBl + off) = bl[u];
+        }
+    };
+    const int64_t steps = (n + 63) / 64;
+    sa.load(0, n, tid);
+    load_b(0);
+    for (int64_t s = 0; s < steps; ++s) {
+        __syncthreads();                                     // the previous step's readers are done
+        sa.store(sA, tid);
+        store_b();
+        __syncthreads();
+        if (s + 1 < steps) {
+            sa.load((s + 1) * 64, n, tid);
+            load_b((s + 1) * 64);
+        }
+        const int arow = wave * 32 + (lane & 31);
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {                     // 16 channels per slice; this lane's 8: bytes [16 sl + 8 g, +8) of its row
+            const int g8 = lane >> 5;
+            const uint2 raw = *(const uint2*)(sA + chunk_off(arow, sl) + 8 * g8);
+            const uint32_t w2[2] = {raw.x ^ 0x80808080u, raw.y ^ 0x80808080u};      // q + 128 as unsigned bytes
+            uint32_t pk[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t w = w2[q >> 1];
+                const int b0 = 2 * (q & 1);
+                const float f0 = (float)((w >> (8 * b0)) & 0xFFu) - 128.0f;
+                const float f1 = (float)((w >> (8 * b0 + 8)) & 0xFFu) - 128.0f;
+                pk[q] = bf16_hi_pair(f0, f1);
+            }
+            const bf16x8_t a = __builtin_bit_cast(bf16x8_t, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+            const int c = 2 * sl + g8;
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                const int brow = 32 * j + (lane & 31);
+                const int off = brow * 128 + ((c ^ ((brow >> 1) & 7)) << 4);
+                const bf16x8_t bhv = *(const bf16x8_t*)(sBh + off);
+                if (SPLIT) {
+                    const bf16x8_t blv = *(const bf16x8_t*)(sBl + off);
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, blv, acc[j], 0, 0, 0);
+                }
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bhv, acc[j], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+        const int col = 32 * j + (lane & 31);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int64_t row = T0 + wave * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            if (row < rows) P[row * ldp + col] = acc[j][e] * xs[row];
+        }
+    }
+}
+
+struct FwdPlan {
+    int r_pad;
+    size_t off_p, off_lah, off_lal, off_lbh, off_lbl, total;
+};
+
+void fwd_plan(int64_t rows, int64_t n, int64_t m, int r, FwdPlan* p) {
+    p->r_pad = (r + 31) / 32 * 32;
+    size_t off = 0;
+    p->off_p = off; off += align_up((size_t)rows * p->r_pad * 4, 256);
+    p->off_lah = off; off += align_up((size_t)m * p->r_pad * 2, 256);
+    p->off_lal = off; off += align_up((size_t)m * p->r_pad * 2, 256);
+    p->off_lbh = off; off += align_up((size_t)p->r_pad * n * 2, 256);
+    p->off_lbl = off; off += align_up((size_t)p->r_pad * n * 2, 256);
+    p->total = r > 0 ? off : 0;
+}
+
+template <typename K>
+int set_lds_once(aser_ctx* ctx, K kern, int bytes, bool* done) {
+    if (ctx->device >= 0 && ctx->device < 16 && !done[ctx->device]) {
+        ASER_HIP(ctx, hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+        done[ctx->device] = true;
+    }
+    return ASER_OK;
+}
+
+template <bool W4, bool SPLIT>
+int launch_main(aser_ctx* ctx, const FwdArgs& g) {
+    static bool done[16] = {false};
+    constexpr int lds = 2 * (kFwdTM * 64 + kFwdTN * 64);
+    auto kern = cf_main_kernel<W4, SPLIT>;
+    ASER_TRY(set_lds_once(ctx, kern, lds, done));
+    dim3 grid((unsigned)ceil_div64(g.m, kFwdTN), (unsigned)ceil_div64(g.rows, kFwdTM));
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, ctx->stream, g);
+    return aser_check_launch(ctx, "compensated_forward");
+}
+
+template <int RB, bool SPLIT>
+int launch_down(aser_ctx* ctx, const int8_t* xq, const float* xs, int64_t rows, int64_t n, const uint16_t* lbh,
+                const uint16_t* lbl, float* P, int64_t ldp) {
+    static bool done[16] = {false};
+    constexpr int lds = 128 * 64 + 2 * (32 * RB * 128);
+    auto kern = cf_down_kernel<RB, SPLIT>;
+    ASER_TRY(set_lds_once(ctx, kern, lds, done));
+    hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div64(rows, 128)), dim3(256), lds, ctx->stream, xq, xs, rows, n, lbh, lbl, P, ldp);
+    return aser_check_launch(ctx, "compensated_forward_down");
+}
+
+}  // namespace
+
+extern "C" size_t aser_forward_workspace_bytes(int64_t rows, int64_t n, int64_t m, int32_t r) {
+    if (rows <= 0 || n <= 0 || m <= 0 || r < 0) return 0;
+    FwdPlan p;
+    fwd_plan(rows, n, m, r, &p);
+    return p.total + kAserWsTail;
+}
+
+extern "C" int aser_compensated_forward(aser_ctx* ctx, const int8_t* x_codes, const float* x_scales, int64_t rows, int64_t n,
+                                        const void* w_codes, int32_t layout, const float* w_scales, int64_t m,
+                                        const float* L_A, const float* L_B, int32_t r, int32_t lowrank_split,
+                                        float* Y, int64_t ldy) {
+    if (!ctx) return ASER_ERR_INVALID_ARG;
+    if (!x_codes || !x_scales || !w_codes || !w_scales || !Y) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "compensated_forward: null pointer");
+    if (rows < 0 || n <= 0 || m <= 0 || ldy < m) ASER_FAIL(ctx, ASER_ERR_SHAPE, "compensated_forward: bad shape");
+    if (n % 32) ASER_FAIL(ctx, ASER_ERR_SHAPE, "compensated_forward: n must be a multiple of 32");
+    if (layout != ASER_CODES_INT8 && layout != ASER_CODES_INT4_PACKED)
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "compensated_forward: unknown code layout");
+    if (r < 0 || r > 128) ASER_FAIL(ctx, ASER_ERR_SHAPE, "compensated_forward: need 0 <= r <= 128");
+    if (r > 0 && (!L_A || !L_B)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "compensated_forward: r > 0 needs L_A and L_B");
+    if (((uintptr_t)x_codes & 15) || ((uintptr_t)w_codes & 15) || ((uintptr_t)x_scales & 3) || ((uintptr_t)w_scales & 3) ||
+        ((uintptr_t)Y & 3))
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "compensated_forward: codes must be 16-byte aligned, scales and Y 4-byte aligned");
+    FwdPlan pl;
+    fwd_plan(rows > 0 ? rows : 1, n, m, r, &pl);
+    if (r > 0 && (!ctx->ws || ctx->ws_bytes < pl.total + kAserWsTail))
+        ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "compensated_forward: workspace too small (%zu needed)", pl.total + kAserWsTail);
+    if (rows == 0) return ASER_OK;
+    ASER_TRY(aser_prepare_device(ctx));
+    const bool split = lowrank_split != 0;
+    FwdArgs g{};
+    g.xq = x_codes; g.xs = x_scales; g.rows = rows; g.n = n;
+    g.wq = w_codes; g.ws = w_scales; g.m = m;
+    g.Y = Y; g.ldy = ldy;
+    if (r > 0) {
+        char* ws = (char*)ctx->ws;
+        float* P = (float*)(ws + pl.off_p);
+        uint16_t* lah = (uint16_t*)(ws + pl.off_lah);
+        uint16_t* lal = (uint16_t*)(ws + pl.off_lal);
+        uint16_t* lbh = (uint16_t*)(ws + pl.off_lbh);
+        uint16_t* lbl = (uint16_t*)(ws + pl.off_lbl);
+        const int rp = pl.r_pad;
+        // the factors as bf16 planes: L_A (m x r) padded to r_pad columns, L_B (r x n) padded to r_pad rows
+        {
+            const int64_t t1 = m * rp;
+            hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)(ceil_div64(t1, 256) < 2048 ? ceil_div64(t1, 256) : 2048)), dim3(256), 0,
+                               ctx->stream, L_A, m, (int64_t)r, (int64_t)r, (int64_t)rp, lah, lal);
+            ASER_TRY(aser_check_launch(ctx, "split_bf16"));
+            ASER_TRY(aser_fill_bytes(ctx, lbh, (size_t)(pl.off_lbl - pl.off_lbh) * 2));
+            const int64_t t2 = (int64_t)r * n;
+            hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)(ceil_div64(t2, 256) < 2048 ? ceil_div64(t2, 256) : 2048)), dim3(256), 0,
+                               ctx->stream, L_B, (int64_t)r, n, n, n, lbh, lbl);
+            ASER_TRY(aser_check_launch(ctx, "split_bf16"));
+        }
+#define ASER_DOWN(RB)                                                                                   \
+    (split ? launch_down<RB, true>(ctx, x_codes, x_scales, rows, n, lbh, lbl, P, rp)                    \
+           : launch_down<RB, false>(ctx, x_codes, x_scales, rows, n, lbh, lbl, P, rp))
+        if (rp == 32) ASER_TRY(ASER_DOWN(1));
+        else if (rp == 64) ASER_TRY(ASER_DOWN(2));
+        else if (rp == 96) ASER_TRY(ASER_DOWN(3));
+        else ASER_TRY(ASER_DOWN(4));
+#undef ASER_DOWN
+        g.P = P; g.ldp = rp; g.la_hi = lah; g.la_lo = lal; g.r_pad = rp;
+    }
+    const bool w4 = layout == ASER_CODES_INT4_PACKED;
+    if (w4) return split ? launch_main<true, true>(ctx, g) : launch_main<true, false>(ctx, g);
+    return split ? launch_main<false, true>(ctx, g) : launch_main<false, false>(ctx, g);
+}

@@ -168,6 +168,21 @@ def test_output_error_validation(ctx):
     assert aser.aser_output_error_workspace_bytes(4096, 4096, 4096, 64) >= 5 * 4096 * 4096 * 4
 
 
+def test_forward_validation(ctx):
+    f = aser.aser_compensated_forward
+    kw = dict(rows=4, n=64, m=8, ldy=8)
+    assert f(ctx, P, P, P, 0, P, None, None, 0, False, None, **kw) == aser.ASER_ERR_INVALID_ARG      # Y missing
+    assert f(ctx, P, P, P, 0, P, None, None, 0, False, P, rows=4, n=48, m=8, ldy=8) == aser.ASER_ERR_SHAPE   # n % 32
+    assert f(ctx, P, P, P, 0, P, None, None, 0, False, P, rows=4, n=64, m=8, ldy=4) == aser.ASER_ERR_SHAPE
+    assert f(ctx, P, P, P, 3, P, None, None, 0, False, P, **kw) == aser.ASER_ERR_INVALID_ARG         # layout
+    assert f(ctx, P, P, P, 0, P, None, None, 8, False, P, **kw) == aser.ASER_ERR_INVALID_ARG         # r > 0 without factors
+    assert f(ctx, P, P, P, 0, P, P, P, 129, False, P, **kw) == aser.ASER_ERR_SHAPE
+    assert f(ctx, P + 8, P, P, 0, P, None, None, 0, False, P, **kw) == aser.ASER_ERR_INVALID_ARG     # codes not 16-byte aligned
+    assert f(ctx, P, P, P, 0, P, P, P, 8, False, P, **kw) == aser.ASER_ERR_WORKSPACE
+    assert f(ctx, P, P, P, 0, P, None, None, 0, False, P, rows=0, n=64, m=8, ldy=8) == aser.ASER_OK  # no tokens: no-op
+    assert aser.aser_forward_workspace_bytes(32768, 4096, 4096, 0) == 256
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2411_07762_amd")
     for dirpath, _, files in os.walk(pkg):
