@@ -26,10 +26,61 @@ if ROOT not in sys.path:
 METRIC = "per-layer ASER calibration ms + Gram/GEMM MFMA util %, 4096×4096 layer"
 BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch at workload c1 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
-# 1 GiB copy (x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE); see profiles/gram_rtn_hbm_traffic.txt.
-MEASURED_TRAFFIC_C1 = {"gram": 435532 * 1024 * 2.0 + 132608 * 1024 * 1.0,
-                       "rtn": 32888 * 1024 * 2.0 + 77731 * 1024 * 1.0}
+INT8_PEAK_TOPS = 5000.0
+FP32_MFMA_PEAK_TFLOPS = 157.3
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gram_rtn_hbm_traffic.txt")
+
+
+def measured_traffic():
+    """HBM bytes per launch of the Gram and RTN kernels at workload c1, from the last line of
+    profiles/gram_rtn_hbm_traffic.txt (written by `bench.py --traffic-summary` from two rocprofv3 --pmc
+    runs of `bench.py --traffic-probe`, FETCH_SIZE and WRITE_SIZE, each scaled by a 1 GiB copy)."""
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            for line in fh:
+                if line.startswith("traffic_bytes_per_launch "):
+                    return json.loads(line.split(" ", 1)[1])
+    except OSError:
+        pass
+    return {}
+
+
+def traffic_summary(fetch_dir, write_dir):
+    """Reads the rocprofv3 result databases of the two counter runs and prints the summary that is kept
+    as profiles/gram_rtn_hbm_traffic.txt."""
+    import collections
+    import glob
+    import sqlite3
+    agg = collections.defaultdict(list)
+    for d in (fetch_dir, write_dir):
+        dbs = sorted(glob.glob(os.path.join(d, "**", "*_results.db"), recursive=True))
+        if not dbs:
+            raise SystemExit("no *_results.db under %s" % d)
+        con = sqlite3.connect(dbs[-1])
+        for k, cn, v in con.execute("select kernel_name, counter_name, value from counters_collection"):
+            agg[(k, cn)].append(float(v))
+    copy = {cn: max(v) for (k, cn), v in agg.items() if "copyBuffer" in k or "CopyBuffer" in k}
+    scale = {"FETCH_SIZE": (1 << 20) / copy["FETCH_SIZE"], "WRITE_SIZE": (1 << 20) / copy["WRITE_SIZE"]}
+    print("HBM traffic of the Gram kernel and the RTN kernel, workload c1, MI355X: rocprofv3 --pmc FETCH_SIZE / "
+          "WRITE_SIZE (KiB per dispatch).\n")
+    print("Commands (from /tmp, TMPDIR=/tmp; one counter per run):")
+    print("  rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pmc_fetch -o fetch -- python3 bench.py --traffic-probe")
+    print("  rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pmc_write -o write -- python3 bench.py --traffic-probe")
+    print("  python3 bench.py --traffic-summary gpurun_out/pmc_fetch gpurun_out/pmc_write > profiles/gram_rtn_hbm_traffic.txt")
+    print("The probe runs a 1 GiB device-to-device copy (1 GiB read, 1 GiB written), the Gram kernel and the RTN "
+          "kernel, three times each.\n")
+    out = {}
+    for (k, cn), v in sorted(agg.items()):
+        if not any(t in k for t in ("gram_dma_kernel", "rtn_kernel", "opyBuffer")):
+            continue
+        print("%-90s %-11s launches=%d avg=%.6g KiB max=%.6g KiB" % (k[:90], cn, len(v), sum(v) / len(v), max(v)))
+        for name in ("gram_dma_kernel", "rtn_kernel"):
+            if name in k:
+                out[name] = out.get(name, 0.0) + sum(v) / len(v) * 1024.0 * scale[cn]
+    print("\nScale factors from the full-size copy (1048576 KiB read and written): FETCH_SIZE x%.3f, WRITE_SIZE x%.3f."
+          % (scale["FETCH_SIZE"], scale["WRITE_SIZE"]))
+    print("Bytes per launch = FETCH_SIZE x its factor + WRITE_SIZE x its factor:")
+    print("traffic_bytes_per_launch " + json.dumps(out))
 
 
 def log(*a):
@@ -173,6 +224,80 @@ def run_block(args):
     print(json.dumps(out))
 
 
+def extras(ctx, aser, torch, spec, buf, W, X, reps):
+    """Timings of the rows beyond the calibration path, on the layer the step has just calibrated: the full
+    spectrum with the rank rule of Eq. 9 and the effective rank of Eq. 3-4, the W4A8 layer-output error on a
+    token sample, and the compensated inference kernel (int8 MFMA) with and without its rank-r branch."""
+    dev = X.device
+    res = {}
+
+    def timed(fn, n=3):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    # full spectrum of T S, rank from alpha, effective rank
+    k = min(spec.m, spec.n)
+    ctx.ensure_workspace(aser.aser_spectrum_workspace_bytes(spec.m, spec.n, True))
+    sig = torch.empty(k, dtype=torch.float64, device=dev)
+    ms = timed(lambda: ctx.check(aser.aser_singular_values(ctx, buf.T, buf.S, sig)), 2)
+    ranks = {}
+    for alpha in (0.1, 0.075, 0.05, 0.03, 0.015):
+        st, r_sel, _ = aser.aser_select_rank(ctx, sig, alpha)
+        ctx.check(st)
+        ranks[str(alpha)] = r_sel
+    st, erank = aser.aser_effective_rank(ctx, sig)
+    ctx.check(st)
+    pass_bytes = 16.0 * k ** 3 / 3.0
+    res["spectrum"] = {"ms": ms, "k": k, "rank_from_alpha": ranks, "effective_rank_of_T_S": erank,
+                       "tridiagonalisation_algorithmic_bytes": pass_bytes,
+                       "note": "bound by the passes over the fp64 trailing matrix (16 k^3 / 3 bytes, served by the "
+                               "last-level cache when the matrix fits) and by 2 (k - 2) launches"}
+    # layer-output error, W4A8 and W4A6, compensated and not, on a sample of the calibration tokens
+    sample = min(2048, spec.tokens)
+    ctx.ensure_workspace(aser.aser_output_error_workspace_bytes(spec.m, spec.n, sample, spec.r))
+    layout = aser.ASER_CODES_INT4_PACKED if buf.packed else aser.ASER_CODES_INT8
+    oe = {}
+    for act_bits, comp in ((8, True), (8, False), (6, True)):
+        st, e, yn = aser.aser_layer_output_error(ctx, W, X[:sample], buf.mdiag, buf.codes, layout, buf.scales,
+                                                 buf.L_A if comp else None, buf.L_B if comp else None,
+                                                 spec.r if comp else 0, act_bits)
+        ctx.check(st)
+        oe["W%dA%d_%s" % (spec.bits, act_bits, "compensated" if comp else "rtn_only")] = e / yn
+    ms = timed(lambda: aser.aser_layer_output_error(ctx, W, X[:sample], buf.mdiag, buf.codes, layout, buf.scales,
+                                                    buf.L_A, buf.L_B, spec.r, 8), 3)
+    res["layer_output_error"] = {"ms": ms, "sample_tokens": sample, "relative_to_exact_output_norm": oe}
+    # compensated inference kernel on the whole calibration stream (tokens x n int8 codes)
+    if spec.n % 32 == 0:
+        xq = torch.empty((spec.tokens, spec.n), dtype=torch.int8, device=dev)
+        xs = torch.empty(spec.tokens, dtype=torch.float32, device=dev)
+        ctx.check(aser.aser_quantize_act_rtn(ctx, X, buf.mdiag, 8, xq, xs))
+        Y = torch.empty((spec.tokens, spec.m), dtype=torch.float32, device=dev)
+        ctx.ensure_workspace(aser.aser_forward_workspace_bytes(spec.tokens, spec.n, spec.m, spec.r))
+        fw = {}
+        for name, r_use, split in (("no_compensation", 0, False), ("rank_r_bf16", spec.r, False), ("rank_r_split", spec.r, True)):
+            fw[name] = timed(lambda: ctx.check(aser.aser_compensated_forward(
+                ctx, xq, xs, buf.codes, layout, buf.scales, buf.L_A if r_use else None, buf.L_B if r_use else None,
+                r_use, split, Y)), max(3, reps // 2))
+        ops = 2.0 * spec.tokens * spec.n * spec.m
+        res["compensated_forward"] = {
+            "ms": fw, "tokens": spec.tokens,
+            "roofline": {"kernel": "cf_main_kernel (int8 MFMA, int4 weight codes widened in flight)", "bound": "mfma",
+                         "achieved": ops / (fw["no_compensation"] * 1e-3) / 1e12, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                         "frac": ops / (fw["no_compensation"] * 1e-3) / 1e12 / INT8_PEAK_TOPS},
+            "overhead_of_rank_r_branch": {"measured_bf16": fw["rank_r_bf16"] / fw["no_compensation"] - 1.0,
+                                          "measured_split": fw["rank_r_split"] / fw["no_compensation"] - 1.0,
+                                          "paper_flops_ratio_2r_over_d": 2.0 * spec.r / spec.n}}
+        del xq, Y
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -182,7 +307,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="run only a 1 GiB copy, the Gram kernel and the RTN kernel (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--traffic-summary", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
+                    help="print the summary of the two counter runs (no GPU needed)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the timings of the rows beyond the calibration path")
     args = ap.parse_args()
+    if args.traffic_summary:
+        return traffic_summary(*args.traffic_summary)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
               file=sys.stderr)
@@ -329,31 +459,50 @@ def main():
     act_gbs = act_bytes / (act_ms * 1e-3) / 1e9
     del act_codes
 
+    _, svd_block, svd_iters = aser.aser_svd_plan(spec.m, spec.n, spec.r)
+    traffic = measured_traffic()
+    # fp32-class contractions of the path: algorithmic flops, and executed MFMA flops (three bf16 products per
+    # fp32 product), against the bf16 dense peak and the fp32 MFMA peak
+    mx = float(max(spec.m, spec.n))
+    alg = {"whiten": spec.n ** 3 / 3.0,
+           "reconstruct": float(spec.m) * spec.n * (spec.n + 1) + (svd_iters + 2) * 4.0 * spec.m * spec.n * svd_block
+                          + (2 * svd_iters + 3) * 4.0 * mx * svd_block * svd_block}
+    stage_util = {}
+    for k, ms in zip(stage_names, stage_ms):
+        if k in alg:
+            tf = alg[k] / (ms * 1e-3) / 1e12
+            stage_util[k] = {"algorithmic_flops": alg[k], "achieved_tflops": round(tf, 2),
+                             "util_alg_of_bf16_peak": round(tf / BF16_PEAK_TFLOPS, 5),
+                             "util_exec_of_bf16_peak": round(3.0 * tf / BF16_PEAK_TFLOPS, 5),
+                             "util_alg_of_fp32_mfma_peak": round(tf / FP32_MFMA_PEAK_TFLOPS, 4)}
     out = {
         "metric": METRIC, "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if spec.x_dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: W %dx%d fp32, X %dx%d %s, W%d per-channel RTN, r=%d, f=%d" %
                                (spec.name, spec.m, spec.n, spec.tokens, spec.n, spec.x_dtype, spec.bits, spec.r, spec.f),
-                   "svd_block": 2 * spec.r if 2 * spec.r <= 128 else 128, "svd_iters": 24 if spec.r > 64 else (12 if max(spec.m, spec.n) > 8192 else 9)},
+                   "svd_block": svd_block, "svd_iters": svd_iters},
         "layers_per_s": 1e3 / ms_per_step,
         "calibration_tokens_per_s": spec.tokens * 1e3 / ms_per_step,
         "stage_ms": {k: round(v, 4) for k, v in zip(stage_names, stage_ms)},
         "gram_mfma_util_pct": 100.0 * gram_tflops / BF16_PEAK_TFLOPS,
+        "stage_util": stage_util,
         "whitened_error": err,
         "roofline": {"kernel": "gram_dma_kernel (Gram update G += X^T X, 256x256 lower-triangle tiles, bf16 MFMA)",
                      "bound": "mfma", "achieved": gram_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gram_tflops / BF16_PEAK_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_C1["gram"] if spec.name == "c1" else None,
+                     "traffic": traffic.get("gram_dma_kernel") if spec.name == "c1" else None,
                      "algorithmic_flops_per_launch": gram_flops, "avg_launch_ms": gram_ms},
         "roofline_hbm": {"kernel": "rtn_kernel (per-channel RTN + target T)", "bound": "hbm", "achieved": rtn_gbs,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rtn_gbs / HBM_PEAK_GBS,
-                         "traffic": MEASURED_TRAFFIC_C1["rtn"] if spec.name == "c1" else None,
+                         "traffic": traffic.get("rtn_kernel") if spec.name == "c1" else None,
                          "algorithmic_bytes_per_launch": rtn_bytes, "avg_launch_ms": rtn_ms},
         "roofline_act_quant": {"kernel": "act_rtn_wave_kernel (per-token A8 quantizer of X M^-1)", "bound": "hbm",
                                "achieved": act_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": act_gbs / HBM_PEAK_GBS,
                                "traffic": None, "algorithmic_bytes_per_launch": act_bytes, "avg_launch_ms": act_ms},
     }
+    if not args.no_extras:
+        out["beyond_calibration"] = extras(ctx, aser, torch, spec, buf, Ws[0], X, reps)
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(spec)
