@@ -224,6 +224,22 @@ def run_block(args):
     print(json.dumps(out))
 
 
+def trace_summary(result_dir, note):
+    """Prints the per-kernel totals of a rocprofv3 --kernel-trace --stats run (kept under profiles/)."""
+    import glob
+    import sqlite3
+    dbs = sorted(glob.glob(os.path.join(result_dir, "**", "*_results.db"), recursive=True))
+    if not dbs:
+        raise SystemExit("no *_results.db under %s" % result_dir)
+    con = sqlite3.connect(dbs[-1])
+    rows = con.execute("select name, total_calls, total_duration, average, percentage from top_kernels limit 40").fetchall()
+    print(note)
+    print("\nPer-kernel totals (durations in microseconds):")
+    print("%-96s %6s %12s %10s %6s" % ("kernel", "calls", "total_us", "avg_us", "pct"))
+    for r in rows:
+        print("%-96s %6d %12.1f %10.2f %6.2f" % (r[0][:96], r[1], r[2], r[3], r[4]))
+
+
 def extras(ctx, aser, torch, spec, buf, W, X, reps):
     """Timings of the rows beyond the calibration path, on the layer the step has just calibrated: the full
     spectrum with the rank rule of Eq. 9 and the effective rank of Eq. 3-4, the W4A8 layer-output error on a
@@ -309,10 +325,14 @@ def main():
                     help="run only a 1 GiB copy, the Gram kernel and the RTN kernel (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--traffic-summary", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
                     help="print the summary of the two counter runs (no GPU needed)")
+    ap.add_argument("--trace-summary", nargs=2, metavar=("RESULT_DIR", "NOTE"),
+                    help="print the per-kernel totals of a rocprofv3 --kernel-trace --stats run (no GPU needed)")
     ap.add_argument("--no-extras", action="store_true", help="skip the timings of the rows beyond the calibration path")
     args = ap.parse_args()
     if args.traffic_summary:
         return traffic_summary(*args.traffic_summary)
+    if args.trace_summary:
+        return trace_summary(*args.trace_summary)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
               file=sys.stderr)
