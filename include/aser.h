@@ -66,9 +66,18 @@ typedef struct aser_svd_opts {
     int32_t block;      /* subspace width b (multiple of 32, r <= b <= 128); default: the
                            smallest multiple of 32 that is >= min(2 r, 128) and >= r        */
     int32_t max_iter;   /* number of subspace iterations (A A^T applications); default 9, 12 when max(m, n) > 8192,
-                           24 when block < 2 r */
+                           14 when m n <= 2^20, 30 when block < 2 r */
     uint32_t seed;      /* seed of the random start block; default 1                       */
 } aser_svd_opts;
+
+/* How fp32 operands enter the bf16 MFMA products of aser_whiten, aser_error_reconstruct and the
+ * fp32-input form of aser_gram_accumulate (bf16 activations are always multiplied exactly). */
+typedef enum aser_precision {
+    ASER_PRECISION_AUTO = 0,    /* default: EXACT for small problems (n <= 1024 for the Gram matrix and the
+                                   whitening, m n <= 2^20 for the reconstruction), FAST otherwise         */
+    ASER_PRECISION_FAST = 1,    /* x = hi + lo (bf16), three products per fp32 product, about 2^-16       */
+    ASER_PRECISION_EXACT = 2    /* x = hi + mid + lo, six products, about 2^-24; about twice the time     */
+} aser_precision;
 
 const char* aser_status_string(int status);
 
@@ -77,6 +86,9 @@ const char* aser_status_string(int status);
 int aser_create(aser_ctx** out, int device, void* hip_stream);
 int aser_destroy(aser_ctx* ctx);
 const char* aser_last_error(const aser_ctx* ctx);
+
+/* Chooses the product form for later calls on ctx (see aser_precision). */
+int aser_set_precision(aser_ctx* ctx, int precision);
 
 /* Binds `bytes` of device memory at `dev_ptr` (256-byte aligned) as scratch space; `bytes` is rounded
  * down to a multiple of 256.  The caller keeps ownership and must keep it alive while calls on ctx may

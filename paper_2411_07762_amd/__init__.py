@@ -25,11 +25,14 @@ ASER_ERR_HIP = 7
 
 ASER_DTYPE_BF16 = 0
 ASER_DTYPE_F32 = 1
+ASER_PRECISION_AUTO = 0
+ASER_PRECISION_FAST = 1
+ASER_PRECISION_EXACT = 2
 ASER_CODES_INT8 = 0
 ASER_CODES_INT4_PACKED = 1
 
 EXPORTS = (
-    "aser_status_string", "aser_create", "aser_destroy", "aser_last_error", "aser_set_workspace",
+    "aser_status_string", "aser_create", "aser_destroy", "aser_last_error", "aser_set_workspace", "aser_set_precision",
     "aser_workspace_bytes", "aser_gram_accumulate", "aser_smooth_outliers", "aser_smooth_outliers_noalloc",
     "aser_quantize_rtn",
     "aser_whiten", "aser_error_reconstruct", "aser_svd_plan", "aser_quantize_act_rtn",
@@ -72,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.aser_last_error.argtypes = [vp]
     lib.aser_set_workspace.restype = ctypes.c_int
     lib.aser_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
+    lib.aser_set_precision.restype = ctypes.c_int
+    lib.aser_set_precision.argtypes = [vp, ctypes.c_int]
     lib.aser_workspace_bytes.restype = ctypes.c_size_t
     lib.aser_workspace_bytes.argtypes = [i64, i64, i32, ctypes.POINTER(aser_svd_opts)]
     lib.aser_gram_accumulate.restype = ctypes.c_int
@@ -175,6 +180,9 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def set_precision(self, mode: int):
+        self.check(self._lib.aser_set_precision(self.handle, int(mode)))
 
     def last_error(self) -> str:
         return self._lib.aser_last_error(self.handle).decode()

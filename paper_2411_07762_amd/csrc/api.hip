@@ -27,6 +27,7 @@ extern "C" int aser_create(aser_ctx** out, int device, void* hip_stream) {
     c->ws = nullptr;
     c->ws_bytes = 0;
     c->device_ready = false;
+    c->precision = ASER_PRECISION_AUTO;
     c->pending_info_dev = nullptr;
     c->pending_sel_dev = nullptr;
     c->err[0] = 0;
@@ -37,6 +38,14 @@ extern "C" int aser_create(aser_ctx** out, int device, void* hip_stream) {
 extern "C" int aser_destroy(aser_ctx* ctx) {
     if (!ctx) return ASER_ERR_INVALID_ARG;
     delete ctx;
+    return ASER_OK;
+}
+
+extern "C" int aser_set_precision(aser_ctx* ctx, int precision) {
+    if (!ctx) return ASER_ERR_INVALID_ARG;
+    if (precision != ASER_PRECISION_AUTO && precision != ASER_PRECISION_FAST && precision != ASER_PRECISION_EXACT)
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "set_precision: unknown mode %d", precision);
+    ctx->precision = precision;
     return ASER_OK;
 }
 

@@ -14,6 +14,7 @@ struct aser_ctx {
     void* ws;
     size_t ws_bytes;
     bool device_ready;
+    int precision;       // aser_precision: how fp32 operands enter the MFMA products
     // aser_whiten without a host `info` leaves its pivot flag on the device (last 256 bytes of the
     // workspace) and does not synchronise; the next synchronising call reads it.
     int32_t* pending_info_dev;
@@ -58,7 +59,6 @@ int aser_set_i32(aser_ctx* ctx, int32_t* p, int32_t v);
     } while (0)
 
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
-static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 size_t aser_reconstruct_workspace(int64_t m, int64_t n, int r, const aser_svd_opts* o);
 
@@ -71,7 +71,21 @@ int aser_check_launch(aser_ctx* ctx, const char* what);
 //   A: K x M row-major (lda), B: K x N row-major (ldb), C: M x N row-major (ldc), all device.
 // Input types: bf16 (one exact MFMA product, fp32 accumulate) or fp32 split on the fly into
 // bf16 hi + lo (three MFMA products: hi*hi + hi*lo + lo*hi).
-enum GemmIn { GEMM_IN_BF16 = 0, GEMM_IN_F32X3 = 1 };
+// GEMM_IN_F32X6: fp32 split into three bf16 terms, the six products down to 2^-24 (fp32-exact class);
+// tiles up to 256 x 128.
+enum GemmIn { GEMM_IN_BF16 = 0, GEMM_IN_F32X3 = 1, GEMM_IN_F32X6 = 2 };
+
+// Input form of an fp32 contraction of a problem whose operands have at most `entries` entries: the
+// three-product split (2^-16 per product) or the six-product one (2^-24).  In the automatic mode small
+// problems take the exact form: it costs microseconds there, and small layers are where a residual can be
+// a few 1e-5 of the matrix norm (int8 weights, a rank near half the width), which 2^-16 does not resolve.
+static inline int aser_f32_form(const aser_ctx* ctx, int64_t entries) {
+    if (ctx->precision == ASER_PRECISION_EXACT) return GEMM_IN_F32X6;
+    if (ctx->precision == ASER_PRECISION_FAST) return GEMM_IN_F32X3;
+    return entries <= ((int64_t)1 << 20) ? GEMM_IN_F32X6 : GEMM_IN_F32X3;
+}
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
 enum GemmEpi {
     GEMM_EPI_STORE = 0,    // C = alpha * acc            (needs k_parts == 1)
     GEMM_EPI_ATOMIC = 1,   // atomicAdd(C, alpha * acc)  (any k_parts)

@@ -32,6 +32,7 @@ constexpr int kThreads = 256;
 template <int IN> struct InTraits;
 template <> struct InTraits<GEMM_IN_BF16> { static constexpr int BK = 64, NP = 1, VEC = 8; };
 template <> struct InTraits<GEMM_IN_F32X3> { static constexpr int BK = 32, NP = 2, VEC = 4; };
+template <> struct InTraits<GEMM_IN_F32X6> { static constexpr int BK = 32, NP = 3, VEC = 4; };
 
 // LDS position (in 16-byte chunks) of row `mn` inside one k-block.  The XOR pattern makes both
 // the transposing stores (8 consecutive rows per lane) and the MFMA operand reads (32
@@ -164,18 +165,24 @@ struct Fetch {
             const float* x = (const float*)st.r;          // x[4*j + c]: row j, column c
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                uint32_t hi[4], lo[4];
+                uint32_t hi[4], lo[4], lo2[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const float a = x[4 * (2 * q) + c], b = x[4 * (2 * q + 1) + c];
                     const uint32_t h = pack_bf16x2(a, b);
                     const float ah = __uint_as_float(h << 16), bh = __uint_as_float(h & 0xFFFF0000u);
                     hi[q] = h;
-                    lo[q] = pack_bf16x2(a - ah, b - bh);
+                    const float ar = a - ah, br = b - bh;           // exact: the remainder has at most 16 significant bits
+                    lo[q] = pack_bf16x2(ar, br);
+                    if (IN == GEMM_IN_F32X6) {
+                        const float am = __uint_as_float(lo[q] << 16), bm = __uint_as_float(lo[q] & 0xFFFF0000u);
+                        lo2[q] = pack_bf16x2(ar - am, br - bm);     // third term: x = hi + mid + lo to 24 bits
+                    }
                 }
                 const int pos = kb * BMN + swz(cg * 4 + c);
                 lds[pos] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
                 lds[KB * BMN + pos] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                if (IN == GEMM_IN_F32X6) lds[2 * KB * BMN + pos] = make_uint4(lo2[0], lo2[1], lo2[2], lo2[3]);
             }
         }
     }
@@ -216,7 +223,7 @@ __device__ __forceinline__ void mfma_step(f32x16_t (&acc)[BM / 64][BN / 64], con
     using Cfg = TileCfg<IN, BM, BN>;
     constexpr int NP = Cfg::NP, KB = Cfg::KB, TM = Cfg::TM, TN = Cfg::TN, KK = Cfg::BK / 16;
     constexpr int R = NP * (TM + TN);                   // LDS reads per k-slice
-    constexpr int MF = TM * TN * (NP == 2 ? 3 : 1);     // MFMAs per k-slice
+    constexpr int MF = TM * TN * (NP == 3 ? 6 : (NP == 2 ? 3 : 1));     // MFMAs per k-slice
     bf16x8_t a[2][NP][TM], b[2][NP][TN];
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
@@ -244,7 +251,13 @@ __device__ __forceinline__ void mfma_step(f32x16_t (&acc)[BM / 64][BN / 64], con
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                if (NP == 2) {
+                if (NP == 3) {
+                    // x = hi + mid + lo: all products down to 2^-24 of hi * hi, smallest first
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][NP - 1][i], b[cur][0][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][NP - 1][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][1][i], b[cur][1][j], acc[i][j], 0, 0, 0);
+                }
+                if (NP >= 2) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][1][i], b[cur][0][j], acc[i][j], 0, 0, 0);
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][0][i], b[cur][1][j], acc[i][j], 0, 0, 0);
                 }
@@ -552,7 +565,13 @@ int launch_pair(aser_ctx* ctx, const GemmArgs& g) {
 template <int IN, bool FAST>
 int dispatch_tile2(aser_ctx* ctx, const GemmArgs& g) {
     if (g.pair_cols) return launch_pair<IN, FAST>(ctx, g);
-    if (g.bm == 256 && g.bn == 256) return launch_plain<IN, 256, 256, FAST>(ctx, g);
+    if (g.bm == 256 && g.bn == 256) {
+        if constexpr (IN == GEMM_IN_F32X6) {
+            ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: the six-product form has no 256 x 256 tile (LDS)");
+        } else {
+            return launch_plain<IN, 256, 256, FAST>(ctx, g);
+        }
+    }
     if (g.bm == 128 && g.bn == 256) return launch_plain<IN, 128, 256, FAST>(ctx, g);
     if (g.bm == 256 && g.bn == 128) return launch_plain<IN, 256, 128, FAST>(ctx, g);
     if (g.bm == 128 && g.bn == 128) return launch_plain<IN, 128, 128, FAST>(ctx, g);
@@ -903,6 +922,7 @@ int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g) {
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_tn: the residual epilogue needs sumsq, k_parts == 1 and 128 x 128 tiles");
     if (g.in_type == GEMM_IN_BF16) return dispatch_tile<GEMM_IN_BF16>(ctx, g);
     if (g.in_type == GEMM_IN_F32X3) return dispatch_tile<GEMM_IN_F32X3>(ctx, g);
+    if (g.in_type == GEMM_IN_F32X6) return dispatch_tile<GEMM_IN_F32X6>(ctx, g);
     ASER_FAIL(ctx, ASER_ERR_DTYPE, "gemm_tn: unknown input type");
 }
 
@@ -914,13 +934,14 @@ int aser_syrk_gram(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int6
     g.A = X; g.lda = ldx; g.B = X; g.ldb = ldx;
     g.C = G; g.ldc = ldg; g.Ct = nullptr; g.ldct = 0;
     g.M = n; g.N = n; g.K = rows; g.alpha = 1.f;
-    g.in_type = (x_dtype == ASER_DTYPE_BF16) ? GEMM_IN_BF16 : GEMM_IN_F32X3;
+    g.in_type = (x_dtype == ASER_DTYPE_BF16) ? GEMM_IN_BF16 : aser_f32_form(ctx, n * n);
     g.epi = GEMM_EPI_ATOMIC; g.tiles = GEMM_TILES_LOWER; g.krange = GEMM_K_FULL;
+    const bool six = g.in_type == GEMM_IN_F32X6;         // no 256 x 256 tile: the plain grid with 128 x 128 tiles
     const int bk = (g.in_type == GEMM_IN_BF16) ? 64 : 32;
     const int64_t ksteps = ceil_div64(rows, bk);
     const int64_t t256 = ceil_div64(n, 256);
     const int64_t T256 = t256 * (t256 + 1) / 2;
-    if (T256 >= 32 && ksteps >= 8 * 16) {
+    if (T256 >= 32 && ksteps >= 8 * 16 && !six) {
         // Number of K chunks: fewest steps on the busiest workgroup, each tile visit charged with
         // the cost of flushing a tile through atomics (about a dozen K steps).
         int best_c = 8;
@@ -937,7 +958,7 @@ int aser_syrk_gram(aser_ctx* ctx, const void* X, int x_dtype, int64_t rows, int6
         return (g.in_type == GEMM_IN_BF16) ? launch_gram_persistent<GEMM_IN_BF16>(ctx, g)
                                            : launch_gram_persistent<GEMM_IN_F32X3>(ctx, g);
     }
-    g.bm = g.bn = (n <= 1024) ? 128 : 256;
+    g.bm = g.bn = (n <= 1024 || six) ? 128 : 256;
     const int64_t t = ceil_div64(n, g.bm), tiles = t * (t + 1) / 2;
     int64_t parts = ceil_div64(1024, tiles);              // aim at >= 4 workgroups per CU
     const int64_t max_parts = ksteps / 16 > 0 ? ksteps / 16 : 1;   // keep >= 16 steps per part

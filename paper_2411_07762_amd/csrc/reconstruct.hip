@@ -86,9 +86,12 @@ int default_block(int r) {
 int make_plan(int64_t m, int64_t n, int r, const aser_svd_opts* o, Plan* p) {
     p->b = (o && o->block > 0) ? o->block : default_block(r);
     // default: 9 iterations, 12 for wide layers (the bulk of the spectrum gets denser with the size),
-    // 24 when the block has fewer than r oversampling columns (r > 64: the wanted directions at the
+    // 30 when the block has fewer than r oversampling columns (r > 64: the wanted directions at the
     // edge of the bulk then converge at the rate of the gap to the next singular value alone)
-    p->iters = (o && o->max_iter > 0) ? o->max_iter : (p->b < 2 * r ? 24 : (((m > n ? m : n) > 8192) ? 12 : 9));
+    // small layers (the ones that also take the six-product form): 14, their spectra were the slowest of a
+    // randomized sweep and an iteration costs them microseconds
+    p->iters = (o && o->max_iter > 0) ? o->max_iter
+             : (p->b < 2 * r ? 30 : (((m > n ? m : n) > 8192) ? 12 : (m * n <= ((int64_t)1 << 20) ? 14 : 9)));
     p->seed = (o && o->seed) ? o->seed : 1u;
     const int64_t mx = m > n ? m : n;
     size_t off = 0;
@@ -114,13 +117,13 @@ size_t aser_reconstruct_workspace(int64_t m, int64_t n, int r, const aser_svd_op
 namespace {
 
 // C += A^T B with K split over workgroups (fp32 atomics); `clear` zeroes C first.
-int gemm_tn_atomic(aser_ctx* ctx, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+int gemm_tn_atomic(aser_ctx* ctx, int form, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
                    int64_t M, int64_t N, int64_t K, int bm, int bn, bool clear, bool upper_only = false) {
     if (clear) ASER_TRY(aser_fill_f32(ctx, C, M, N, ldc, 0.f));
     GemmArgs g{};
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.Ct = nullptr; g.ldct = 0;
     g.M = M; g.N = N; g.K = K; g.alpha = 1.f;
-    g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_ATOMIC; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
+    g.in_type = form; g.epi = GEMM_EPI_ATOMIC; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
     g.bm = bm; g.bn = bn; g.upper_only = upper_only ? 1 : 0;
     // Split K by the cost model of aser_split_k_parts.  Every part pays a pipeline fill and an atomic
     // flush of its whole tile, so parts keep at least 8 K steps (4 when the output is tiny and the
@@ -139,9 +142,9 @@ constexpr int32_t kPivotBase = -1000;
 // entry and is zero again on return.  The first clear_rows rows of Y are cleared after they have
 // been read (0: Y is left alone).  Lmul / Cmul / with_beta: the factorisation kernel also leaves
 // Cmul = alpha Lmul R^-1 (see aser_chol_block); both null: nothing.
-int chol_qr(aser_ctx* ctx, float* Y, float* out, int64_t rows, int64_t clear_rows, int b, float* Mb, float* Rinv,
+int chol_qr(aser_ctx* ctx, int form, float* Y, float* out, int64_t rows, int64_t clear_rows, int b, float* Mb, float* Rinv,
             int32_t* info, const float* Lmul = nullptr, float* Cmul = nullptr, bool with_beta = false) {
-    ASER_TRY(gemm_tn_atomic(ctx, Y, b, Y, b, Mb, b, b, b, rows, 128, 128, false, /*upper_only=*/true));
+    ASER_TRY(gemm_tn_atomic(ctx, form, Y, b, Y, b, Mb, b, b, b, rows, 128, 128, false, /*upper_only=*/true));
     ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rinv, info, kPivotBase, /*clear_d=*/true, Lmul, Cmul, with_beta));
     return aser_gemm_small_f32(ctx, Y, b, Rinv, b, out, b, rows, b, b, clear_rows);
 }
@@ -199,6 +202,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
 
     char* ws = (char*)ctx->ws;
     const int b = p.b;
+    const int form = aser_f32_form(ctx, m * n);          // three or six bf16 products per fp32 product
     float* big0 = (float*)(ws + p.off_big0);     // T^T (n x m)
     float* A = (float*)(ws + p.off_big1);        // m x n
     float* At = (float*)(ws + p.off_big2);       // A^T (n x m), written by the same product as A
@@ -229,7 +233,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         GemmArgs g{};
         g.A = big0; g.lda = m; g.B = S; g.ldb = lds; g.C = A; g.ldc = n; g.Ct = At; g.ldct = m;
         g.M = m; g.N = n; g.K = n; g.alpha = 1.f;
-        g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_STORE; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_GE_COL;
+        g.in_type = form; g.epi = GEMM_EPI_STORE; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_GE_COL;
         g.k_parts = 1;
         // S is lower triangular, so the K range of a tile shrinks with its column: pairing column j with
         // column tn - 1 - j gives every workgroup the same work
@@ -260,27 +264,27 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
             ASER_TRY(aser_check_launch(ctx, "lead_columns"));
         }
     }
-    ASER_TRY(chol_qr(ctx, Qacc, Qcur, m, 0, b, Mb, Rq_inv, info));                 // Q_0
+    ASER_TRY(chol_qr(ctx, form, Qacc, Qcur, m, 0, b, Mb, Rq_inv, info));                 // Q_0
     const int bmA = 128, bnB = 128;
     for (int it = 0; it < p.iters; ++it) {
-        ASER_TRY(gemm_tn_atomic(ctx, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // Zt = A^T Q_k = Z R_z
+        ASER_TRY(gemm_tn_atomic(ctx, form, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // Zt = A^T Q_k = Z R_z
         // R_z^-1 (Z itself is never formed); from the second iteration on also Bm = -beta P_k R_z^-1
-        ASER_TRY(gemm_tn_atomic(ctx, Zt, b, Zt, b, Mb, b, b, b, n, 128, 128, false, /*upper_only=*/true));
+        ASER_TRY(gemm_tn_atomic(ctx, form, Zt, b, Zt, b, Mb, b, b, b, n, 128, 128, false, /*upper_only=*/true));
         ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rz_inv, info, kPivotBase, /*clear_d=*/true, it ? Pm : nullptr, it ? Bm : nullptr, true));
-        ASER_TRY(gemm_tn_atomic(ctx, At, m, Zt, b, Qraw, b, m, b, n, bmA, bnB, false));   // A Zt
+        ASER_TRY(gemm_tn_atomic(ctx, form, At, m, Zt, b, Qraw, b, m, b, n, bmA, bnB, false));   // A Zt
         // A Z + momentum term = (A Zt) R_z^-1 + Q_{k-1} Bm; Qraw and Zt are zero again afterwards
         ASER_TRY(aser_combine_f32(ctx, Qraw, Rz_inv, it ? Qold : nullptr, Bm, Qacc, m, b, Zt, n));
         // = Q_{k+1} R_q, into the old block; also P_{k+1} = R_z^-1 R_q^-1
-        ASER_TRY(chol_qr(ctx, Qacc, Qold, m, 0, b, Mb, Rq_inv, info, Rz_inv, Pm, false));
+        ASER_TRY(chol_qr(ctx, form, Qacc, Qold, m, 0, b, Mb, Rq_inv, info, Rz_inv, Pm, false));
         { float* t = Qold; Qold = Qcur; Qcur = t; }
     }
-    ASER_TRY(chol_qr(ctx, Qcur, Qacc, m, 0, b, Mb, Rq_inv, info));                 // second pass: orthonormal to fp32
+    ASER_TRY(chol_qr(ctx, form, Qcur, Qacc, m, 0, b, Mb, Rq_inv, info));                 // second pass: orthonormal to fp32
     float* Qp = Qacc;
     // Rayleigh-Ritz: Z = A^T Q, eigen-pairs of Z^T Z = Q^T A A^T Q
-    ASER_TRY(gemm_tn_atomic(ctx, A, n, Qp, b, Zt, b, n, b, m, bmA, bnB, false));
+    ASER_TRY(gemm_tn_atomic(ctx, form, A, n, Qp, b, Zt, b, n, b, m, bmA, bnB, false));
     float* Zp = Zt;
     float* tp = Qraw;
-    ASER_TRY(gemm_tn_atomic(ctx, Zp, b, Zp, b, Mb, b, b, b, n, 128, 128, false));
+    ASER_TRY(gemm_tn_atomic(ctx, form, Zp, b, Zp, b, Mb, b, b, b, n, 128, 128, false));
     ASER_TRY(aser_tridiag_eig(ctx, Mb, b, lambda, Uhat, refl, tri, cluster));
     ASER_TRY(aser_jacobi_eig(ctx, Mb, b, lambda, Uhat, cluster));      // only runs if eigenvalues cluster
     hipLaunchKernelGGL(ritz_factors_kernel, dim3(16), dim3(256), 0, ctx->stream, (const float*)lambda, (const float*)Uhat, b,
@@ -296,7 +300,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         GemmArgs g{};
         g.A = tp; g.lda = m; g.B = L_B; g.ldb = n; g.C = A; g.ldc = n; g.Ct = nullptr; g.ldct = 0;
         g.M = m; g.N = n; g.K = r; g.alpha = -1.f; g.sumsq = normA2;
-        g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_RESID; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
+        g.in_type = form; g.epi = GEMM_EPI_RESID; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
         g.k_parts = 1;
         g.bm = 128; g.bn = 128;                           // short K: many small workgroups hide the latency of reading A
         ASER_TRY(aser_gemm_tn(ctx, g));
@@ -304,7 +308,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     // L_A = Q (Uhat_r Sigma_r)
     ASER_TRY(aser_gemm_small_f32(ctx, Qp, b, WA, r, L_A, r, m, b, r));
     // L_B^T = (T^T Q) (Uhat_r Sigma_r^-1)  ->  L_B
-    ASER_TRY(gemm_tn_atomic(ctx, T, ldt, Qp, b, Zp, b, n, b, m, bmA, bnB, true));  // C^T = T^T Q (n x b)
+    ASER_TRY(gemm_tn_atomic(ctx, form, T, ldt, Qp, b, Zp, b, n, b, m, bmA, bnB, true));  // C^T = T^T Q (n x b)
     ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, WBt, r, L_B, n, n, b, r, 0, true));   // (n x r)^T = L_B
 
     double h_res2 = 0.0;

@@ -348,7 +348,7 @@ extern "C" int aser_singular_values(aser_ctx* ctx, const float* T, int64_t m, in
         GemmArgs g{};
         g.A = Tt; g.lda = m; g.B = S; g.ldb = lds; g.C = A; g.ldc = n; g.Ct = At; g.ldct = m;
         g.M = m; g.N = n; g.K = n; g.alpha = 1.f;
-        g.in_type = GEMM_IN_F32X3; g.epi = GEMM_EPI_STORE; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_GE_COL;
+        g.in_type = aser_f32_form(ctx, m * n); g.epi = GEMM_EPI_STORE; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_GE_COL;
         g.k_parts = 1;
         g.pair_cols = (m > 1024 && n > 1024) ? 1 : 0;
         g.bm = g.pair_cols ? 256 : 128; g.bn = 128;

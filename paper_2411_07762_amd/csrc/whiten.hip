@@ -132,12 +132,15 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
     // fp32 operand element once per 256 instead of 128 result columns or rows); the second block row of
     // a pair then still lacks the contribution of the first, a K = 128 update of its own.
     const bool pairs = n >= 12288;   // measured: 11008 columns are still faster one block row at a time
+    const int form = aser_f32_form(ctx, n * n);   // three or six bf16 products per fp32 product
+    const bool six = form == GEMM_IN_F32X6;
     auto update = [&](int64_t row0, int64_t rows, int64_t kfrom, int64_t klen, int bm, int bn) -> int {
         GemmArgs u{};
         u.A = S + kfrom * lds + row0; u.lda = lds; u.B = S + kfrom * lds + row0; u.ldb = lds;
         u.C = S + row0 * lds + row0; u.ldc = lds; u.Ct = nullptr; u.ldct = 0;
         u.M = rows; u.N = n - row0; u.K = klen; u.alpha = -1.f;
-        u.in_type = GEMM_IN_F32X3; u.epi = GEMM_EPI_ATOMIC; u.tiles = GEMM_TILES_ALL; u.krange = GEMM_K_FULL;
+        u.in_type = form; u.epi = GEMM_EPI_ATOMIC; u.tiles = GEMM_TILES_ALL; u.krange = GEMM_K_FULL;
+        if (six && bm == 256 && bn == 256) bn = 128;    // the six-product form has no 256 x 256 tile
         u.bm = bm; u.bn = bn; u.upper_only = 1;
         const int64_t tiles = ceil_div64(u.M, u.bm) * ceil_div64(u.N, u.bn), ksteps = ceil_div64(klen, 32);
         u.k_parts = aser_split_k_parts(tiles, ksteps, 4, (double)(bm * bn) / (128.0 * 128.0));
@@ -163,7 +166,7 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
         p.A = Rinv; p.lda = b; p.B = S12; p.ldb = lds; p.C = S12; p.ldc = lds;
         p.Ct = nullptr; p.ldct = 0;
         p.M = b; p.N = rem; p.K = b; p.alpha = 1.f;
-        p.in_type = GEMM_IN_F32X3; p.epi = GEMM_EPI_STORE; p.tiles = GEMM_TILES_ALL; p.krange = GEMM_K_FULL;
+        p.in_type = form; p.epi = GEMM_EPI_STORE; p.tiles = GEMM_TILES_ALL; p.krange = GEMM_K_FULL;
         p.k_parts = 1; p.bm = 128; p.bn = 128;           // K = 128 only: twice the workgroups beat the wider tile (16.6 -> 12 us at c1)
         ASER_TRY(aser_gemm_tn(ctx, p));
     }

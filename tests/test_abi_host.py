@@ -65,6 +65,14 @@ def test_workspace_rules(ctx):
     assert "workspace" in ctx._lib.aser_last_error(ctx.handle).decode()
 
 
+def test_precision_modes(ctx):
+    lib = ctx._lib
+    for mode in (aser.ASER_PRECISION_FAST, aser.ASER_PRECISION_EXACT, aser.ASER_PRECISION_AUTO):
+        assert lib.aser_set_precision(ctx.handle, mode) == aser.ASER_OK
+    assert lib.aser_set_precision(ctx.handle, 7) == aser.ASER_ERR_INVALID_ARG
+    assert lib.aser_set_precision(None, 0) == aser.ASER_ERR_INVALID_ARG
+
+
 def test_gram_validation(ctx):
     g = aser.aser_gram_accumulate
     assert g(ctx, None, P, rows=8, n=8, ldx=8, ldg=8, x_dtype=0) == aser.ASER_ERR_INVALID_ARG
@@ -121,9 +129,9 @@ def test_whiten_and_reconstruct_validation(ctx):
 def test_svd_plan_reports_what_the_iteration_will_use():
     assert aser.aser_svd_plan(4096, 4096, 64) == (aser.ASER_OK, 128, 9)
     assert aser.aser_svd_plan(4096, 11008, 64) == (aser.ASER_OK, 128, 12)
-    assert aser.aser_svd_plan(8192, 28672, 128) == (aser.ASER_OK, 128, 24)       # no oversampling columns
-    assert aser.aser_svd_plan(256, 256, 16) == (aser.ASER_OK, 32, 9)
-    assert aser.aser_svd_plan(322, 74, 23) == (aser.ASER_OK, 64, 9)              # 2 r = 46 -> 64 fits in n = 74
+    assert aser.aser_svd_plan(8192, 28672, 128) == (aser.ASER_OK, 128, 30)       # no oversampling columns
+    assert aser.aser_svd_plan(256, 256, 16) == (aser.ASER_OK, 32, 14)
+    assert aser.aser_svd_plan(322, 74, 23) == (aser.ASER_OK, 64, 14)              # 2 r = 46 -> 64 fits in n = 74
     assert aser.aser_svd_plan(300, 40, 23)[:2] == (aser.ASER_OK, 32)             # shrunk to fit the matrix
     assert aser.aser_svd_plan(695, 44, 40)[0] == aser.ASER_ERR_SHAPE
     o = aser.aser_svd_opts(block=96, max_iter=5, seed=0)
