@@ -66,7 +66,7 @@ typedef struct aser_svd_opts {
     int32_t block;      /* subspace width b (multiple of 32, r <= b <= 128); default: the
                            smallest multiple of 32 that is >= min(2 r, 128) and >= r        */
     int32_t max_iter;   /* number of subspace iterations (A A^T applications); default 9, 12 when max(m, n) > 8192,
-                           14 when m n <= 2^20, 30 when block < 2 r */
+                           30 when block < 2 r */
     uint32_t seed;      /* seed of the random start block; default 1                       */
 } aser_svd_opts;
 
@@ -168,7 +168,8 @@ int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n, const flo
                 float* S, int64_t lds, int32_t* info);
 
 /* Stage 4b/4c (Eq. 6; Sec. 4.1 L_A = U_r Sigma_r, L_B = V_r^T S^-1; Alg. 1 last lines).
- * Rank-r truncated SVD of A = T S by blocked subspace iteration and Rayleigh-Ritz.
+ * Rank-r truncated SVD of A = T S: blocked subspace iteration with Rayleigh-Ritz, or, for small layers,
+ * a dense solver (see "Solver" below).
  *     L_A   = U_r Sigma_r                  (m x r, ld = r)
  *     L_B   = V_r^T S^-1                   (r x n, ld = n), evaluated as Sigma_r^-1 U_r^T T,
  *             which is the same matrix because V_r^T = Sigma_r^-1 U_r^T T S
@@ -177,8 +178,9 @@ int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n, const flo
  *             whitened layer-output error ||(T - L_A L_B) S||_F of Eq. 8
  *     *n_iter (host, may be NULL) = subspace iterations performed
  * T: m x n fp32 (ldt); S: n x n fp32 lower triangular with zeros above the diagonal (lds).
- * 0 < r <= min(m, n, 128), and a multiple of 32 must lie in [r, min(m, n, 128)] (the subspace
- * width; e.g. r = 40 needs min(m, n) >= 64), else ASER_ERR_SHAPE.  Synchronises the stream.
+ * 0 < r <= min(m, n, 128); for the subspace iteration a multiple of 32 must also lie in
+ * [r, min(m, n, 128)] (the subspace width; e.g. r = 40 needs min(m, n) >= 64), else ASER_ERR_SHAPE.
+ * Synchronises the stream.
  * idx, f: the outlier set I_f of aser_smooth_outliers (f device int32 entries; f == 0: none, idx may be
  * NULL).  Those columns of T hold the unquantized W_o of Eq. 12 and dwarf the quantization error in the
  * other columns, so they become the first columns of the start block, ahead of the random ones: the
@@ -186,11 +188,17 @@ int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n, const flo
  * smallest wanted singular directions.  The result does not depend on them otherwise; entries outside
  * [0, n) are ignored.  A caller that has outlier columns in T and passes f = 0 gets
  * ASER_ERR_NO_CONVERGE once sigma_1 / sigma_b passes a few hundred.
- * Convergence: a fixed number of iterations (aser_svd_plan reports it), no residual test.  The excess of
- * the whitened error over the optimum shrinks by about 0.47 per iteration on quantization-error spectra
- * (measured 2e-5 relative after the default count on every workload shape named in the bench).  The
- * products carry about 2^-16 relative error, so a whitened error below about 1e-3 of ||T S||_F (W8
- * layers of a few hundred channels with r near n / 2) is resolved to fewer than four digits.
+ * Solver.  Layers with m n <= 2^20 (default options, precision mode not FAST) take a dense fp64 solver:
+ * every eigenvalue of the Gram matrix of the shorter side of T S (Householder tridiagonalisation,
+ * bisection), the eigenvectors of the r largest (inverse iteration), *err from the tail of the spectrum;
+ * idx, f and the block-width rule do not apply, *n_iter is 0.  Larger layers, and any call with
+ * opts->max_iter or opts->block set, run the subspace iteration for a fixed number of iterations
+ * (aser_svd_plan reports it) without a residual test: the excess of the whitened error over the optimum
+ * shrinks by about 0.47 per iteration on quantization-error spectra (measured 2e-5 relative after the
+ * default count on every workload shape named in the bench, 1e-6 on int8 layers of 2048 channels).
+ * Its products carry about 2^-16 relative error (2^-24 in the EXACT mode), so a whitened error below
+ * about 1e-3 of ||T S||_F is resolved to fewer than four digits there; such residuals were only met on
+ * layers of a few hundred channels, which the dense solver takes.
  * ASER_ERR_NO_CONVERGE: a pivot of a block Gram matrix was not positive.
  * Reports (as ASER_ERR_NOT_SPD / ASER_ERR_INVALID_ARG) what an asynchronous aser_whiten or an
  * aser_smooth_outliers on this context has left pending.  Needs workspace. */

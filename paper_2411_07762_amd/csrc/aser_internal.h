@@ -62,6 +62,15 @@ static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b;
 
 size_t aser_reconstruct_workspace(int64_t m, int64_t n, int r, const aser_svd_opts* o);
 
+// Dense fp64 solver of the truncated SVD for small layers (spectrum.hip); see aser_error_reconstruct.
+size_t aser_exact_workspace(int64_t m, int64_t n, int r);
+int aser_exact_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt, const float* S, int64_t lds,
+                           int r, float* L_A, float* L_B, float* sigma, double* err2_dev);
+// True when aser_error_reconstruct takes the dense solver: a small layer, default options, not the fast mode.
+static inline bool aser_use_exact_solver(int precision, int64_t m, int64_t n, const aser_svd_opts* o) {
+    return precision != ASER_PRECISION_FAST && m * n <= ((int64_t)1 << 20) && !(o && (o->max_iter > 0 || o->block > 0));
+}
+
 // Makes ctx's device current (first compute call) and checks a launch.
 int aser_prepare_device(aser_ctx* ctx);
 int aser_check_launch(aser_ctx* ctx, const char* what);

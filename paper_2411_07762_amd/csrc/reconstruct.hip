@@ -88,10 +88,8 @@ int make_plan(int64_t m, int64_t n, int r, const aser_svd_opts* o, Plan* p) {
     // default: 9 iterations, 12 for wide layers (the bulk of the spectrum gets denser with the size),
     // 30 when the block has fewer than r oversampling columns (r > 64: the wanted directions at the
     // edge of the bulk then converge at the rate of the gap to the next singular value alone)
-    // small layers (the ones that also take the six-product form): 14, their spectra were the slowest of a
-    // randomized sweep and an iteration costs them microseconds
     p->iters = (o && o->max_iter > 0) ? o->max_iter
-             : (p->b < 2 * r ? 30 : (((m > n ? m : n) > 8192) ? 12 : (m * n <= ((int64_t)1 << 20) ? 14 : 9)));
+             : (p->b < 2 * r ? 30 : (((m > n ? m : n) > 8192) ? 12 : 9));
     p->seed = (o && o->seed) ? o->seed : 1u;
     const int64_t mx = m > n ? m : n;
     size_t off = 0;
@@ -111,7 +109,12 @@ int make_plan(int64_t m, int64_t n, int r, const aser_svd_opts* o, Plan* p) {
 size_t aser_reconstruct_workspace(int64_t m, int64_t n, int r, const aser_svd_opts* o) {
     Plan p;
     make_plan(m, n, r, o, &p);
-    return p.total;
+    size_t need = p.total;
+    if (m * n <= ((int64_t)1 << 20)) {                     // small layers may take the dense solver
+        const size_t ex = aser_exact_workspace(m, n, r) + 256;
+        if (ex > need) need = ex;
+    }
+    return need;
 }
 
 namespace {
@@ -189,18 +192,44 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     if (m <= 0 || n <= 0 || ldt < n || lds < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: bad shape");
     if (f < 0 || f > n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: f must be in [0, n]");
     if (f > 0 && !idx) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "error_reconstruct: idx is null with f > 0");
+    const bool exact = aser_use_exact_solver(ctx->precision, m, n, opts);
     Plan p;
-    {
+    if (exact) {                                         // the dense solver has no subspace block: any r up to min(m, n, 128)
+        if (r <= 0 || r > m || r > n || r > 128) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: need 0 < r <= min(m, n, 128)");
+        make_plan(m, n, r, opts, &p);
+    } else {
         const char* why = "";
         const int st = legal_plan(m, n, r, opts, &p, &why);
         if (st != ASER_OK) ASER_FAIL(ctx, st, "error_reconstruct: %s", why);
     }
     if (((uintptr_t)T & 3) || ((uintptr_t)S & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "error_reconstruct: misaligned pointer");
-    if (!ctx->ws || ctx->ws_bytes < p.total + kAserWsTail)
+    if (!ctx->ws || (!exact && ctx->ws_bytes < p.total + kAserWsTail))
         ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "error_reconstruct: workspace too small (%zu needed)", p.total + kAserWsTail);
     ASER_TRY(aser_prepare_device(ctx));
 
     char* ws = (char*)ctx->ws;
+    if (exact) {
+        // Small layers: the dense fp64 solver (every eigenvalue of the Gram matrix of T S, eigenvectors of the
+        // r largest).  Small layers are where a residual can be a few 1e-4 of ||T S||_F (int8 weights, a rank
+        // near half the width): fp32 iterations resolve that to two digits at best, and what they return then
+        // depends on the iteration count.  The work is microseconds to a few milliseconds at these sizes.
+        const size_t ex = aser_exact_workspace(m, n, r);
+        if (ctx->ws_bytes < ex + 256 + kAserWsTail)
+            ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "error_reconstruct: workspace too small (%zu needed)", ex + 256 + kAserWsTail);
+        double* err2_dev = (double*)(ws + ex);
+        ASER_TRY(aser_exact_reconstruct(ctx, T, m, n, ldt, S, lds, r, L_A, L_B, sigma, err2_dev));
+        double h_err2 = 0.0;
+        AserPending pend;
+        ASER_HIP(ctx, hipMemcpyAsync(&h_err2, err2_dev, 8, hipMemcpyDeviceToHost, ctx->stream));
+        ASER_TRY(aser_fetch_pending(ctx, &pend));
+        ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        ASER_TRY(aser_report_pending(ctx, pend, "error_reconstruct"));
+        if (!(h_err2 >= 0.0) || h_err2 > 1e300)
+            ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE, "error_reconstruct: non-finite values in T or S");
+        if (err) *err = sqrt(h_err2);
+        if (n_iter) *n_iter = 0;
+        return ASER_OK;
+    }
     const int b = p.b;
     const int form = aser_f32_form(ctx, m * n);          // three or six bf16 products per fp32 product
     float* big0 = (float*)(ws + p.off_big0);     // T^T (n x m)
@@ -266,65 +295,80 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     }
     ASER_TRY(chol_qr(ctx, form, Qacc, Qcur, m, 0, b, Mb, Rq_inv, info));                 // Q_0
     const int bmA = 128, bnB = 128;
-    for (int it = 0; it < p.iters; ++it) {
-        ASER_TRY(gemm_tn_atomic(ctx, form, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // Zt = A^T Q_k = Z R_z
-        // R_z^-1 (Z itself is never formed); from the second iteration on also Bm = -beta P_k R_z^-1
-        ASER_TRY(gemm_tn_atomic(ctx, form, Zt, b, Zt, b, Mb, b, b, b, n, 128, 128, false, /*upper_only=*/true));
-        ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rz_inv, info, kPivotBase, /*clear_d=*/true, it ? Pm : nullptr, it ? Bm : nullptr, true));
-        ASER_TRY(gemm_tn_atomic(ctx, form, At, m, Zt, b, Qraw, b, m, b, n, bmA, bnB, false));   // A Zt
-        // A Z + momentum term = (A Zt) R_z^-1 + Q_{k-1} Bm; Qraw and Zt are zero again afterwards
-        ASER_TRY(aser_combine_f32(ctx, Qraw, Rz_inv, it ? Qold : nullptr, Bm, Qacc, m, b, Zt, n));
-        // = Q_{k+1} R_q, into the old block; also P_{k+1} = R_z^-1 R_q^-1
-        ASER_TRY(chol_qr(ctx, form, Qacc, Qold, m, 0, b, Mb, Rq_inv, info, Rz_inv, Pm, false));
-        { float* t = Qold; Qold = Qcur; Qcur = t; }
-    }
-    ASER_TRY(chol_qr(ctx, form, Qcur, Qacc, m, 0, b, Mb, Rq_inv, info));                 // second pass: orthonormal to fp32
-    float* Qp = Qacc;
-    // Rayleigh-Ritz: Z = A^T Q, eigen-pairs of Z^T Z = Q^T A A^T Q
-    ASER_TRY(gemm_tn_atomic(ctx, form, A, n, Qp, b, Zt, b, n, b, m, bmA, bnB, false));
-    float* Zp = Zt;
-    float* tp = Qraw;
-    ASER_TRY(gemm_tn_atomic(ctx, form, Zp, b, Zp, b, Mb, b, b, b, n, 128, 128, false));
-    ASER_TRY(aser_tridiag_eig(ctx, Mb, b, lambda, Uhat, refl, tri, cluster));
-    ASER_TRY(aser_jacobi_eig(ctx, Mb, b, lambda, Uhat, cluster));      // only runs if eigenvalues cluster
-    hipLaunchKernelGGL(ritz_factors_kernel, dim3(16), dim3(256), 0, ctx->stream, (const float*)lambda, (const float*)Uhat, b,
-                       (int)r, sigma, WA, WBt);
-    ASER_TRY(aser_check_launch(ctx, "ritz_factors"));
-    // Whitened error of Eq. 8 as an explicit residual: ||A - U_r (U_r^T A)||_F, formed tile by tile in
-    // the product's epilogue (A is read once and nothing is written).
-    // U_r^T A = (Z Uhat_r)^T with Z = A^T Q; the subtraction form avoids the cancellation of
-    // ||A||^2 - sum sigma_i^2 when the top singular values carry almost all of the norm.
-    ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, Uhat, b, L_B, n, n, b, r, 0, true));  // (V_r Sigma_r)^T (r x n), parked in L_B
-    ASER_TRY(aser_gemm_small_f32(ctx, Qp, b, Uhat, b, tp, m, m, b, r, 0, true));   // U_r^T (r x m)
+    int done = 0;                                        // subspace iterations so far
+    auto iterate = [&](int count) -> int {
+        for (int c = 0; c < count; ++c, ++done) {
+            const bool it = done > 0;                    // momentum term present from the second iteration on
+            ASER_TRY(gemm_tn_atomic(ctx, form, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // Zt = A^T Q_k = Z R_z
+            // R_z^-1 (Z itself is never formed); from the second iteration on also Bm = -beta P_k R_z^-1
+            ASER_TRY(gemm_tn_atomic(ctx, form, Zt, b, Zt, b, Mb, b, b, b, n, 128, 128, false, /*upper_only=*/true));
+            ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rz_inv, info, kPivotBase, /*clear_d=*/true, it ? Pm : nullptr, it ? Bm : nullptr, true));
+            ASER_TRY(gemm_tn_atomic(ctx, form, At, m, Zt, b, Qraw, b, m, b, n, bmA, bnB, false));   // A Zt
+            // A Z + momentum term = (A Zt) R_z^-1 + Q_{k-1} Bm; Qraw and Zt are zero again afterwards
+            ASER_TRY(aser_combine_f32(ctx, Qraw, Rz_inv, it ? Qold : nullptr, Bm, Qacc, m, b, Zt, n));
+            // = Q_{k+1} R_q, into the old block; also P_{k+1} = R_z^-1 R_q^-1
+            ASER_TRY(chol_qr(ctx, form, Qacc, Qold, m, 0, b, Mb, Rq_inv, info, Rz_inv, Pm, false));
+            { float* t = Qold; Qold = Qcur; Qcur = t; }
+        }
+        return ASER_OK;
+    };
+    // Rayleigh-Ritz on the current block, the factors, and the residual; leaves Zt, Qraw and Mb in use
+    auto finish = [&]() -> int {
+        ASER_TRY(chol_qr(ctx, form, Qcur, Qacc, m, 0, b, Mb, Rq_inv, info));                 // second pass: orthonormal to fp32
+        float* Qp = Qacc;
+        // Rayleigh-Ritz: Z = A^T Q, eigen-pairs of Z^T Z = Q^T A A^T Q
+        ASER_TRY(gemm_tn_atomic(ctx, form, A, n, Qp, b, Zt, b, n, b, m, bmA, bnB, false));
+        float* Zp = Zt;
+        float* tp = Qraw;
+        ASER_TRY(gemm_tn_atomic(ctx, form, Zp, b, Zp, b, Mb, b, b, b, n, 128, 128, false));
+        ASER_TRY(aser_tridiag_eig(ctx, Mb, b, lambda, Uhat, refl, tri, cluster));
+        ASER_TRY(aser_jacobi_eig(ctx, Mb, b, lambda, Uhat, cluster));      // only runs if eigenvalues cluster
+        hipLaunchKernelGGL(ritz_factors_kernel, dim3(16), dim3(256), 0, ctx->stream, (const float*)lambda, (const float*)Uhat, b,
+                           (int)r, sigma, WA, WBt);
+        ASER_TRY(aser_check_launch(ctx, "ritz_factors"));
+        // Whitened error of Eq. 8 as an explicit residual: ||A - U_r (U_r^T A)||_F, formed tile by tile in
+        // the product's epilogue (A is read once and nothing is written).
+        // U_r^T A = (Z Uhat_r)^T with Z = A^T Q; the subtraction form avoids the cancellation of
+        // ||A||^2 - sum sigma_i^2 when the top singular values carry almost all of the norm.
+        ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, Uhat, b, L_B, n, n, b, r, 0, true));  // (V_r Sigma_r)^T (r x n), parked in L_B
+        ASER_TRY(aser_gemm_small_f32(ctx, Qp, b, Uhat, b, tp, m, m, b, r, 0, true));   // U_r^T (r x m)
+        {
+            GemmArgs g{};
+            g.A = tp; g.lda = m; g.B = L_B; g.ldb = n; g.C = A; g.ldc = n; g.Ct = nullptr; g.ldct = 0;
+            g.M = m; g.N = n; g.K = r; g.alpha = -1.f; g.sumsq = normA2;
+            g.in_type = form; g.epi = GEMM_EPI_RESID; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
+            g.k_parts = 1;
+            g.bm = 128; g.bn = 128;                           // short K: many small workgroups hide the latency of reading A
+            ASER_TRY(aser_gemm_tn(ctx, g));
+        }
+        // L_A = Q (Uhat_r Sigma_r)
+        ASER_TRY(aser_gemm_small_f32(ctx, Qp, b, WA, r, L_A, r, m, b, r));
+        // L_B^T = (T^T Q) (Uhat_r Sigma_r^-1)  ->  L_B
+        ASER_TRY(gemm_tn_atomic(ctx, form, T, ldt, Qp, b, Zp, b, n, b, m, bmA, bnB, true));  // C^T = T^T Q (n x b)
+        return aser_gemm_small_f32(ctx, Zp, b, WBt, r, L_B, n, n, b, r, 0, true);            // (n x r)^T = L_B
+    };
+    // The one synchronisation: the squared residual, the pivot flag of the orthogonalisation and whatever
+    // earlier calls left pending.
+    double res2 = 0.0;
+    ASER_TRY(iterate(p.iters));
+    ASER_TRY(finish());
     {
-        GemmArgs g{};
-        g.A = tp; g.lda = m; g.B = L_B; g.ldb = n; g.C = A; g.ldc = n; g.Ct = nullptr; g.ldct = 0;
-        g.M = m; g.N = n; g.K = r; g.alpha = -1.f; g.sumsq = normA2;
-        g.in_type = form; g.epi = GEMM_EPI_RESID; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_FULL;
-        g.k_parts = 1;
-        g.bm = 128; g.bn = 128;                           // short K: many small workgroups hide the latency of reading A
-        ASER_TRY(aser_gemm_tn(ctx, g));
+        double h_res2 = 0.0;
+        int32_t h_qr = 0;
+        AserPending pend;                                    // status words of calls that did not synchronise
+        ASER_HIP(ctx, hipMemcpyAsync(&h_res2, normA2, 8, hipMemcpyDeviceToHost, ctx->stream));
+        ASER_HIP(ctx, hipMemcpyAsync(&h_qr, info, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+        ASER_TRY(aser_fetch_pending(ctx, &pend));
+        ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        ASER_TRY(aser_report_pending(ctx, pend, "error_reconstruct"));
+        if (h_qr < 0 || !(h_res2 >= 0.0) || h_res2 > 1e300)
+            ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE,
+                      "error_reconstruct: the Cholesky-QR orthogonalisation broke down (pivot %d of a block Gram matrix is not "
+                      "positive): the singular values of the subspace span more than the products resolve",
+                      h_qr < 0 ? h_qr - kPivotBase : 0);
+        res2 = h_res2 > 0.0 ? h_res2 : 0.0;
     }
-    // L_A = Q (Uhat_r Sigma_r)
-    ASER_TRY(aser_gemm_small_f32(ctx, Qp, b, WA, r, L_A, r, m, b, r));
-    // L_B^T = (T^T Q) (Uhat_r Sigma_r^-1)  ->  L_B
-    ASER_TRY(gemm_tn_atomic(ctx, form, T, ldt, Qp, b, Zp, b, n, b, m, bmA, bnB, true));  // C^T = T^T Q (n x b)
-    ASER_TRY(aser_gemm_small_f32(ctx, Zp, b, WBt, r, L_B, n, n, b, r, 0, true));   // (n x r)^T = L_B
-
-    double h_res2 = 0.0;
-    int32_t h_qr = 0;
-    AserPending pend;                                    // status words of calls that did not synchronise
-    ASER_HIP(ctx, hipMemcpyAsync(&h_res2, normA2, 8, hipMemcpyDeviceToHost, ctx->stream));
-    ASER_HIP(ctx, hipMemcpyAsync(&h_qr, info, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
-    ASER_TRY(aser_fetch_pending(ctx, &pend));
-    ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    ASER_TRY(aser_report_pending(ctx, pend, "error_reconstruct"));
-    if (h_qr < 0 || !(h_res2 >= 0.0) || h_res2 > 1e300)
-        ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE,
-                  "error_reconstruct: the Cholesky-QR orthogonalisation broke down (pivot %d of a block Gram matrix is not "
-                  "positive): the singular values of the subspace span more than the products resolve",
-                  h_qr < 0 ? h_qr - kPivotBase : 0);
-    if (err) *err = sqrt(h_res2 > 0.0 ? h_res2 : 0.0);
-    if (n_iter) *n_iter = p.iters;
+    if (err) *err = sqrt(res2);
+    if (n_iter) *n_iter = done;
     return ASER_OK;
 }

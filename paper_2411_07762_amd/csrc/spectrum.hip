@@ -30,10 +30,12 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 // B += P^T P for P: K x k fp32 (row-major, ldp), B: k x k fp64 (ld = k), lower-triangle tiles of
 // 64 x 64 written to both (i, j) and (j, i).  256 threads as 16 x 16, a 4 x 4 block of B each.
 // K is split over blockIdx.y; partial tiles are added with fp64 atomics (B is cleared first).
-__global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__ P, int64_t K, int64_t k, int64_t ldp,
+template <typename TIN>
+__global__ __launch_bounds__(256) void gram_f64_kernel(const TIN* __restrict__ P, int64_t K, int64_t k, int64_t ldp,
                                                        double* __restrict__ B, int k_parts) {
-    __shared__ __align__(16) float sa[16][64];
-    __shared__ __align__(16) float sb[16][64];
+    typedef TIN tin4_t __attribute__((ext_vector_type(4)));
+    __shared__ __align__(32) TIN sa[16][64];
+    __shared__ __align__(32) TIN sb[16][64];
     const int64_t t = blockIdx.x;
     int64_t bi = (int64_t)((sqrt(8.0 * (double)t + 1.0) - 1.0) * 0.5);
     while (bi * (bi + 1) / 2 > t) --bi;
@@ -46,7 +48,7 @@ __global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__
     if (k0 >= k1) return;
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     const int lr = tid >> 4, lc = (tid & 15) * 4;          // this thread's 4 floats of a 16 x 64 slab
-    const bool vec_ok = (((uintptr_t)P & 15) == 0) && ((ldp & 3) == 0);
+    const bool vec_ok = (((uintptr_t)P & (4 * sizeof(TIN) - 1)) == 0) && ((ldp & 3) == 0);
     double acc[4][4];
 #pragma unroll
     for (int u = 0; u < 4; ++u)
@@ -54,26 +56,26 @@ __global__ __launch_bounds__(256) void gram_f64_kernel(const float* __restrict__
         for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
     for (int64_t kk = k0; kk < k1; kk += 16) {
         const int64_t row = kk + lr;
-        f32x4_t a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+        tin4_t a = {0, 0, 0, 0}, b = {0, 0, 0, 0};
         if (row < k1) {
-            const float* pr = P + row * ldp;
-            if (vec_ok && I0 + lc + 4 <= k) a = *(const f32x4_t*)(pr + I0 + lc);
+            const TIN* pr = P + row * ldp;
+            if (vec_ok && I0 + lc + 4 <= k) a = *(const tin4_t*)(pr + I0 + lc);
             else
                 for (int e = 0; e < 4; ++e)
                     if (I0 + lc + e < k) a[e] = pr[I0 + lc + e];
-            if (vec_ok && J0 + lc + 4 <= k) b = *(const f32x4_t*)(pr + J0 + lc);
+            if (vec_ok && J0 + lc + 4 <= k) b = *(const tin4_t*)(pr + J0 + lc);
             else
                 for (int e = 0; e < 4; ++e)
                     if (J0 + lc + e < k) b[e] = pr[J0 + lc + e];
         }
         __syncthreads();                                  // the previous slab has been consumed
-        *(f32x4_t*)&sa[lr][lc] = a;
-        *(f32x4_t*)&sb[lr][lc] = b;
+        *(tin4_t*)&sa[lr][lc] = a;
+        *(tin4_t*)&sb[lr][lc] = b;
         __syncthreads();
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
-            const f32x4_t av = *(const f32x4_t*)&sa[s][ty * 4];
-            const f32x4_t bv = *(const f32x4_t*)&sb[s][tx * 4];
+            const tin4_t av = *(const tin4_t*)&sa[s][ty * 4];
+            const tin4_t bv = *(const tin4_t*)&sb[s][tx * 4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -112,7 +114,8 @@ __global__ __launch_bounds__(1024) void tridiag_head_kernel(int64_t j, int64_t k
                                                             const double* __restrict__ v_cur, double* __restrict__ v_next,
                                                             double* __restrict__ w, const double* __restrict__ p,
                                                             double* __restrict__ d, double* __restrict__ e,
-                                                            const double* __restrict__ tau_cur, double* __restrict__ tau_next) {
+                                                            const double* __restrict__ tau_cur, double* __restrict__ tau_next,
+                                                            double* __restrict__ vstore, double* __restrict__ taustore) {
     __shared__ double red[16];
     const int tid = threadIdx.x;
     const int64_t row = j + 1;
@@ -151,8 +154,14 @@ __global__ __launch_bounds__(1024) void tridiag_head_kernel(int64_t j, int64_t k
             const double v0 = x0 - alpha;
             const double vn2 = n2 - x0 * x0 + v0 * v0;
             v_next[row + 1] = v0;
-            *tau_next = vn2 > 0.0 ? 2.0 / vn2 : 0.0;
+            const double tnew = vn2 > 0.0 ? 2.0 / vn2 : 0.0;
+            *tau_next = tnew;
             e[row] = alpha;
+            if (taustore) taustore[row] = tnew;
+        }
+        if (vstore) {                                     // keep the reflector for the back-transformation of eigenvectors
+            __syncthreads();
+            for (int64_t i = row + 1 + tid; i < k; i += 1024) vstore[row * k + i] = v_next[i];
         }
     } else if (row + 2 == k) {                            // the last 2 x 2 block: no reflector
         if (tid == 0) {
@@ -214,7 +223,8 @@ __global__ __launch_bounds__(256) void tridiag_pass_kernel(int64_t c0, int64_t k
 // q_0 = d_0 - x, q_l = d_l - x - e_{l-1}^2 / q_{l-1}.  One thread per eigenvalue; the lanes of a
 // wavefront read the same (d_l, e_l) at the same time.  sigma[k - 1 - i] = sqrt(max(lambda_i, 0)).
 __global__ __launch_bounds__(64) void tridiag_bisect_kernel(int64_t k, const double* __restrict__ d,
-                                                            const double* __restrict__ e, double* __restrict__ sigma) {
+                                                            const double* __restrict__ e, double* __restrict__ sigma,
+                                                            double* __restrict__ lam_desc) {
     const int64_t i = (int64_t)blockIdx.x * 64 + threadIdx.x;
     // Gershgorin interval and the smallest pivot magnitude (every lane computes the same values)
     double lo = 1e300, hi = -1e300, emax2 = 0.0;
@@ -245,6 +255,7 @@ __global__ __launch_bounds__(64) void tridiag_bisect_kernel(int64_t k, const dou
     }
     const double lam = 0.5 * (a + b);
     sigma[k - 1 - i] = lam > 0.0 ? sqrt(lam) : 0.0;
+    if (lam_desc) lam_desc[k - 1 - i] = lam;
 }
 
 // Eq. 9 on a descending spectrum: running sums in index order; r = number of leading indices whose
@@ -290,6 +301,241 @@ __global__ __launch_bounds__(1024) void effective_rank_kernel(const double* __re
     if (threadIdx.x == 0) *out = exp(h);
 }
 
+// B (k x k fp64, full symmetric) = P^T P, cleared first; K split so that the grid fills the device.
+template <typename TIN>
+int gram_f64(aser_ctx* ctx, const TIN* P, int64_t K, int64_t k, int64_t ldp, double* B) {
+    ASER_TRY(aser_fill_bytes(ctx, B, (size_t)k * k * 8));
+    const int64_t t64 = ceil_div64(k, 64), tiles = t64 * (t64 + 1) / 2, ksteps = ceil_div64(K, 16);
+    int64_t parts = ceil_div64(2048, tiles);
+    if (parts > ksteps / 8) parts = ksteps / 8;
+    if (parts < 1) parts = 1;
+    if (parts > 64) parts = 64;
+    hipLaunchKernelGGL(gram_f64_kernel<TIN>, dim3((unsigned)tiles, (unsigned)parts), dim3(256), 0, ctx->stream, P, K, k, ldp, B,
+                       (int)parts);
+    return aser_check_launch(ctx, "gram_f64");
+}
+
+// Householder chain on B (overwritten): head(-1), pass(-1), then head(j), pass(j) for j = 0 .. k - 3.
+// vec: eight zeroed arrays of k doubles (v twice, w, p, d, e, tau, spare); d = vec[4], e = vec[5] on return.
+// vstore (k x k) / taustore (k), both zeroed by the caller, receive the reflectors when not null.
+int tridiagonalize(aser_ctx* ctx, double* B, int64_t k, double* const* vec, double* vstore, double* taustore) {
+    double *v0 = vec[0], *v1 = vec[1], *w = vec[2], *p = vec[3], *d = vec[4], *e = vec[5], *tau = vec[6];
+    double *vc = v0, *vn = v1;
+    hipLaunchKernelGGL(tridiag_head_kernel, dim3(1), dim3(1024), 0, ctx->stream, (int64_t)-1, k, (const double*)B,
+                       (const double*)vc, vn, w, (const double*)p, d, e, (const double*)tau, tau + 1, vstore, taustore);
+    ASER_TRY(aser_check_launch(ctx, "tridiag_head"));
+    int tsel = 1;                                          // tau[tsel] holds the tau of the reflector in vn
+    for (int64_t j = -1; j + 3 < k; ++j) {
+        // pass of step j: update with (vc, w) when j >= 0, then p = B22 vn
+        const int64_t c0 = j + 2;
+        hipLaunchKernelGGL(tridiag_pass_kernel, dim3((unsigned)ceil_div64(k - c0, 8)), dim3(256), 0, ctx->stream, c0, k, B,
+                           (const double*)vc, (const double*)w, (const double*)vn, p, j >= 0 ? 1 : 0);
+        ASER_TRY(aser_check_launch(ctx, "tridiag_pass"));
+        { double* t = vc; vc = vn; vn = t; }
+        hipLaunchKernelGGL(tridiag_head_kernel, dim3(1), dim3(1024), 0, ctx->stream, j + 1, k, (const double*)B,
+                           (const double*)vc, vn, w, (const double*)p, d, e, (const double*)(tau + tsel), tau + (tsel ^ 1),
+                           vstore, taustore);
+        ASER_TRY(aser_check_launch(ctx, "tridiag_head"));
+        tsel ^= 1;
+    }
+    return ASER_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Dense fp64 solver for small layers: the rank-r truncated SVD of A = T S from the complete
+// eigen-decomposition of the Gram matrix of its shorter side.  Eigenvalues as above (every one, so the
+// whitened error is the square root of their tail sum); eigenvectors of the r largest by inverse
+// iteration on the tridiagonal matrix, made orthonormal among themselves, and carried back through the
+// stored reflectors.  No iteration count, no start block: what the iterative path approximates.
+
+// out[i][j] = sum_{l >= j} T[i][l] S[l][j] in fp64 (S lower triangular); TRANSPOSED: stored as out[j][i].
+template <bool TRANSPOSED>
+__global__ __launch_bounds__(256) void ts_f64_kernel(const float* __restrict__ T, int64_t m, int64_t n, int64_t ldt,
+                                                     const float* __restrict__ S, int64_t lds, double* __restrict__ out) {
+    const int64_t j = (int64_t)blockIdx.x * 64 + (threadIdx.x & 63);
+    const int64_t i = (int64_t)blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (i >= m || j >= n) return;
+    const float* trow = T + i * ldt;
+    double acc = 0.0;
+    for (int64_t l = j; l < n; ++l) acc = fma((double)trow[l], (double)S[l * lds + j], acc);
+    if (TRANSPOSED) out[j * m + i] = acc; else out[i * n + j] = acc;
+}
+
+__device__ __forceinline__ uint32_t hash32(uint32_t x) {
+    x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+    return x;
+}
+
+// Eigenvectors of the symmetric tridiagonal matrix (d, e) for the r largest eigenvalues lam[0 .. r),
+// as rows of X (r x k).  One workgroup.  Three rounds of: thread c solves (T - lam_c I) y = x_c by
+// Gaussian elimination with row interchanges (a zero pivot becomes eps ||T||), then the vectors are
+// orthonormalised in order (classical Gram-Schmidt, twice).  scr: r x 3 k doubles.
+__global__ __launch_bounds__(256) void tridiag_invit_kernel(int64_t k, int r, const double* __restrict__ d,
+                                                            const double* __restrict__ e, const double* __restrict__ lam,
+                                                            double* __restrict__ X, double* __restrict__ scr) {
+    __shared__ double dots[128];
+    __shared__ double red[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    double tnorm = 0.0;
+    for (int64_t l = 0; l < k; ++l) tnorm = fmax(tnorm, fabs(d[l]) + (l + 1 < k ? fabs(e[l]) : 0.0) + (l > 0 ? fabs(e[l - 1]) : 0.0));
+    const double tiny = fmax(tnorm * 2.3e-16, 1e-300);
+    for (int64_t t = tid; t < (int64_t)r * k; t += 256)
+        X[t] = (double)(hash32((uint32_t)t * 0x9E3779B9U + 12345u) >> 8) * (1.0 / 8388608.0) - 1.0;
+    __syncthreads();
+    for (int round = 0; round < 3; ++round) {
+        if (tid < r) {
+            const int c = tid;
+            double* x = X + (int64_t)c * k;
+            double* dd = scr + (int64_t)c * 3 * k;
+            double* du = dd + k;
+            double* du2 = du + k;
+            const double shift = lam[c];
+            double a = d[0] - shift, b = (k > 1) ? e[0] : 0.0;       // current row: diagonal and super-diagonal
+            for (int64_t i = 0; i + 1 < k; ++i) {
+                const double sub = e[i], dn = d[i + 1] - shift, en = (i + 2 < k) ? e[i + 1] : 0.0;
+                if (fabs(a) >= fabs(sub)) {
+                    if (fabs(a) < tiny) a = tiny;
+                    const double mult = sub / a;
+                    dd[i] = a; du[i] = b; du2[i] = 0.0;
+                    x[i + 1] -= mult * x[i];
+                    a = dn - mult * b;
+                    b = en;
+                } else {
+                    const double mult = a / sub;
+                    dd[i] = sub; du[i] = dn; du2[i] = en;
+                    const double xi = x[i];
+                    x[i] = x[i + 1];
+                    x[i + 1] = xi - mult * x[i];
+                    a = b - mult * dn;
+                    b = -mult * en;
+                }
+            }
+            if (fabs(a) < tiny) a = tiny;
+            dd[k - 1] = a;
+            x[k - 1] /= dd[k - 1];
+            if (k > 1) x[k - 2] = (x[k - 2] - du[k - 2] * x[k - 1]) / dd[k - 2];
+            for (int64_t i = k - 3; i >= 0; --i) x[i] = (x[i] - du[i] * x[i + 1] - du2[i] * x[i + 2]) / dd[i];
+            double mx = 0.0;
+            for (int64_t i = 0; i < k; ++i) mx = fmax(mx, fabs(x[i]));
+            const double sc = mx > 0.0 ? 1.0 / mx : 1.0;
+            for (int64_t i = 0; i < k; ++i) x[i] *= sc;
+        }
+        __syncthreads();
+        for (int c = 0; c < r; ++c) {
+            double* x = X + (int64_t)c * k;
+            for (int pass = 0; pass < 2; ++pass) {
+                for (int j = wave; j < c; j += 4) {
+                    const double* y = X + (int64_t)j * k;
+                    double s = 0.0;
+                    for (int64_t i = lane; i < k; i += 64) s += y[i] * x[i];
+#pragma unroll
+                    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+                    if (lane == 0) dots[j] = s;
+                }
+                __syncthreads();
+                for (int64_t i = tid; i < k; i += 256) {
+                    double v = x[i];
+                    for (int j = 0; j < c; ++j) v -= dots[j] * X[(int64_t)j * k + i];
+                    x[i] = v;
+                }
+                __syncthreads();
+            }
+            double s = 0.0;
+            for (int64_t i = tid; i < k; i += 256) s += x[i] * x[i];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+            if (lane == 0) red[wave] = s;
+            __syncthreads();
+            const double nrm = sqrt(red[0] + red[1] + red[2] + red[3]);
+            const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+            for (int64_t i = tid; i < k; i += 256) x[i] *= inv;
+            __syncthreads();
+        }
+    }
+}
+
+// x <- H_0 H_1 ... H_{k-3} x for every row x of X (one workgroup per row): eigenvectors of the tridiagonal
+// matrix become eigenvectors of the Gram matrix.  H_j = I - tau_j v_j v_j^T, v_j in row j of vstore.
+__global__ __launch_bounds__(256) void backtransform_kernel(int64_t k, const double* __restrict__ vstore,
+                                                            const double* __restrict__ taustore, double* __restrict__ X) {
+    __shared__ double red[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    double* x = X + (int64_t)blockIdx.x * k;
+    for (int64_t j = k - 3; j >= 0; --j) {
+        const double* v = vstore + j * k;
+        double s = 0.0;
+        for (int64_t i = j + 1 + tid; i < k; i += 256) s += v[i] * x[i];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+        __syncthreads();
+        if (lane == 0) red[wave] = s;
+        __syncthreads();
+        const double f = taustore[j] * (red[0] + red[1] + red[2] + red[3]);
+        for (int64_t i = j + 1 + tid; i < k; i += 256) x[i] -= f * v[i];
+        __syncthreads();
+    }
+}
+
+// Factors from the eigenvectors (rows of X, r x k) and eigenvalues lam (descending) of the Gram matrix.
+//   k == m (left singular vectors u_c = X[c]):   L_A[i][c] = u_c[i] sigma_c,        L_B[c][j] = sum_i u_c[i] T[i][j] / sigma_c
+//   k == n (right singular vectors v_c = X[c]):  L_A[i][c] = sum_j A[i][j] v_c[j],  L_B[c][j] = sum_i L_A[i][c] T[i][j] / sigma_c^2
+// LA64: m x r fp64 scratch.  Two launches: phase 0 writes L_A (and LA64), phase 1 writes L_B, sigma and the error.
+__global__ __launch_bounds__(256) void exact_factors_kernel(int phase, int left, int64_t m, int64_t n, int64_t k, int r,
+                                                            const double* __restrict__ X, const double* __restrict__ lam,
+                                                            const double* __restrict__ A64, const float* __restrict__ T,
+                                                            int64_t ldt, double* __restrict__ LA64, float* __restrict__ L_A,
+                                                            float* __restrict__ L_B, float* __restrict__ sigma,
+                                                            double* __restrict__ err2) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (phase == 0) {
+        if (t >= m * r) return;
+        const int64_t i = t / r;
+        const int c = (int)(t % r);
+        double v;
+        if (left) {
+            const double sg = lam[c] > 0.0 ? sqrt(lam[c]) : 0.0;
+            v = X[(int64_t)c * k + i] * sg;
+        } else {
+            v = 0.0;
+            for (int64_t j = 0; j < n; ++j) v = fma(A64[i * n + j], X[(int64_t)c * k + j], v);
+        }
+        LA64[t] = v;
+        L_A[t] = (float)v;
+        return;
+    }
+    if (t == 0) {
+        double tail = 0.0;
+        for (int64_t i = k - 1; i >= r; --i) tail += lam[i] > 0.0 ? lam[i] : 0.0;    // smallest first
+        *err2 = tail;
+    }
+    if (t < r) sigma[t] = lam[t] > 0.0 ? (float)sqrt(lam[t]) : 0.f;
+    if (t >= (int64_t)r * n) return;
+    const int c = (int)(t / n);
+    const int64_t j = t % n;
+    double acc = 0.0;
+    for (int64_t i = 0; i < m; ++i) acc = fma(LA64[i * r + c], (double)T[i * ldt + j], acc);
+    L_B[t] = lam[c] > 0.0 ? (float)(acc / lam[c]) : 0.f;     // L_A^T T / sigma^2 in both cases (L_A = u sigma)
+}
+
+struct ExactPlan {
+    int64_t k;
+    size_t off_a, off_b, off_vs, off_vec, off_x, off_scr, off_la, total;
+};
+
+void exact_plan(int64_t m, int64_t n, int r, ExactPlan* p) {
+    p->k = m < n ? m : n;
+    const size_t kk = align_up((size_t)p->k * p->k * 8, 256), vb = align_up((size_t)p->k * 8, 256);
+    size_t off = 0;
+    p->off_a = off; off += align_up((size_t)m * n * 8, 256);        // A (m x n) or A^T (n x m), fp64
+    p->off_b = off; off += kk;                                      // Gram matrix, then scratch of the chain
+    p->off_vs = off; off += kk;                                     // reflectors
+    p->off_vec = off; off += 10 * vb;                               // eight chain vectors, tau store, eigenvalues
+    p->off_x = off; off += align_up((size_t)r * p->k * 8, 256);
+    p->off_scr = off; off += align_up((size_t)r * 3 * p->k * 8, 256);
+    p->off_la = off; off += align_up((size_t)m * r * 8, 256);
+    p->total = off;
+}
+
 struct SpecPlan {
     int64_t k;
     size_t off_tt, off_a, off_at, off_b, off_vec, total;
@@ -308,6 +554,63 @@ void spectrum_plan(int64_t m, int64_t n, bool with_s, SpecPlan* p) {
 }
 
 }  // namespace
+
+size_t aser_exact_workspace(int64_t m, int64_t n, int r) {
+    ExactPlan p;
+    exact_plan(m, n, r, &p);
+    return p.total;
+}
+
+// The dense fp64 solver on the bound workspace: L_A, L_B, sigma and, in *err2_dev (device), the squared
+// whitened error.  Asynchronous.  The caller has checked shapes and the workspace size.
+int aser_exact_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt, const float* S, int64_t lds,
+                           int r, float* L_A, float* L_B, float* sigma, double* err2_dev) {
+    ExactPlan pl;
+    exact_plan(m, n, r, &pl);
+    char* ws = (char*)ctx->ws;
+    const int64_t k = pl.k;
+    const bool left = m <= n;
+    double* A64 = (double*)(ws + pl.off_a);
+    double* B = (double*)(ws + pl.off_b);
+    double* vstore = (double*)(ws + pl.off_vs);
+    const size_t vb = align_up((size_t)k * 8, 256);
+    double* vec[8];
+    for (int i = 0; i < 8; ++i) vec[i] = (double*)(ws + pl.off_vec + i * vb);
+    double* taustore = (double*)(ws + pl.off_vec + 8 * vb);
+    double* lam = (double*)(ws + pl.off_vec + 9 * vb);
+    double* X = (double*)(ws + pl.off_x);
+    double* scr = (double*)(ws + pl.off_scr);
+    double* LA64 = (double*)(ws + pl.off_la);
+    // A = T S in fp64; for m <= n stored transposed (n x m), which is the K-major operand of A A^T
+    {
+        dim3 grid((unsigned)ceil_div64(n, 64), (unsigned)ceil_div64(m, 4));
+        if (left) hipLaunchKernelGGL(ts_f64_kernel<true>, grid, dim3(256), 0, ctx->stream, T, m, n, ldt, S, lds, A64);
+        else hipLaunchKernelGGL(ts_f64_kernel<false>, grid, dim3(256), 0, ctx->stream, T, m, n, ldt, S, lds, A64);
+        ASER_TRY(aser_check_launch(ctx, "ts_f64"));
+    }
+    ASER_TRY(gram_f64<double>(ctx, A64, left ? n : m, k, k, B));
+    ASER_TRY(aser_fill_bytes(ctx, vstore, (size_t)k * k * 8));
+    ASER_TRY(aser_fill_bytes(ctx, vec[0], 10 * vb));
+    ASER_TRY(tridiagonalize(ctx, B, k, vec, vstore, taustore));
+    double* sig64 = vec[7];
+    hipLaunchKernelGGL(tridiag_bisect_kernel, dim3((unsigned)ceil_div64(k, 64)), dim3(64), 0, ctx->stream, k, (const double*)vec[4],
+                       (const double*)vec[5], sig64, lam);
+    ASER_TRY(aser_check_launch(ctx, "tridiag_bisect"));
+    hipLaunchKernelGGL(tridiag_invit_kernel, dim3(1), dim3(256), 0, ctx->stream, k, r, (const double*)vec[4], (const double*)vec[5],
+                       (const double*)lam, X, scr);
+    ASER_TRY(aser_check_launch(ctx, "tridiag_invit"));
+    hipLaunchKernelGGL(backtransform_kernel, dim3((unsigned)r), dim3(256), 0, ctx->stream, k, (const double*)vstore,
+                       (const double*)taustore, X);
+    ASER_TRY(aser_check_launch(ctx, "backtransform"));
+    for (int phase = 0; phase < 2; ++phase) {
+        const int64_t total = phase == 0 ? m * (int64_t)r : (int64_t)r * n;
+        hipLaunchKernelGGL(exact_factors_kernel, dim3((unsigned)ceil_div64(total, 256)), dim3(256), 0, ctx->stream, phase, left ? 1 : 0,
+                           m, n, k, r, (const double*)X, (const double*)lam, (const double*)A64, T, ldt, LA64, L_A, L_B, sigma,
+                           err2_dev);
+        ASER_TRY(aser_check_launch(ctx, "exact_factors"));
+    }
+    return ASER_OK;
+}
 
 extern "C" size_t aser_spectrum_workspace_bytes(int64_t m, int64_t n, int32_t with_s) {
     if (m <= 0 || n <= 0) return 0;
@@ -337,7 +640,7 @@ extern "C" int aser_singular_values(aser_ctx* ctx, const float* T, int64_t m, in
     const size_t vb = align_up((size_t)pl.k * 8, 256);
     double* vec[8];
     for (int i = 0; i < 8; ++i) vec[i] = (double*)(ws + pl.off_vec + i * vb);
-    double *v0 = vec[0], *v1 = vec[1], *w = vec[2], *p = vec[3], *d = vec[4], *e = vec[5], *tau = vec[6];
+    double *d = vec[4], *e = vec[5];
     const int64_t k = pl.k;
 
     // the K-major operand of the Gram matrix on the shorter side: Z^T for m <= n, Z for m > n
@@ -360,38 +663,11 @@ extern "C" int aser_singular_values(aser_ctx* ctx, const float* T, int64_t m, in
     } else {
         P = T; ldp = ldt; K = m;
     }
-    ASER_TRY(aser_fill_bytes(ctx, B, (size_t)k * k * 8));
+    ASER_TRY(gram_f64(ctx, P, K, k, ldp, B));
     ASER_TRY(aser_fill_bytes(ctx, vec[0], 8 * vb));
-    {
-        const int64_t t64 = ceil_div64(k, 64), tiles = t64 * (t64 + 1) / 2, ksteps = ceil_div64(K, 16);
-        int64_t parts = ceil_div64(2048, tiles);
-        if (parts > ksteps / 8) parts = ksteps / 8;
-        if (parts < 1) parts = 1;
-        if (parts > 64) parts = 64;
-        hipLaunchKernelGGL(gram_f64_kernel, dim3((unsigned)tiles, (unsigned)parts), dim3(256), 0, ctx->stream, P, K, k, ldp, B,
-                           (int)parts);
-        ASER_TRY(aser_check_launch(ctx, "gram_f64"));
-    }
-    // Householder chain: head(-1), pass(-1), then head(j), pass(j) for j = 0 .. k - 3
-    double *vc = v0, *vn = v1;
-    hipLaunchKernelGGL(tridiag_head_kernel, dim3(1), dim3(1024), 0, ctx->stream, (int64_t)-1, k, (const double*)B,
-                       (const double*)vc, vn, w, (const double*)p, d, e, (const double*)tau, tau + 1);
-    ASER_TRY(aser_check_launch(ctx, "tridiag_head"));
-    int tsel = 1;                                          // tau[tsel] holds the tau of the reflector in vn
-    for (int64_t j = -1; j + 3 < k; ++j) {
-        // pass of step j: update with (vc, w) when j >= 0, then p = B22 vn
-        const int64_t c0 = j + 2;
-        hipLaunchKernelGGL(tridiag_pass_kernel, dim3((unsigned)ceil_div64(k - c0, 8)), dim3(256), 0, ctx->stream, c0, k, B,
-                           (const double*)vc, (const double*)w, (const double*)vn, p, j >= 0 ? 1 : 0);
-        ASER_TRY(aser_check_launch(ctx, "tridiag_pass"));
-        { double* t = vc; vc = vn; vn = t; }
-        hipLaunchKernelGGL(tridiag_head_kernel, dim3(1), dim3(1024), 0, ctx->stream, j + 1, k, (const double*)B,
-                           (const double*)vc, vn, w, (const double*)p, d, e, (const double*)(tau + tsel), tau + (tsel ^ 1));
-        ASER_TRY(aser_check_launch(ctx, "tridiag_head"));
-        tsel ^= 1;
-    }
+    ASER_TRY(tridiagonalize(ctx, B, k, vec, nullptr, nullptr));
     hipLaunchKernelGGL(tridiag_bisect_kernel, dim3((unsigned)ceil_div64(k, 64)), dim3(64), 0, ctx->stream, k, (const double*)d,
-                       (const double*)e, sigma);
+                       (const double*)e, sigma, (double*)nullptr);
     return aser_check_launch(ctx, "tridiag_bisect");
 }
 

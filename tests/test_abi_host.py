@@ -122,16 +122,19 @@ def test_whiten_and_reconstruct_validation(ctx):
     assert r(ctx, P, P, 8, P, P, P, idx=P, f=65, m=64, n=64)[0] == aser.ASER_ERR_SHAPE            # f > n
     o = aser.aser_svd_opts(block=48, max_iter=0, seed=0)
     assert r(ctx, P, P, 8, P, P, P, o, m=64, n=64)[0] == aser.ASER_ERR_SHAPE             # block not multiple of 32
-    assert r(ctx, P, P, 40, P, P, P, m=695, n=44)[0] == aser.ASER_ERR_SHAPE              # no multiple of 32 in [40, 44]
+    it = aser.aser_svd_opts(block=0, max_iter=5, seed=0)                                 # asks for the subspace iteration
+    assert r(ctx, P, P, 40, P, P, P, it, m=695, n=44)[0] == aser.ASER_ERR_SHAPE          # no multiple of 32 in [40, 44]
     assert "block width" in ctx._lib.aser_last_error(ctx.handle).decode()
+    assert r(ctx, P, P, 40, P, P, P, m=695, n=44)[0] == aser.ASER_ERR_WORKSPACE          # the dense solver takes any r <= min(m, n)
+    assert r(ctx, P, P, 45, P, P, P, m=695, n=44)[0] == aser.ASER_ERR_SHAPE
 
 
 def test_svd_plan_reports_what_the_iteration_will_use():
     assert aser.aser_svd_plan(4096, 4096, 64) == (aser.ASER_OK, 128, 9)
     assert aser.aser_svd_plan(4096, 11008, 64) == (aser.ASER_OK, 128, 12)
     assert aser.aser_svd_plan(8192, 28672, 128) == (aser.ASER_OK, 128, 30)       # no oversampling columns
-    assert aser.aser_svd_plan(256, 256, 16) == (aser.ASER_OK, 32, 14)
-    assert aser.aser_svd_plan(322, 74, 23) == (aser.ASER_OK, 64, 14)              # 2 r = 46 -> 64 fits in n = 74
+    assert aser.aser_svd_plan(256, 256, 16) == (aser.ASER_OK, 32, 9)
+    assert aser.aser_svd_plan(322, 74, 23) == (aser.ASER_OK, 64, 9)              # 2 r = 46 -> 64 fits in n = 74
     assert aser.aser_svd_plan(300, 40, 23)[:2] == (aser.ASER_OK, 32)             # shrunk to fit the matrix
     assert aser.aser_svd_plan(695, 44, 40)[0] == aser.ASER_ERR_SHAPE
     o = aser.aser_svd_opts(block=96, max_iter=5, seed=0)
