@@ -30,6 +30,7 @@ extern "C" int aser_create(aser_ctx** out, int device, void* hip_stream) {
     c->precision = ASER_PRECISION_AUTO;
     c->pending_info_dev = nullptr;
     c->pending_sel_dev = nullptr;
+    c->host_status = nullptr;
     c->err[0] = 0;
     *out = c;
     return ASER_OK;
@@ -37,6 +38,7 @@ extern "C" int aser_create(aser_ctx** out, int device, void* hip_stream) {
 
 extern "C" int aser_destroy(aser_ctx* ctx) {
     if (!ctx) return ASER_ERR_INVALID_ARG;
+    if (ctx->host_status) (void)hipHostFree(ctx->host_status);
     delete ctx;
     return ASER_OK;
 }
@@ -59,8 +61,7 @@ extern "C" int aser_set_workspace(aser_ctx* ctx, void* dev_ptr, size_t bytes) {
     if (ctx->pending_info_dev || ctx->pending_sel_dev) {
         // deferred status words live in the old workspace: fetch them before that memory goes away
         AserPending pend;
-        ASER_TRY(aser_fetch_pending(ctx, &pend));
-        ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        ASER_TRY(aser_sync_status(ctx, &pend));
         pending_status = aser_report_pending(ctx, pend, "set_workspace");
     }
     ctx->ws = dev_ptr;
@@ -83,6 +84,7 @@ extern "C" size_t aser_workspace_bytes(int64_t m, int64_t n, int32_t r, const as
 int aser_prepare_device(aser_ctx* ctx) {
     if (!ctx->device_ready) {
         ASER_HIP(ctx, hipSetDevice(ctx->device));
+        if (!ctx->host_status) ASER_HIP(ctx, hipHostMalloc(&ctx->host_status, 64, hipHostMallocDefault));
         ctx->device_ready = true;
     } else {
         int cur = -1;
@@ -92,13 +94,23 @@ int aser_prepare_device(aser_ctx* ctx) {
     return ASER_OK;
 }
 
-int aser_fetch_pending(aser_ctx* ctx, AserPending* p) {
+int aser_sync_status(aser_ctx* ctx, AserPending* p) {
     p->pivot = INT_MAX;
     p->sel = 0;
-    if (ctx->pending_info_dev)
-        ASER_HIP(ctx, hipMemcpyAsync(&p->pivot, ctx->pending_info_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
-    if (ctx->pending_sel_dev)
-        ASER_HIP(ctx, hipMemcpyAsync(&p->sel, ctx->pending_sel_dev, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    p->qr = 0;
+    p->res2 = 0.0;
+    if (!ctx->ws || ctx->ws_bytes < kAserWsTail) {           // no workspace: nothing can be pending
+        ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        return ASER_OK;
+    }
+    ASER_TRY(aser_prepare_device(ctx));
+    ASER_HIP(ctx, hipMemcpyAsync(ctx->host_status, aser_status_dev(ctx), sizeof(AserStatusBlock), hipMemcpyDeviceToHost, ctx->stream));
+    ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    const AserStatusBlock* h = (const AserStatusBlock*)ctx->host_status;
+    if (ctx->pending_info_dev) p->pivot = h->pivot;
+    if (ctx->pending_sel_dev) p->sel = h->sel;
+    p->qr = h->qr;
+    p->res2 = h->res2;
     return ASER_OK;
 }
 

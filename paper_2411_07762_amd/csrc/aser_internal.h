@@ -21,22 +21,37 @@ struct aser_ctx {
     // aser_smooth_outliers never synchronises; when fewer than f channels have a usable score its
     // selection kernel raises the word behind the pivot flag, which the next synchronising call reads.
     int32_t* pending_sel_dev;
+    // 64 bytes of pinned host memory (allocated with the first compute call): every synchronising call brings
+    // the status block at the head of the workspace tail to the host in one copy.
+    void* host_status;
     char err[256];
 };
 
-// Bytes at the end of the bound workspace that hold the deferred status words: the whitening's pivot
-// flag (word 0) and the outlier selection's "no usable candidate" flag (word 1); bytes 64 .. 135 carry
-// the scalar results of aser_select_rank and aser_effective_rank to the host.
+// Bytes at the end of the bound workspace.  The first 32 are the status block that a synchronising call copies
+// to the host in one piece: the whitening's pivot flag (word 0), the outlier selection's "no usable candidate"
+// flag (word 1), the pivot flag of the Cholesky-QR steps of aser_error_reconstruct (word 2) and, at byte 16,
+// the squared whitened error as a double.  Bytes 64 .. 135 carry the scalar results of aser_select_rank and
+// aser_effective_rank.
 static const size_t kAserWsTail = 256;
+struct AserStatusBlock {
+    int32_t pivot, sel, qr, pad;
+    double res2;
+    double spare;
+};
+static inline AserStatusBlock* aser_status_dev(const aser_ctx* ctx) {
+    return (AserStatusBlock*)((char*)ctx->ws + ctx->ws_bytes - kAserWsTail);
+}
 
 // Host copies of the deferred status words; INT_MAX / 0 mean "nothing pending or nothing wrong".
 struct AserPending {
     int32_t pivot;
     int32_t sel;
+    int32_t qr;        // word 2 as it is
+    double res2;       // the double at byte 16 as it is
 };
-// Enqueues the copies of whatever is pending into *p (the caller synchronises the stream, then calls
-// aser_report_pending, which clears the pending state and turns a raised word into a status).
-int aser_fetch_pending(aser_ctx* ctx, AserPending* p);
+// Enqueues the one copy of the status block, waits for the stream, and fills *p (words nobody has pending read
+// as "nothing wrong"); aser_report_pending then clears the pending state and turns a raised word into a status.
+int aser_sync_status(aser_ctx* ctx, AserPending* p);
 int aser_report_pending(aser_ctx* ctx, const AserPending& p, const char* who);
 int aser_set_i32(aser_ctx* ctx, int32_t* p, int32_t v);
 
@@ -125,6 +140,7 @@ struct GemmArgs {
     int pair_cols;             // TILES_ALL, k_parts == 1, 256 x 128 tiles: a workgroup takes tile columns j and tn - 1 - j of its tile row
                                // (equal work per workgroup when K shrinks linearly with the column, K_GE_COL)
     double* sumsq;             // RESID only: device scalar that receives the sum of squares (accumulates)
+    const int* gate;           // plain schedules only (may be null): every workgroup returns at once when *gate == 0
 };
 int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g);
 
@@ -160,14 +176,17 @@ int aser_col_abs_sum_w(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int6
 int aser_transpose_f32(aser_ctx* ctx, const float* A, int64_t rows, int64_t cols, int64_t lda, float* At, int64_t ldat);
 
 // Small dense kernels (one workgroup, matrices in LDS)
-// Upper Cholesky of the b x b block D (ld) in place: upper part <- R (D = R^T R), lower part <- R^T;
+// Upper Cholesky of the b x b block D (ld) in place: upper part <- R (D = R^T R), the part below the diagonal is neither read nor written;
 // Rinv (b x b, ld = b) <- R^-1 (upper).  b <= 128.  On a non-positive pivot at column j,
 // atomicMin(info, pivot_base + j + 1) and the factor is meaningless from that column on.  clear_d: D is overwritten with
 // zeros instead of the factor (callers that only need R^-1 and reuse D as an accumulation target).
-// Lmul / Cmul (both may be null): Cmul = alpha Lmul R^-1 for an upper triangular b x b Lmul (ld = b);
-// alpha = 1, or with_beta: alpha = -(0.9 s^2 / 2)^2 with s the smallest diagonal entry of R.
+// Lmul / Cmul (both may be null): Cmul = Lmul R^-1 for an upper triangular b x b Lmul (ld = b).
+// beta_out (device, two words, may be null): word 0 receives -(0.9 s^2 / 2)^2 as a float, s the smallest diagonal
+// entry of R; word 1 receives, as an int, 1 when the largest diagonal entry of R exceeds 64 s and else 0.
+// gate (device, may be null): the kernel returns at once when *gate == 0.
 int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base,
-                    bool clear_d = false, const float* Lmul = nullptr, float* Cmul = nullptr, bool with_beta = false);
+                    bool clear_d = false, const float* Lmul = nullptr, float* Cmul = nullptr, float* beta_out = nullptr,
+                    const int* gate = nullptr);
 // Symmetric eigen-decomposition of the b x b matrix Mb (ld = b) by cyclic Jacobi: eigenvalues
 // descending into lambda (b), eigenvectors as columns of V (b x b, ld = b).  b <= 128, b even.
 // `gate` (device, may be null): the kernel returns at once when *gate == 0.
@@ -180,10 +199,10 @@ int aser_tridiag_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float
 // C (rows x c) = A (rows x k) * B (k x c), plain fp32 FMA; k, c <= 128, k % 4 == 0, A 16-byte aligned with
 // lda % 4 == 0.  C may not alias A.  The first clear_rows rows of A (k columns each; may exceed `rows`) are
 // set to zero after they have been read.  transposed: the result is stored as C^T (c x rows, leading dimension ldc).
-// C (rows x b) = A1 B1 + A2 B2 (A2 null: one term); tall blocks and b x b factors, all with leading
-// dimension b <= 128 (b % 4 == 0), 16-byte aligned.  Afterwards the rows of A1 and the first zrows rows
-// of Zclr (may be null) are zero.
-int aser_combine_f32(aser_ctx* ctx, float* A1, const float* B1, const float* A2, const float* B2, float* C, int64_t rows,
-                     int b, float* Zclr, int64_t zrows);
+// C (rows x b) = (A1 + alpha A2 P) B1 (A2 null: C = A1 B1); tall blocks and b x b factors, all with leading
+// dimension b <= 128 (b % 4 == 0), 16-byte aligned; alpha is read from device memory.  Afterwards the rows of A1
+// and the first zrows rows of Zclr (may be null) are zero.
+int aser_combine_f32(aser_ctx* ctx, float* A1, const float* B1, const float* A2, const float* P, const float* alpha_dev,
+                     float* C, int64_t rows, int b, float* Zclr, int64_t zrows);
 int aser_gemm_small_f32(aser_ctx* ctx, float* A, int64_t lda, const float* B, int64_t ldb,
                         float* C, int64_t ldc, int64_t rows, int k, int c, int64_t clear_rows = 0, bool transposed = false);

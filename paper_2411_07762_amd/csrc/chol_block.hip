@@ -62,8 +62,9 @@ __device__ __forceinline__ void trailing_tile(float* As, int o, int ti, int tc, 
 
 __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t ld, int b, float* Rinv, int32_t* info,
                                                               int32_t pivot_base, int clear_d, const float* Lmul,
-                                                              float* Cmul, int with_beta) {
+                                                              float* Cmul, float* beta_out, const int* gate) {
     extern __shared__ __align__(16) float sm[];
+    if (gate && *gate == 0) return;
     float* As = sm;                      // working matrix, upper triangle -> R
     float* Xs = As + kN * kP;            // R^-1 (upper), zero elsewhere
     float* Ys = Xs + kN * kP;            // 96 x 32 scratch, then 64 words that take masked-off stores
@@ -73,8 +74,29 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
     // 16 x 16 tile roles of this lane
     const int t_i = lane & 15, t_q = lane >> 4;
 
-    // all global loads of a thread are issued before the first LDS store
-    {
+    // all global loads of a thread are issued before the first LDS store; 16-byte loads when the block allows it
+    const bool vec = (((uintptr_t)D | (uintptr_t)Rinv) & 15) == 0 && (ld & 3) == 0 && (b & 3) == 0;
+    if (vec) {
+        constexpr int kPer = kN * kN / 4 / kThreads;
+        float4 v[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int t = tid + u * kThreads, i = t >> 5, k = (t & 31) * 4;
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k + 3 >= i && k < b && i < b) v[u] = *(const float4*)(D + (int64_t)i * ld + k);
+        }
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int t = tid + u * kThreads, i = t >> 5, k = (t & 31) * 4;
+            const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bool in = k + q >= i && k + q < b && i < b;
+                As[i * kP + k + q] = in ? e[q] : ((k + q == i) ? 1.f : 0.f);
+                Xs[i * kP + k + q] = 0.f;
+            }
+        }
+    } else {
         constexpr int kPer = kN * kN / kThreads;
         float v[kPer];
 #pragma unroll
@@ -233,19 +255,58 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
         }
     }
 
-    // write out: R above the diagonal, R^T below it (or zeros over the input when clear_d), and R^-1
-    for (int t = tid; t < b * kN; t += kThreads) {
-        const int i = t >> 7, k = t & 127;
-        if (k < b) {
-            D[(int64_t)i * ld + k] = clear_d ? 0.f : ((k >= i) ? As[i * kP + k] : As[k * kP + i]);
-            Rinv[i * b + k] = (k >= i) ? Xs[i * kP + k] : 0.f;
+    // write out: R on and above the diagonal (or zeros over the whole input when clear_d; the part below the
+    // diagonal is otherwise left as it is), and R^-1
+    if (vec) {
+        for (int t = tid; t < b * (kN / 4); t += kThreads) {
+            const int i = t >> 5, k = (t & 31) * 4;
+            if (k >= b) continue;
+            float r[4], x[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                r[q] = (clear_d || k + q < i) ? 0.f : As[i * kP + k + q];
+                x[q] = (k + q >= i) ? Xs[i * kP + k + q] : 0.f;
+            }
+            float* drow = D + (int64_t)i * ld + k;
+            if (clear_d || k >= i) *(float4*)drow = make_float4(r[0], r[1], r[2], r[3]);
+            else if (k + 3 >= i) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (k + q >= i) drow[q] = r[q];
+            }
+            *(float4*)(Rinv + i * b + k) = make_float4(x[0], x[1], x[2], x[3]);
+        }
+    } else {
+        for (int t = tid; t < b * kN; t += kThreads) {
+            const int i = t >> 7, k = t & 127;
+            if (k < b) {
+                if (clear_d || k >= i) D[(int64_t)i * ld + k] = clear_d ? 0.f : As[i * kP + k];
+                Rinv[i * b + k] = (k >= i) ? Xs[i * kP + k] : 0.f;
+            }
+        }
+    }
+    if (!Lmul && !beta_out) return;
+    // ---- optional: the momentum coefficient of the subspace iteration, -(0.9 s^2 / 2)^2 with s the smallest
+    // diagonal entry of R, and whether the diagonal of R spans more than a factor of 64
+    if (beta_out) {
+        float smin = 3.0e38f, smax = 0.f;
+        if (tid < b) smin = smax = 1.0f / fabsf(Xs[tid * kP + tid]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            smin = fminf(smin, __shfl_xor(smin, o, 64));
+            smax = fmaxf(smax, __shfl_xor(smax, o, 64));
+        }
+        if (lane == 0 && wave < 2) { Ys[wave] = smin; Ys[2 + wave] = smax; }
+        __syncthreads();
+        if (tid == 0) {
+            const float s = fminf(Ys[0], Ys[1]), hbeta = 0.45f * s * s;
+            beta_out[0] = -hbeta * hbeta;
+            ((int*)beta_out)[1] = (fmaxf(Ys[2], Ys[3]) > 64.f * s) ? 1 : 0;
         }
     }
     if (!Lmul) return;
 
-    // ---- optional: Cmul = alpha Lmul R^-1 for an upper triangular b x b Lmul (ld = b), with R^-1 still
-    // in LDS.  with_beta: alpha = -(0.9 s^2 / 2)^2, s = the smallest diagonal entry of R (the momentum
-    // coefficient of the subspace iteration); else alpha = 1.
+    // ---- optional: Cmul = Lmul R^-1 for an upper triangular b x b Lmul (ld = b), with R^-1 still in LDS
     __syncthreads();                                      // everyone has read R out of As
     {
         constexpr int kPer = kN * kN / kThreads;
@@ -261,18 +322,7 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
             As[i * kP + k] = v[u];
         }
     }
-    float alpha = 1.f;
-    if (with_beta) {
-        float sdiag = 3.0e38f;
-        if (tid < b) sdiag = 1.0f / fabsf(Xs[tid * kP + tid]);
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) sdiag = fminf(sdiag, __shfl_xor(sdiag, o, 64));
-        if (lane == 0) Ys[wave] = sdiag;
-        __syncthreads();
-        sdiag = fminf(Ys[0], Ys[1]);
-        const float hbeta = 0.45f * sdiag * sdiag;
-        alpha = -hbeta * hbeta;
-    }
+    const float alpha = 1.f;
     __syncthreads();
     // 36 upper tiles of 16 x 16, longest k range first: tile (ti, tj) needs k in [16 ti, 16 tj + 16)
     for (int job = wave; job < 36; job += kWaves) {
@@ -296,7 +346,7 @@ __global__ __launch_bounds__(kThreads) void chol_block_kernel(float* D, int64_t 
 }  // namespace
 
 int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int32_t* info, int32_t pivot_base, bool clear_d,
-                    const float* Lmul, float* Cmul, bool with_beta) {
+                    const float* Lmul, float* Cmul, float* beta_out, const int* gate) {
     if (b <= 0 || b > kN) ASER_FAIL(ctx, ASER_ERR_SHAPE, "chol_block: block size out of range");
     static bool attr_set[16] = {false};
     const size_t lds = (size_t)(2 * kN * kP + 96 * kPY + 64) * sizeof(float);
@@ -305,6 +355,6 @@ int aser_chol_block(aser_ctx* ctx, float* D, int64_t ld, int b, float* Rinv, int
         attr_set[ctx->device] = true;
     }
     hipLaunchKernelGGL(chol_block_kernel, dim3(1), dim3(kThreads), lds, ctx->stream, D, ld, b, Rinv, info, pivot_base,
-                       clear_d ? 1 : 0, Lmul, Cmul, with_beta ? 1 : 0);
+                       clear_d ? 1 : 0, Lmul, Cmul, beta_out, gate);
     return aser_check_launch(ctx, "chol_block");
 }

@@ -208,12 +208,14 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(float* __restrict__ A, 
     }
 }
 
-// C (rows x b) = A1 B1 + A2 B2 for two tall blocks and two b x b factors (A2 null: one term), b a
-// multiple of 4 up to 128, all leading dimensions b.  After they have been read, the rows of A1 and
-// the first zrows rows of Zclr (may be null) are cleared: both are accumulation targets of the
-// products that follow.  Same staging as gemm_small_kernel, one term after the other.
+// C (rows x b) = (A1 + alpha A2 P) B1 for two tall blocks and two b x b factors (A2 null: C = A1 B1), alpha read
+// from device memory; b a multiple of 4 up to 128, all leading dimensions b.  After they have been read, the rows
+// of A1 and the first zrows rows of Zclr (may be null) are cleared: both are accumulation targets of the products
+// that follow.  Same staging as gemm_small_kernel: A2 P first, then the sum goes back to LDS as the left operand
+// of the second product.
 __global__ __launch_bounds__(256) void combine_kernel(float* __restrict__ A1, const float* __restrict__ B1,
-                                                      const float* __restrict__ A2, const float* __restrict__ B2,
+                                                      const float* __restrict__ A2, const float* __restrict__ P,
+                                                      const float* __restrict__ alpha_dev,
                                                       float* __restrict__ C, int64_t rows, int b,
                                                       float* __restrict__ Zclr, int64_t zrows) {
     extern __shared__ __align__(16) float gs_sm[];
@@ -223,18 +225,25 @@ __global__ __launch_bounds__(256) void combine_kernel(float* __restrict__ A1, co
     const int64_t r0 = (int64_t)blockIdx.x * kGsRows;
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
     float acc[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-    for (int term = 0; term < 2; ++term) {
-        const float* A = term ? A2 : A1;
-        const float* B = term ? B2 : B1;
-        if (!A) break;
+    // this thread's 1 x 8 piece of A1 (the columns it will own in the sum), read before A1 is cleared
+    float4 u0 = zero4, u1 = zero4;
+    const int64_t gr = r0 + ty;
+    if (gr < rows && 8 * tx < b) {
+        u0 = *(const float4*)(A1 + gr * b + 8 * tx);
+        if (8 * tx + 4 < b) u1 = *(const float4*)(A1 + gr * b + 8 * tx + 4);
+    }
+    const float alpha = A2 ? *alpha_dev : 0.f;
+    for (int term = A2 ? 0 : 1; term < 2; ++term) {
+        const float* A = term ? nullptr : A2;
+        const float* B = term ? B1 : P;
         float4 av[2], bv[16];
+        if (A) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
-            av[u] = zero4;
-            if (r0 + r < rows && k4 < b) av[u] = *(const float4*)(A + (r0 + r) * b + k4);
+            for (int u = 0; u < 2; ++u) {
+                const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
+                av[u] = zero4;
+                if (r0 + r < rows && k4 < b) av[u] = *(const float4*)(A + (r0 + r) * b + k4);
+            }
         }
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
@@ -242,13 +251,30 @@ __global__ __launch_bounds__(256) void combine_kernel(float* __restrict__ A1, co
             bv[u] = zero4;
             if (kk < b && c4 < b) bv[u] = *(const float4*)(B + (int64_t)kk * b + c4);
         }
-        if (term) __syncthreads();                      // the first term's readers are done with the stages
+        __syncthreads();                                // the previous product's readers (and the readers of A1) are done
+        if (A) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
-            *(float4*)(As + r * kGsPitch + k4) = av[u];
-            if (!term && r0 + r < rows && k4 < b) *(float4*)(A1 + (r0 + r) * b + k4) = zero4;
-            if (!term && Zclr && r0 + r < zrows && k4 < b) *(float4*)(Zclr + (r0 + r) * b + k4) = zero4;
+            for (int u = 0; u < 2; ++u) {
+                const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
+                *(float4*)(As + r * kGsPitch + k4) = av[u];
+            }
+        } else {
+            // left operand of the second product: A1 + alpha (A2 P), this thread's 1 x 8 piece
+            if (A2) {
+                u0.x = fmaf(alpha, acc[0], u0.x); u0.y = fmaf(alpha, acc[1], u0.y);
+                u0.z = fmaf(alpha, acc[2], u0.z); u0.w = fmaf(alpha, acc[3], u0.w);
+                u1.x = fmaf(alpha, acc[4], u1.x); u1.y = fmaf(alpha, acc[5], u1.y);
+                u1.z = fmaf(alpha, acc[6], u1.z); u1.w = fmaf(alpha, acc[7], u1.w);
+            }
+            *(float4*)(As + ty * kGsPitch + 8 * tx) = u0;
+            *(float4*)(As + ty * kGsPitch + 8 * tx + 4) = u1;
+            // the two accumulation targets are clear again
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
+                if (r0 + r < rows && k4 < b) *(float4*)(A1 + (r0 + r) * b + k4) = zero4;
+                if (Zclr && r0 + r < zrows && k4 < b) *(float4*)(Zclr + (r0 + r) * b + k4) = zero4;
+            }
         }
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
@@ -256,6 +282,8 @@ __global__ __launch_bounds__(256) void combine_kernel(float* __restrict__ A1, co
             *(float4*)(Bs + kk * kGsPitch + c4) = bv[u];
         }
         __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
         const float* arow = As + ty * kGsPitch;
         const float* bcol = Bs + 8 * tx;
 #pragma unroll 4
@@ -273,7 +301,6 @@ __global__ __launch_bounds__(256) void combine_kernel(float* __restrict__ A1, co
             }
         }
     }
-    const int64_t gr = r0 + ty;
     if (gr < rows) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -315,13 +342,14 @@ int aser_gemm_small_f32(aser_ctx* ctx, float* A, int64_t lda, const float* B, in
     return aser_check_launch(ctx, "gemm_small");
 }
 
-int aser_combine_f32(aser_ctx* ctx, float* A1, const float* B1, const float* A2, const float* B2, float* C, int64_t rows,
-                     int b, float* Zclr, int64_t zrows) {
+int aser_combine_f32(aser_ctx* ctx, float* A1, const float* B1, const float* A2, const float* P, const float* alpha_dev,
+                     float* C, int64_t rows, int b, float* Zclr, int64_t zrows) {
     if (rows <= 0) return ASER_OK;
     if (b <= 0 || b > 128 || (b & 3)) ASER_FAIL(ctx, ASER_ERR_SHAPE, "combine: need 0 < b <= 128, b % 4 == 0");
-    if (((uintptr_t)A1 & 15) || ((uintptr_t)B1 & 15) || ((uintptr_t)A2 & 15) || ((uintptr_t)B2 & 15) || ((uintptr_t)C & 15) ||
+    if (((uintptr_t)A1 & 15) || ((uintptr_t)B1 & 15) || ((uintptr_t)A2 & 15) || ((uintptr_t)P & 15) || ((uintptr_t)C & 15) ||
         ((uintptr_t)Zclr & 15))
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "combine: operands must be 16-byte aligned");
+    if (A2 && (!P || !alpha_dev)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "combine: the second term needs its factor and its coefficient");
     static bool attr_set[16] = {false};
     const size_t lds = (size_t)(kGsRows + 128) * kGsPitch * sizeof(float);
     if (ctx->device >= 0 && ctx->device < 16 && !attr_set[ctx->device]) {
@@ -329,7 +357,7 @@ int aser_combine_f32(aser_ctx* ctx, float* A1, const float* B1, const float* A2,
         attr_set[ctx->device] = true;
     }
     const int64_t cover = (Zclr && zrows > rows) ? zrows : rows;
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)ceil_div64(cover, kGsRows)), dim3(256), lds, ctx->stream, A1, B1, A2, B2,
-                       C, rows, b, Zclr, zrows);
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)ceil_div64(cover, kGsRows)), dim3(256), lds, ctx->stream, A1, B1, A2, P,
+                       alpha_dev, C, rows, b, Zclr, zrows);
     return aser_check_launch(ctx, "combine");
 }

@@ -478,6 +478,7 @@ template <int IN, int BM, int BN, bool FAST>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_tn_kernel(GemmArgs g) {
     extern __shared__ uint4 smem[];
     constexpr int BK = InTraits<IN>::BK;
+    if (g.gate && *g.gate == 0) return;
     const int64_t tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
     int64_t ti, tj;
     const int64_t t = blockIdx.x;

@@ -12,14 +12,16 @@
 //
 // The subspace iteration carries a momentum term (the heavy-ball acceleration of the power method,
 // in block form): with X_k = Q_k C_k the un-normalised iterates, X_{k+1} = (A A^T) X_k - beta X_{k-1}.
-// In terms of the orthonormal blocks and the triangular factors of the two Cholesky-QR steps of
-// iteration k (A^T Q_k = Z R_z, then Y = Q_{k+1} R_q):
-//     Y = A Z - beta Q_{k-1} P_k R_z^-1,      P_{k+1} = R_z^-1 R_q^-1,
-// so the extra work is two products of b x b triangular matrices (done by the factorisation
-// kernel while R^-1 is still in LDS) and a second term in the tall-times-small product that applies
-// R_z^-1: Y = (A Zt) R_z^-1 + Q_{k-1} (-beta P_k R_z^-1) in one kernel, which also clears the two
-// accumulation targets it has read.  beta = (0.9 s^2 / 2)^2
-// with s the smallest diagonal entry of R_z: s^2 stays below the b-th eigenvalue of A A^T, which
+// In terms of the orthonormal blocks, with any invertible R~ that makes Zt R~^-1 well conditioned and the
+// Cholesky-QR step Y = Q_{k+1} R_q:
+//     Y = (A Zt + beta' Q_{k-1} P_k) R~^-1,   Zt = A^T Q_k,   P_{k+1} = R~^-1 R_q^-1,   beta' = -beta,
+// formed by one kernel from the two tall blocks and the two b x b factors (it also clears the two
+// accumulation targets it has read); Z = Zt R~^-1 itself is never formed.  R~ is the Cholesky factor of
+// Zt^T Zt (a second Cholesky-QR) in the first iterations, while the subspace still turns, and then only in
+// every other iteration: between two refreshes the factor of the previous iteration serves (the iterate is
+// the same in exact arithmetic, R~ only keeps the columns of A Zt R~^-1 from collapsing onto the leading
+// directions, and Zt of consecutive iterations differ by the convergence error).  beta = (0.9 s^2 / 2)^2
+// with s the smallest diagonal entry of R~: s^2 stays below the b-th eigenvalue of A A^T, which
 // keeps every wanted direction (eigenvalue above 2 sqrt(beta)) in the amplified regime.  On the
 // bulk of a quantisation-error spectrum this reaches in 10 iterations what the plain iteration
 // needs about 16 for; the excess over the optimal whitened error halves with every iteration.
@@ -48,7 +50,9 @@ __global__ void lead_columns_kernel(const float* __restrict__ T, int64_t m, int6
 }
 
 // Start block: uniform values in [-1, 1) from a counter-based hash of (seed, index).
-__global__ void random_block_kernel(float* Q, int64_t total, uint32_t seed) {
+// Also resets the two status words of the solver (thread 0).
+__global__ void random_block_kernel(float* Q, int64_t total, uint32_t seed, double* res2, int32_t* qr) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) { *res2 = 0.0; *qr = 0; }
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
         const uint32_t h = mix32((uint32_t)i * 0x9E3779B9U + mix32(seed + (uint32_t)(i >> 32)));
         Q[i] = (float)(h >> 8) * (1.0f / 8388608.0f) - 1.0f;
@@ -119,10 +123,9 @@ size_t aser_reconstruct_workspace(int64_t m, int64_t n, int r, const aser_svd_op
 
 namespace {
 
-// C += A^T B with K split over workgroups (fp32 atomics); `clear` zeroes C first.
-int gemm_tn_atomic(aser_ctx* ctx, int form, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
-                   int64_t M, int64_t N, int64_t K, int bm, int bn, bool clear, bool upper_only = false) {
-    if (clear) ASER_TRY(aser_fill_f32(ctx, C, M, N, ldc, 0.f));
+// Arguments of C += A^T B with K split over workgroups (fp32 atomics).
+GemmArgs atomic_args(int form, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+                     int64_t M, int64_t N, int64_t K, int bm, int bn, bool upper_only = false) {
     GemmArgs g{};
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.Ct = nullptr; g.ldct = 0;
     g.M = M; g.N = N; g.K = K; g.alpha = 1.f;
@@ -134,7 +137,14 @@ int gemm_tn_atomic(aser_ctx* ctx, int form, const float* A, int64_t lda, const f
     const int64_t tiles = ceil_div64(M, bm) * ceil_div64(N, bn);
     const int64_t ksteps = ceil_div64(K, 32);
     g.k_parts = aser_split_k_parts(tiles, ksteps, tiles <= 4 ? 4 : 8, (double)(bm * bn) / (128.0 * 128.0));
-    return aser_gemm_tn(ctx, g);
+    return g;
+}
+
+// C += A^T B with K split over workgroups (fp32 atomics); `clear` zeroes C first.
+int gemm_tn_atomic(aser_ctx* ctx, int form, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+                   int64_t M, int64_t N, int64_t K, int bm, int bn, bool clear, bool upper_only = false) {
+    if (clear) ASER_TRY(aser_fill_f32(ctx, C, M, N, ldc, 0.f));
+    return aser_gemm_tn(ctx, atomic_args(form, A, lda, B, ldb, C, ldc, M, N, K, bm, bn, upper_only));
 }
 
 // The factorisation kernel reports a non-positive pivot with atomicMin(info, base + column + 1); the
@@ -143,12 +153,12 @@ constexpr int32_t kPivotBase = -1000;
 
 // out (rows x b) = Y R^-1 with R^T R = Y^T Y (Cholesky-QR); R^-1 is left in Rinv.  Mb must be zero on
 // entry and is zero again on return.  The first clear_rows rows of Y are cleared after they have
-// been read (0: Y is left alone).  Lmul / Cmul / with_beta: the factorisation kernel also leaves
-// Cmul = alpha Lmul R^-1 (see aser_chol_block); both null: nothing.
+// been read (0: Y is left alone).  Lmul / Cmul: the factorisation kernel also leaves Cmul = Lmul R^-1
+// (see aser_chol_block); both null: nothing.
 int chol_qr(aser_ctx* ctx, int form, float* Y, float* out, int64_t rows, int64_t clear_rows, int b, float* Mb, float* Rinv,
-            int32_t* info, const float* Lmul = nullptr, float* Cmul = nullptr, bool with_beta = false) {
+            int32_t* info, const float* Lmul = nullptr, float* Cmul = nullptr) {
     ASER_TRY(gemm_tn_atomic(ctx, form, Y, b, Y, b, Mb, b, b, b, rows, 128, 128, false, /*upper_only=*/true));
-    ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rinv, info, kPivotBase, /*clear_d=*/true, Lmul, Cmul, with_beta));
+    ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rinv, info, kPivotBase, /*clear_d=*/true, Lmul, Cmul));
     return aser_gemm_small_f32(ctx, Y, b, Rinv, b, out, b, rows, b, b, clear_rows);
 }
 
@@ -216,14 +226,11 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         const size_t ex = aser_exact_workspace(m, n, r);
         if (ctx->ws_bytes < ex + 256 + kAserWsTail)
             ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "error_reconstruct: workspace too small (%zu needed)", ex + 256 + kAserWsTail);
-        double* err2_dev = (double*)(ws + ex);
-        ASER_TRY(aser_exact_reconstruct(ctx, T, m, n, ldt, S, lds, r, L_A, L_B, sigma, err2_dev));
-        double h_err2 = 0.0;
+        ASER_TRY(aser_exact_reconstruct(ctx, T, m, n, ldt, S, lds, r, L_A, L_B, sigma, &aser_status_dev(ctx)->res2));
         AserPending pend;
-        ASER_HIP(ctx, hipMemcpyAsync(&h_err2, err2_dev, 8, hipMemcpyDeviceToHost, ctx->stream));
-        ASER_TRY(aser_fetch_pending(ctx, &pend));
-        ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        ASER_TRY(aser_sync_status(ctx, &pend));
         ASER_TRY(aser_report_pending(ctx, pend, "error_reconstruct"));
+        const double h_err2 = pend.res2;
         if (!(h_err2 >= 0.0) || h_err2 > 1e300)
             ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE, "error_reconstruct: non-finite values in T or S");
         if (err) *err = sqrt(h_err2);
@@ -244,11 +251,12 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     float* Uhat = (float*)(sm + 2 * bb);
     float* Rq_inv = (float*)(sm + 3 * bb);
     float* Pm = (float*)(sm + 4 * bb);
-    float* Bm = (float*)(sm + 5 * bb);
+    float* beta_dev = (float*)(sm + 5 * bb);               // the momentum coefficient beta' (one float) and, behind it,
+    const int* gate_dev = (const int*)(beta_dev + 1);      // whether the next iteration has to renew R~ (see iterate)
     sm += 3 * bb;                                          // the scalars and the r-wide blocks follow the six matrices
     float* lambda = (float*)(sm + 3 * bb);                 // b floats
-    double* normA2 = (double*)(sm + 3 * bb + 1024);
-    int32_t* info = (int32_t*)(sm + 3 * bb + 2048);
+    double* normA2 = &aser_status_dev(ctx)->res2;          // both in the status block that the one copy at the end brings to the host
+    int32_t* info = &aser_status_dev(ctx)->qr;
     int32_t* cluster = (int32_t*)(sm + 3 * bb + 3072);
     float* tri = (float*)(sm + 3 * bb + 4096);             // 384 floats
     const size_t b128 = align_up((size_t)b * 128 * 4, 256);
@@ -281,7 +289,7 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     {
         const int64_t total = m * (int64_t)b;
         const int blocks = (int)(ceil_div64(total, 256) < 2048 ? ceil_div64(total, 256) : 2048);
-        hipLaunchKernelGGL(random_block_kernel, dim3(blocks), dim3(256), 0, ctx->stream, Qacc, total, p.seed);
+        hipLaunchKernelGGL(random_block_kernel, dim3(blocks), dim3(256), 0, ctx->stream, Qacc, total, p.seed, normA2, info);
         ASER_TRY(aser_check_launch(ctx, "random_block"));
         if (f > 0) {
             // graded start: the unquantized outlier columns of T first (their span holds the largest left
@@ -299,15 +307,23 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     auto iterate = [&](int count) -> int {
         for (int c = 0; c < count; ++c, ++done) {
             const bool it = done > 0;                    // momentum term present from the second iteration on
-            ASER_TRY(gemm_tn_atomic(ctx, form, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // Zt = A^T Q_k = Z R_z
-            // R_z^-1 (Z itself is never formed); from the second iteration on also Bm = -beta P_k R_z^-1
-            ASER_TRY(gemm_tn_atomic(ctx, form, Zt, b, Zt, b, Mb, b, b, b, n, 128, 128, false, /*upper_only=*/true));
-            ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rz_inv, info, kPivotBase, /*clear_d=*/true, it ? Pm : nullptr, it ? Bm : nullptr, true));
+            // R~ from this iteration's Zt; in the odd iterations from the fourth on only if the last factor's
+            // diagonal spans more than a factor of 64 (the factorisation kernel left that decision in gate_dev:
+            // with a wide spread the columns of Zt R~^-1 for a stale R~ drift apart faster than the next
+            // Cholesky-QR tolerates), otherwise the previous iteration's factor serves and both kernels return at once
+            const int* gate = (done < 3 || (done & 1) == 0) ? nullptr : gate_dev;
+            ASER_TRY(gemm_tn_atomic(ctx, form, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // Zt = A^T Q_k
+            {
+                GemmArgs gz = atomic_args(form, Zt, b, Zt, b, Mb, b, b, b, n, 128, 128, /*upper_only=*/true);
+                gz.gate = gate;
+                ASER_TRY(aser_gemm_tn(ctx, gz));
+                ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rz_inv, info, kPivotBase, /*clear_d=*/true, nullptr, nullptr, beta_dev, gate));
+            }
             ASER_TRY(gemm_tn_atomic(ctx, form, At, m, Zt, b, Qraw, b, m, b, n, bmA, bnB, false));   // A Zt
-            // A Z + momentum term = (A Zt) R_z^-1 + Q_{k-1} Bm; Qraw and Zt are zero again afterwards
-            ASER_TRY(aser_combine_f32(ctx, Qraw, Rz_inv, it ? Qold : nullptr, Bm, Qacc, m, b, Zt, n));
-            // = Q_{k+1} R_q, into the old block; also P_{k+1} = R_z^-1 R_q^-1
-            ASER_TRY(chol_qr(ctx, form, Qacc, Qold, m, 0, b, Mb, Rq_inv, info, Rz_inv, Pm, false));
+            // (A Zt + beta' Q_{k-1} P_k) R~^-1; Qraw and Zt are zero again afterwards
+            ASER_TRY(aser_combine_f32(ctx, Qraw, Rz_inv, it ? Qold : nullptr, Pm, beta_dev, Qacc, m, b, Zt, n));
+            // = Q_{k+1} R_q, into the old block; also P_{k+1} = R~^-1 R_q^-1
+            ASER_TRY(chol_qr(ctx, form, Qacc, Qold, m, 0, b, Mb, Rq_inv, info, Rz_inv, Pm));
             { float* t = Qold; Qold = Qcur; Qcur = t; }
         }
         return ASER_OK;
@@ -353,14 +369,11 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
     ASER_TRY(iterate(p.iters));
     ASER_TRY(finish());
     {
-        double h_res2 = 0.0;
-        int32_t h_qr = 0;
-        AserPending pend;                                    // status words of calls that did not synchronise
-        ASER_HIP(ctx, hipMemcpyAsync(&h_res2, normA2, 8, hipMemcpyDeviceToHost, ctx->stream));
-        ASER_HIP(ctx, hipMemcpyAsync(&h_qr, info, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
-        ASER_TRY(aser_fetch_pending(ctx, &pend));
-        ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        AserPending pend;                                    // with the status words of calls that did not synchronise
+        ASER_TRY(aser_sync_status(ctx, &pend));
         ASER_TRY(aser_report_pending(ctx, pend, "error_reconstruct"));
+        const double h_res2 = pend.res2;
+        const int32_t h_qr = pend.qr;
         if (h_qr < 0 || !(h_res2 >= 0.0) || h_res2 > 1e300)
             ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE,
                       "error_reconstruct: the Cholesky-QR orthogonalisation broke down (pivot %d of a block Gram matrix is not "

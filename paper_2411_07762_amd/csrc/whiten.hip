@@ -179,8 +179,7 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
     }
     ctx->pending_info_dev = info_dev;
     AserPending pend;
-    ASER_TRY(aser_fetch_pending(ctx, &pend));
-    ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    ASER_TRY(aser_sync_status(ctx, &pend));
     *info = (pend.pivot == INT_MAX) ? 0 : pend.pivot;
     return aser_report_pending(ctx, pend, "whiten");
 }
