@@ -25,6 +25,8 @@
 // mode, also lo = bf16(x - hi) (three products hi hi + hi lo + lo hi per fp32 product; the activation
 // codes are exact in bf16, so P needs two).  The plain mode uses hi alone, as an inference kernel that
 // keeps the factors in 16-bit would.
+#include <type_traits>
+
 #include "aser_internal.h"
 
 namespace {
@@ -276,6 +278,295 @@ __global__ __launch_bounds__(256) void cf_main_kernel(FwdArgs g) {
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same product for layers of at least 256 tokens x 256 outputs, without a register stage: a workgroup
+// (4 waves, 2 x 2, one per SIMD) owns 256 tokens x 256 outputs, all 256 accumulator registers of a wave hold
+// its 128 x 128 part.  Per step 64 channels: global_load_lds_dwordx4 copies 16-byte chunks of the code rows
+// straight into LDS (a wavefront instruction fills 1 KB of consecutive LDS; every lane picks the chunk it
+// fetches, which gives the XOR swizzle of chunk_off), a ring of four stages keeps three steps of loads in
+// flight, one barrier per step.  int8 rows are 64 bytes per step and feed the MFMA through one 16-byte read
+// per operand; packed int4 rows are 32 bytes per step, a lane reads the 8 bytes of its 16 channels and widens
+// them in registers to (even channels, odd channels) x 2 as 16 q bytes, and the activation operand gets the same
+// channel order from four byte permutes.  The loads are inline assembly for the reason given at the Gram
+// kernel: the compiler would make every LDS read wait for all LDS-direct loads in flight.
+// Workgroup b runs on XCD b % 8; the tiles are numbered so that an XCD works on consecutive (token tile,
+// output tile) pairs: its 32 workgroups share two token tiles and one sweep over the weight codes per step.
+__device__ uint4 g_fwd_zero[4];
+
+constexpr int kDmaTM = 256, kDmaTN = 256, kDmaStages = 4;
+
+template <bool W4, bool SPLIT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void cf_dma_kernel(FwdArgs g, int tiles_n, int64_t tiles_total) {
+    extern __shared__ __align__(16) char smem[];
+    constexpr int A_BYTES = kDmaTM * 64, B_ROW = W4 ? 32 : 64, B_BYTES = kDmaTN * B_ROW, STAGE = A_BYTES + B_BYTES;
+    constexpr int NLB = W4 ? 2 : 4;                       // LDS-direct loads of the weight slab per wave and stage (4 for the activations)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+    const int64_t per_xcd = (tiles_total + 7) / 8;
+    const int64_t tile = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= tiles_total) return;
+    const int64_t T0 = (tile / tiles_n) * kDmaTM, O0 = (tile % tiles_n) * kDmaTN;
+
+    // ---- fetch roles.  Activations: instruction t of this wave is slab rows 16 (4 wave + t) + lane / 4, chunk
+    // slot lane % 4.  Weights (int8) alike; packed int4: rows 32 (2 wave + t) + lane / 2, slot lane % 2.
+    const char* zero = (const char*)g_fwd_zero;
+    const char* gp[2][4];
+    int64_t gstep[2][4];
+    bool tail_ok[2];                                      // the lane's chunk exists in a last step of 32 channels
+    {
+        const int ca = (lane & 3) ^ ((lane >> 4) & 3);
+        tail_ok[0] = ca < 2;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int64_t row = T0 + 16 * (4 * wave + t) + (lane >> 2);
+            const bool ok = row < g.rows;
+            gp[0][t] = ok ? (const char*)g.xq + row * g.n + 16 * ca : zero;
+            gstep[0][t] = ok ? 64 : 0;
+        }
+        if (W4) {
+            const int cb = (lane & 1) ^ ((lane >> 4) & 1);
+            tail_ok[1] = cb < 1;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int64_t row = O0 + 32 * (2 * wave + (t & 1)) + (lane >> 1);
+                const bool ok = row < g.m && t < 2;
+                gp[1][t] = ok ? (const char*)g.wq + row * (g.n / 2) + 16 * cb : zero;
+                gstep[1][t] = ok ? 32 : 0;
+            }
+        } else {
+            tail_ok[1] = ca < 2;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int64_t row = O0 + 16 * (4 * wave + t) + (lane >> 2);
+                const bool ok = row < g.m;
+                gp[1][t] = ok ? (const char*)g.wq + row * g.n + 16 * ca : zero;
+                gstep[1][t] = ok ? 64 : 0;
+            }
+        }
+    }
+    const uint32_t ring = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+    auto issue_one = [&](int64_t step, int op, int t, bool tail) {
+        const char* src = gp[op][t];
+        if (tail && !tail_ok[op]) src = zero;
+        const uint32_t dst = ring + (uint32_t)(step & (kDmaStages - 1)) * STAGE +
+                             (op ? A_BYTES + (NLB * wave + t) * 1024 : (4 * wave + t) * 1024);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst), "v"(src) : "memory", "m0");
+        gp[op][t] += gstep[op][t];
+    };
+    const int64_t nsteps = (g.n + 63) / 64;
+    auto issue_all = [&](int64_t step) {
+        const bool tail = 64 * (step + 1) > g.n;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) issue_one(step, 0, t, tail);
+#pragma unroll
+        for (int t = 0; t < NLB; ++t) issue_one(step, 1, t, tail);
+    };
+
+    // ---- operand read offsets inside a stage for the first 32-channel slice; the second slice is the
+    // neighbouring chunk pair: offset ^ 32 (^ 16 for packed int4)
+    int offa[4], offb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        offa[i] = chunk_off(wm0 + 32 * i + (lane & 31), lane >> 5);
+        const int brow = wn0 + 32 * i + (lane & 31);
+        offb[i] = A_BYTES + (W4 ? brow * 32 + (((brow >> 3) & 1) << 4) + 8 * (lane >> 5) : chunk_off(brow, lane >> 5));
+    }
+    constexpr int kXorA = 32, kXorB = W4 ? 16 : 32;
+    struct RawB { uint32_t x, y, z, w; };
+    auto read_a = [&](const char* st, int sl, int i) { return *(const v4i_t*)(st + (offa[i] ^ (sl ? kXorA : 0))); };
+    auto read_b = [&](const char* st, int sl, int i) {
+        v4i_t r;
+        if (W4) {
+            const uint2 q = *(const uint2*)(st + (offb[i] ^ (sl ? kXorB : 0)));
+            r = v4i_t{(int)q.x, (int)q.y, 0, 0};
+        } else {
+            r = *(const v4i_t*)(st + (offb[i] ^ (sl ? kXorB : 0)));
+        }
+        return r;
+    };
+    // channel order of the widened int4 operand: (0 2 4 6)(1 3 5 7)(8 10 12 14)(9 11 13 15) of the lane's 16
+    auto conv_a = [&](v4i_t a) {
+        if (!W4) return a;
+        return v4i_t{(int)__builtin_amdgcn_perm((uint32_t)a.y, (uint32_t)a.x, 0x06040200u), (int)__builtin_amdgcn_perm((uint32_t)a.y, (uint32_t)a.x, 0x07050301u),
+                     (int)__builtin_amdgcn_perm((uint32_t)a.w, (uint32_t)a.z, 0x06040200u), (int)__builtin_amdgcn_perm((uint32_t)a.w, (uint32_t)a.z, 0x07050301u)};
+    };
+    auto conv_b = [&](v4i_t b) {
+        if (!W4) return b;
+        const uint32_t w0 = (uint32_t)b.x, w1 = (uint32_t)b.y;
+        return v4i_t{(int)((w0 << 4) & 0xF0F0F0F0u), (int)(w0 & 0xF0F0F0F0u), (int)((w1 << 4) & 0xF0F0F0F0u), (int)(w1 & 0xF0F0F0F0u)};
+    };
+
+    v16i_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+    // vmcnt values: one stage of this wave's loads is 4 + NLB instructions
+    auto wait_loads = [&](int stages_in_flight) {
+        if (W4) {
+            if (stages_in_flight == 2) __builtin_amdgcn_s_waitcnt(0x0F7C);          // vmcnt(12)
+            else if (stages_in_flight == 1) __builtin_amdgcn_s_waitcnt(0x0F76);     // vmcnt(6)
+            else __builtin_amdgcn_s_waitcnt(0x0F70);
+        } else {
+            if (stages_in_flight == 2) __builtin_amdgcn_s_waitcnt(0x4F70);          // vmcnt(16)
+            else if (stages_in_flight == 1) __builtin_amdgcn_s_waitcnt(0x0F78);     // vmcnt(8)
+            else __builtin_amdgcn_s_waitcnt(0x0F70);
+        }
+    };
+    for (int64_t s = 0; s < kDmaStages - 1 && s < nsteps; ++s) issue_all(s);
+    wait_loads(nsteps >= 3 ? 2 : (nsteps == 2 ? 1 : 0));                            // stage 0 landed
+    __syncthreads();
+    v4i_t a0[4], b0[4], a1[4], b1[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a0[i] = conv_a(read_a(smem, 0, i));
+        b0[i] = conv_b(read_b(smem, 0, i));
+    }
+    auto step = [&](int64_t s, auto steady_tag) {
+        constexpr bool STEADY = decltype(steady_tag)::value;
+        const char* st = smem + (int)(s & (kDmaStages - 1)) * STAGE;
+        const char* sn = smem + (int)((s + 1) & (kDmaStages - 1)) * STAGE;
+        const bool more = STEADY || s + 1 < nsteps;
+        const bool fetch = STEADY || s + kDmaStages - 1 < nsteps;
+        const bool tail = !STEADY && fetch && 64 * (s + kDmaStages) > g.n;
+        // slice 0: the raw operands of slice 1 are read under rows 0 and 1 and put in order under rows 2 and 3
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[i], b0[j], acc[i][j], 0, 0, 0);
+                if (i == 0) a1[j] = read_a(st, 1, j);
+                if (i == 1) b1[j] = read_b(st, 1, j);
+                if (i == 2) a1[j] = conv_a(a1[j]);
+                if (i == 3) b1[j] = conv_b(b1[j]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // slice 1: row 0 covers the wait and the barrier and the reads of the next step's slice 0, row 1 the
+        // rest of those reads and the loads of stage s + 3, rows 2 and 3 the reordering of what was read
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[i], b1[j], acc[i][j], 0, 0, 0);
+                if (i == 0 && j == 1 && more) {
+                    // stage s + 1 has landed when at most the loads of stage s + 2 are in flight
+                    wait_loads((STEADY || s + 2 < nsteps) ? 1 : 0);
+                    __syncthreads();                      // everyone's share landed; stage s - 1 is free
+                }
+                if (more && i == 0 && j >= 2) { a0[2 * (j - 2)] = read_a(sn, 0, 2 * (j - 2)); a0[2 * (j - 2) + 1] = read_a(sn, 0, 2 * (j - 2) + 1); }
+                if (more && i == 1 && j < 2) { b0[2 * j] = read_b(sn, 0, 2 * j); b0[2 * j + 1] = read_b(sn, 0, 2 * j + 1); }
+                if (fetch && i == 1 && j >= 2) { issue_one(s + kDmaStages - 1, 0, 2 * (j - 2), tail); issue_one(s + kDmaStages - 1, 0, 2 * (j - 2) + 1, tail); }
+                if (fetch && i == 2 && j < 2) {
+                    if (W4) issue_one(s + kDmaStages - 1, 1, j, tail);
+                    else { issue_one(s + kDmaStages - 1, 1, 2 * j, tail); issue_one(s + kDmaStages - 1, 1, 2 * j + 1, tail); }
+                }
+                if (more && i == 2 && j >= 2) { a0[2 * (j - 2)] = conv_a(a0[2 * (j - 2)]); a0[2 * (j - 2) + 1] = conv_a(a0[2 * (j - 2) + 1]); }
+                if (more && i == 3) b0[j] = conv_b(b0[j]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    const int64_t full_steps = g.n / 64;
+    int64_t s = 0;
+    for (; s + kDmaStages - 1 < full_steps; ++s) step(s, std::true_type{});
+    for (; s < nsteps; ++s) step(s, std::false_type{});
+
+    // ---- epilogue.  acc[i][j][e] is (token, output) = (32 i + 8 (e / 4) + 4 (lane / 32) + e % 4, 32 j + lane % 32)
+    // of the wave's part.  The scaled values take the place of the integer sums (the same registers); the tile's
+    // token scales and output scales go through LDS (free after the barrier: every wave is out of the loop).
+    const float wfix = W4 ? (1.0f / 16.0f) : 1.0f;
+    __syncthreads();
+    float* sxl = (float*)smem;
+    float* swl = sxl + kDmaTM;
+    sxl[tid] = (T0 + tid < g.rows) ? g.xs[T0 + tid] : 0.f;
+    swl[tid] = (O0 + tid < g.m) ? g.ws[O0 + tid] * wfix : 0.f;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float sx[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sx[e] = sxl[wm0 + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float cw = swl[wn0 + 32 * j + (lane & 31)];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = __float_as_int((float)acc[i][j][e] * (sx[e] * cw));
+        }
+    }
+    if (g.P) {
+#pragma nounroll
+        for (int kk = 0; kk < g.r_pad; kk += 16) {
+            const int kq = kk + 8 * (lane >> 5);
+            bf16x8_t ph[4], pl[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t row = T0 + wm0 + 32 * i + (lane & 31);
+                f32x4_t p0 = {0.f, 0.f, 0.f, 0.f}, p1 = {0.f, 0.f, 0.f, 0.f};
+                if (row < g.rows) {
+                    p0 = *(const f32x4_t*)(g.P + row * g.ldp + kq);
+                    p1 = *(const f32x4_t*)(g.P + row * g.ldp + kq + 4);
+                }
+                const float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                uint32_t h[4], l[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t h0 = bf16_rne(pv[2 * q]), h1 = bf16_rne(pv[2 * q + 1]);
+                    h[q] = h0 | (h1 << 16);
+                    l[q] = SPLIT ? (bf16_rne(pv[2 * q] - __uint_as_float(h0 << 16)) | (bf16_rne(pv[2 * q + 1] - __uint_as_float(h1 << 16)) << 16)) : 0u;
+                }
+                ph[i] = __builtin_bit_cast(bf16x8_t, make_uint4(h[0], h[1], h[2], h[3]));
+                pl[i] = __builtin_bit_cast(bf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t col = O0 + wn0 + 32 * j + (lane & 31);
+                uint4 vh = make_uint4(0u, 0u, 0u, 0u), vl = make_uint4(0u, 0u, 0u, 0u);
+                if (col < g.m) {
+                    vh = *(const uint4*)(g.la_hi + col * g.r_pad + kq);
+                    if (SPLIT) vl = *(const uint4*)(g.la_lo + col * g.r_pad + kq);
+                }
+                const bf16x8_t lh = __builtin_bit_cast(bf16x8_t, vh), ll = __builtin_bit_cast(bf16x8_t, vl);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    f32x16_t y = __builtin_bit_cast(f32x16_t, acc[i][j]);
+                    if (SPLIT) {
+                        y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pl[i], lh, y, 0, 0, 0);
+                        y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph[i], ll, y, 0, 0, 0);
+                    }
+                    y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ph[i], lh, y, 0, 0, 0);
+                    acc[i][j] = __builtin_bit_cast(v16i_t, y);
+                }
+            }
+        }
+    }
+    // a tile that lies inside the output takes the store loop without the per-element tests
+    const bool inner = T0 + kDmaTM <= g.rows && O0 + kDmaTN <= g.m;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t row0 = T0 + wm0 + 32 * i + 4 * (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t col = O0 + wn0 + 32 * j + (lane & 31);
+            float* yb = g.Y + row0 * g.ldy + col;
+            if (inner) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) yb[(int64_t)(8 * (e >> 2) + (e & 3)) * g.ldy] = __int_as_float(acc[i][j][e]);
+            } else if (col < g.m) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int dr = 8 * (e >> 2) + (e & 3);
+                    if (row0 + dr < g.rows) yb[(int64_t)dr * g.ldy] = __int_as_float(acc[i][j][e]);
+                }
+            }
+        }
+    }
+}
+
 // P[t][k] = s_t sum_i xq[t][i] L_B[k][i] for 128 tokens per workgroup (32 per wave) and all r_pad
 // columns (RB blocks of 32).  L_B comes as bf16 planes [r_pad][n] (hi, lo).  Per step 64 channels: the
 // code tile as in the main kernel (no reordering), the L_B tiles as 16-byte chunks of 8 bf16 with an
@@ -412,6 +703,18 @@ int launch_main(aser_ctx* ctx, const FwdArgs& g) {
     return aser_check_launch(ctx, "compensated_forward");
 }
 
+template <bool W4, bool SPLIT>
+int launch_dma(aser_ctx* ctx, const FwdArgs& g) {
+    static bool done[16] = {false};
+    constexpr int lds = kDmaStages * (kDmaTM * 64 + kDmaTN * (W4 ? 32 : 64));
+    auto kern = cf_dma_kernel<W4, SPLIT>;
+    ASER_TRY(set_lds_once(ctx, kern, lds, done));
+    const int64_t tn = ceil_div64(g.m, kDmaTN), total = tn * ceil_div64(g.rows, kDmaTM);
+    const int64_t per_xcd = ceil_div64(total, 8);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * per_xcd)), dim3(256), lds, ctx->stream, g, (int)tn, total);
+    return aser_check_launch(ctx, "compensated_forward");
+}
+
 template <int RB, bool SPLIT>
 int launch_down(aser_ctx* ctx, const int8_t* xq, const float* xs, int64_t rows, int64_t n, const uint16_t* lbh,
                 const uint16_t* lbl, float* P, int64_t ldp) {
@@ -489,6 +792,10 @@ extern "C" int aser_compensated_forward(aser_ctx* ctx, const int8_t* x_codes, co
         g.P = P; g.ldp = rp; g.la_hi = lah; g.la_lo = lal; g.r_pad = rp;
     }
     const bool w4 = layout == ASER_CODES_INT4_PACKED;
+    if (rows >= kDmaTM && m >= kDmaTN) {                 // the 256 x 256 tiles without a register stage
+        if (w4) return split ? launch_dma<true, true>(ctx, g) : launch_dma<true, false>(ctx, g);
+        return split ? launch_dma<false, true>(ctx, g) : launch_dma<false, false>(ctx, g);
+    }
     if (w4) return split ? launch_main<true, true>(ctx, g) : launch_main<true, false>(ctx, g);
     return split ? launch_main<false, true>(ctx, g) : launch_main<false, false>(ctx, g);
 }
