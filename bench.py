@@ -304,7 +304,8 @@ def extras(ctx, aser, torch, spec, buf, W, X, reps):
         ops = 2.0 * spec.tokens * spec.n * spec.m
         res["compensated_forward"] = {
             "ms": fw, "tokens": spec.tokens,
-            "roofline": {"kernel": "cf_main_kernel (int8 MFMA, int4 weight codes widened in flight)", "bound": "mfma",
+            "roofline": {"kernel": "cf_dma_kernel (int8 MFMA, 256 x 256 tiles, LDS-direct loads, int4 weight codes widened after the LDS read)",
+                         "bound": "mfma",
                          "achieved": ops / (fw["no_compensation"] * 1e-3) / 1e12, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                          "frac": ops / (fw["no_compensation"] * 1e-3) / 1e12 / INT8_PEAK_TOPS},
             "overhead_of_rank_r_branch": {"measured_bf16": fw["rank_r_bf16"] / fw["no_compensation"] - 1.0,
@@ -479,6 +480,17 @@ def main():
     act_gbs = act_bytes / (act_ms * 1e-3) / 1e9
     del act_codes
 
+    # What a loop of nothing but MFMA instructions reaches on this device (the clock drops under that load):
+    # one workgroup of four wavefronts per compute unit, which is the occupancy of the Gram kernel and of the
+    # inference kernel (256 accumulator registers per lane), and four per compute unit.
+    mfma_loop = {}
+    for name, kind in (("bf16", 0), ("int8", 1)):
+        for wgs in (1, 4):
+            st, rate = aser.aser_mfma_rate_probe(ctx, kind, wgs, 4000)
+            ctx.check(st)
+            mfma_loop["%s_%dwg_per_cu" % (name, wgs)] = round(rate, 1)
+    mfma_loop["unit"] = "TFLOP/s (bf16, v_mfma_f32_32x32x16_bf16), TOP/s (int8, v_mfma_i32_32x32x32_i8)"
+
     _, svd_block, svd_iters = aser.aser_svd_plan(spec.m, spec.n, spec.r)
     traffic = measured_traffic()
     # fp32-class contractions of the path: algorithmic flops, and executed MFMA flops (three bf16 products per
@@ -512,7 +524,9 @@ def main():
                      "bound": "mfma", "achieved": gram_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gram_tflops / BF16_PEAK_TFLOPS,
                      "traffic": traffic.get("gram_dma_kernel") if spec.name == "c1" else None,
-                     "algorithmic_flops_per_launch": gram_flops, "avg_launch_ms": gram_ms},
+                     "algorithmic_flops_per_launch": gram_flops, "avg_launch_ms": gram_ms,
+                     "frac_of_mfma_only_loop": gram_tflops / mfma_loop["bf16_1wg_per_cu"]},
+        "mfma_only_loop": mfma_loop,
         "roofline_hbm": {"kernel": "rtn_kernel (per-channel RTN + target T)", "bound": "hbm", "achieved": rtn_gbs,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rtn_gbs / HBM_PEAK_GBS,
                          "traffic": traffic.get("rtn_kernel") if spec.name == "c1" else None,
@@ -523,6 +537,9 @@ def main():
     }
     if not args.no_extras:
         out["beyond_calibration"] = extras(ctx, aser, torch, spec, buf, Ws[0], X, reps)
+        fwd = out["beyond_calibration"].get("compensated_forward")
+        if fwd:
+            fwd["roofline"]["frac_of_mfma_only_loop"] = fwd["roofline"]["achieved"] / mfma_loop["int8_1wg_per_cu"]
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(spec)

@@ -281,6 +281,14 @@ int aser_compensated_forward(aser_ctx* ctx, const int8_t* x_codes, const float* 
                              const float* L_A, const float* L_B, int32_t r, int32_t lowrank_split,
                              float* Y, int64_t ldy);
 
+/* Measurement aid (not a step of the method; bench.py reports it next to the nominal peaks): the rate, in
+ * 10^12 operations per second, that a loop of nothing but MFMA instructions reaches on the device, with
+ * `workgroups_per_cu` (1 .. 4) workgroups of four wavefronts per compute unit and `iters` rounds of 16
+ * instructions per wavefront.  kind 0: v_mfma_f32_32x32x16_bf16, kind 1: v_mfma_i32_32x32x32_i8.  The hot
+ * kernels of this library hold 256 accumulator registers per lane and so run one workgroup per compute unit.
+ * Needs 256 KiB of workspace per workgroup_per_cu; synchronises the stream. */
+int aser_mfma_rate_probe(aser_ctx* ctx, int32_t kind, int32_t workgroups_per_cu, int32_t iters, double* tops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -38,7 +38,7 @@ EXPORTS = (
     "aser_whiten", "aser_error_reconstruct", "aser_svd_plan", "aser_quantize_act_rtn",
     "aser_spectrum_workspace_bytes", "aser_singular_values", "aser_select_rank", "aser_effective_rank",
     "aser_output_error_workspace_bytes", "aser_layer_output_error",
-    "aser_forward_workspace_bytes", "aser_compensated_forward",
+    "aser_forward_workspace_bytes", "aser_compensated_forward", "aser_mfma_rate_probe",
 )
 
 
@@ -116,6 +116,8 @@ def load_library() -> ctypes.CDLL:
     lib.aser_compensated_forward.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i64, vp, vp, i32, i32, vp, i64]
     lib.aser_quantize_act_rtn.restype = ctypes.c_int
     lib.aser_quantize_act_rtn.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, vp, i32, vp, vp]
+    lib.aser_mfma_rate_probe.restype = ctypes.c_int
+    lib.aser_mfma_rate_probe.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_double)]
     _lib = lib
     return lib
 
@@ -351,6 +353,13 @@ def aser_compensated_forward(ctx: Context, x_codes, x_scales, w_codes, layout: i
 
 
 # ----------------------------------------------------------------------------------- one layer, end to end
+def aser_mfma_rate_probe(ctx: Context, kind: int, workgroups_per_cu: int = 1, iters: int = 20000):
+    """(status, 10^12 operations per second) of a pure MFMA loop: kind 0 bf16, kind 1 int8 (measurement aid)."""
+    out = ctypes.c_double(0.0)
+    st = ctx._lib.aser_mfma_rate_probe(ctx.handle, int(kind), int(workgroups_per_cu), int(iters), ctypes.byref(out))
+    return st, out.value
+
+
 class LayerBuffers:
     """Device buffers of one layer's calibration state and outputs (allocated with torch)."""
 
