@@ -131,7 +131,7 @@ struct CodeStage {
 struct FwdArgs {
     const int8_t* xq; const float* xs; int64_t rows, n;
     const void* wq; const float* ws; int64_t m;
-    const float* P; int64_t ldp;                 // rows x r_pad fp32 (null: no rank-r branch)
+    const uint16_t* p_hi; const uint16_t* p_lo;   // P = s_t (x_q L_B^T) as bf16 planes, rows x r_pad (p_hi null: no rank-r branch)
     const uint16_t* la_hi; const uint16_t* la_lo; int r_pad;   // m x r_pad bf16 planes
     float* Y; int64_t ldy;
 };
@@ -218,28 +218,20 @@ __global__ __launch_bounds__(256) void cf_main_kernel(FwdArgs g) {
                 y[i][j][e] = (float)acc[i][j][e] * (sx * cw);
             }
     }
-    if (g.P) {
+    if (g.p_hi) {
         for (int kk = 0; kk < g.r_pad; kk += 16) {
             const int kq = kk + 8 * (lane >> 5);
             bf16x8_t ph[2], pl[2], lh[4], ll[4];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int64_t row = T0 + wm * 64 + 32 * i + (lane & 31);
-                f32x4_t p0 = {0.f, 0.f, 0.f, 0.f}, p1 = {0.f, 0.f, 0.f, 0.f};
+                uint4 vh = make_uint4(0u, 0u, 0u, 0u), vl = make_uint4(0u, 0u, 0u, 0u);
                 if (row < g.rows) {
-                    p0 = *(const f32x4_t*)(g.P + row * g.ldp + kq);
-                    p1 = *(const f32x4_t*)(g.P + row * g.ldp + kq + 4);
+                    vh = *(const uint4*)(g.p_hi + row * g.r_pad + kq);
+                    if (SPLIT) vl = *(const uint4*)(g.p_lo + row * g.r_pad + kq);
                 }
-                const float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-                uint32_t h[4], l[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t h0 = bf16_rne(pv[2 * q]), h1 = bf16_rne(pv[2 * q + 1]);
-                    h[q] = h0 | (h1 << 16);
-                    l[q] = bf16_rne(pv[2 * q] - __uint_as_float(h0 << 16)) | (bf16_rne(pv[2 * q + 1] - __uint_as_float(h1 << 16)) << 16);
-                }
-                ph[i] = __builtin_bit_cast(bf16x8_t, make_uint4(h[0], h[1], h[2], h[3]));
-                pl[i] = __builtin_bit_cast(bf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
+                ph[i] = __builtin_bit_cast(bf16x8_t, vh);
+                pl[i] = __builtin_bit_cast(bf16x8_t, vl);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -498,7 +490,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             for (int e = 0; e < 16; ++e) acc[i][j][e] = __float_as_int((float)acc[i][j][e] * (sx[e] * cw));
         }
     }
-    if (g.P) {
+    if (g.p_hi) {
 #pragma nounroll
         for (int kk = 0; kk < g.r_pad; kk += 16) {
             const int kq = kk + 8 * (lane >> 5);
@@ -506,21 +498,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int64_t row = T0 + wm0 + 32 * i + (lane & 31);
-                f32x4_t p0 = {0.f, 0.f, 0.f, 0.f}, p1 = {0.f, 0.f, 0.f, 0.f};
+                uint4 vh = make_uint4(0u, 0u, 0u, 0u), vl = make_uint4(0u, 0u, 0u, 0u);
                 if (row < g.rows) {
-                    p0 = *(const f32x4_t*)(g.P + row * g.ldp + kq);
-                    p1 = *(const f32x4_t*)(g.P + row * g.ldp + kq + 4);
+                    vh = *(const uint4*)(g.p_hi + row * g.r_pad + kq);
+                    if (SPLIT) vl = *(const uint4*)(g.p_lo + row * g.r_pad + kq);
                 }
-                const float pv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-                uint32_t h[4], l[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t h0 = bf16_rne(pv[2 * q]), h1 = bf16_rne(pv[2 * q + 1]);
-                    h[q] = h0 | (h1 << 16);
-                    l[q] = SPLIT ? (bf16_rne(pv[2 * q] - __uint_as_float(h0 << 16)) | (bf16_rne(pv[2 * q + 1] - __uint_as_float(h1 << 16)) << 16)) : 0u;
-                }
-                ph[i] = __builtin_bit_cast(bf16x8_t, make_uint4(h[0], h[1], h[2], h[3]));
-                pl[i] = __builtin_bit_cast(bf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
+                ph[i] = __builtin_bit_cast(bf16x8_t, vh);
+                pl[i] = __builtin_bit_cast(bf16x8_t, vl);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -574,7 +558,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 template <int RB, bool SPLIT>
 __global__ __launch_bounds__(256) void cf_down_kernel(const int8_t* __restrict__ xq, const float* __restrict__ xs, int64_t rows,
                                                       int64_t n, const uint16_t* __restrict__ lb_hi,
-                                                      const uint16_t* __restrict__ lb_lo, float* __restrict__ P, int64_t ldp) {
+                                                      const uint16_t* __restrict__ lb_lo, uint16_t* __restrict__ p_hi,
+                                                      uint16_t* __restrict__ p_lo, int64_t ldp) {
     extern __shared__ __align__(16) char smem[];
     constexpr int RP = 32 * RB;                              // r_pad
     constexpr int A_BYTES = 128 * 64, B_BYTES = RP * 128;    // 64 bf16 per row
@@ -662,7 +647,12 @@ __global__ __launch_bounds__(256) void cf_down_kernel(const int8_t* __restrict__
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int64_t row = T0 + wave * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-            if (row < rows) P[row * ldp + col] = acc[j][e] * xs[row];
+            if (row < rows) {
+                const float pv = acc[j][e] * xs[row];
+                const uint32_t h = bf16_rne(pv);
+                p_hi[row * ldp + col] = (uint16_t)h;
+                if (SPLIT) p_lo[row * ldp + col] = (uint16_t)bf16_rne(pv - __uint_as_float(h << 16));
+            }
         }
     }
 }
@@ -717,12 +707,12 @@ int launch_dma(aser_ctx* ctx, const FwdArgs& g) {
 
 template <int RB, bool SPLIT>
 int launch_down(aser_ctx* ctx, const int8_t* xq, const float* xs, int64_t rows, int64_t n, const uint16_t* lbh,
-                const uint16_t* lbl, float* P, int64_t ldp) {
+                const uint16_t* lbl, uint16_t* p_hi, uint16_t* p_lo, int64_t ldp) {
     static bool done[16] = {false};
     constexpr int lds = 128 * 64 + 2 * (32 * RB * 128);
     auto kern = cf_down_kernel<RB, SPLIT>;
     ASER_TRY(set_lds_once(ctx, kern, lds, done));
-    hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div64(rows, 128)), dim3(256), lds, ctx->stream, xq, xs, rows, n, lbh, lbl, P, ldp);
+    hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div64(rows, 128)), dim3(256), lds, ctx->stream, xq, xs, rows, n, lbh, lbl, p_hi, p_lo, ldp);
     return aser_check_launch(ctx, "compensated_forward_down");
 }
 
@@ -763,7 +753,8 @@ extern "C" int aser_compensated_forward(aser_ctx* ctx, const int8_t* x_codes, co
     g.Y = Y; g.ldy = ldy;
     if (r > 0) {
         char* ws = (char*)ctx->ws;
-        float* P = (float*)(ws + pl.off_p);
+        uint16_t* p_hi = (uint16_t*)(ws + pl.off_p);          // two bf16 planes in the room of one fp32 matrix
+        uint16_t* p_lo = p_hi + (size_t)rows * pl.r_pad;
         uint16_t* lah = (uint16_t*)(ws + pl.off_lah);
         uint16_t* lal = (uint16_t*)(ws + pl.off_lal);
         uint16_t* lbh = (uint16_t*)(ws + pl.off_lbh);
@@ -782,14 +773,14 @@ extern "C" int aser_compensated_forward(aser_ctx* ctx, const int8_t* x_codes, co
             ASER_TRY(aser_check_launch(ctx, "split_bf16"));
         }
 #define ASER_DOWN(RB)                                                                                   \
-    (split ? launch_down<RB, true>(ctx, x_codes, x_scales, rows, n, lbh, lbl, P, rp)                    \
-           : launch_down<RB, false>(ctx, x_codes, x_scales, rows, n, lbh, lbl, P, rp))
+    (split ? launch_down<RB, true>(ctx, x_codes, x_scales, rows, n, lbh, lbl, p_hi, p_lo, rp)           \
+           : launch_down<RB, false>(ctx, x_codes, x_scales, rows, n, lbh, lbl, p_hi, p_lo, rp))
         if (rp == 32) ASER_TRY(ASER_DOWN(1));
         else if (rp == 64) ASER_TRY(ASER_DOWN(2));
         else if (rp == 96) ASER_TRY(ASER_DOWN(3));
         else ASER_TRY(ASER_DOWN(4));
 #undef ASER_DOWN
-        g.P = P; g.ldp = rp; g.la_hi = lah; g.la_lo = lal; g.r_pad = rp;
+        g.p_hi = p_hi; g.p_lo = p_lo; g.la_hi = lah; g.la_lo = lal; g.r_pad = rp;
     }
     const bool w4 = layout == ASER_CODES_INT4_PACKED;
     if (rows >= kDmaTM && m >= kDmaTN) {                 // the 256 x 256 tiles without a register stage
