@@ -189,6 +189,23 @@ def run_block(args):
             layer_ms[i] += ev[i].elapsed_time(ev[i + 1]) / args.steps
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
+    # W4A8 layer-output error of every layer (Sec. 5.3 error figure metric, relative to ||X W^T||_F) on a sample of
+    # its calibration tokens: with the factors, and for RTN alone
+    sample = 2048
+    w4a8 = {}
+    for spec, st, buf, W in layers:
+        ctx.ensure_workspace(aser.aser_output_error_workspace_bytes(spec.m, spec.n, sample, spec.r))
+        vals = {}
+        for comp in (True, False):
+            s_, e, yn = aser.aser_layer_output_error(ctx, W, st["X"][:sample], buf.mdiag, buf.codes, aser.ASER_CODES_INT4_PACKED,
+                                                     buf.scales, buf.L_A if comp else None, buf.L_B if comp else None,
+                                                     spec.r if comp else 0, 8)
+            ctx.check(s_)
+            vals["compensated" if comp else "rtn_only"] = e / yn
+        w4a8[spec.name] = vals
+    for spec, st, buf, W in layers:
+        ctx.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, spec.r))
+
     # the Gram kernel of the widest stream alone, for the roofline object
     spec, st, buf, _ = layers[-1]
     G2 = torch.zeros_like(buf.G)
@@ -215,6 +232,7 @@ def run_block(args):
                                "131072 bf16 tokens per input stream; W4 per-channel RTN, A8 per-token, r=64, f=32"},
         "layer_ms": {sp.name: round(ms, 3) for (sp, _, _, _), ms in zip(layers, layer_ms)},
         "whitened_error": {sp.name: e for (sp, _, _, _), e in zip(layers, errs)},
+        "w4a8_output_error_relative": {"sample_tokens": sample, "layers": w4a8},
         "roofline": {"kernel": "gram_dma_kernel (Gram update of the 14336-channel stream)", "bound": "mfma",
                      "achieved": gram_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gram_tflops / BF16_PEAK_TFLOPS, "traffic": None,
