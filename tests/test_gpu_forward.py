@@ -79,6 +79,12 @@ CASES = [
     ("r_not_multiple_of_32_a6", synth.mini("fw2", 600, 96, 700, r=40, f=4), 129, True, 6, 0),
     ("w8_tall", synth.mini("fw3", 700, 160, 900, x_dtype="f32", r=16, f=5, bits=8), 513, False, 8, 0),
     ("c1_shape_small", synth.CONFIGS["c1"].with_(m=768, n=1024, tokens=4096, r=64, f=16), 2048, True, 8, 0),
+    # the 256 x 256 tiles with LDS-direct loads: a last step of 32 channels with packed int4 and with int8 codes, fewer
+    # steps than the ring has stages, ragged tokens and outputs, a padded output
+    ("w4_half_step_at_the_end", synth.mini("fw4", 300, 352, 1400, r=24, f=5), 600, True, 8, 4),
+    ("w4_one_and_a_half_steps", synth.mini("fw5", 260, 96, 900, r=8, f=2), 700, True, 8, 0),
+    ("w8_half_a_step", synth.mini("fw6", 257, 32, 600, x_dtype="f32", r=8, f=1, bits=8), 257, False, 8, 0),
+    ("w8_two_steps_split_tiles", synth.mini("fw7", 513, 128, 1200, r=16, f=3, bits=8), 1025, False, 8, 0),
 ]
 
 
