@@ -508,6 +508,14 @@ def main():
             ctx.check(st)
             mfma_loop["%s_%dwg_per_cu" % (name, wgs)] = round(rate, 1)
     mfma_loop["unit"] = "TFLOP/s (bf16, v_mfma_f32_32x32x16_bf16), TOP/s (int8, v_mfma_i32_32x32x32_i8)"
+    # The same instructions with the operand traffic of a 256 x 256 tile around them and nothing else (32 KB of
+    # LDS-direct loads per 64-byte K step and workgroup, the fragment reads, one barrier): what moving the
+    # operands costs on this device, whatever the kernel does besides.
+    ctx.ensure_workspace((33 << 20) + (1 << 20))
+    for name, kind in (("bf16", 2), ("int8", 3)):
+        st, rate = aser.aser_mfma_rate_probe(ctx, kind, 1, 4000)
+        ctx.check(st)
+        mfma_loop["%s_with_operand_traffic" % name] = round(rate, 1)
 
     _, svd_block, svd_iters = aser.aser_svd_plan(spec.m, spec.n, spec.r)
     traffic = measured_traffic()
@@ -543,7 +551,8 @@ def main():
                      "frac": gram_tflops / BF16_PEAK_TFLOPS,
                      "traffic": traffic.get("gram_dma_kernel") if spec.name == "c1" else None,
                      "algorithmic_flops_per_launch": gram_flops, "avg_launch_ms": gram_ms,
-                     "frac_of_mfma_only_loop": gram_tflops / mfma_loop["bf16_1wg_per_cu"]},
+                     "frac_of_mfma_only_loop": gram_tflops / mfma_loop["bf16_1wg_per_cu"],
+                     "frac_of_mfma_loop_with_operand_traffic": gram_tflops / mfma_loop["bf16_with_operand_traffic"]},
         "mfma_only_loop": mfma_loop,
         "roofline_hbm": {"kernel": "rtn_kernel (per-channel RTN + target T)", "bound": "hbm", "achieved": rtn_gbs,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rtn_gbs / HBM_PEAK_GBS,
@@ -558,6 +567,7 @@ def main():
         fwd = out["beyond_calibration"].get("compensated_forward")
         if fwd:
             fwd["roofline"]["frac_of_mfma_only_loop"] = fwd["roofline"]["achieved"] / mfma_loop["int8_1wg_per_cu"]
+            fwd["roofline"]["frac_of_mfma_loop_with_operand_traffic"] = fwd["roofline"]["achieved"] / mfma_loop["int8_with_operand_traffic"]
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(spec)

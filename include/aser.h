@@ -286,7 +286,11 @@ int aser_compensated_forward(aser_ctx* ctx, const int8_t* x_codes, const float* 
  * `workgroups_per_cu` (1 .. 4) workgroups of four wavefronts per compute unit and `iters` rounds of 16
  * instructions per wavefront.  kind 0: v_mfma_f32_32x32x16_bf16, kind 1: v_mfma_i32_32x32x32_i8.  The hot
  * kernels of this library hold 256 accumulator registers per lane and so run one workgroup per compute unit.
- * Needs 256 KiB of workspace per workgroup_per_cu; synchronises the stream. */
+ * kind 2 (bf16) and kind 3 (int8): the same instructions with the operand traffic of a 256 x 256 tile with
+ * 64-byte K steps around them and nothing else (32 KB of LDS-direct loads per step and workgroup from a 32 MiB
+ * operand image that the call writes, 16 fragment reads per wavefront, one barrier); workgroups_per_cu must
+ * be 1.  Needs 256 KiB of workspace per workgroup_per_cu, kinds 2 and 3 another 32 MiB; synchronises the
+ * stream.  Errors: ASER_ERR_INVALID_ARG (kind, null), ASER_ERR_SHAPE, ASER_ERR_WORKSPACE. */
 int aser_mfma_rate_probe(aser_ctx* ctx, int32_t kind, int32_t workgroups_per_cu, int32_t iters, double* tops);
 
 #ifdef __cplusplus

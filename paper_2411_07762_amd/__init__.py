@@ -354,7 +354,8 @@ def aser_compensated_forward(ctx: Context, x_codes, x_scales, w_codes, layout: i
 
 # ----------------------------------------------------------------------------------- one layer, end to end
 def aser_mfma_rate_probe(ctx: Context, kind: int, workgroups_per_cu: int = 1, iters: int = 20000):
-    """(status, 10^12 operations per second) of a pure MFMA loop: kind 0 bf16, kind 1 int8 (measurement aid)."""
+    """(status, 10^12 operations per second) of a pure MFMA loop: kind 0 bf16, kind 1 int8; kinds 2 and 3: the
+    same with the operand traffic of a 256 x 256 tile around the instructions (measurement aid)."""
     out = ctypes.c_double(0.0)
     st = ctx._lib.aser_mfma_rate_probe(ctx.handle, int(kind), int(workgroups_per_cu), int(iters), ctypes.byref(out))
     return st, out.value

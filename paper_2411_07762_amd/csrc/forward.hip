@@ -277,9 +277,11 @@ __global__ __launch_bounds__(256) void cf_main_kernel(FwdArgs g) {
 // straight into LDS (a wavefront instruction fills 1 KB of consecutive LDS; every lane picks the chunk it
 // fetches, which gives the XOR swizzle of chunk_off), a ring of four stages keeps three steps of loads in
 // flight, one barrier per step.  int8 rows are 64 bytes per step and feed the MFMA through one 16-byte read
-// per operand; packed int4 rows are 32 bytes per step, a lane reads the 8 bytes of its 16 channels and widens
-// them in registers to (even channels, odd channels) x 2 as 16 q bytes, and the activation operand gets the same
-// channel order from four byte permutes.  The loads are inline assembly for the reason given at the Gram
+// per operand; packed int4 rows are 32 bytes per step and a lane reads 16 of them once per step: lane group
+// g = lane / 32 takes channels [32 g, 32 g + 32) of the step, the first 16 in the first MFMA slice and the other
+// 16 in the second (so the activation operand of slice sl is 16-byte chunk 2 g + sl of its row), widens each
+// half in registers to (even channels, odd channels) x 2 as 16 q bytes, and the activation operand gets the
+// same channel order from four byte permutes.  The loads are inline assembly for the reason given at the Gram
 // kernel: the compiler would make every LDS read wait for all LDS-direct loads in flight.
 // Workgroup b runs on XCD b % 8; the tiles are numbered so that an XCD works on consecutive (token tile,
 // output tile) pairs: its 32 workgroups share two token tiles and one sweep over the weight codes per step.
@@ -356,36 +358,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     };
 
     // ---- operand read offsets inside a stage for the first 32-channel slice; the second slice is the
-    // neighbouring chunk pair: offset ^ 32 (^ 16 for packed int4)
+    // neighbouring chunk pair of the activations: offset ^ 32 (int4 weights: the neighbouring chunk, offset ^ 16;
+    // the weight fragment of both slices comes with one read)
     int offa[4], offb[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        offa[i] = chunk_off(wm0 + 32 * i + (lane & 31), lane >> 5);
+        offa[i] = chunk_off(wm0 + 32 * i + (lane & 31), W4 ? 2 * (lane >> 5) : lane >> 5);
         const int brow = wn0 + 32 * i + (lane & 31);
-        offb[i] = A_BYTES + (W4 ? brow * 32 + (((brow >> 3) & 1) << 4) + 8 * (lane >> 5) : chunk_off(brow, lane >> 5));
+        offb[i] = A_BYTES + (W4 ? brow * 32 + (((lane >> 5) ^ ((brow >> 3) & 1)) << 4) : chunk_off(brow, lane >> 5));
     }
-    constexpr int kXorA = 32, kXorB = W4 ? 16 : 32;
+    constexpr int kXorA = W4 ? 16 : 32, kXorB = 32;
     struct RawB { uint32_t x, y, z, w; };
     auto read_a = [&](const char* st, int sl, int i) { return *(const v4i_t*)(st + (offa[i] ^ (sl ? kXorA : 0))); };
-    auto read_b = [&](const char* st, int sl, int i) {
-        v4i_t r;
-        if (W4) {
-            const uint2 q = *(const uint2*)(st + (offb[i] ^ (sl ? kXorB : 0)));
-            r = v4i_t{(int)q.x, (int)q.y, 0, 0};
-        } else {
-            r = *(const v4i_t*)(st + (offb[i] ^ (sl ? kXorB : 0)));
-        }
-        return r;
-    };
+    auto read_b = [&](const char* st, int sl, int i) { return *(const v4i_t*)(st + (W4 ? offb[i] : (offb[i] ^ (sl ? kXorB : 0)))); };
     // channel order of the widened int4 operand: (0 2 4 6)(1 3 5 7)(8 10 12 14)(9 11 13 15) of the lane's 16
     auto conv_a = [&](v4i_t a) {
         if (!W4) return a;
         return v4i_t{(int)__builtin_amdgcn_perm((uint32_t)a.y, (uint32_t)a.x, 0x06040200u), (int)__builtin_amdgcn_perm((uint32_t)a.y, (uint32_t)a.x, 0x07050301u),
                      (int)__builtin_amdgcn_perm((uint32_t)a.w, (uint32_t)a.z, 0x06040200u), (int)__builtin_amdgcn_perm((uint32_t)a.w, (uint32_t)a.z, 0x07050301u)};
     };
-    auto conv_b = [&](v4i_t b) {
+    auto conv_b = [&](v4i_t b, int sl) {
         if (!W4) return b;
-        const uint32_t w0 = (uint32_t)b.x, w1 = (uint32_t)b.y;
+        const uint32_t w0 = (uint32_t)(sl ? b.z : b.x), w1 = (uint32_t)(sl ? b.w : b.y);
         return v4i_t{(int)((w0 << 4) & 0xF0F0F0F0u), (int)(w0 & 0xF0F0F0F0u), (int)((w1 << 4) & 0xF0F0F0F0u), (int)(w1 & 0xF0F0F0F0u)};
     };
 
@@ -412,11 +406,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int64_t s = 0; s < kDmaStages - 1 && s < nsteps; ++s) issue_all(s);
     wait_loads(nsteps >= 3 ? 2 : (nsteps == 2 ? 1 : 0));                            // stage 0 landed
     __syncthreads();
-    v4i_t a0[4], b0[4], a1[4], b1[4];
+    v4i_t a0[4], b0[4], a1[4], b1[4], braw[4];            // braw: a step's packed int4 fragments (both slices in one read)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         a0[i] = conv_a(read_a(smem, 0, i));
-        b0[i] = conv_b(read_b(smem, 0, i));
+        braw[i] = read_b(smem, 0, i);
+        b0[i] = conv_b(braw[i], 0);
     }
     auto step = [&](int64_t s, auto steady_tag) {
         constexpr bool STEADY = decltype(steady_tag)::value;
@@ -432,9 +427,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             for (int j = 0; j < 4; ++j) {
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[i], b0[j], acc[i][j], 0, 0, 0);
                 if (i == 0) a1[j] = read_a(st, 1, j);
-                if (i == 1) b1[j] = read_b(st, 1, j);
+                if (!W4 && i == 1) b1[j] = read_b(st, 1, j);
                 if (i == 2) a1[j] = conv_a(a1[j]);
-                if (i == 3) b1[j] = conv_b(b1[j]);
+                if (W4 && i == 3) b1[j] = conv_b(braw[j], 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -451,14 +446,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                     __syncthreads();                      // everyone's share landed; stage s - 1 is free
                 }
                 if (more && i == 0 && j >= 2) { a0[2 * (j - 2)] = read_a(sn, 0, 2 * (j - 2)); a0[2 * (j - 2) + 1] = read_a(sn, 0, 2 * (j - 2) + 1); }
-                if (more && i == 1 && j < 2) { b0[2 * j] = read_b(sn, 0, 2 * j); b0[2 * j + 1] = read_b(sn, 0, 2 * j + 1); }
+                if (more && i == 1 && j < 2) {
+                    if (W4) { braw[2 * j] = read_b(sn, 0, 2 * j); braw[2 * j + 1] = read_b(sn, 0, 2 * j + 1); }
+                    else { b0[2 * j] = read_b(sn, 0, 2 * j); b0[2 * j + 1] = read_b(sn, 0, 2 * j + 1); }
+                }
                 if (fetch && i == 1 && j >= 2) { issue_one(s + kDmaStages - 1, 0, 2 * (j - 2), tail); issue_one(s + kDmaStages - 1, 0, 2 * (j - 2) + 1, tail); }
                 if (fetch && i == 2 && j < 2) {
                     if (W4) issue_one(s + kDmaStages - 1, 1, j, tail);
                     else { issue_one(s + kDmaStages - 1, 1, 2 * j, tail); issue_one(s + kDmaStages - 1, 1, 2 * j + 1, tail); }
                 }
                 if (more && i == 2 && j >= 2) { a0[2 * (j - 2)] = conv_a(a0[2 * (j - 2)]); a0[2 * (j - 2) + 1] = conv_a(a0[2 * (j - 2) + 1]); }
-                if (more && i == 3) b0[j] = conv_b(b0[j]);
+                if (W4 && more && i == 3) b0[j] = conv_b(braw[j], 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }

@@ -194,6 +194,17 @@ def test_forward_validation(ctx):
     assert aser.aser_forward_workspace_bytes(32768, 4096, 4096, 0) == 256
 
 
+def test_mfma_rate_probe_validation(ctx):
+    assert aser.aser_mfma_rate_probe(ctx, 4, 1, 100)[0] == aser.ASER_ERR_INVALID_ARG       # unknown kind
+    assert aser.aser_mfma_rate_probe(ctx, -1, 1, 100)[0] == aser.ASER_ERR_INVALID_ARG
+    assert aser.aser_mfma_rate_probe(ctx, 2, 2, 100)[0] == aser.ASER_ERR_SHAPE             # with operand traffic: one per compute unit
+    assert aser.aser_mfma_rate_probe(ctx, 0, 0, 100)[0] == aser.ASER_ERR_SHAPE             # workgroups per compute unit
+    assert aser.aser_mfma_rate_probe(ctx, 0, 5, 100)[0] == aser.ASER_ERR_SHAPE
+    assert aser.aser_mfma_rate_probe(ctx, 1, 1, 0)[0] == aser.ASER_ERR_SHAPE               # iterations
+    assert aser.aser_mfma_rate_probe(ctx, 1, 1, 100)[0] == aser.ASER_ERR_WORKSPACE         # nothing bound
+    assert aser.aser_mfma_rate_probe(ctx, 3, 1, 100)[0] == aser.ASER_ERR_WORKSPACE
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2411_07762_amd")
     for dirpath, _, files in os.walk(pkg):

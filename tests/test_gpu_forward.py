@@ -92,3 +92,23 @@ CASES = [
 def test_compensated_forward(name, spec, sample, packed, act_bits, pad):
     say("forward case %s m=%d n=%d tokens=%d r=%d" % (name, spec.m, spec.n, sample, spec.r))
     forward_case(name, spec, sample, packed, act_bits, pad)
+
+
+def test_mfma_rate_probe_runs():
+    """The measurement aid: a loop of nothing but MFMA instructions must land between a tenth of the nominal peak and
+    the nominal peak (2.5 PFLOP/s bf16, 5.0 POP/s int8); with the operand traffic of a tile around the instructions
+    it cannot be faster than without (5 % for the clock's wander between launches)."""
+    ctx = new_ctx()
+    ctx.ensure_workspace((33 << 20) + 4 * 256 * 1024 + 256)
+    for kind, peak in ((0, 2500.0), (1, 5000.0)):
+        alone = {}
+        for wgs in (1, 4):
+            st, rate = aser.aser_mfma_rate_probe(ctx, kind, wgs, 2000)
+            ctx.check(st)
+            say("MFMA-only loop kind %d, %d workgroup(s) per compute unit: %.0f T op/s" % (kind, wgs, rate))
+            assert 0.1 * peak < rate <= 1.001 * peak
+            alone[wgs] = rate
+        st, rate = aser.aser_mfma_rate_probe(ctx, kind + 2, 1, 2000)
+        ctx.check(st)
+        say("MFMA loop with operand traffic, kind %d: %.0f T op/s" % (kind + 2, rate))
+        assert 0.1 * peak < rate <= 1.05 * alone[1]
