@@ -258,6 +258,38 @@ def trace_summary(result_dir, note):
         print("%-96s %6d %12.1f %10.2f %6.2f" % (r[0][:96], r[1], r[2], r[3], r[4]))
 
 
+def clock_summary(result_dir, note):
+    """Prints, per MFMA-bound kernel of a `rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE` run, the average
+    duration and the shader clock it ran at: GRBM_GUI_ACTIVE counts the cycles a die (XCD) is busy and the tool
+    sums it over the 8 dies, so cycles / 8 / duration is the clock (kept under profiles/)."""
+    import collections
+    import glob
+    import sqlite3
+    dbs = sorted(glob.glob(os.path.join(result_dir, "**", "*_results.db"), recursive=True))
+    if not dbs:
+        raise SystemExit("no *_results.db under %s" % result_dir)
+    con = sqlite3.connect(dbs[-1])
+    dur = {r[0]: r[2] - r[1] for r in con.execute("select dispatch_id, start, end from kernels")}
+    agg = collections.OrderedDict()
+    for did, name, cn, v in con.execute("select dispatch_id, kernel_name, counter_name, value from counters_collection"):
+        if cn != "GRBM_GUI_ACTIVE" or did not in dur:
+            continue
+        e = agg.setdefault(did, [name, 0.0])
+        e[1] += v
+    per = collections.OrderedDict()
+    for did, (name, cyc) in agg.items():
+        if dur[did] < 100e3:                      # launches under 100 us: the counter's start and stop weigh too much
+            continue
+        per.setdefault(name, []).append((dur[did] * 1e-3, cyc / 8.0 / dur[did]))
+    print(note)
+    print("\nKernels of at least 100 us (clock = GRBM_GUI_ACTIVE / 8 / duration):")
+    print("%-100s %5s %10s %9s %9s %9s" % ("kernel", "calls", "avg_us", "GHz_avg", "GHz_min", "GHz_max"))
+    for name, v in sorted(per.items(), key=lambda kv: -sum(x[0] for x in kv[1])):
+        ghz = [x[1] for x in v]
+        print("%-100s %5d %10.1f %9.2f %9.2f %9.2f" % (name[:100], len(v), sum(x[0] for x in v) / len(v),
+                                                      sum(ghz) / len(ghz), min(ghz), max(ghz)))
+
+
 def extras(ctx, aser, torch, spec, buf, W, X, reps):
     """Timings of the rows beyond the calibration path, on the layer the step has just calibrated: the full
     spectrum with the rank rule of Eq. 9 and the effective rank of Eq. 3-4, the W4A8 layer-output error on a
@@ -329,6 +361,21 @@ def extras(ctx, aser, torch, spec, buf, W, X, reps):
             "overhead_of_rank_r_branch": {"measured_bf16": fw["rank_r_bf16"] / fw["no_compensation"] - 1.0,
                                           "measured_split": fw["rank_r_split"] / fw["no_compensation"] - 1.0,
                                           "paper_flops_ratio_2r_over_d": 2.0 * spec.r / spec.n}}
+        # Context, not a target and not part of the path: the vendor library's plain GEMMs of the same shapes
+        # through torch (no scales, no rank-r branch, int32 output for int8; the full X^T X, of which the Gram
+        # kernel computes the lower-triangle tiles).
+        lib = {}
+        try:
+            if X.dtype == torch.bfloat16:
+                ms_l = timed(lambda: torch.matmul(X.t(), X), 3)
+                lib["bf16_full_XtX"] = {"ms": ms_l, "tflops": 2.0 * spec.tokens * spec.n * spec.n / (ms_l * 1e-3) / 1e12}
+            wq8 = torch.randint(-127, 128, (spec.m, spec.n), dtype=torch.int8, device=dev)
+            ms_l = timed(lambda: torch._int_mm(xq, wq8.t()), 3)
+            lib["int8_x_wT_int32_out"] = {"ms": ms_l, "tops": ops / (ms_l * 1e-3) / 1e12}
+            del wq8
+        except Exception as exc:                          # an op the installed torch build lacks: report, do not fail
+            lib["unavailable"] = repr(exc)[:200]
+        res["library_gemm_same_shapes"] = lib
         del xq, Y
     return res
 
@@ -346,12 +393,16 @@ def main():
                     help="print the summary of the two counter runs (no GPU needed)")
     ap.add_argument("--trace-summary", nargs=2, metavar=("RESULT_DIR", "NOTE"),
                     help="print the per-kernel totals of a rocprofv3 --kernel-trace --stats run (no GPU needed)")
+    ap.add_argument("--clock-summary", nargs=2, metavar=("RESULT_DIR", "NOTE"),
+                    help="print per-kernel shader clocks of a rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE run (no GPU needed)")
     ap.add_argument("--no-extras", action="store_true", help="skip the timings of the rows beyond the calibration path")
     args = ap.parse_args()
     if args.traffic_summary:
         return traffic_summary(*args.traffic_summary)
     if args.trace_summary:
         return trace_summary(*args.trace_summary)
+    if args.clock_summary:
+        return clock_summary(*args.clock_summary)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus,
               file=sys.stderr)
