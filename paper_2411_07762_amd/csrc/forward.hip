@@ -47,16 +47,28 @@ __device__ __forceinline__ uint32_t bf16_rne(float x) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-// hi[i][j] = bf16(src[i][j]), lo[i][j] = bf16(src[i][j] - hi) for j < cols, 0 for cols <= j < cols_pad.
-__global__ __launch_bounds__(256) void split_bf16_kernel(const float* __restrict__ src, int64_t rows, int64_t cols, int64_t ld,
-                                                         int64_t cols_pad, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo) {
-    const int64_t total = rows * cols_pad;
+// Both factors as bf16 planes in one launch: hi = bf16(x), lo = bf16(x - hi).  L_A (m x r) goes to [m][r_pad]
+// with zero columns r .. r_pad, L_B (r x n) to [r_pad][n] with zero rows r .. r_pad.
+__global__ __launch_bounds__(256) void split_factors_kernel(const float* __restrict__ L_A, const float* __restrict__ L_B, int64_t m,
+                                                            int64_t n, int64_t r, int64_t r_pad, uint16_t* __restrict__ la_hi,
+                                                            uint16_t* __restrict__ la_lo, uint16_t* __restrict__ lb_hi,
+                                                            uint16_t* __restrict__ lb_lo) {
+    const int64_t ta = m * r_pad, total = ta + r_pad * n;
     for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
-        const int64_t i = t / cols_pad, j = t % cols_pad;
-        const float x = j < cols ? src[i * ld + j] : 0.f;
+        float x;
+        uint16_t *hi, *lo;
+        if (t < ta) {
+            const int64_t i = t / r_pad, j = t % r_pad;
+            x = j < r ? L_A[i * r + j] : 0.f;
+            hi = la_hi + t; lo = la_lo + t;
+        } else {
+            const int64_t u = t - ta, k = u / n;
+            x = k < r ? L_B[u] : 0.f;
+            hi = lb_hi + u; lo = lb_lo + u;
+        }
         const uint32_t h = bf16_rne(x);
-        hi[t] = (uint16_t)h;
-        lo[t] = (uint16_t)bf16_rne(x - __uint_as_float(h << 16));
+        *hi = (uint16_t)h;
+        *lo = (uint16_t)bf16_rne(x - __uint_as_float(h << 16));
     }
 }
 
@@ -549,69 +561,106 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
 }
 
-// P[t][k] = s_t sum_i xq[t][i] L_B[k][i] for 128 tokens per workgroup (32 per wave) and all r_pad
-// columns (RB blocks of 32).  L_B comes as bf16 planes [r_pad][n] (hi, lo).  Per step 64 channels: the
-// code tile as in the main kernel (no reordering), the L_B tiles as 16-byte chunks of 8 bf16 with an
-// XOR swizzle; codes become bf16 exactly (|q| <= 128) on their way into the MFMA.
+// P[t][k] = s_t sum_i xq[t][i] L_B[k][i] for 128 tokens per workgroup and all r_pad columns (RB blocks of
+// 32).  L_B comes as bf16 planes [r_pad][n] (hi, lo).  Per step 64 channels: the code tile as in the main
+// kernel (no reordering), the L_B tiles as 16-byte chunks of 8 bf16 with an XOR swizzle; codes become bf16
+// exactly (|q| <= 128) on their way into the MFMA.  The launch is one workgroup per compute unit for 32768
+// tokens, and a step is a chain of waits (tile stores, barrier, fragment reads, conversion, MFMA), so the
+// workgroup has eight wavefronts, two per SIMD: wavefront w takes tokens 32 (w % 4) .. + 32 and the 16-channel
+// slices 2 (w / 4), 2 (w / 4) + 1 of every step; the two halves of the sum meet in LDS at the end.  The loads
+// of step s + 3 are issued in step s (three register stages, the step loop unrolled by three so that they are
+// named at compile time), the LDS tiles are double buffered, one barrier per step.
+constexpr int kDownThreads = 512;
+
 template <int RB, bool SPLIT>
-__global__ __launch_bounds__(256) void cf_down_kernel(const int8_t* __restrict__ xq, const float* __restrict__ xs, int64_t rows,
-                                                      int64_t n, const uint16_t* __restrict__ lb_hi,
-                                                      const uint16_t* __restrict__ lb_lo, uint16_t* __restrict__ p_hi,
-                                                      uint16_t* __restrict__ p_lo, int64_t ldp) {
+__global__ __launch_bounds__(kDownThreads) void cf_down_kernel(const int8_t* __restrict__ xq, const float* __restrict__ xs, int64_t rows,
+                                                               int64_t n, const uint16_t* __restrict__ lb_hi,
+                                                               const uint16_t* __restrict__ lb_lo, uint16_t* __restrict__ p_hi,
+                                                               uint16_t* __restrict__ p_lo, int64_t ldp) {
     extern __shared__ __align__(16) char smem[];
     constexpr int RP = 32 * RB;                              // r_pad
     constexpr int A_BYTES = 128 * 64, B_BYTES = RP * 128;    // 64 bf16 per row
-    constexpr int BCH = RP * 8 / 256;                        // 16-byte chunks of a B plane per thread
-    char* sA = smem;
-    char* sBh = smem + A_BYTES;
-    char* sBl = sBh + B_BYTES;
+    constexpr int BUF = A_BYTES + 2 * B_BYTES;
+    constexpr int BCHUNKS = RP * 8;                          // 16-byte chunks of a B plane per step
+    constexpr int BCH = (BCHUNKS + kDownThreads - 1) / kDownThreads;
+    constexpr int kAhead = 3;
+    static_assert(2 * BUF >= 4 * RB * 16 * 64 * 4 + 128 * 4, "the partial sums of wavefronts 4 .. 7 and the token scales must fit the tile buffers");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tb = wave & 3, sh = wave >> 2;
     const int64_t T0 = (int64_t)blockIdx.x * 128;
-    CodeStage<STAGE_PLAIN, 1> sa;
-    sa.init(xq, T0, rows, n, tid);
+    // staging role: 16-byte chunk tid % 4 of code row tid / 4
+    const int srow = tid >> 2, sc = tid & 3;
+    const bool srow_ok = T0 + srow < rows;
+    const char* ap = (const char*)xq + (srow_ok ? T0 + srow : 0) * n + 16 * sc;
+    const uint32_t amask = srow_ok ? 0xFFFFFFFFu : 0u;       // rows past the end read row 0 and drop it
     f32x16_t acc[RB];
 #pragma unroll
     for (int j = 0; j < RB; ++j)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
-    uint4 bh[BCH], bl[BCH];
-    auto load_b = [&](int64_t k0) {
+    uint4 ar[kAhead], bh[kAhead][BCH], bl[kAhead][BCH];
+    // STEADY: all 64 channels of the step exist; the loads are unconditional (clamped addresses, the value
+    // dropped afterwards), so that the loop body is straight-line code and the compiler's counting of the
+    // loads in flight stays exact
+    auto fetch = [&](auto utag, int64_t s, auto steady_tag) {
+        constexpr int U = decltype(utag)::value;
+        constexpr bool STEADY = decltype(steady_tag)::value;
+        const int64_t k0 = s * 64;
+        if (STEADY) {
+            const uint4 v = *(const uint4*)(ap + k0);
+            ar[U] = make_uint4(v.x & amask, v.y & amask, v.z & amask, v.w & amask);
+        } else {
+            ar[U] = make_uint4(0u, 0u, 0u, 0u);
+            if (srow_ok && k0 + 16 * sc < n) ar[U] = *(const uint4*)(ap + k0);      // n % 32 == 0: a chunk of 16 is whole or absent
+        }
 #pragma unroll
         for (int u = 0; u < BCH; ++u) {
-            const int q = tid + 256 * u, row = q >> 3, c = q & 7;
+            const int q = tid + kDownThreads * u, c = q & 7;
+            const int row = (q >> 3) < RP ? (q >> 3) : RP - 1;
             const int64_t k = k0 + 8 * c;
-            bh[u] = make_uint4(0u, 0u, 0u, 0u);
-            bl[u] = make_uint4(0u, 0u, 0u, 0u);
-            if (k < n) {                                     // n % 32 == 0: a chunk of 8 is whole or absent
-                bh[u] = *(const uint4*)(lb_hi + (int64_t)row * n + k);
-                if (SPLIT) bl[u] = *(const uint4*)(lb_lo + (int64_t)row * n + k);
+            if (STEADY) {
+                bh[U][u] = *(const uint4*)(lb_hi + (int64_t)row * n + k);
+                if (SPLIT) bl[U][u] = *(const uint4*)(lb_lo + (int64_t)row * n + k);
+            } else {
+                bh[U][u] = make_uint4(0u, 0u, 0u, 0u);
+                bl[U][u] = make_uint4(0u, 0u, 0u, 0u);
+                if (k < n) {
+                    bh[U][u] = *(const uint4*)(lb_hi + (int64_t)row * n + k);
+                    if (SPLIT) bl[U][u] = *(const uint4*)(lb_lo + (int64_t)row * n + k);
+                }
             }
         }
     };
-    auto store_b = [&]() {
+    const int64_t steps = (n + 63) / 64;
+    const int64_t full_steps = n / 64;
+    fetch(std::integral_constant<int, 0>{}, 0, std::false_type{});
+    if (steps > 1) fetch(std::integral_constant<int, 1>{}, 1, std::false_type{});
+    if (steps > 2) fetch(std::integral_constant<int, 2>{}, 2, std::false_type{});
+    auto step = [&](auto utag, int64_t s, auto steady_tag) {
+        constexpr int U = decltype(utag)::value;
+        constexpr bool STEADY = decltype(steady_tag)::value;
+        // buffer s % 2 was last read in step s - 2; every wavefront has left that step's reads behind it when
+        // the first one passes the barrier of step s - 1
+        char* sA = smem + (int)(s & 1) * BUF;
+        char* sBh = sA + A_BYTES;
+        char* sBl = sBh + B_BYTES;
+        *(uint4*)(sA + chunk_off(srow, sc)) = ar[U];
 #pragma unroll
         for (int u = 0; u < BCH; ++u) {
-            const int q = tid + 256 * u, row = q >> 3, c = q & 7;
+            const int q = tid + kDownThreads * u, row = q >> 3, c = q & 7;
             const int off = row * 128 + ((c ^ ((row >> 1) & 7)) << 4);
-            *(uint4*)(sBh + off) = bh[u];
-            if (SPLIT) *(uint4*)(sBl + off) = bl[u];
+            if (q < BCHUNKS) {
+                *(uint4*)(sBh + off) = bh[U][u];
+                if (SPLIT) *(uint4*)(sBl + off) = bl[U][u];
+            }
         }
-    };
-    const int64_t steps = (n + 63) / 64;
-    sa.load(0, n, tid);
-    load_b(0);
-    for (int64_t s = 0; s < steps; ++s) {
-        __syncthreads();                                     // the previous step's readers are done
-        sa.store(sA, tid);
-        store_b();
+        if (STEADY) fetch(utag, s + kAhead, std::true_type{});
+        else if (s + kAhead < steps) fetch(utag, s + kAhead, std::false_type{});
         __syncthreads();
-        if (s + 1 < steps) {
-            sa.load((s + 1) * 64, n, tid);
-            load_b((s + 1) * 64);
-        }
-        const int arow = wave * 32 + (lane & 31);
+        const int arow = tb * 32 + (lane & 31);
 #pragma unroll
-        for (int sl = 0; sl < 4; ++sl) {                     // 16 channels per slice; this lane's 8: bytes [16 sl + 8 g, +8) of its row
+        for (int ss = 0; ss < 2; ++ss) {                     // 16 channels per slice; this lane's 8: bytes [16 sl + 8 g, +8) of its row
+            const int sl = 2 * sh + ss;
             const int g8 = lane >> 5;
             const uint2 raw = *(const uint2*)(sA + chunk_off(arow, sl) + 8 * g8);
             const uint32_t w2[2] = {raw.x ^ 0x80808080u, raw.y ^ 0x80808080u};      // q + 128 as unsigned bytes
@@ -638,15 +687,50 @@ __global__ __launch_bounds__(256) void cf_down_kernel(const int8_t* __restrict__
                 acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bhv, acc[j], 0, 0, 0);
             }
         }
+    };
+    int64_t s = 0;
+    // Twelve steps per trip first: the compiler lets all loads in flight land at a loop's head, and that wait
+    // should come once in twelve steps, not once in three.  The steps fetched, up to s + 14, are whole.
+    for (; s + 5 * kAhead <= full_steps; s += 4 * kAhead) {
+#pragma unroll
+        for (int rep = 0; rep < 4; ++rep) {
+            step(std::integral_constant<int, 0>{}, s + 3 * rep, std::true_type{});
+            step(std::integral_constant<int, 1>{}, s + 3 * rep + 1, std::true_type{});
+            step(std::integral_constant<int, 2>{}, s + 3 * rep + 2, std::true_type{});
+        }
     }
+    for (; s + 2 * kAhead <= full_steps; s += kAhead) {     // the steps these three fetch, up to s + 5, are whole
+        step(std::integral_constant<int, 0>{}, s, std::true_type{});
+        step(std::integral_constant<int, 1>{}, s + 1, std::true_type{});
+        step(std::integral_constant<int, 2>{}, s + 2, std::true_type{});
+    }
+    for (; s < steps; s += kAhead) {
+        step(std::integral_constant<int, 0>{}, s, std::false_type{});
+        if (s + 1 < steps) step(std::integral_constant<int, 1>{}, s + 1, std::false_type{});
+        if (s + 2 < steps) step(std::integral_constant<int, 2>{}, s + 2, std::false_type{});
+    }
+    // the sums over slices 2, 3 (wavefronts 4 .. 7) join those over slices 0, 1 of the same tokens; the tile's
+    // token scales go through LDS as well (one load per token instead of one per accumulator register)
+    __syncthreads();
+    float* part = (float*)smem;
+    float* xsl = part + 4 * RB * 16 * 64;
+    if (tid < 128) xsl[tid] = (T0 + tid < rows) ? xs[T0 + tid] : 0.f;
+    if (sh == 1) {
+#pragma unroll
+        for (int j = 0; j < RB; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) part[((tb * RB + j) * 16 + e) * 64 + lane] = acc[j][e];
+    }
+    __syncthreads();
+    if (sh == 1) return;
 #pragma unroll
     for (int j = 0; j < RB; ++j) {
         const int col = 32 * j + (lane & 31);
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const int64_t row = T0 + wave * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            const int64_t row = T0 + tb * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
             if (row < rows) {
-                const float pv = acc[j][e] * xs[row];
+                const float pv = (acc[j][e] + part[((tb * RB + j) * 16 + e) * 64 + lane]) * xsl[row - T0];
                 const uint32_t h = bf16_rne(pv);
                 p_hi[row * ldp + col] = (uint16_t)h;
                 if (SPLIT) p_lo[row * ldp + col] = (uint16_t)bf16_rne(pv - __uint_as_float(h << 16));
@@ -707,10 +791,10 @@ template <int RB, bool SPLIT>
 int launch_down(aser_ctx* ctx, const int8_t* xq, const float* xs, int64_t rows, int64_t n, const uint16_t* lbh,
                 const uint16_t* lbl, uint16_t* p_hi, uint16_t* p_lo, int64_t ldp) {
     static bool done[16] = {false};
-    constexpr int lds = 128 * 64 + 2 * (32 * RB * 128);
+    constexpr int lds = 2 * (128 * 64 + 2 * (32 * RB * 128));   // two buffers of (codes, L_B hi, L_B lo)
     auto kern = cf_down_kernel<RB, SPLIT>;
     ASER_TRY(set_lds_once(ctx, kern, lds, done));
-    hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div64(rows, 128)), dim3(256), lds, ctx->stream, xq, xs, rows, n, lbh, lbl, p_hi, p_lo, ldp);
+    hipLaunchKernelGGL(kern, dim3((unsigned)ceil_div64(rows, 128)), dim3(kDownThreads), lds, ctx->stream, xq, xs, rows, n, lbh, lbl, p_hi, p_lo, ldp);
     return aser_check_launch(ctx, "compensated_forward_down");
 }
 
@@ -760,15 +844,10 @@ extern "C" int aser_compensated_forward(aser_ctx* ctx, const int8_t* x_codes, co
         const int rp = pl.r_pad;
         // the factors as bf16 planes: L_A (m x r) padded to r_pad columns, L_B (r x n) padded to r_pad rows
         {
-            const int64_t t1 = m * rp;
-            hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)(ceil_div64(t1, 256) < 2048 ? ceil_div64(t1, 256) : 2048)), dim3(256), 0,
-                               ctx->stream, L_A, m, (int64_t)r, (int64_t)r, (int64_t)rp, lah, lal);
-            ASER_TRY(aser_check_launch(ctx, "split_bf16"));
-            ASER_TRY(aser_fill_bytes(ctx, lbh, (size_t)(pl.off_lbl - pl.off_lbh) * 2));
-            const int64_t t2 = (int64_t)r * n;
-            hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)(ceil_div64(t2, 256) < 2048 ? ceil_div64(t2, 256) : 2048)), dim3(256), 0,
-                               ctx->stream, L_B, (int64_t)r, n, n, n, lbh, lbl);
-            ASER_TRY(aser_check_launch(ctx, "split_bf16"));
+            const int64_t total = (m + n) * rp, blocks = ceil_div64(total, 256);
+            hipLaunchKernelGGL(split_factors_kernel, dim3((unsigned)(blocks < 2048 ? blocks : 2048)), dim3(256), 0, ctx->stream,
+                               L_A, L_B, m, n, (int64_t)r, (int64_t)rp, lah, lal, lbh, lbl);
+            ASER_TRY(aser_check_launch(ctx, "split_factors"));
         }
 #define ASER_DOWN(RB)                                                                                   \
     (split ? launch_down<RB, true>(ctx, x_codes, x_scales, rows, n, lbh, lbl, p_hi, p_lo, rp)           \
