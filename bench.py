@@ -380,6 +380,42 @@ def extras(ctx, aser, torch, spec, buf, W, X, reps):
     return res
 
 
+def layers_in_flight(aser, torch, spec, X, Ws, n_ctx, n_layers):
+    """Throughput of Algorithm 1's loop over layers with n_ctx layers in flight (aser_calibrate_layers: one host
+    thread, n_ctx contexts with their own streams, buffers and workspaces; every layer is a full pass of the
+    workload from the shared X, statistics cleared first).  Returns wall-clock ms per layer and the errors."""
+    # streams that really run side by side: the runtime maps streams to four hardware queues per process
+    pool = [torch.cuda.Stream(device=0) for _ in range(16)]
+    st, picked = aser.aser_pick_concurrent_streams([s.cuda_stream for s in pool], n_ctx)
+    if st != aser.ASER_OK:
+        raise aser.AserError(st, "aser_pick_concurrent_streams")
+    streams = [pool[i] for i in picked]
+    n_ctx = len(streams)
+    ctxs = [aser.Context(0, stream=s.cuda_stream) for s in streams]
+    bufs = [aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed=True) for _ in range(n_ctx)]
+    for c in ctxs:
+        c.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, spec.r))
+    torch.cuda.synchronize()
+
+    def run(count):
+        descs = [aser.layer_desc(Ws[k % len(Ws)], bufs[k % n_ctx], X=X, clear_stats=True) for k in range(count)]
+        st = aser.aser_calibrate_layers(ctxs, descs)
+        if st != aser.ASER_OK:
+            bad = next(k for k, d in enumerate(descs) if d.status != aser.ASER_OK)
+            raise aser.AserError(st, "layer %d: %s" % (bad, ctxs[bad % n_ctx].last_error()))
+        return [d.err for d in descs]
+
+    run(2 * n_ctx)                                        # untimed
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    errs = run(n_layers)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for c in ctxs:
+        c.close()
+    return wall * 1e3 / n_layers, errs, n_ctx
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -396,6 +432,8 @@ def main():
     ap.add_argument("--clock-summary", nargs=2, metavar=("RESULT_DIR", "NOTE"),
                     help="print per-kernel shader clocks of a rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE run (no GPU needed)")
     ap.add_argument("--no-extras", action="store_true", help="skip the timings of the rows beyond the calibration path")
+    ap.add_argument("--in-flight", default="2,4", help="also time aser_calibrate_layers with this many layers in flight "
+                    "(comma-separated counts; empty to skip)")
     args = ap.parse_args()
     if args.traffic_summary:
         return traffic_summary(*args.traffic_summary)
@@ -494,6 +532,16 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     stage_ms = [s / args.steps for s in stage_ms]
+
+    # Throughput with several layers in flight (separate contexts and streams); `value` stays the one-layer latency
+    in_flight = {}
+    for tok in [t for t in args.in_flight.split(",") if t.strip()]:
+        nl = int(tok)
+        ms_l, errs_l, got = layers_in_flight(aser, torch, spec, X, Ws, nl, nl * args.steps)
+        in_flight[str(nl)] = {"ms_per_layer": round(ms_l, 4), "layers_per_s": round(1e3 / ms_l, 2),
+                              "concurrent_streams": got,
+                              "whitened_error_max_rel_dev": max(abs(e / err - 1.0) for e in errs_l)}
+        log("layers in flight %d: %.3f ms per layer" % (nl, ms_l))
 
     # Dominant kernel alone: the Gram MFMA kernel (no statistics pass), HIP events on the launch stream, one
     # pair around every launch, and a whole layer step between two launches as in the pipeline.  (Launched
@@ -596,6 +644,7 @@ def main():
         "stage_ms": {k: round(v, 4) for k, v in zip(stage_names, stage_ms)},
         "gram_mfma_util_pct": 100.0 * gram_tflops / BF16_PEAK_TFLOPS,
         "stage_util": stage_util,
+        "layers_in_flight": in_flight,
         "whitened_error": err,
         "roofline": {"kernel": "gram_dma_kernel (Gram update G += X^T X, 256x256 lower-triangle tiles, bf16 MFMA)",
                      "bound": "mfma", "achieved": gram_tflops, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

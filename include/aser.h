@@ -207,6 +207,63 @@ int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, 
                            const aser_svd_opts* opts,
                            float* L_A, float* L_B, float* sigma, double* err, int32_t* n_iter);
 
+/* aser_error_reconstruct in two halves, for callers that keep several layers in flight on several contexts
+ * (Algorithm 1's loop over layers: once the activations are stored a layer reads nothing of another).
+ * aser_error_reconstruct_enqueue validates and enqueues everything, including the copy of the status block
+ * to pinned host memory, and returns without waiting for the device: same arguments, same results in the
+ * same buffers.  aser_finish waits for the context's stream and returns what aser_error_reconstruct
+ * returns: its status (with what asynchronous calls left pending), *err and *n_iter (host, may be NULL).
+ * Between the two, the context accepts no other call that synchronises or rebinds the workspace
+ * (ASER_ERR_INVALID_ARG), and the workspace and all buffers of the layer stay untouched by the caller. */
+int aser_error_reconstruct_enqueue(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt,
+                                   const float* S, int64_t lds, int32_t r, const int32_t* idx, int32_t f,
+                                   const aser_svd_opts* opts, float* L_A, float* L_B, float* sigma);
+int aser_finish(aser_ctx* ctx, double* err, int32_t* n_iter);
+
+/* One layer of Algorithm 1's loop, as the five stage calls take it: every pointer is a DEVICE pointer with the
+ * meaning, layout and alignment documented at the stage call that consumes it; the last three fields are
+ * written by aser_calibrate_layers on the HOST. */
+typedef struct aser_layer_desc {
+    /* stage 1, aser_gram_accumulate.  X == NULL: G, abs_sum and count already hold the finished statistics
+     * of this layer's input when aser_calibrate_layers is called (layers that share an input: accumulate
+     * once, before the call).  clear_stats != 0 (with X): G (n x n, ldg), abs_sum and count are cleared first. */
+    const void* X; int32_t x_dtype; int32_t clear_stats; int64_t rows; int64_t ldx;
+    float* G; int64_t ldg; double* abs_sum; int64_t* count;
+    /* stage 2, aser_smooth_outliers */
+    const float* W; int64_t m; int64_t n; int64_t ldw; int32_t f; int32_t bits;
+    int32_t* idx; float* mdiag;
+    /* stage 3, aser_quantize_rtn */
+    int32_t layout; int32_t r; void* codes; float* scales; float* T; int64_t ldt;
+    /* stage 4, aser_whiten (asynchronous form) and aser_error_reconstruct */
+    float damp; int32_t reserved; float* S; int64_t lds;
+    const aser_svd_opts* opts; float* L_A; float* L_B; float* sigma;
+    /* results (host) */
+    double err; int32_t n_iter; int32_t status;
+} aser_layer_desc;
+
+/* Algorithm 1's loop over layers with n_ctx layers in flight: layer k runs on context k mod n_ctx (each
+ * with its own stream and its own workspace of at least aser_workspace_bytes of every layer it will get);
+ * the five stages of a layer are enqueued without a host wait, and a context is waited for only when
+ * its next layer is due.  The dependent chain of small launches that bounds one layer (whitening,
+ * subspace iteration) leaves most of the device idle, and the chains of the other layers run there.
+ * Per layer: layers[k].status, .err, .n_iter as aser_error_reconstruct returns them (a layer whose
+ * arguments are refused is skipped, the others still run); the text of a layer's failure stays in
+ * aser_last_error of its context until that context's next layer.  Returns ASER_OK when every layer did,
+ * else the first failing layer's status; ASER_ERR_INVALID_ARG for null arguments or n_ctx < 1.
+ * Layers on different contexts must not share output buffers; inputs (X, W, finished statistics) may
+ * be shared.  Host code runs on the calling thread only. */
+int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_layer_desc* layers, int32_t n_layers);
+
+/* Streams for aser_calibrate_layers.  A process has few hardware queues (four by default) and the runtime maps
+ * every stream to one of them; two streams on the same queue run one after the other, however independent their
+ * work.  From `n_candidates` streams (hipStream_t, created by the caller, idle) this picks up to `want` that
+ * run concurrently with one another: chosen[0 .. *n_chosen) are indices into `candidates` (HOST arrays).
+ * It times a delay kernel of one wavefront (about 0.2 ms, bounded) on a candidate alone and next to each
+ * stream already chosen; a candidate whose pair takes as long as two in a row shares a queue and is passed over.
+ * Synchronises the candidate streams; a few milliseconds per candidate.  ASER_ERR_INVALID_ARG, ASER_ERR_HIP. */
+int aser_pick_concurrent_streams(int32_t device, void* const* candidates, int32_t n_candidates, int32_t want,
+                                 int32_t* chosen, int32_t* n_chosen);
+
 /* The subspace width and the iteration count aser_error_reconstruct will use for this shape and these
  * options (either pointer may be NULL).  ASER_ERR_SHAPE where aser_error_reconstruct would refuse. */
 int aser_svd_plan(int64_t m, int64_t n, int32_t r, const aser_svd_opts* opts, int32_t* block, int32_t* iters);

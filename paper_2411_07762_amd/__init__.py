@@ -39,11 +39,25 @@ EXPORTS = (
     "aser_spectrum_workspace_bytes", "aser_singular_values", "aser_select_rank", "aser_effective_rank",
     "aser_output_error_workspace_bytes", "aser_layer_output_error",
     "aser_forward_workspace_bytes", "aser_compensated_forward", "aser_mfma_rate_probe",
+    "aser_error_reconstruct_enqueue", "aser_finish", "aser_calibrate_layers", "aser_pick_concurrent_streams",
 )
 
 
 class aser_svd_opts(ctypes.Structure):
     _fields_ = [("block", ctypes.c_int32), ("max_iter", ctypes.c_int32), ("seed", ctypes.c_uint32)]
+
+
+class aser_layer_desc(ctypes.Structure):
+    """Mirror of the C struct of the same name (one layer of aser_calibrate_layers)."""
+    _vp, _i64, _i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    _fields_ = [("X", _vp), ("x_dtype", _i32), ("clear_stats", _i32), ("rows", _i64), ("ldx", _i64),
+                ("G", _vp), ("ldg", _i64), ("abs_sum", _vp), ("count", _vp),
+                ("W", _vp), ("m", _i64), ("n", _i64), ("ldw", _i64), ("f", _i32), ("bits", _i32),
+                ("idx", _vp), ("mdiag", _vp),
+                ("layout", _i32), ("r", _i32), ("codes", _vp), ("scales", _vp), ("T", _vp), ("ldt", _i64),
+                ("damp", ctypes.c_float), ("reserved", _i32), ("S", _vp), ("lds", _i64),
+                ("opts", ctypes.POINTER(aser_svd_opts)), ("L_A", _vp), ("L_B", _vp), ("sigma", _vp),
+                ("err", ctypes.c_double), ("n_iter", _i32), ("status", _i32)]
 
 
 class AserError(RuntimeError):
@@ -93,6 +107,14 @@ def load_library() -> ctypes.CDLL:
     lib.aser_error_reconstruct.argtypes = [vp, vp, i64, i64, i64, vp, i64, i32, vp, i32, ctypes.POINTER(aser_svd_opts),
                                            vp, vp, vp, ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int32)]
+    lib.aser_error_reconstruct_enqueue.restype = ctypes.c_int
+    lib.aser_error_reconstruct_enqueue.argtypes = lib.aser_error_reconstruct.argtypes[:-2]
+    lib.aser_finish.restype = ctypes.c_int
+    lib.aser_finish.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
+    lib.aser_calibrate_layers.restype = ctypes.c_int
+    lib.aser_calibrate_layers.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(aser_layer_desc), i32]
+    lib.aser_pick_concurrent_streams.restype = ctypes.c_int
+    lib.aser_pick_concurrent_streams.argtypes = [i32, ctypes.POINTER(vp), i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.aser_svd_plan.restype = ctypes.c_int
     lib.aser_svd_plan.argtypes = [i64, i64, i32, ctypes.POINTER(aser_svd_opts), ctypes.POINTER(ctypes.c_int32),
                                   ctypes.POINTER(ctypes.c_int32)]
@@ -274,6 +296,25 @@ def aser_error_reconstruct(ctx: Context, T, S, r: int, L_A, L_B, sigma, opts: Op
     return st, err.value, nit.value
 
 
+def aser_error_reconstruct_enqueue(ctx: Context, T, S, r: int, L_A, L_B, sigma, opts: Optional[aser_svd_opts] = None, *,
+                                   idx=None, f: int = 0, m=None, n=None, ldt=None, lds=None) -> int:
+    """aser_error_reconstruct without its wait; aser_finish(ctx) returns the results."""
+    m = T.shape[0] if m is None else m
+    n = T.shape[1] if n is None else n
+    return ctx._lib.aser_error_reconstruct_enqueue(ctx.handle, _ptr(T), m, n, _ld(T, n) if ldt is None else ldt, _ptr(S),
+                                                   _ld(S, n) if lds is None else lds, r, _ptr(idx) if f > 0 else None, f,
+                                                   ctypes.byref(opts) if opts is not None else None, _ptr(L_A),
+                                                   _ptr(L_B), _ptr(sigma))
+
+
+def aser_finish(ctx: Context):
+    """Returns (status, err, n_iter) of the enqueued aser_error_reconstruct."""
+    err = ctypes.c_double(0.0)
+    nit = ctypes.c_int32(0)
+    st = ctx._lib.aser_finish(ctx.handle, ctypes.byref(err), ctypes.byref(nit))
+    return st, err.value, nit.value
+
+
 def aser_svd_plan(m: int, n: int, r: int, opts: Optional[aser_svd_opts] = None):
     """Returns (status, block, iters): what aser_error_reconstruct will use for this shape."""
     b, it = ctypes.c_int32(0), ctypes.c_int32(0)
@@ -409,3 +450,46 @@ def calibrate_layer(ctx: Context, W, X, buf: LayerBuffers, opts: Optional[aser_s
     ctx.check(st)
     buf.err = err
     return buf
+
+
+def layer_desc(W, buf: "LayerBuffers", X=None, clear_stats: bool = False, opts: Optional[aser_svd_opts] = None,
+               damp: float = 0.0) -> aser_layer_desc:
+    """The descriptor of one layer for aser_calibrate_layers from its weight, its buffers and (unless the
+    statistics in `buf` are already finished) its activations.  The tensors must outlive the call."""
+    d = aser_layer_desc()
+    if X is not None:
+        d.X, d.x_dtype, d.rows, d.ldx = _ptr(X), _dtype_code(X), X.shape[0], _ld(X, buf.n)
+    d.clear_stats = 1 if clear_stats else 0
+    d.G, d.ldg, d.abs_sum, d.count = _ptr(buf.G), _ld(buf.G, buf.n), _ptr(buf.abs_sum), _ptr(buf.count)
+    d.W, d.m, d.n, d.ldw, d.f, d.bits = _ptr(W), buf.m, buf.n, _ld(W, buf.n), buf.f, buf.bits
+    d.idx, d.mdiag = _ptr(buf.idx), _ptr(buf.mdiag)
+    d.layout = ASER_CODES_INT4_PACKED if buf.packed else ASER_CODES_INT8
+    d.r, d.codes, d.scales, d.T, d.ldt = buf.r, _ptr(buf.codes), _ptr(buf.scales), _ptr(buf.T), _ld(buf.T, buf.n)
+    d.damp, d.S, d.lds = damp, _ptr(buf.S), _ld(buf.S, buf.n)
+    if opts is not None:
+        d.opts = ctypes.pointer(opts)
+    d.L_A, d.L_B, d.sigma = _ptr(buf.L_A), _ptr(buf.L_B), _ptr(buf.sigma)
+    return d
+
+
+def aser_calibrate_layers(ctxs, descs) -> int:
+    """Runs the layers `descs` (aser_layer_desc) with len(ctxs) of them in flight; per-layer status, err and
+    n_iter are left in the descriptors.  Returns the first failing status, or ASER_OK."""
+    lib = load_library()
+    handles = (ctypes.c_void_p * len(ctxs))(*[c.handle for c in ctxs])
+    arr = (aser_layer_desc * len(descs))(*descs)
+    st = lib.aser_calibrate_layers(handles, len(ctxs), arr, len(descs))
+    for d, a in zip(descs, arr):
+        d.err, d.n_iter, d.status = a.err, a.n_iter, a.status
+    return st
+
+
+def aser_pick_concurrent_streams(stream_handles, want: int, device: int = 0):
+    """Returns (status, indices): up to `want` of the candidate streams (raw hipStream_t handles) that run
+    concurrently with one another."""
+    n = len(stream_handles)
+    cand = (ctypes.c_void_p * n)(*stream_handles)
+    chosen = (ctypes.c_int32 * max(n, 1))()
+    cnt = ctypes.c_int32(0)
+    st = load_library().aser_pick_concurrent_streams(device, cand, n, want, chosen, ctypes.byref(cnt))
+    return st, [chosen[i] for i in range(cnt.value)]

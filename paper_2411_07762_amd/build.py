@@ -19,7 +19,7 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libaser.so")
 OBJDIR = os.path.join(PKG, "_build")
 
-SOURCES = ["api.hip", "gemm_tn.hip", "bandwidth.hip", "smooth.hip", "dense_small.hip", "chol_block.hip", "eig_sym.hip", "whiten.hip", "reconstruct.hip", "spectrum.hip", "evaluate.hip", "forward.hip", "probe.hip"]
+SOURCES = ["api.hip", "gemm_tn.hip", "bandwidth.hip", "smooth.hip", "dense_small.hip", "chol_block.hip", "eig_sym.hip", "whiten.hip", "reconstruct.hip", "spectrum.hip", "evaluate.hip", "forward.hip", "probe.hip", "layers.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-I", INCLUDE, "-I", CSRC]

@@ -31,6 +31,9 @@ extern "C" int aser_create(aser_ctx** out, int device, void* hip_stream) {
     c->pending_info_dev = nullptr;
     c->pending_sel_dev = nullptr;
     c->host_status = nullptr;
+    c->rec_pending = false;
+    c->rec_exact = false;
+    c->rec_iters = 0;
     c->err[0] = 0;
     *out = c;
     return ASER_OK;
@@ -57,6 +60,7 @@ extern "C" int aser_set_workspace(aser_ctx* ctx, void* dev_ptr, size_t bytes) {
     if (!ctx) return ASER_ERR_INVALID_ARG;
     if (dev_ptr && ((uintptr_t)dev_ptr & 255)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "set_workspace: pointer must be 256-byte aligned");
     if (!dev_ptr && bytes) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "set_workspace: null pointer with non-zero size");
+    if (ctx->rec_pending) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "set_workspace: an enqueued aser_error_reconstruct still uses the workspace (aser_finish first)");
     int pending_status = ASER_OK;
     if (ctx->pending_info_dev || ctx->pending_sel_dev) {
         // deferred status words live in the old workspace: fetch them before that memory goes away
@@ -94,24 +98,31 @@ int aser_prepare_device(aser_ctx* ctx) {
     return ASER_OK;
 }
 
-int aser_sync_status(aser_ctx* ctx, AserPending* p) {
+int aser_enqueue_status_copy(aser_ctx* ctx) {
+    if (!ctx->ws || ctx->ws_bytes < kAserWsTail) return ASER_OK;   // no workspace: nothing can be pending
+    ASER_TRY(aser_prepare_device(ctx));
+    ASER_HIP(ctx, hipMemcpyAsync(ctx->host_status, aser_status_dev(ctx), sizeof(AserStatusBlock), hipMemcpyDeviceToHost, ctx->stream));
+    return ASER_OK;
+}
+
+int aser_wait_status(aser_ctx* ctx, AserPending* p) {
     p->pivot = INT_MAX;
     p->sel = 0;
     p->qr = 0;
     p->res2 = 0.0;
-    if (!ctx->ws || ctx->ws_bytes < kAserWsTail) {           // no workspace: nothing can be pending
-        ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        return ASER_OK;
-    }
-    ASER_TRY(aser_prepare_device(ctx));
-    ASER_HIP(ctx, hipMemcpyAsync(ctx->host_status, aser_status_dev(ctx), sizeof(AserStatusBlock), hipMemcpyDeviceToHost, ctx->stream));
     ASER_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (!ctx->ws || ctx->ws_bytes < kAserWsTail || !ctx->host_status) return ASER_OK;
     const AserStatusBlock* h = (const AserStatusBlock*)ctx->host_status;
     if (ctx->pending_info_dev) p->pivot = h->pivot;
     if (ctx->pending_sel_dev) p->sel = h->sel;
     p->qr = h->qr;
     p->res2 = h->res2;
     return ASER_OK;
+}
+
+int aser_sync_status(aser_ctx* ctx, AserPending* p) {
+    ASER_TRY(aser_enqueue_status_copy(ctx));
+    return aser_wait_status(ctx, p);
 }
 
 int aser_report_pending(aser_ctx* ctx, const AserPending& p, const char* who) {

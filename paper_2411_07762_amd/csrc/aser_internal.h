@@ -24,6 +24,10 @@ struct aser_ctx {
     // 64 bytes of pinned host memory (allocated with the first compute call): every synchronising call brings
     // the status block at the head of the workspace tail to the host in one copy.
     void* host_status;
+    // aser_error_reconstruct_enqueue has left its status copy in flight; aser_finish waits for it
+    bool rec_pending;
+    bool rec_exact;      // the dense solver ran (no orthogonalisation flag to look at)
+    int32_t rec_iters;
     char err[256];
 };
 
@@ -52,6 +56,9 @@ struct AserPending {
 // Enqueues the one copy of the status block, waits for the stream, and fills *p (words nobody has pending read
 // as "nothing wrong"); aser_report_pending then clears the pending state and turns a raised word into a status.
 int aser_sync_status(aser_ctx* ctx, AserPending* p);
+// The two halves of aser_sync_status: the copy alone (asynchronous), and the wait with the read-out.
+int aser_enqueue_status_copy(aser_ctx* ctx);
+int aser_wait_status(aser_ctx* ctx, AserPending* p);
 int aser_report_pending(aser_ctx* ctx, const AserPending& p, const char* who);
 int aser_set_i32(aser_ctx* ctx, int32_t* p, int32_t v);
 

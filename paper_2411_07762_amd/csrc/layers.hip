@@ -1,0 +1,106 @@
+// Algorithm 1's loop over the layers of a model with several layers in flight.  A layer's calibration is a
+// dependent chain of a few hundred launches, most of them small (the block-row steps of the Cholesky
+// factorisation, the products and factorisations of the subspace iteration); layers do not depend on one
+// another once their inputs are stored, so the chains of different layers run side by side on different
+// streams.  The host enqueues a whole layer without waiting and waits for a context only when it needs it
+// for the next layer.
+#include <time.h>
+
+#include "aser_internal.h"
+
+namespace {
+
+// Keeps one wavefront busy for about `ticks` ticks of the constant-rate wall clock (100 MHz), and no longer than
+// `max_rounds` rounds of the loop whatever that clock does.
+__global__ void delay_kernel(long long ticks, int max_rounds, long long* sink) {
+    const long long t0 = wall_clock64();
+    long long t = t0;
+    for (int i = 0; i < max_rounds && t - t0 < ticks; ++i) {
+        __builtin_amdgcn_s_sleep(32);
+        t = wall_clock64();
+    }
+    if (sink && threadIdx.x == 0) *sink = t - t0;
+}
+
+// Host wall-clock ms of `reps` delay kernels on a (and, if given, as many on b), both streams idle before and after.
+int timed_delays(hipStream_t a, hipStream_t b, bool use_b, int reps, double* ms) {
+    if (hipStreamSynchronize(a) != hipSuccess || (use_b && hipStreamSynchronize(b) != hipSuccess)) return ASER_ERR_HIP;
+    timespec t0, t1;
+    clock_gettime(CLOCK_MONOTONIC, &t0);
+    for (int i = 0; i < reps; ++i) {
+        hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, a, (long long)20000, 1 << 16, (long long*)nullptr);
+        if (use_b) hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, b, (long long)20000, 1 << 16, (long long*)nullptr);
+    }
+    if (hipGetLastError() != hipSuccess) return ASER_ERR_HIP;
+    if (hipStreamSynchronize(a) != hipSuccess || (use_b && hipStreamSynchronize(b) != hipSuccess)) return ASER_ERR_HIP;
+    clock_gettime(CLOCK_MONOTONIC, &t1);
+    *ms = (t1.tv_sec - t0.tv_sec) * 1e3 + (t1.tv_nsec - t0.tv_nsec) * 1e-6;
+    return ASER_OK;
+}
+
+int enqueue_layer(aser_ctx* ctx, const aser_layer_desc& L) {
+    if (L.X) {
+        if (L.clear_stats) {
+            if (!L.G || L.n <= 0 || L.ldg < L.n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "calibrate_layers: bad Gram matrix");
+            ASER_TRY(aser_prepare_device(ctx));
+            ASER_TRY(aser_fill_f32(ctx, L.G, L.n, L.n, L.ldg, 0.f));
+            if (L.abs_sum) ASER_TRY(aser_fill_bytes(ctx, L.abs_sum, (size_t)L.n * 8));
+            if (L.count) ASER_TRY(aser_fill_bytes(ctx, L.count, 8));
+        }
+        ASER_TRY(aser_gram_accumulate(ctx, L.X, L.x_dtype, L.rows, L.n, L.ldx, L.G, L.ldg, L.abs_sum, L.count));
+    }
+    ASER_TRY(aser_smooth_outliers(ctx, L.W, L.m, L.n, L.ldw, L.abs_sum, L.count, L.f, L.idx, L.mdiag, nullptr, nullptr));
+    ASER_TRY(aser_quantize_rtn(ctx, L.W, L.m, L.n, L.ldw, L.idx, L.mdiag, L.f, L.bits, L.layout, L.codes, L.scales, L.T, L.ldt));
+    ASER_TRY(aser_whiten(ctx, L.G, L.ldg, L.n, L.mdiag, L.damp, L.S, L.lds, nullptr));
+    return aser_error_reconstruct_enqueue(ctx, L.T, L.m, L.n, L.ldt, L.S, L.lds, L.r, L.idx, L.f, L.opts, L.L_A, L.L_B, L.sigma);
+}
+
+}  // namespace
+
+extern "C" int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_layer_desc* layers, int32_t n_layers) {
+    if (!ctxs || n_ctx < 1 || n_layers < 0 || (n_layers > 0 && !layers)) return ASER_ERR_INVALID_ARG;
+    for (int c = 0; c < n_ctx; ++c)
+        if (!ctxs[c] || ctxs[c]->rec_pending) return ASER_ERR_INVALID_ARG;
+    int first_bad = ASER_OK;
+    auto finish = [&](int k) {
+        aser_layer_desc& L = layers[k];
+        aser_ctx* ctx = ctxs[k % n_ctx];
+        if (ctx->rec_pending) L.status = aser_finish(ctx, &L.err, &L.n_iter);
+        if (L.status != ASER_OK && first_bad == ASER_OK) first_bad = L.status;
+    };
+    for (int k = 0; k < n_layers; ++k) {
+        if (k >= n_ctx) finish(k - n_ctx);                     // the context's previous layer
+        layers[k].err = 0.0;
+        layers[k].n_iter = 0;
+        layers[k].status = enqueue_layer(ctxs[k % n_ctx], layers[k]);
+    }
+    for (int k = (n_layers > n_ctx ? n_layers - n_ctx : 0); k < n_layers; ++k) finish(k);
+    return first_bad;
+}
+
+extern "C" int aser_pick_concurrent_streams(int32_t device, void* const* candidates, int32_t n_candidates, int32_t want,
+                                            int32_t* chosen, int32_t* n_chosen) {
+    if (device < 0 || !candidates || n_candidates < 1 || want < 1 || !chosen || !n_chosen) return ASER_ERR_INVALID_ARG;
+    if (hipSetDevice(device) != hipSuccess) return ASER_ERR_HIP;
+    *n_chosen = 0;
+    double single = 0.0;
+    {
+        double warm;
+        const int st = timed_delays((hipStream_t)candidates[0], nullptr, false, 2, &warm);
+        if (st != ASER_OK) return st;
+    }
+    for (int c = 0; c < n_candidates && *n_chosen < want; ++c) {
+        hipStream_t sc = (hipStream_t)candidates[c];
+        int st = timed_delays(sc, nullptr, false, 3, &single);
+        if (st != ASER_OK) return st;
+        bool ok = true;
+        for (int k = 0; k < *n_chosen && ok; ++k) {
+            double pair = 0.0;
+            st = timed_delays((hipStream_t)candidates[chosen[k]], sc, true, 3, &pair);
+            if (st != ASER_OK) return st;
+            ok = pair < 1.5 * single;                        // serialised streams take twice as long
+        }
+        if (ok) chosen[(*n_chosen)++] = c;
+    }
+    return ASER_OK;
+}

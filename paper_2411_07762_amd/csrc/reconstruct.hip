@@ -193,11 +193,11 @@ extern "C" int aser_svd_plan(int64_t m, int64_t n, int32_t r, const aser_svd_opt
     return ASER_OK;
 }
 
-extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt,
-                                      const float* S, int64_t lds, int32_t r, const int32_t* idx, int32_t f,
-                                      const aser_svd_opts* opts,
-                                      float* L_A, float* L_B, float* sigma, double* err, int32_t* n_iter) {
+extern "C" int aser_error_reconstruct_enqueue(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt,
+                                              const float* S, int64_t lds, int32_t r, const int32_t* idx, int32_t f,
+                                              const aser_svd_opts* opts, float* L_A, float* L_B, float* sigma) {
     if (!ctx) return ASER_ERR_INVALID_ARG;
+    if (ctx->rec_pending) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "error_reconstruct_enqueue: the previous one has not been finished (aser_finish)");
     if (!T || !S || !L_A || !L_B || !sigma) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "error_reconstruct: null pointer");
     if (m <= 0 || n <= 0 || ldt < n || lds < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: bad shape");
     if (f < 0 || f > n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: f must be in [0, n]");
@@ -227,15 +227,10 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         if (ctx->ws_bytes < ex + 256 + kAserWsTail)
             ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "error_reconstruct: workspace too small (%zu needed)", ex + 256 + kAserWsTail);
         ASER_TRY(aser_exact_reconstruct(ctx, T, m, n, ldt, S, lds, r, L_A, L_B, sigma, &aser_status_dev(ctx)->res2));
-        AserPending pend;
-        ASER_TRY(aser_sync_status(ctx, &pend));
-        ASER_TRY(aser_report_pending(ctx, pend, "error_reconstruct"));
-        const double h_err2 = pend.res2;
-        if (!(h_err2 >= 0.0) || h_err2 > 1e300)
-            ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE, "error_reconstruct: non-finite values in T or S");
-        if (err) *err = sqrt(h_err2);
-        if (n_iter) *n_iter = 0;
-        return ASER_OK;
+        ctx->rec_pending = true;
+        ctx->rec_exact = true;
+        ctx->rec_iters = 0;
+        return aser_enqueue_status_copy(ctx);
     }
     const int b = p.b;
     const int form = aser_f32_form(ctx, m * n);          // three or six bf16 products per fp32 product
@@ -363,25 +358,42 @@ extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, 
         ASER_TRY(gemm_tn_atomic(ctx, form, T, ldt, Qp, b, Zp, b, n, b, m, bmA, bnB, true));  // C^T = T^T Q (n x b)
         return aser_gemm_small_f32(ctx, Zp, b, WBt, r, L_B, n, n, b, r, 0, true);            // (n x r)^T = L_B
     };
-    // The one synchronisation: the squared residual, the pivot flag of the orthogonalisation and whatever
-    // earlier calls left pending.
-    double res2 = 0.0;
     ASER_TRY(iterate(p.iters));
     ASER_TRY(finish());
-    {
-        AserPending pend;                                    // with the status words of calls that did not synchronise
-        ASER_TRY(aser_sync_status(ctx, &pend));
-        ASER_TRY(aser_report_pending(ctx, pend, "error_reconstruct"));
-        const double h_res2 = pend.res2;
-        const int32_t h_qr = pend.qr;
-        if (h_qr < 0 || !(h_res2 >= 0.0) || h_res2 > 1e300)
-            ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE,
-                      "error_reconstruct: the Cholesky-QR orthogonalisation broke down (pivot %d of a block Gram matrix is not "
-                      "positive): the singular values of the subspace span more than the products resolve",
-                      h_qr < 0 ? h_qr - kPivotBase : 0);
-        res2 = h_res2 > 0.0 ? h_res2 : 0.0;
+    // Nothing above waits for the device.  The squared residual, the pivot flag of the orthogonalisation and
+    // whatever earlier calls left pending travel to the host in one copy, which aser_finish waits for.
+    ctx->rec_pending = true;
+    ctx->rec_exact = false;
+    ctx->rec_iters = done;
+    return aser_enqueue_status_copy(ctx);
+}
+
+extern "C" int aser_finish(aser_ctx* ctx, double* err, int32_t* n_iter) {
+    if (!ctx) return ASER_ERR_INVALID_ARG;
+    if (!ctx->rec_pending) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "finish: no aser_error_reconstruct_enqueue is pending on this context");
+    ctx->rec_pending = false;
+    AserPending pend;                                        // with the status words of calls that did not synchronise
+    ASER_TRY(aser_wait_status(ctx, &pend));
+    ASER_TRY(aser_report_pending(ctx, pend, "error_reconstruct"));
+    const double h_res2 = pend.res2;
+    if (ctx->rec_exact) {
+        if (!(h_res2 >= 0.0) || h_res2 > 1e300)
+            ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE, "error_reconstruct: non-finite values in T or S");
+    } else if (pend.qr < 0 || !(h_res2 >= 0.0) || h_res2 > 1e300) {
+        ASER_FAIL(ctx, ASER_ERR_NO_CONVERGE,
+                  "error_reconstruct: the Cholesky-QR orthogonalisation broke down (pivot %d of a block Gram matrix is not "
+                  "positive): the singular values of the subspace span more than the products resolve",
+                  pend.qr < 0 ? pend.qr - kPivotBase : 0);
     }
-    if (err) *err = sqrt(res2);
-    if (n_iter) *n_iter = done;
+    if (err) *err = sqrt(h_res2 > 0.0 ? h_res2 : 0.0);
+    if (n_iter) *n_iter = ctx->rec_iters;
     return ASER_OK;
+}
+
+extern "C" int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt,
+                                      const float* S, int64_t lds, int32_t r, const int32_t* idx, int32_t f,
+                                      const aser_svd_opts* opts,
+                                      float* L_A, float* L_B, float* sigma, double* err, int32_t* n_iter) {
+    ASER_TRY(aser_error_reconstruct_enqueue(ctx, T, m, n, ldt, S, lds, r, idx, f, opts, L_A, L_B, sigma));
+    return aser_finish(ctx, err, n_iter);
 }

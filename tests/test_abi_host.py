@@ -129,6 +129,31 @@ def test_whiten_and_reconstruct_validation(ctx):
     assert r(ctx, P, P, 45, P, P, P, m=695, n=44)[0] == aser.ASER_ERR_SHAPE
 
 
+def test_layers_in_flight_validation(ctx):
+    lib = aser.load_library()
+    # nothing enqueued: nothing to finish
+    st, _, _ = aser.aser_finish(ctx)
+    assert st == aser.ASER_ERR_INVALID_ARG and "pending" in ctx.last_error()
+    assert lib.aser_calibrate_layers(None, 1, None, 0) == aser.ASER_ERR_INVALID_ARG
+    handles = (ctypes.c_void_p * 1)(ctx.handle)
+    assert lib.aser_calibrate_layers(handles, 0, None, 0) == aser.ASER_ERR_INVALID_ARG
+    assert lib.aser_calibrate_layers(handles, 1, None, 0) == aser.ASER_OK                # no layers: nothing to do
+    assert lib.aser_calibrate_layers(handles, 1, None, 2) == aser.ASER_ERR_INVALID_ARG
+    # a layer whose arguments a stage refuses is reported in its descriptor and the others are still visited
+    bad = aser.aser_layer_desc()                                                       # all null: stage 2 refuses W
+    worse = aser.aser_layer_desc()
+    worse.X, worse.x_dtype, worse.rows, worse.n, worse.ldx, worse.G, worse.ldg = P, 7, 4, 16, 16, P, 16   # unknown dtype
+    st = aser.aser_calibrate_layers([ctx], [bad, worse])
+    assert st == aser.ASER_ERR_INVALID_ARG
+    assert bad.status == aser.ASER_ERR_INVALID_ARG and worse.status == aser.ASER_ERR_DTYPE
+    cnt, chosen = ctypes.c_int32(0), (ctypes.c_int32 * 2)()
+    assert lib.aser_pick_concurrent_streams(0, None, 2, 1, chosen, ctypes.byref(cnt)) == aser.ASER_ERR_INVALID_ARG
+    assert lib.aser_pick_concurrent_streams(0, handles, 1, 0, chosen, ctypes.byref(cnt)) == aser.ASER_ERR_INVALID_ARG
+    assert lib.aser_pick_concurrent_streams(-1, handles, 1, 1, chosen, ctypes.byref(cnt)) == aser.ASER_ERR_INVALID_ARG
+    # the struct the binding marshals has the layout the header declares (sizes of the C compiler's struct)
+    assert ctypes.sizeof(aser.aser_layer_desc) == 232
+
+
 def test_svd_plan_reports_what_the_iteration_will_use():
     assert aser.aser_svd_plan(4096, 4096, 64) == (aser.ASER_OK, 128, 9)
     assert aser.aser_svd_plan(4096, 11008, 64) == (aser.ASER_OK, 128, 12)

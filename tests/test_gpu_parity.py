@@ -460,6 +460,12 @@ def run_e2e(name, spec, packed, x_np=None, ref=None, precision=None):
     buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed)
     aser.calibrate_layer(ctx, torch.from_numpy(W).to(DEV), to_dev_x(spec, x_np), buf)
     torch.cuda.synchronize()
+    check_layer(name, spec, packed, buf, ref)
+    return buf, ref
+
+
+def check_layer(name, spec, packed, buf, ref):
+    """Every bar of a calibrated layer in `buf` against the oracle's `ref`."""
     if spec.f:
         assert buf.idx.cpu().numpy()[:spec.f].tolist() == ref.smooth.idx.tolist()
         planted, _ = synth.outlier_channels(spec)
@@ -470,13 +476,76 @@ def run_e2e(name, spec, packed, x_np=None, ref=None, precision=None):
     assert np.array_equal(codes, ref.quant.codes)
     assert np.array_equal(buf.scales.cpu().numpy(), ref.quant.scales)
     check_reconstruction(spec, ref, buf.L_A.cpu().numpy(), buf.L_B.cpu().numpy(), buf.sigma.cpu().numpy(), buf.err, name)
-    return buf, ref
 
 
 @pytest.mark.parametrize("name,spec,packed", E2E_CASES, ids=[c[0] for c in E2E_CASES])
 def test_end_to_end_layer(name, spec, packed):
     say("e2e case %s m=%d n=%d N=%d r=%d f=%d" % (name, spec.m, spec.n, spec.tokens, spec.r, spec.f))
     run_e2e(name, spec, packed)
+
+
+def test_layers_in_flight():
+    """aser_calibrate_layers: layers of different shapes, bit widths and solvers on three contexts (three streams),
+    two of them sharing one input's finished statistics, one with empty statistics in the middle.  Every layer
+    meets the bars against the oracle; the layer without tokens is reported in its own descriptor and disturbs
+    no other; aser_error_reconstruct_enqueue / aser_finish refuse what their protocol forbids."""
+    picks = [E2E_CASES[i] for i in (2, 3, 4, 6, 9)]                 # ragged, c1 / c2 shapes, W8 with outliers, tiny block
+    pool = [torch.cuda.Stream(device=0) for _ in range(12)]
+    st, picked = aser.aser_pick_concurrent_streams([s.cuda_stream for s in pool], 3)
+    assert st == aser.ASER_OK and len(set(picked)) == len(picked) == 3           # four hardware queues per process
+    streams = [pool[i] for i in picked]
+    ctxs = [aser.Context(0, stream=s.cuda_stream) for s in streams]
+    layers, need = [], 0
+    for name, spec, packed in picks:
+        W = synth.make_weight(spec)
+        x_np = synth.make_activations(spec)
+        buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed)
+        layers.append(dict(name=name, spec=spec, packed=packed, W=torch.from_numpy(W).to(DEV), X=to_dev_x(spec, x_np), buf=buf,
+                           ref=oracle_layer(spec, W, x_np)))
+        need = max(need, aser.aser_workspace_bytes(spec.m, spec.n, spec.r))
+    # a second layer on the first one's input (another weight, same shape): its statistics are accumulated before the call
+    name, spec, packed = picks[0]
+    spec2 = spec.with_(name=spec.name + "_b", layer_id=spec.layer_id + 1)      # another weight, the same input stream
+    W2 = synth.make_weight(spec2)
+    assert not np.array_equal(W2, synth.make_weight(spec))
+    x_np = synth.make_activations(spec)
+    shared = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed)
+    c0 = new_ctx()
+    c0.check(aser.aser_gram_accumulate(c0, layers[0]["X"], shared.G, shared.abs_sum, shared.count))
+    layers.append(dict(name=name + "_shared_input", spec=spec2, packed=packed, W=torch.from_numpy(W2).to(DEV), X=None, buf=shared,
+                       ref=oracle_layer(spec2, W2, x_np)))
+    # a layer without tokens: statistics all zero
+    empty = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed)
+    layers.insert(2, dict(name="no_tokens", spec=spec, packed=packed, W=layers[0]["W"], X=None, buf=empty, ref=None))
+    torch.cuda.synchronize()
+    for c in ctxs:
+        c.ensure_workspace(need)
+    descs = [aser.layer_desc(L["W"], L["buf"], X=L["X"], clear_stats=L["X"] is not None) for L in layers]
+    for L in layers:
+        if L["X"] is not None:
+            L["buf"].G.fill_(7.0)                                   # clear_stats has to remove this
+    torch.cuda.synchronize()
+    say("layers in flight: %s on %d contexts" % ([L["name"] for L in layers], len(ctxs)))
+    st = aser.aser_calibrate_layers(ctxs, descs)
+    torch.cuda.synchronize()
+    assert st == aser.ASER_ERR_INVALID_ARG                          # the first failing layer's status
+    for L, d in zip(layers, descs):
+        if L["ref"] is None:
+            assert d.status == aser.ASER_ERR_INVALID_ARG
+            continue
+        assert d.status == aser.ASER_OK, (L["name"], d.status)
+        L["buf"].err = d.err
+        check_layer(L["name"], L["spec"], L["packed"], L["buf"], L["ref"])
+    # the protocol of the two halves
+    L = layers[0]
+    b, ctx = L["buf"], ctxs[0]
+    st = aser.aser_error_reconstruct_enqueue(ctx, b.T, b.S, b.r, b.L_A, b.L_B, b.sigma, idx=b.idx, f=b.f)
+    assert st == aser.ASER_OK
+    assert aser.aser_error_reconstruct_enqueue(ctx, b.T, b.S, b.r, b.L_A, b.L_B, b.sigma, idx=b.idx, f=b.f) == aser.ASER_ERR_INVALID_ARG
+    assert aser.aser_set_workspace(ctx, None, 0) == aser.ASER_ERR_INVALID_ARG
+    st, err, _ = aser.aser_finish(ctx)
+    assert st == aser.ASER_OK and abs(err - descs[0].err) <= 1e-5 * err
+    assert aser.aser_finish(ctx)[0] == aser.ASER_ERR_INVALID_ARG
 
 
 # Layers that a randomized sweep found beyond the bars while every fp32 product was three bf16 products
