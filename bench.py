@@ -189,6 +189,59 @@ def run_block(args):
             layer_ms[i] += ev[i].elapsed_time(ev[i + 1]) / args.steps
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
+    # The same block with four layers in flight: the four Gram updates first (each fills the device), then the
+    # seven layers through aser_calibrate_layers on the finished statistics, the widest first, then the seven
+    # per-token quantizers spread over the same streams.
+    in_flight = None
+    counts = [int(t) for t in args.in_flight.split(",") if t.strip()]
+    if counts:
+        pool = [torch.cuda.Stream(device=0) for _ in range(16)]
+        s_, picked = aser.aser_pick_concurrent_streams([s.cuda_stream for s in pool], max(counts))
+        ctx.check(s_)
+        fctx = [aser.Context(0, stream=pool[i].cuda_stream) for i in picked]
+        need = max(aser.aser_workspace_bytes(sp.m, sp.n, sp.r) for sp in specs)
+        for c in fctx:
+            c.ensure_workspace(need)
+        order = sorted(range(len(layers)), key=lambda i: -(layers[i][0].m * layers[i][0].n * layers[i][0].n))
+        owners = [(st, buf) for (_, st, buf, _) in layers if st["owner"] is buf]
+
+        phase_ms = {"grams": 0.0, "layers": 0.0, "act_quant": 0.0}
+
+        def block_in_flight():
+            t_a = time.perf_counter()
+            for st, buf in owners:                         # one after the other: each of them fills the device
+                buf.reset_statistics()
+                ctx.check(aser.aser_gram_accumulate(ctx, st["X"], buf.G, buf.abs_sum, buf.count))
+            torch.cuda.synchronize()
+            t_b = time.perf_counter()
+            descs = [aser.layer_desc(layers[i][3], layers[i][2]) for i in order]
+            s2 = aser.aser_calibrate_layers(fctx, descs)
+            if s2 != aser.ASER_OK:
+                raise aser.AserError(s2, "aser_calibrate_layers on the block")
+            t_c = time.perf_counter()
+            for k, i in enumerate(order):
+                spec, st, buf, _ = layers[i]
+                c = fctx[k % len(fctx)]
+                c.check(aser.aser_quantize_act_rtn(c, st["X"], buf.mdiag, 8, st["codes"], st["scales"]))
+            torch.cuda.synchronize()
+            t_d = time.perf_counter()
+            for key, dt in (("grams", t_b - t_a), ("layers", t_c - t_b), ("act_quant", t_d - t_c)):
+                phase_ms[key] += dt * 1e3 / args.steps
+            return {layers[i][0].name: d.err for i, d in zip(order, descs)}
+
+        block_in_flight()
+        torch.cuda.synchronize()
+        phase_ms = dict.fromkeys(phase_ms, 0.0)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            errs_f = block_in_flight()
+        in_flight = {"layers_in_flight": len(fctx), "block_ms": round((time.perf_counter() - t0) * 1e3 / args.steps, 3),
+                     "phase_ms": {k: round(v, 3) for k, v in phase_ms.items()},
+                     "whitened_error_max_rel_dev": max(abs(errs_f[sp.name] / e - 1.0) for (sp, _, _, _), e in zip(layers, errs))}
+        log("block with %d layers in flight: %.2f ms" % (len(fctx), in_flight["block_ms"]))
+        for c in fctx:
+            c.close()
+
     # W4A8 layer-output error of every layer (Sec. 5.3 error figure metric, relative to ||X W^T||_F) on a sample of
     # its calibration tokens: with the factors, and for RTN alone
     sample = 2048
@@ -231,6 +284,7 @@ def run_block(args):
         "config": {"workload": "c3: q 4096x4096, k/v 1024x4096, o 4096x4096, gate/up 14336x4096, down 4096x14336; "
                                "131072 bf16 tokens per input stream; W4 per-channel RTN, A8 per-token, r=64, f=32"},
         "layer_ms": {sp.name: round(ms, 3) for (sp, _, _, _), ms in zip(layers, layer_ms)},
+        "block_with_layers_in_flight": in_flight,
         "whitened_error": {sp.name: e for (sp, _, _, _), e in zip(layers, errs)},
         "w4a8_output_error_relative": {"sample_tokens": sample, "layers": w4a8},
         "roofline": {"kernel": "gram_dma_kernel (Gram update of the 14336-channel stream)", "bound": "mfma",

@@ -241,17 +241,18 @@ typedef struct aser_layer_desc {
     double err; int32_t n_iter; int32_t status;
 } aser_layer_desc;
 
-/* Algorithm 1's loop over layers with n_ctx layers in flight: layer k runs on context k mod n_ctx (each
- * with its own stream and its own workspace of at least aser_workspace_bytes of every layer it will get);
- * the five stages of a layer are enqueued without a host wait, and a context is waited for only when
- * its next layer is due.  The dependent chain of small launches that bounds one layer (whitening,
- * subspace iteration) leaves most of the device idle, and the chains of the other layers run there.
+/* Algorithm 1's loop over layers with up to n_ctx (<= 64) layers in flight.  Layers are started in the order
+ * given, each on a context that is free or, when all are busy, on the first one whose stream has drained
+ * (every context has its own stream and its own workspace of at least aser_workspace_bytes of EVERY layer);
+ * the five stages of a layer are enqueued without a host wait.  The dependent chain of small launches that
+ * bounds one layer (whitening, subspace iteration) leaves most of the device idle, and the chains of the
+ * other layers run there; give long layers first.
  * Per layer: layers[k].status, .err, .n_iter as aser_error_reconstruct returns them (a layer whose
  * arguments are refused is skipped, the others still run); the text of a layer's failure stays in
  * aser_last_error of its context until that context's next layer.  Returns ASER_OK when every layer did,
- * else the first failing layer's status; ASER_ERR_INVALID_ARG for null arguments or n_ctx < 1.
- * Layers on different contexts must not share output buffers; inputs (X, W, finished statistics) may
- * be shared.  Host code runs on the calling thread only. */
+ * else the first status that was not; ASER_ERR_INVALID_ARG for null arguments or n_ctx outside [1, 64].
+ * Layers in flight together must not share output buffers; inputs (X, W, finished statistics) may be
+ * shared.  Host code runs on the calling thread only. */
 int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_layer_desc* layers, int32_t n_layers);
 
 /* Streams for aser_calibrate_layers.  A process has few hardware queues (four by default) and the runtime maps

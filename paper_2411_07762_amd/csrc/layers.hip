@@ -58,23 +58,42 @@ int enqueue_layer(aser_ctx* ctx, const aser_layer_desc& L) {
 }  // namespace
 
 extern "C" int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_layer_desc* layers, int32_t n_layers) {
-    if (!ctxs || n_ctx < 1 || n_layers < 0 || (n_layers > 0 && !layers)) return ASER_ERR_INVALID_ARG;
+    constexpr int kMaxCtx = 64;
+    if (!ctxs || n_ctx < 1 || n_ctx > kMaxCtx || n_layers < 0 || (n_layers > 0 && !layers)) return ASER_ERR_INVALID_ARG;
     for (int c = 0; c < n_ctx; ++c)
         if (!ctxs[c] || ctxs[c]->rec_pending) return ASER_ERR_INVALID_ARG;
     int first_bad = ASER_OK;
-    auto finish = [&](int k) {
-        aser_layer_desc& L = layers[k];
-        aser_ctx* ctx = ctxs[k % n_ctx];
-        if (ctx->rec_pending) L.status = aser_finish(ctx, &L.err, &L.n_iter);
+    int running[kMaxCtx];                                      // the layer in flight on each context, or -1
+    for (int c = 0; c < n_ctx; ++c) running[c] = -1;
+    auto finish = [&](int c) {
+        if (running[c] < 0) return;
+        aser_layer_desc& L = layers[running[c]];
+        L.status = aser_finish(ctxs[c], &L.err, &L.n_iter);
         if (L.status != ASER_OK && first_bad == ASER_OK) first_bad = L.status;
+        running[c] = -1;
     };
     for (int k = 0; k < n_layers; ++k) {
-        if (k >= n_ctx) finish(k - n_ctx);                     // the context's previous layer
-        layers[k].err = 0.0;
-        layers[k].n_iter = 0;
-        layers[k].status = enqueue_layer(ctxs[k % n_ctx], layers[k]);
+        // the next layer goes to a free context, else to the first one whose stream has drained
+        int c = -1;
+        for (int i = 0; i < n_ctx && c < 0; ++i)
+            if (running[i] < 0) c = i;
+        while (c < 0) {
+            for (int i = 0; i < n_ctx && c < 0; ++i)
+                if (hipStreamQuery(ctxs[i]->stream) != hipErrorNotReady) c = i;   // drained, or an error that aser_finish reports
+            if (c < 0) {
+                const timespec nap = {0, 20000};
+                nanosleep(&nap, nullptr);
+            }
+        }
+        finish(c);
+        aser_layer_desc& L = layers[k];
+        L.err = 0.0;
+        L.n_iter = 0;
+        L.status = enqueue_layer(ctxs[c], L);
+        if (ctxs[c]->rec_pending) running[c] = k;
+        else if (L.status != ASER_OK && first_bad == ASER_OK) first_bad = L.status;
     }
-    for (int k = (n_layers > n_ctx ? n_layers - n_ctx : 0); k < n_layers; ++k) finish(k);
+    for (int c = 0; c < n_ctx; ++c) finish(c);
     return first_bad;
 }
 
