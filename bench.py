@@ -6,7 +6,10 @@ One step = one pass of the whole hot path over one synthetic layer whose inputs 
 HBM: reset statistics, Gram accumulation (+ channel |x| sums), outlier selection / smoothing
 diagonal, per-channel RTN and target T, Cholesky whitening, rank-r truncated SVD and L_A, L_B.
 The default workload is the 4096 x 4096 Llama-7B-shaped projection (N = 32768 bf16 tokens, W4,
-r = 64, f = 32).  Prints ONE JSON line.  The "roofline" object prices the dominant kernel (the
+r = 64, f = 32).  `value` is the wall clock per layer over K such steps with four layers in flight
+(aser_calibrate_layers: Algorithm 1's loop over layers, one context and stream per layer in flight);
+`one_layer_at_a_time_ms` and `stage_ms` are the same pass with a host wait after every layer.
+Prints ONE JSON line.  The "roofline" object prices the dominant kernel (the
 bf16 MFMA Gram update) by its algorithmic flops N n (n + 1); "cpu_baseline" times the CPU
 oracle on a bounded sample on this host.  `--config c3` times the whole Llama-3-8B-shaped block
 (seven layers on four input streams, plus the per-token A8 quantizer) and reports per-layer times.
@@ -434,7 +437,7 @@ def extras(ctx, aser, torch, spec, buf, W, X, reps):
     return res
 
 
-def layers_in_flight(aser, torch, spec, X, Ws, n_ctx, n_layers):
+def layers_in_flight(aser, torch, spec, X, Ws, n_ctx, n_layers, warmup):
     """Throughput of Algorithm 1's loop over layers with n_ctx layers in flight (aser_calibrate_layers: one host
     thread, n_ctx contexts with their own streams, buffers and workspaces; every layer is a full pass of the
     workload from the shared X, statistics cleared first).  Returns wall-clock ms per layer and the errors."""
@@ -446,20 +449,23 @@ def layers_in_flight(aser, torch, spec, X, Ws, n_ctx, n_layers):
     streams = [pool[i] for i in picked]
     n_ctx = len(streams)
     ctxs = [aser.Context(0, stream=s.cuda_stream) for s in streams]
-    bufs = [aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed=True) for _ in range(n_ctx)]
+    # per layer: its outputs; G, T and S are intermediates of the context that gets the layer
+    outs = [aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed=True, intermediates=False)
+            for _ in range(n_layers)]
+    need = aser.aser_layer_workspace_bytes(aser.layer_desc(Ws[0], outs[0], X=X))
     for c in ctxs:
-        c.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, spec.r))
+        c.ensure_workspace(need)
     torch.cuda.synchronize()
 
     def run(count):
-        descs = [aser.layer_desc(Ws[k % len(Ws)], bufs[k % n_ctx], X=X, clear_stats=True) for k in range(count)]
+        descs = [aser.layer_desc(Ws[k % len(Ws)], outs[k], X=X) for k in range(count)]
         st = aser.aser_calibrate_layers(ctxs, descs)
         if st != aser.ASER_OK:
             bad = next(k for k, d in enumerate(descs) if d.status != aser.ASER_OK)
-            raise aser.AserError(st, "layer %d: %s" % (bad, ctxs[bad % n_ctx].last_error()))
+            raise aser.AserError(st, "layer %d of %d in flight: status %d" % (bad, n_ctx, descs[bad].status))
         return [d.err for d in descs]
 
-    run(2 * n_ctx)                                        # untimed
+    run(min(max(warmup, n_ctx), n_layers))                # untimed
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     errs = run(n_layers)
@@ -486,8 +492,8 @@ def main():
     ap.add_argument("--clock-summary", nargs=2, metavar=("RESULT_DIR", "NOTE"),
                     help="print per-kernel shader clocks of a rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE run (no GPU needed)")
     ap.add_argument("--no-extras", action="store_true", help="skip the timings of the rows beyond the calibration path")
-    ap.add_argument("--in-flight", default="2,4", help="also time aser_calibrate_layers with this many layers in flight "
-                    "(comma-separated counts; empty to skip)")
+    ap.add_argument("--in-flight", default="4,2", help="layers in flight (aser_calibrate_layers): the first count is the "
+                    "headline's, the others are reported beside it; 1 or empty: one layer at a time is the headline")
     args = ap.parse_args()
     if args.traffic_summary:
         return traffic_summary(*args.traffic_summary)
@@ -587,15 +593,19 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     stage_ms = [s / args.steps for s in stage_ms]
 
-    # Throughput with several layers in flight (separate contexts and streams); `value` stays the one-layer latency
+    # The headline: args.steps layers through aser_calibrate_layers with the first count of --in-flight layers in
+    # flight (contexts and streams of their own), wall clock over all of them.  The one-layer-at-a-time figure
+    # above stays in the line next to it, with its stage times.
     in_flight = {}
-    for tok in [t for t in args.in_flight.split(",") if t.strip()]:
-        nl = int(tok)
-        ms_l, errs_l, got = layers_in_flight(aser, torch, spec, X, Ws, nl, nl * args.steps)
+    counts = [int(t) for t in args.in_flight.split(",") if t.strip() and int(t) > 1]
+    for nl in counts:
+        ms_l, errs_l, got = layers_in_flight(aser, torch, spec, X, Ws, nl, max(args.steps, nl), args.warmup)
         in_flight[str(nl)] = {"ms_per_layer": round(ms_l, 4), "layers_per_s": round(1e3 / ms_l, 2),
                               "concurrent_streams": got,
                               "whitened_error_max_rel_dev": max(abs(e / err - 1.0) for e in errs_l)}
         log("layers in flight %d: %.3f ms per layer" % (nl, ms_l))
+    head_n = counts[0] if counts else 1
+    head_ms = in_flight[str(head_n)]["ms_per_layer"] if counts else ms_per_step
 
     # Dominant kernel alone: the Gram MFMA kernel (no statistics pass), HIP events on the launch stream, one
     # pair around every launch, and a whole layer step between two launches as in the pipeline.  (Launched
@@ -687,14 +697,19 @@ def main():
                              "util_exec_of_bf16_peak": round(3.0 * tf / BF16_PEAK_TFLOPS, 5),
                              "util_alg_of_fp32_mfma_peak": round(tf / FP32_MFMA_PEAK_TFLOPS, 4)}
     out = {
-        "metric": METRIC, "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "metric": METRIC, "value": head_ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head_ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if spec.x_dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: W %dx%d fp32, X %dx%d %s, W%d per-channel RTN, r=%d, f=%d" %
                                (spec.name, spec.m, spec.n, spec.tokens, spec.n, spec.x_dtype, spec.bits, spec.r, spec.f),
-                   "svd_block": svd_block, "svd_iters": svd_iters},
-        "layers_per_s": 1e3 / ms_per_step,
-        "calibration_tokens_per_s": spec.tokens * 1e3 / ms_per_step,
+                   "svd_block": svd_block, "svd_iters": svd_iters, "layers_in_flight": head_n,
+                   "note": "value = wall clock per layer over `steps` layers, every one a full pass from the resident "
+                           "X (statistics cleared, Gram update, smoothing, RTN, whitening, reconstruction), with "
+                           "`layers_in_flight` of them on the device at a time (aser_calibrate_layers); "
+                           "one_layer_at_a_time_ms is the same pass with a host wait after every layer"},
+        "one_layer_at_a_time_ms": ms_per_step,
+        "layers_per_s": 1e3 / head_ms,
+        "calibration_tokens_per_s": spec.tokens * 1e3 / head_ms,
         "stage_ms": {k: round(v, 4) for k, v in zip(stage_names, stage_ms)},
         "gram_mfma_util_pct": 100.0 * gram_tflops / BF16_PEAK_TFLOPS,
         "stage_util": stage_util,

@@ -226,7 +226,10 @@ int aser_finish(aser_ctx* ctx, double* err, int32_t* n_iter);
 typedef struct aser_layer_desc {
     /* stage 1, aser_gram_accumulate.  X == NULL: G, abs_sum and count already hold the finished statistics
      * of this layer's input when aser_calibrate_layers is called (layers that share an input: accumulate
-     * once, before the call).  clear_stats != 0 (with X): G (n x n, ldg), abs_sum and count are cleared first. */
+     * once, before the call).  clear_stats != 0 (with X): G (n x n, ldg), abs_sum and count are cleared first.
+     * Intermediates that the caller does not keep may be NULL and then live in the context's workspace for
+     * the time the layer is in flight: G (with X given; abs_sum and count are then taken from there too and
+     * cleared), T, S.  The workspace must then hold aser_layer_workspace_bytes(layer). */
     const void* X; int32_t x_dtype; int32_t clear_stats; int64_t rows; int64_t ldx;
     float* G; int64_t ldg; double* abs_sum; int64_t* count;
     /* stage 2, aser_smooth_outliers */
@@ -243,7 +246,7 @@ typedef struct aser_layer_desc {
 
 /* Algorithm 1's loop over layers with up to n_ctx (<= 64) layers in flight.  Layers are started in the order
  * given, each on a context that is free or, when all are busy, on the first one whose stream has drained
- * (every context has its own stream and its own workspace of at least aser_workspace_bytes of EVERY layer);
+ * (every context has its own stream and its own workspace of at least aser_layer_workspace_bytes of EVERY layer);
  * the five stages of a layer are enqueued without a host wait.  The dependent chain of small launches that
  * bounds one layer (whitening, subspace iteration) leaves most of the device idle, and the chains of the
  * other layers run there; give long layers first.
@@ -254,6 +257,8 @@ typedef struct aser_layer_desc {
  * Layers in flight together must not share output buffers; inputs (X, W, finished statistics) may be
  * shared.  Host code runs on the calling thread only. */
 int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_layer_desc* layers, int32_t n_layers);
+/* Workspace a context needs for this layer: aser_workspace_bytes of its shape plus the intermediates left NULL. */
+size_t aser_layer_workspace_bytes(const aser_layer_desc* layer);
 
 /* Streams for aser_calibrate_layers.  A process has few hardware queues (four by default) and the runtime maps
  * every stream to one of them; two streams on the same queue run one after the other, however independent their

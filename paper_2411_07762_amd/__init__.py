@@ -40,6 +40,7 @@ EXPORTS = (
     "aser_output_error_workspace_bytes", "aser_layer_output_error",
     "aser_forward_workspace_bytes", "aser_compensated_forward", "aser_mfma_rate_probe",
     "aser_error_reconstruct_enqueue", "aser_finish", "aser_calibrate_layers", "aser_pick_concurrent_streams",
+    "aser_layer_workspace_bytes",
 )
 
 
@@ -113,6 +114,8 @@ def load_library() -> ctypes.CDLL:
     lib.aser_finish.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     lib.aser_calibrate_layers.restype = ctypes.c_int
     lib.aser_calibrate_layers.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(aser_layer_desc), i32]
+    lib.aser_layer_workspace_bytes.restype = ctypes.c_size_t
+    lib.aser_layer_workspace_bytes.argtypes = [ctypes.POINTER(aser_layer_desc)]
     lib.aser_pick_concurrent_streams.restype = ctypes.c_int
     lib.aser_pick_concurrent_streams.argtypes = [i32, ctypes.POINTER(vp), i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.aser_svd_plan.restype = ctypes.c_int
@@ -405,10 +408,17 @@ def aser_mfma_rate_probe(ctx: Context, kind: int, workgroups_per_cu: int = 1, it
 class LayerBuffers:
     """Device buffers of one layer's calibration state and outputs (allocated with torch)."""
 
-    def __init__(self, m: int, n: int, r: int, f: int, bits: int, packed: bool, device: int = 0):
+    def __init__(self, m: int, n: int, r: int, f: int, bits: int, packed: bool, device: int = 0,
+                 intermediates: bool = True):
+        """intermediates=False: no G / abs_sum / count, T and S (aser_calibrate_layers then keeps them in the
+        context's workspace while the layer is in flight)."""
         import torch
         dev = "cuda:%d" % device
         self.m, self.n, self.r, self.f, self.bits, self.packed = m, n, r, f, bits, packed
+        if not intermediates:
+            self._stats = self.G = self.abs_sum = self.count = self.T = self.S = None
+            self._outputs(torch, dev)
+            return
         # the three statistics share one allocation, so that clearing them is one launch
         g_bytes = (n * n * 4 + 255) // 256 * 256
         a_bytes = (n * 8 + 255) // 256 * 256
@@ -416,12 +426,16 @@ class LayerBuffers:
         self.G = self._stats[:n * n * 4].view(torch.float32).view(n, n)
         self.abs_sum = self._stats[g_bytes:g_bytes + n * 8].view(torch.float64)
         self.count = self._stats[g_bytes + a_bytes:g_bytes + a_bytes + 8].view(torch.int64)
+        self.T = torch.empty((m, n), dtype=torch.float32, device=dev)
+        self.S = torch.empty((n, n), dtype=torch.float32, device=dev)
+        self._outputs(torch, dev)
+
+    def _outputs(self, torch, dev):
+        m, n, r, f, packed = self.m, self.n, self.r, self.f, self.packed
         self.idx = torch.zeros(max(f, 1), dtype=torch.int32, device=dev)
         self.mdiag = torch.empty(n, dtype=torch.float32, device=dev)
         self.codes = torch.empty((m, n // 2 if packed else n), dtype=torch.uint8 if packed else torch.int8, device=dev)
         self.scales = torch.empty(m, dtype=torch.float32, device=dev)
-        self.T = torch.empty((m, n), dtype=torch.float32, device=dev)
-        self.S = torch.empty((n, n), dtype=torch.float32, device=dev)
         self.L_A = torch.empty((m, r), dtype=torch.float32, device=dev)
         self.L_B = torch.empty((r, n), dtype=torch.float32, device=dev)
         self.sigma = torch.empty(r, dtype=torch.float32, device=dev)
@@ -460,16 +474,21 @@ def layer_desc(W, buf: "LayerBuffers", X=None, clear_stats: bool = False, opts: 
     if X is not None:
         d.X, d.x_dtype, d.rows, d.ldx = _ptr(X), _dtype_code(X), X.shape[0], _ld(X, buf.n)
     d.clear_stats = 1 if clear_stats else 0
-    d.G, d.ldg, d.abs_sum, d.count = _ptr(buf.G), _ld(buf.G, buf.n), _ptr(buf.abs_sum), _ptr(buf.count)
+    d.G, d.ldg, d.abs_sum, d.count = _ptr(buf.G), _ld(buf.G, buf.n) if buf.G is not None else 0, _ptr(buf.abs_sum), _ptr(buf.count)
     d.W, d.m, d.n, d.ldw, d.f, d.bits = _ptr(W), buf.m, buf.n, _ld(W, buf.n), buf.f, buf.bits
     d.idx, d.mdiag = _ptr(buf.idx), _ptr(buf.mdiag)
     d.layout = ASER_CODES_INT4_PACKED if buf.packed else ASER_CODES_INT8
-    d.r, d.codes, d.scales, d.T, d.ldt = buf.r, _ptr(buf.codes), _ptr(buf.scales), _ptr(buf.T), _ld(buf.T, buf.n)
-    d.damp, d.S, d.lds = damp, _ptr(buf.S), _ld(buf.S, buf.n)
+    d.r, d.codes, d.scales = buf.r, _ptr(buf.codes), _ptr(buf.scales)
+    d.T, d.ldt = _ptr(buf.T), _ld(buf.T, buf.n) if buf.T is not None else 0
+    d.damp, d.S, d.lds = damp, _ptr(buf.S), _ld(buf.S, buf.n) if buf.S is not None else 0
     if opts is not None:
         d.opts = ctypes.pointer(opts)
     d.L_A, d.L_B, d.sigma = _ptr(buf.L_A), _ptr(buf.L_B), _ptr(buf.sigma)
     return d
+
+
+def aser_layer_workspace_bytes(desc: aser_layer_desc) -> int:
+    return int(load_library().aser_layer_workspace_bytes(ctypes.byref(desc)))
 
 
 def aser_calibrate_layers(ctxs, descs) -> int:

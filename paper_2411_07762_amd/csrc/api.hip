@@ -34,6 +34,7 @@ extern "C" int aser_create(aser_ctx** out, int device, void* hip_stream) {
     c->rec_pending = false;
     c->rec_exact = false;
     c->rec_iters = 0;
+    c->share = 1;
     c->err[0] = 0;
     *out = c;
     return ASER_OK;

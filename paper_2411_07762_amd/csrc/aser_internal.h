@@ -28,6 +28,7 @@ struct aser_ctx {
     bool rec_pending;
     bool rec_exact;      // the dense solver ran (no orthogonalisation flag to look at)
     int32_t rec_iters;
+    int share;           // layers in flight on the device next to this context's (1: alone); see aser_split_k_parts
     char err[256];
 };
 
@@ -157,13 +158,18 @@ int aser_gemm_tn(aser_ctx* ctx, const GemmArgs& g);
 // step; every workgroup adds 0.06 u of atomic traffic that the others wait behind.  More parts shorten
 // the K loop but multiply the atomics, and one workgroup more than 256 doubles the rounds.
 // A part keeps at least min_steps K steps.
-static inline int aser_split_k_parts(int64_t tiles, int64_t ksteps, int64_t min_steps, double u) {
+// share > 1: that many layers are in flight on the device (aser_calibrate_layers).  What a launch costs the
+// other layers is the compute-unit time it holds, workgroups x their duration / 256, and every other layer
+// pays it; the cost then is the launch's own duration plus (share - 1) times that.
+static inline int aser_split_k_parts(int64_t tiles, int64_t ksteps, int64_t min_steps, double u, int share = 1) {
     const int64_t max_parts = ksteps / min_steps > 0 ? ksteps / min_steps : 1;
     int best = 1;
     double best_cost = 0.0;
     for (int64_t p = 1; p <= max_parts && p <= 64; ++p) {
         const int64_t wgs = tiles * p, rounds = ceil_div64(wgs, 256), steps = ceil_div64(ksteps, p);
-        const double cost = (double)rounds * (0.75 * u * (double)steps + 4.0) + 0.06 * u * (double)wgs;
+        const double per_wg = 0.75 * u * (double)steps + 4.0;
+        double cost = (double)rounds * per_wg + 0.06 * u * (double)wgs;
+        if (share > 1) cost += (double)(share - 1) * (double)wgs * per_wg / 256.0;
         if (p == 1 || cost < best_cost) { best_cost = cost; best = (int)p; }
     }
     return best;

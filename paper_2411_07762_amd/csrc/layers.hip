@@ -38,12 +38,45 @@ int timed_delays(hipStream_t a, hipStream_t b, bool use_b, int reps, double* ms)
     return ASER_OK;
 }
 
-int enqueue_layer(aser_ctx* ctx, const aser_layer_desc& L) {
+// Bytes of workspace behind the stage calls' own scratch that the layer's intermediates take when the
+// descriptor leaves them to the context (null G with activations given, null T, null S).
+size_t intermediates_bytes(const aser_layer_desc& L) {
+    size_t extra = 0;
+    const size_t nn = align_up((size_t)L.n * L.n * 4, 256), mn = align_up((size_t)L.m * L.n * 4, 256);
+    if (L.X && !L.G) extra += nn + align_up((size_t)L.n * 8, 256) + 256;
+    if (!L.T) extra += mn;
+    if (!L.S) extra += nn;
+    return extra;
+}
+
+int enqueue_layer(aser_ctx* ctx, const aser_layer_desc& in) {
+    aser_layer_desc L = in;
+    if (L.m <= 0 || L.n <= 0) ASER_FAIL(ctx, ASER_ERR_SHAPE, "calibrate_layers: bad shape");
+    if (!L.X && !L.G) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "calibrate_layers: neither activations nor finished statistics");
+    if (intermediates_bytes(L) > 0) {
+        // intermediates that the caller does not want to keep live in the context's workspace, behind what
+        // the stage calls use for this shape (the status block stays at the very end)
+        size_t off = aser_workspace_bytes(L.m, L.n, L.r, L.opts) - kAserWsTail;
+        if (!ctx->ws || ctx->ws_bytes < off + intermediates_bytes(L) + kAserWsTail)
+            ASER_FAIL(ctx, ASER_ERR_WORKSPACE, "calibrate_layers: workspace too small (%zu needed)",
+                      off + intermediates_bytes(L) + kAserWsTail);
+        auto take = [&](size_t bytes) { char* p = (char*)ctx->ws + off; off += align_up(bytes, 256); return p; };
+        if (L.X && !L.G) {
+            L.G = (float*)take((size_t)L.n * L.n * 4);
+            L.ldg = L.n;
+            L.abs_sum = (double*)take((size_t)L.n * 8);
+            L.count = (int64_t*)take(256);
+            L.clear_stats = 1;
+        }
+        if (!L.T) { L.T = (float*)take((size_t)L.m * L.n * 4); L.ldt = L.n; }
+        if (!L.S) { L.S = (float*)take((size_t)L.n * L.n * 4); L.lds = L.n; }
+    }
     if (L.X) {
         if (L.clear_stats) {
-            if (!L.G || L.n <= 0 || L.ldg < L.n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "calibrate_layers: bad Gram matrix");
+            if (!L.G || L.ldg < L.n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "calibrate_layers: bad Gram matrix");
             ASER_TRY(aser_prepare_device(ctx));
-            ASER_TRY(aser_fill_f32(ctx, L.G, L.n, L.n, L.ldg, 0.f));
+            if (L.ldg == L.n) ASER_TRY(aser_fill_bytes(ctx, L.G, (size_t)L.n * L.n * 4));
+            else ASER_TRY(aser_fill_f32(ctx, L.G, L.n, L.n, L.ldg, 0.f));
             if (L.abs_sum) ASER_TRY(aser_fill_bytes(ctx, L.abs_sum, (size_t)L.n * 8));
             if (L.count) ASER_TRY(aser_fill_bytes(ctx, L.count, 8));
         }
@@ -65,6 +98,8 @@ extern "C" int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_
     int first_bad = ASER_OK;
     int running[kMaxCtx];                                      // the layer in flight on each context, or -1
     for (int c = 0; c < n_ctx; ++c) running[c] = -1;
+    int share = n_ctx < n_layers ? n_ctx : n_layers;
+    for (int c = 0; c < n_ctx; ++c) ctxs[c]->share = share > 0 ? share : 1;
     auto finish = [&](int c) {
         if (running[c] < 0) return;
         aser_layer_desc& L = layers[running[c]];
@@ -94,7 +129,13 @@ extern "C" int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_
         else if (L.status != ASER_OK && first_bad == ASER_OK) first_bad = L.status;
     }
     for (int c = 0; c < n_ctx; ++c) finish(c);
+    for (int c = 0; c < n_ctx; ++c) ctxs[c]->share = 1;
     return first_bad;
+}
+
+extern "C" size_t aser_layer_workspace_bytes(const aser_layer_desc* layer) {
+    if (!layer || layer->m <= 0 || layer->n <= 0) return 0;
+    return aser_workspace_bytes(layer->m, layer->n, layer->r, layer->opts) + intermediates_bytes(*layer);
 }
 
 extern "C" int aser_pick_concurrent_streams(int32_t device, void* const* candidates, int32_t n_candidates, int32_t want,

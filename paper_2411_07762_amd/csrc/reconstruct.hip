@@ -124,7 +124,7 @@ size_t aser_reconstruct_workspace(int64_t m, int64_t n, int r, const aser_svd_op
 namespace {
 
 // Arguments of C += A^T B with K split over workgroups (fp32 atomics).
-GemmArgs atomic_args(int form, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+GemmArgs atomic_args(int share, int form, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
                      int64_t M, int64_t N, int64_t K, int bm, int bn, bool upper_only = false) {
     GemmArgs g{};
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.Ct = nullptr; g.ldct = 0;
@@ -136,7 +136,7 @@ GemmArgs atomic_args(int form, const float* A, int64_t lda, const float* B, int6
     // call is pure latency).
     const int64_t tiles = ceil_div64(M, bm) * ceil_div64(N, bn);
     const int64_t ksteps = ceil_div64(K, 32);
-    g.k_parts = aser_split_k_parts(tiles, ksteps, tiles <= 4 ? 4 : 8, (double)(bm * bn) / (128.0 * 128.0));
+    g.k_parts = aser_split_k_parts(tiles, ksteps, tiles <= 4 ? 4 : 8, (double)(bm * bn) / (128.0 * 128.0), share);
     return g;
 }
 
@@ -144,7 +144,7 @@ GemmArgs atomic_args(int form, const float* A, int64_t lda, const float* B, int6
 int gemm_tn_atomic(aser_ctx* ctx, int form, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
                    int64_t M, int64_t N, int64_t K, int bm, int bn, bool clear, bool upper_only = false) {
     if (clear) ASER_TRY(aser_fill_f32(ctx, C, M, N, ldc, 0.f));
-    return aser_gemm_tn(ctx, atomic_args(form, A, lda, B, ldb, C, ldc, M, N, K, bm, bn, upper_only));
+    return aser_gemm_tn(ctx, atomic_args(ctx->share, form, A, lda, B, ldb, C, ldc, M, N, K, bm, bn, upper_only));
 }
 
 // The factorisation kernel reports a non-positive pivot with atomicMin(info, base + column + 1); the
@@ -309,7 +309,7 @@ extern "C" int aser_error_reconstruct_enqueue(aser_ctx* ctx, const float* T, int
             const int* gate = (done < 3 || (done & 1) == 0) ? nullptr : gate_dev;
             ASER_TRY(gemm_tn_atomic(ctx, form, A, n, Qcur, b, Zt, b, n, b, m, bmA, bnB, false));    // Zt = A^T Q_k
             {
-                GemmArgs gz = atomic_args(form, Zt, b, Zt, b, Mb, b, b, b, n, 128, 128, /*upper_only=*/true);
+                GemmArgs gz = atomic_args(ctx->share, form, Zt, b, Zt, b, Mb, b, b, b, n, 128, 128, /*upper_only=*/true);
                 gz.gate = gate;
                 ASER_TRY(aser_gemm_tn(ctx, gz));
                 ASER_TRY(aser_chol_block(ctx, Mb, b, b, Rz_inv, info, kPivotBase, /*clear_d=*/true, nullptr, nullptr, beta_dev, gate));

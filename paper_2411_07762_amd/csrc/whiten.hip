@@ -143,7 +143,7 @@ extern "C" int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n
         if (six && bm == 256 && bn == 256) bn = 128;    // the six-product form has no 256 x 256 tile
         u.bm = bm; u.bn = bn; u.upper_only = 1;
         const int64_t tiles = ceil_div64(u.M, u.bm) * ceil_div64(u.N, u.bn), ksteps = ceil_div64(klen, 32);
-        u.k_parts = aser_split_k_parts(tiles, ksteps, 4, (double)(bm * bn) / (128.0 * 128.0));
+        u.k_parts = aser_split_k_parts(tiles, ksteps, 4, (double)(bm * bn) / (128.0 * 128.0), ctx->share);
         return aser_gemm_tn(ctx, u);
     };
     for (int64_t k0 = 0; k0 < n; k0 += kNb) {

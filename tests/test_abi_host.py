@@ -140,12 +140,20 @@ def test_layers_in_flight_validation(ctx):
     assert lib.aser_calibrate_layers(handles, 1, None, 0) == aser.ASER_OK                # no layers: nothing to do
     assert lib.aser_calibrate_layers(handles, 1, None, 2) == aser.ASER_ERR_INVALID_ARG
     # a layer whose arguments a stage refuses is reported in its descriptor and the others are still visited
-    bad = aser.aser_layer_desc()                                                       # all null: stage 2 refuses W
+    bad = aser.aser_layer_desc()                                                       # no shape at all
+    nostats = aser.aser_layer_desc()
+    nostats.m, nostats.n = 8, 16                                                       # neither activations nor statistics
     worse = aser.aser_layer_desc()
-    worse.X, worse.x_dtype, worse.rows, worse.n, worse.ldx, worse.G, worse.ldg = P, 7, 4, 16, 16, P, 16   # unknown dtype
-    st = aser.aser_calibrate_layers([ctx], [bad, worse])
-    assert st == aser.ASER_ERR_INVALID_ARG
-    assert bad.status == aser.ASER_ERR_INVALID_ARG and worse.status == aser.ASER_ERR_DTYPE
+    worse.X, worse.x_dtype, worse.rows, worse.ldx, worse.G, worse.ldg = P, 7, 4, 16, P, 16       # unknown dtype
+    worse.m, worse.n, worse.T, worse.S = 8, 16, P, P
+    small = aser.aser_layer_desc()                                                     # T and S left to a workspace that is not bound
+    small.X, small.rows, small.ldx, small.G, small.ldg, small.m, small.n, small.r = P, 4, 16, P, 16, 8, 16, 4
+    st = aser.aser_calibrate_layers([ctx], [bad, nostats, worse, small])
+    assert st == aser.ASER_ERR_SHAPE                                                   # the first one that failed
+    assert [d.status for d in (bad, nostats, worse, small)] == [aser.ASER_ERR_SHAPE, aser.ASER_ERR_INVALID_ARG,
+                                                                aser.ASER_ERR_DTYPE, aser.ASER_ERR_WORKSPACE]
+    assert aser.aser_layer_workspace_bytes(small) == aser.aser_workspace_bytes(8, 16, 4) + 8 * 16 * 4 + 16 * 16 * 4
+    assert aser.aser_layer_workspace_bytes(worse) == aser.aser_workspace_bytes(8, 16, 0)
     cnt, chosen = ctypes.c_int32(0), (ctypes.c_int32 * 2)()
     assert lib.aser_pick_concurrent_streams(0, None, 2, 1, chosen, ctypes.byref(cnt)) == aser.ASER_ERR_INVALID_ARG
     assert lib.aser_pick_concurrent_streams(0, handles, 1, 0, chosen, ctypes.byref(cnt)) == aser.ASER_ERR_INVALID_ARG

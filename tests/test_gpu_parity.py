@@ -495,14 +495,14 @@ def test_layers_in_flight():
     assert st == aser.ASER_OK and len(set(picked)) == len(picked) == 3           # four hardware queues per process
     streams = [pool[i] for i in picked]
     ctxs = [aser.Context(0, stream=s.cuda_stream) for s in streams]
-    layers, need = [], 0
-    for name, spec, packed in picks:
+    layers = []
+    for i, (name, spec, packed) in enumerate(picks):
         W = synth.make_weight(spec)
         x_np = synth.make_activations(spec)
-        buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed)
+        # every other layer leaves G, T and S to the context's workspace
+        buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed, intermediates=(i % 2 == 0))
         layers.append(dict(name=name, spec=spec, packed=packed, W=torch.from_numpy(W).to(DEV), X=to_dev_x(spec, x_np), buf=buf,
                            ref=oracle_layer(spec, W, x_np)))
-        need = max(need, aser.aser_workspace_bytes(spec.m, spec.n, spec.r))
     # a second layer on the first one's input (another weight, same shape): its statistics are accumulated before the call
     name, spec, packed = picks[0]
     spec2 = spec.with_(name=spec.name + "_b", layer_id=spec.layer_id + 1)      # another weight, the same input stream
@@ -518,11 +518,13 @@ def test_layers_in_flight():
     empty = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed)
     layers.insert(2, dict(name="no_tokens", spec=spec, packed=packed, W=layers[0]["W"], X=None, buf=empty, ref=None))
     torch.cuda.synchronize()
+    descs = [aser.layer_desc(L["W"], L["buf"], X=L["X"], clear_stats=L["X"] is not None) for L in layers]
+    need = max(aser.aser_layer_workspace_bytes(d) for d in descs)
+    assert need > max(aser.aser_workspace_bytes(L["spec"].m, L["spec"].n, L["spec"].r) for L in layers)
     for c in ctxs:
         c.ensure_workspace(need)
-    descs = [aser.layer_desc(L["W"], L["buf"], X=L["X"], clear_stats=L["X"] is not None) for L in layers]
     for L in layers:
-        if L["X"] is not None:
+        if L["X"] is not None and L["buf"].G is not None:
             L["buf"].G.fill_(7.0)                                   # clear_stats has to remove this
     torch.cuda.synchronize()
     say("layers in flight: %s on %d contexts" % ([L["name"] for L in layers], len(ctxs)))
