@@ -300,19 +300,31 @@ def run_block(args):
 
 
 def trace_summary(result_dir, note):
-    """Prints the per-kernel totals of a rocprofv3 --kernel-trace --stats run (kept under profiles/)."""
+    """Prints the per-kernel totals of a rocprofv3 --kernel-trace --stats run (kept under profiles/): first the
+    launches on the default stream (the one-layer-at-a-time pass and the kernel timing loops: kernels that have
+    the device to themselves, which is what the roofline figures refer to), then the launches on the other
+    streams (the layers in flight, whose kernels share the device and take longer each)."""
+    import collections
     import glob
     import sqlite3
     dbs = sorted(glob.glob(os.path.join(result_dir, "**", "*_results.db"), recursive=True))
     if not dbs:
         raise SystemExit("no *_results.db under %s" % result_dir)
     con = sqlite3.connect(dbs[-1])
-    rows = con.execute("select name, total_calls, total_duration, average, percentage from top_kernels limit 40").fetchall()
+    agg = {True: collections.defaultdict(list), False: collections.defaultdict(list)}
+    for name, stream, dur in con.execute("select name, stream, duration from kernels"):
+        agg[stream is None or "Default" in stream][name].append(dur * 1e-3)
     print(note)
-    print("\nPer-kernel totals (durations in microseconds):")
-    print("%-96s %6s %12s %10s %6s" % ("kernel", "calls", "total_us", "avg_us", "pct"))
-    for r in rows:
-        print("%-96s %6d %12.1f %10.2f %6.2f" % (r[0][:96], r[1], r[2], r[3], r[4]))
+    for alone, title in ((True, "Launches on the default stream (kernels running alone)"),
+                         (False, "Launches on the streams of the layers in flight (kernels sharing the device)")):
+        rows = sorted(agg[alone].items(), key=lambda kv: -sum(kv[1]))[:40]
+        if not rows:
+            continue
+        total = sum(sum(v) for v in agg[alone].values())
+        print("\n%s; durations in microseconds:" % title)
+        print("%-96s %6s %12s %10s %6s" % ("kernel", "calls", "total_us", "avg_us", "pct"))
+        for name, v in rows:
+            print("%-96s %6d %12.1f %10.2f %6.2f" % (name[:96], len(v), sum(v), sum(v) / len(v), 100.0 * sum(v) / total))
 
 
 def clock_summary(result_dir, note):
