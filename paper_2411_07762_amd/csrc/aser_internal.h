@@ -209,7 +209,7 @@ int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float*
 // close for that method, else 0; the caller then runs aser_jacobi_eig gated on the flag.  2 <= b <= 128.
 int aser_tridiag_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float* V, float* refl, float* tri,
                      int* cluster_flag);
-// C (rows x c) = A (rows x k) * B (k x c), plain fp32 FMA; k, c <= 128, k % 4 == 0, A 16-byte aligned with
+// C (rows x c) = A (rows x k) * B (k x c), fp32 MFMA; k, c <= 128, k % 4 == 0, A 16-byte aligned with
 // lda % 4 == 0.  C may not alias A.  The first clear_rows rows of A (k columns each; may exceed `rows`) are
 // set to zero after they have been read.  transposed: the result is stored as C^T (c x rows, leading dimension ldc).
 // C (rows x b) = (A1 + alpha A2 P) B1 (A2 null: C = A1 B1); tall blocks and b x b factors, all with leading

@@ -1,5 +1,5 @@
 // The Jacobi eigen-solver (fallback of the Rayleigh-Ritz step of the truncated SVD, Eq. 6), one
-// workgroup with its matrices in LDS, and a plain fp32 FMA product for "tall times small" updates.
+// workgroup with its matrices in LDS, and an fp32 MFMA product for "tall times small" updates.
 #include "aser_internal.h"
 
 namespace {
@@ -118,27 +118,44 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const float* Mb, int b, fl
 }
 
 // ------------------------------------------------------------------------------------ small fp32 product
-// C (rows x c) = A (rows x k) * B (k x c) in plain fp32 FMAs, k, c <= 128.  A workgroup owns 16 rows;
-// its A rows and all of B go to LDS in one shot (every global load is issued before the first LDS
-// store: one memory round trip), a thread owns 1 row x 8 columns.  The first clear_rows rows of A
-// (may exceed `rows`) are cleared once they have been read, which leaves A ready as the target of
-// an accumulating product.
-constexpr int kGsRows = 16;
+// C (rows x c) = A (rows x k) * B (k x c) in fp32, k, c <= 128, on the fp32 MFMA instruction (16 x 16 x 4:
+// true fp32 products and sums).  A workgroup owns 32 rows; its A rows and all of B go to LDS in one shot
+// (every global load is issued before the first LDS store: one memory round trip); wavefront w owns
+// the 16 x 64 piece (row tile w / 2, column tiles 4 (w % 2) ...), four accumulator tiles.  The first
+// clear_rows rows of A (may exceed `rows`) are cleared once they have been read, which leaves A ready
+// as the target of an accumulating product.
+typedef float gs_f4v __attribute__((ext_vector_type(4)));
+constexpr int kGsRows = 32;
 constexpr int kGsPitch = 132;
+
+// acc[j] += A-rows (16 rt ...) x B-columns (16 (ct0 + j) ...) over k: lane (t_i, t_q) feeds A(t_i, 4 s + t_q) and
+// B(4 s + t_q, t_i); acc[j][e] is row 4 t_q + e, column t_i of tile j.
+__device__ __forceinline__ void small_product(gs_f4v (&acc)[4], const float* As, const float* Bs, int k, int rt, int ct0,
+                                              int t_i, int t_q) {
+    const float* pa = As + (16 * rt + t_i) * kGsPitch + t_q;
+    const float* pb = Bs + t_q * kGsPitch + 16 * ct0 + t_i;
+    for (int s = 0; s < k / 4; ++s) {
+        const float a = pa[4 * s];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, pb[4 * s * kGsPitch + 16 * j], acc[j], 0, 0, 0);
+    }
+}
 
 __global__ __launch_bounds__(256) void gemm_small_kernel(float* __restrict__ A, int64_t lda, const float* __restrict__ B,
                                                          int64_t ldb, float* __restrict__ C, int64_t ldc, int64_t rows,
                                                          int k, int c, int64_t clear_rows, int vec_b, int transposed) {
     extern __shared__ __align__(16) float gs_sm[];
-    float* As = gs_sm;                          // [16][132]
+    float* As = gs_sm;                          // [32][132]
     float* Bs = gs_sm + kGsRows * kGsPitch;     // [128][132]
-    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t_i = lane & 15, t_q = lane >> 4, rt = wave >> 1, ct0 = (wave & 1) * 4;
     const int64_t r0 = (int64_t)blockIdx.x * kGsRows;
 
-    // A: 16 rows x 128 k = 512 float4, two per thread (k is a multiple of 4 and rows are 16-byte aligned)
-    float4 av[2];
+    // A: 32 rows x 128 k = 1024 float4, four per thread (k is a multiple of 4 and rows are 16-byte aligned)
+    float4 av[4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < 4; ++u) {
         const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
         av[u] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (r0 + r < rows && k4 < k) av[u] = *(const float4*)(A + (r0 + r) * lda + k4);
@@ -164,7 +181,7 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(float* __restrict__ A, 
         }
     }
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < 4; ++u) {
         const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
         *(float4*)(As + r * kGsPitch + k4) = av[u];
         if (r0 + r < clear_rows && k4 < k) *(float4*)(A + (r0 + r) * lda + k4) = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -176,33 +193,19 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(float* __restrict__ A, 
     }
     __syncthreads();
 
-    float acc[8];
+    gs_f4v acc[4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-    const float* arow = As + ty * kGsPitch;
-    const float* bcol = Bs + 8 * tx;
-#pragma unroll 4
-    for (int k4 = 0; k4 < k; k4 += 4) {
-        const float4 a4 = *(const float4*)(arow + k4);
-        const float aa[4] = {a4.x, a4.y, a4.z, a4.w};
+    for (int j = 0; j < 4; ++j) acc[j] = gs_f4v{0.f, 0.f, 0.f, 0.f};
+    small_product(acc, As, Bs, k, rt, ct0, t_i, t_q);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int cc = 16 * (ct0 + j) + t_i;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float4 b0 = *(const float4*)(bcol + (k4 + e) * kGsPitch);
-            const float4 b1 = *(const float4*)(bcol + (k4 + e) * kGsPitch + 4);
-            acc[0] = fmaf(aa[e], b0.x, acc[0]); acc[1] = fmaf(aa[e], b0.y, acc[1]);
-            acc[2] = fmaf(aa[e], b0.z, acc[2]); acc[3] = fmaf(aa[e], b0.w, acc[3]);
-            acc[4] = fmaf(aa[e], b1.x, acc[4]); acc[5] = fmaf(aa[e], b1.y, acc[5]);
-            acc[6] = fmaf(aa[e], b1.z, acc[6]); acc[7] = fmaf(aa[e], b1.w, acc[7]);
-        }
-    }
-    const int64_t gr = r0 + ty;
-    if (gr < rows) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int cc = 8 * tx + j;
-            if (cc < c) {
-                if (transposed) C[(int64_t)cc * ldc + gr] = acc[j];      // C^T (c x rows, ld = ldc)
-                else C[gr * ldc + cc] = acc[j];
+            const int64_t gr = r0 + 16 * rt + 4 * t_q + e;
+            if (gr < rows && cc < c) {
+                if (transposed) C[(int64_t)cc * ldc + gr] = acc[j][e];      // C^T (c x rows, ld = ldc)
+                else C[gr * ldc + cc] = acc[j][e];
             }
         }
     }
@@ -211,35 +214,42 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(float* __restrict__ A, 
 // C (rows x b) = (A1 + alpha A2 P) B1 for two tall blocks and two b x b factors (A2 null: C = A1 B1), alpha read
 // from device memory; b a multiple of 4 up to 128, all leading dimensions b.  After they have been read, the rows
 // of A1 and the first zrows rows of Zclr (may be null) are cleared: both are accumulation targets of the products
-// that follow.  Same staging as gemm_small_kernel: A2 P first, then the sum goes back to LDS as the left operand
-// of the second product.
+// that follow.  Same staging and the same MFMA product as gemm_small_kernel: A2 P first, then the sum goes back to
+// LDS (every lane writes the entries its accumulators hold) as the left operand of the second product.
 __global__ __launch_bounds__(256) void combine_kernel(float* __restrict__ A1, const float* __restrict__ B1,
                                                       const float* __restrict__ A2, const float* __restrict__ P,
                                                       const float* __restrict__ alpha_dev,
                                                       float* __restrict__ C, int64_t rows, int b,
                                                       float* __restrict__ Zclr, int64_t zrows) {
     extern __shared__ __align__(16) float gs_sm[];
-    float* As = gs_sm;                          // [16][132]
+    float* As = gs_sm;                          // [32][132]
     float* Bs = gs_sm + kGsRows * kGsPitch;     // [128][132]
-    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t_i = lane & 15, t_q = lane >> 4, rt = wave >> 1, ct0 = (wave & 1) * 4;
     const int64_t r0 = (int64_t)blockIdx.x * kGsRows;
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    float acc[8];
-    // this thread's 1 x 8 piece of A1 (the columns it will own in the sum), read before A1 is cleared
-    float4 u0 = zero4, u1 = zero4;
-    const int64_t gr = r0 + ty;
-    if (gr < rows && 8 * tx < b) {
-        u0 = *(const float4*)(A1 + gr * b + 8 * tx);
-        if (8 * tx + 4 < b) u1 = *(const float4*)(A1 + gr * b + 8 * tx + 4);
+    gs_f4v acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] = gs_f4v{0.f, 0.f, 0.f, 0.f};
+    // this lane's entries of A1 (those its accumulators will hold in the sum), read before A1 is cleared
+    float u1[4][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int cc = 16 * (ct0 + j) + t_i;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int64_t gr = r0 + 16 * rt + 4 * t_q + e;
+            u1[j][e] = (gr < rows && cc < b) ? A1[gr * b + cc] : 0.f;
+        }
     }
     const float alpha = A2 ? *alpha_dev : 0.f;
     for (int term = A2 ? 0 : 1; term < 2; ++term) {
         const float* A = term ? nullptr : A2;
         const float* B = term ? B1 : P;
-        float4 av[2], bv[16];
+        float4 av[4], bv[16];
         if (A) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < 4; ++u) {
                 const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
                 av[u] = zero4;
                 if (r0 + r < rows && k4 < b) av[u] = *(const float4*)(A + (r0 + r) * b + k4);
@@ -254,23 +264,20 @@ __global__ __launch_bounds__(256) void combine_kernel(float* __restrict__ A1, co
         __syncthreads();                                // the previous product's readers (and the readers of A1) are done
         if (A) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < 4; ++u) {
                 const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
                 *(float4*)(As + r * kGsPitch + k4) = av[u];
             }
         } else {
-            // left operand of the second product: A1 + alpha (A2 P), this thread's 1 x 8 piece
-            if (A2) {
-                u0.x = fmaf(alpha, acc[0], u0.x); u0.y = fmaf(alpha, acc[1], u0.y);
-                u0.z = fmaf(alpha, acc[2], u0.z); u0.w = fmaf(alpha, acc[3], u0.w);
-                u1.x = fmaf(alpha, acc[4], u1.x); u1.y = fmaf(alpha, acc[5], u1.y);
-                u1.z = fmaf(alpha, acc[6], u1.z); u1.w = fmaf(alpha, acc[7], u1.w);
-            }
-            *(float4*)(As + ty * kGsPitch + 8 * tx) = u0;
-            *(float4*)(As + ty * kGsPitch + 8 * tx + 4) = u1;
+            // left operand of the second product: A1 + alpha (A2 P), the entries this lane's accumulators hold
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    As[(16 * rt + 4 * t_q + e) * kGsPitch + 16 * (ct0 + j) + t_i] = fmaf(alpha, acc[j][e], u1[j][e]);
             // the two accumulation targets are clear again
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < 4; ++u) {
                 const int q = tid + 256 * u, r = q >> 5, k4 = (q & 31) * 4;
                 if (r0 + r < rows && k4 < b) *(float4*)(A1 + (r0 + r) * b + k4) = zero4;
                 if (Zclr && r0 + r < zrows && k4 < b) *(float4*)(Zclr + (r0 + r) * b + k4) = zero4;
@@ -283,29 +290,16 @@ __global__ __launch_bounds__(256) void combine_kernel(float* __restrict__ A1, co
         }
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-        const float* arow = As + ty * kGsPitch;
-        const float* bcol = Bs + 8 * tx;
-#pragma unroll 4
-        for (int k4 = 0; k4 < b; k4 += 4) {
-            const float4 a4 = *(const float4*)(arow + k4);
-            const float aa[4] = {a4.x, a4.y, a4.z, a4.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float4 b0 = *(const float4*)(bcol + (k4 + e) * kGsPitch);
-                const float4 b1 = *(const float4*)(bcol + (k4 + e) * kGsPitch + 4);
-                acc[0] = fmaf(aa[e], b0.x, acc[0]); acc[1] = fmaf(aa[e], b0.y, acc[1]);
-                acc[2] = fmaf(aa[e], b0.z, acc[2]); acc[3] = fmaf(aa[e], b0.w, acc[3]);
-                acc[4] = fmaf(aa[e], b1.x, acc[4]); acc[5] = fmaf(aa[e], b1.y, acc[5]);
-                acc[6] = fmaf(aa[e], b1.z, acc[6]); acc[7] = fmaf(aa[e], b1.w, acc[7]);
-            }
-        }
+        for (int j = 0; j < 4; ++j) acc[j] = gs_f4v{0.f, 0.f, 0.f, 0.f};
+        small_product(acc, As, Bs, b, rt, ct0, t_i, t_q);
     }
-    if (gr < rows) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int cc = 8 * tx + j;
-            if (cc < b) C[gr * b + cc] = acc[j];
+    for (int j = 0; j < 4; ++j) {
+        const int cc = 16 * (ct0 + j) + t_i;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int64_t gr = r0 + 16 * rt + 4 * t_q + e;
+            if (gr < rows && cc < b) C[gr * b + cc] = acc[j][e];
         }
     }
 }
@@ -327,8 +321,8 @@ int aser_jacobi_eig(aser_ctx* ctx, const float* Mb, int b, float* lambda, float*
 int aser_gemm_small_f32(aser_ctx* ctx, float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
                         int64_t rows, int k, int c, int64_t clear_rows, bool transposed) {
     if (rows <= 0) return ASER_OK;
-    if (k <= 0 || c <= 0 || k > 128 || c > 128 || (k & 3)) ASER_FAIL(ctx, ASER_ERR_SHAPE, "gemm_small: need 0 < k, c <= 128, k % 4 == 0");
-    if (((uintptr_t)A & 15) || (lda & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_small: A must be 16-byte aligned with lda % 4 == 0");
+    if (k <= 0 || c <= 0 || k > 128 || c > 128 || (k & 3)) ASER_FAIL(ctx, ASER_ERR_SHAPE, "gemm_small: need 0 < k, c <= 128, k %% 4 == 0");
+    if (((uintptr_t)A & 15) || (lda & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "gemm_small: A must be 16-byte aligned with lda %% 4 == 0");
     const int vec_b = (((uintptr_t)B & 15) == 0 && (ldb & 3) == 0 && (c & 3) == 0) ? 1 : 0;
     static bool attr_set[16] = {false};
     const size_t lds = (size_t)(kGsRows + 128) * kGsPitch * sizeof(float);
@@ -345,7 +339,7 @@ int aser_gemm_small_f32(aser_ctx* ctx, float* A, int64_t lda, const float* B, in
 int aser_combine_f32(aser_ctx* ctx, float* A1, const float* B1, const float* A2, const float* P, const float* alpha_dev,
                      float* C, int64_t rows, int b, float* Zclr, int64_t zrows) {
     if (rows <= 0) return ASER_OK;
-    if (b <= 0 || b > 128 || (b & 3)) ASER_FAIL(ctx, ASER_ERR_SHAPE, "combine: need 0 < b <= 128, b % 4 == 0");
+    if (b <= 0 || b > 128 || (b & 3)) ASER_FAIL(ctx, ASER_ERR_SHAPE, "combine: need 0 < b <= 128, b %% 4 == 0");
     if (((uintptr_t)A1 & 15) || ((uintptr_t)B1 & 15) || ((uintptr_t)A2 & 15) || ((uintptr_t)P & 15) || ((uintptr_t)C & 15) ||
         ((uintptr_t)Zclr & 15))
         ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "combine: operands must be 16-byte aligned");
