@@ -12,6 +12,9 @@
  *   aser_error_reconstruct  rank-r SVD of T S, L_A = U_r Sigma_r,
  *                           L_B = V_r^T S^-1                              (Eq. 6, Sec. 4.1)
  *   aser_quantize_act_rtn   per-token RTN of X M^-1 (evaluation only)     (Sec. 5.1)
+ *   aser_calibrate_layers   Algorithm 1's loop over the layers of a model, several layers in flight on
+ *                           contexts and streams of their own (layers are independent once their inputs
+ *                           are stored)                                    (Alg. 1, loop over the layers W^l)
  *
  * Orientation.  The paper stores activations as (in x tokens) and writes the Gram matrix
  * X X^T.  This library stores activations tokens x in (N x n, row-major, channel
