@@ -394,6 +394,22 @@ def extras(ctx, aser, torch, spec, buf, W, X, reps):
                        "tridiagonalisation_algorithmic_bytes": pass_bytes,
                        "note": "bound by the passes over the fp64 trailing matrix (16 k^3 / 3 bytes, served by the "
                                "last-level cache when the matrix fits) and by 2 (k - 2) launches"}
+    # a rank beyond the widest subspace block of the iteration (the rule of Eq. 9 can ask for one): the dense fp64 solver
+    r_big = 200
+    if min(spec.m, spec.n) >= r_big and min(spec.m, spec.n) <= 16384 and spec.r <= 128:
+        ctx.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, r_big))
+        la = torch.empty((spec.m, r_big), dtype=torch.float32, device=dev)
+        lb = torch.empty((r_big, spec.n), dtype=torch.float32, device=dev)
+        sg = torch.empty(r_big, dtype=torch.float32, device=dev)
+        errs = []
+
+        def big():
+            st_, e_, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, r_big, la, lb, sg)
+            ctx.check(st_)
+            errs.append(e_)
+
+        res["reconstruct_rank_200_dense_solver"] = {"ms": timed(big, 1), "whitened_error": errs[-1]}
+        del la, lb, sg
     # layer-output error, W4A8 and W4A6, compensated and not, on a sample of the calibration tokens
     sample = min(2048, spec.tokens)
     ctx.ensure_workspace(aser.aser_output_error_workspace_bytes(spec.m, spec.n, sample, spec.r))

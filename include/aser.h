@@ -181,8 +181,9 @@ int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n, const flo
  *             whitened layer-output error ||(T - L_A L_B) S||_F of Eq. 8
  *     *n_iter (host, may be NULL) = subspace iterations performed
  * T: m x n fp32 (ldt); S: n x n fp32 lower triangular with zeros above the diagonal (lds).
- * 0 < r <= min(m, n, 128); for the subspace iteration a multiple of 32 must also lie in
+ * 0 < r <= min(m, n, 256); for the subspace iteration (r <= 128) a multiple of 32 must also lie in
  * [r, min(m, n, 128)] (the subspace width; e.g. r = 40 needs min(m, n) >= 64), else ASER_ERR_SHAPE.
+ * r > 128 always takes the dense solver below, which then needs min(m, n) <= 16384.
  * Synchronises the stream.
  * idx, f: the outlier set I_f of aser_smooth_outliers (f device int32 entries; f == 0: none, idx may be
  * NULL).  Those columns of T hold the unquantized W_o of Eq. 12 and dwarf the quantization error in the
@@ -191,7 +192,9 @@ int aser_whiten(aser_ctx* ctx, const float* G, int64_t ldg, int64_t n, const flo
  * smallest wanted singular directions.  The result does not depend on them otherwise; entries outside
  * [0, n) are ignored.  A caller that has outlier columns in T and passes f = 0 gets
  * ASER_ERR_NO_CONVERGE once sigma_1 / sigma_b passes a few hundred.
- * Solver.  Layers with m n <= 2^20 (default options, precision mode not FAST) take a dense fp64 solver:
+ * Solver.  Layers with m n <= 2^20 (default options, precision mode not FAST), and every call with r > 128
+ * (the widest subspace block is 128: tens to hundreds of milliseconds on layers of thousands of channels,
+ * against milliseconds for the iteration), take a dense fp64 solver:
  * every eigenvalue of the Gram matrix of the shorter side of T S (Householder tridiagonalisation,
  * bisection), the eigenvectors of the r largest (inverse iteration), *err from the tail of the spectrum;
  * idx, f and the block-width rule do not apply, *n_iter is 0.  Larger layers, and any call with
@@ -274,7 +277,8 @@ int aser_pick_concurrent_streams(int32_t device, void* const* candidates, int32_
                                  int32_t* chosen, int32_t* n_chosen);
 
 /* The subspace width and the iteration count aser_error_reconstruct will use for this shape and these
- * options (either pointer may be NULL).  ASER_ERR_SHAPE where aser_error_reconstruct would refuse. */
+ * options (either pointer may be NULL); both 0 for r > 128, which the dense solver takes.  ASER_ERR_SHAPE
+ * where aser_error_reconstruct would refuse. */
 int aser_svd_plan(int64_t m, int64_t n, int32_t r, const aser_svd_opts* opts, int32_t* block, int32_t* iters);
 
 /* All min(m, n) singular values of T S, descending, as fp64 (S == NULL: of T itself): the spectrum that

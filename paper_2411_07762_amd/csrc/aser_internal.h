@@ -89,8 +89,13 @@ size_t aser_reconstruct_workspace(int64_t m, int64_t n, int r, const aser_svd_op
 size_t aser_exact_workspace(int64_t m, int64_t n, int r);
 int aser_exact_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt, const float* S, int64_t lds,
                            int r, float* L_A, float* L_B, float* sigma, double* err2_dev);
-// True when aser_error_reconstruct takes the dense solver: a small layer, default options, not the fast mode.
-static inline bool aser_use_exact_solver(int precision, int64_t m, int64_t n, const aser_svd_opts* o) {
+// True when aser_error_reconstruct takes the dense solver: a small layer with default options outside the fast
+// mode, or a rank beyond the widest subspace block of the iteration (kAserMaxIterRank), whatever the options.
+static const int kAserMaxIterRank = 128;
+static const int kAserMaxRank = 256;          // one thread per wanted eigenvector in the dense solver's inverse iteration
+static const int64_t kAserMaxDenseSide = 16384;
+static inline bool aser_use_exact_solver(int precision, int64_t m, int64_t n, int r, const aser_svd_opts* o) {
+    if (r > kAserMaxIterRank) return true;
     return precision != ASER_PRECISION_FAST && m * n <= ((int64_t)1 << 20) && !(o && (o->max_iter > 0 || o->block > 0));
 }
 

@@ -114,6 +114,7 @@ size_t aser_reconstruct_workspace(int64_t m, int64_t n, int r, const aser_svd_op
     Plan p;
     make_plan(m, n, r, o, &p);
     size_t need = p.total;
+    if (r > kAserMaxIterRank) return aser_exact_workspace(m, n, r) + 256;   // only the dense solver takes such a rank
     if (m * n <= ((int64_t)1 << 20)) {                     // small layers may take the dense solver
         const size_t ex = aser_exact_workspace(m, n, r) + 256;
         if (ex > need) need = ex;
@@ -184,6 +185,12 @@ int legal_plan(int64_t m, int64_t n, int r, const aser_svd_opts* opts, Plan* p, 
 }  // namespace
 
 extern "C" int aser_svd_plan(int64_t m, int64_t n, int32_t r, const aser_svd_opts* opts, int32_t* block, int32_t* iters) {
+    if (r > kAserMaxIterRank) {                            // the dense solver: no block, no iterations
+        if (m <= 0 || n <= 0 || r > m || r > n || r > kAserMaxRank || (m < n ? m : n) > kAserMaxDenseSide) return ASER_ERR_SHAPE;
+        if (block) *block = 0;
+        if (iters) *iters = 0;
+        return ASER_OK;
+    }
     Plan p;
     const char* why = "";
     const int st = legal_plan(m, n, r, opts, &p, &why);
@@ -202,11 +209,15 @@ extern "C" int aser_error_reconstruct_enqueue(aser_ctx* ctx, const float* T, int
     if (m <= 0 || n <= 0 || ldt < n || lds < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: bad shape");
     if (f < 0 || f > n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: f must be in [0, n]");
     if (f > 0 && !idx) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "error_reconstruct: idx is null with f > 0");
-    const bool exact = aser_use_exact_solver(ctx->precision, m, n, opts);
+    const bool exact = aser_use_exact_solver(ctx->precision, m, n, r, opts);
     Plan p;
-    if (exact) {                                         // the dense solver has no subspace block: any r up to min(m, n, 128)
-        if (r <= 0 || r > m || r > n || r > 128) ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: need 0 < r <= min(m, n, 128)");
-        make_plan(m, n, r, opts, &p);
+    if (exact) {                                         // the dense solver has no subspace block: any r up to min(m, n, 256)
+        if (r <= 0 || r > m || r > n || r > kAserMaxRank)
+            ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: need 0 < r <= min(m, n, %d)", kAserMaxRank);
+        if (r > kAserMaxIterRank && (m < n ? m : n) > kAserMaxDenseSide)
+            ASER_FAIL(ctx, ASER_ERR_SHAPE, "error_reconstruct: r > %d takes the dense solver, which needs min(m, n) <= %lld",
+                      kAserMaxIterRank, (long long)kAserMaxDenseSide);
+        make_plan(m, n, r <= kAserMaxIterRank ? r : kAserMaxIterRank, opts, &p);
     } else {
         const char* why = "";
         const int st = legal_plan(m, n, r, opts, &p, &why);

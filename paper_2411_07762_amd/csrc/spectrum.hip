@@ -373,7 +373,7 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x) {
 __global__ __launch_bounds__(256) void tridiag_invit_kernel(int64_t k, int r, const double* __restrict__ d,
                                                             const double* __restrict__ e, const double* __restrict__ lam,
                                                             double* __restrict__ X, double* __restrict__ scr) {
-    __shared__ double dots[128];
+    __shared__ double dots[256];                      // r <= 256
     __shared__ double red[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     double tnorm = 0.0;

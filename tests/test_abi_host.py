@@ -116,7 +116,9 @@ def test_whiten_and_reconstruct_validation(ctx):
     r = aser.aser_error_reconstruct
     assert r(ctx, P, P, 0, P, P, P, m=64, n=64)[0] == aser.ASER_ERR_SHAPE
     assert r(ctx, P, P, 65, P, P, P, m=64, n=256)[0] == aser.ASER_ERR_SHAPE             # r > min(m, n)
-    assert r(ctx, P, P, 129, P, P, P, m=512, n=512)[0] == aser.ASER_ERR_SHAPE
+    assert r(ctx, P, P, 257, P, P, P, m=512, n=512)[0] == aser.ASER_ERR_SHAPE            # the dense solver's limit
+    assert r(ctx, P, P, 129, P, P, P, m=512, n=512)[0] == aser.ASER_ERR_WORKSPACE        # accepted: dense solver, no workspace bound
+    assert r(ctx, P, P, 129, P, P, P, m=20000, n=20000)[0] == aser.ASER_ERR_SHAPE        # dense solver: shorter side <= 16384
     assert r(ctx, P, P, 8, None, P, P, m=64, n=64)[0] == aser.ASER_ERR_INVALID_ARG
     assert r(ctx, P, P, 8, P, P, P, idx=None, f=3, m=64, n=64)[0] == aser.ASER_ERR_INVALID_ARG   # f > 0 needs idx
     assert r(ctx, P, P, 8, P, P, P, idx=P, f=65, m=64, n=64)[0] == aser.ASER_ERR_SHAPE            # f > n
@@ -166,6 +168,11 @@ def test_svd_plan_reports_what_the_iteration_will_use():
     assert aser.aser_svd_plan(4096, 4096, 64) == (aser.ASER_OK, 128, 9)
     assert aser.aser_svd_plan(4096, 11008, 64) == (aser.ASER_OK, 128, 12)
     assert aser.aser_svd_plan(8192, 28672, 128) == (aser.ASER_OK, 128, 30)       # no oversampling columns
+    # ranks beyond the widest subspace block go to the dense solver: no block, no iterations
+    assert aser.aser_svd_plan(4096, 4096, 200) == (aser.ASER_OK, 0, 0)
+    assert aser.aser_svd_plan(4096, 4096, 257)[0] == aser.ASER_ERR_SHAPE
+    assert aser.aser_svd_plan(20000, 28672, 200)[0] == aser.ASER_ERR_SHAPE       # dense solver: shorter side <= 16384
+    assert aser.aser_workspace_bytes(2048, 2048, 192) > 3 * 2048 * 2048 * 8      # fp64 product, Gram matrix, reflectors
     assert aser.aser_svd_plan(256, 256, 16) == (aser.ASER_OK, 32, 9)
     assert aser.aser_svd_plan(322, 74, 23) == (aser.ASER_OK, 64, 9)              # 2 r = 46 -> 64 fits in n = 74
     assert aser.aser_svd_plan(300, 40, 23)[:2] == (aser.ASER_OK, 32)             # shrunk to fit the matrix

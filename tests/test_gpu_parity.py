@@ -442,6 +442,10 @@ E2E_CASES = [
     ("w8_outliers_silu_f32", synth.mini("fz8", 181, 548, 1501, x_dtype="f32", x_dist="silu_prod", n_outliers=6, r=40, f=23,
                                         bits=8, seed_id=708), False),
     ("w8_few_outliers", synth.mini("fz21", 145, 410, 1105, n_outliers=3, r=31, f=3, bits=8, seed_id=721), False),
+    # ranks beyond the widest subspace block (128) take the dense solver whatever the size of the layer
+    ("rank_160_dense_solver", synth.mini("rk1", 700, 1536, 4096, n_outliers=8, r=160, f=16, seed_id=731), True),
+    ("rank_192_dense_solver_tall", synth.mini("rk2", 2304, 2048, 6144, x_dist="silu_prod", n_outliers=8, r=192, f=32,
+                                              seed_id=732, out=(40.0, 40.0)), True),
     # the subspace block is nearly as wide as the matrix (b = 64 of n = 74): the end of the spectrum is in it
     ("block_as_wide_as_matrix", synth.mini("fz7", 322, 74, 333, x_dtype="f32", x_dist="silu_prod", n_outliers=6, r=23, f=6,
                                            bits=4, seed_id=707), True),
@@ -491,7 +495,7 @@ def test_layers_in_flight():
     no other; aser_error_reconstruct_enqueue / aser_finish refuse what their protocol forbids."""
     # ragged, c1 / c2 shapes, a c4-shaped layer that takes the subspace iteration (the others are small enough for
     # the dense solver), W8 with outliers, tiny block
-    picks = [E2E_CASES[i] for i in (2, 3, 4, 5, 6, 9)]
+    picks = [E2E_CASES[i] for i in (2, 3, 4, 5, 6, 11)]
     assert picks[3][0] == "c4_shape_small"
     pool = [torch.cuda.Stream(device=0) for _ in range(12)]
     st, picked = aser.aser_pick_concurrent_streams([s.cuda_stream for s in pool], 3)
@@ -611,6 +615,15 @@ def test_headline_layer_full_size_rank_at_the_spectral_gap():
     say("e2e case c1 full size with r = 16")
     _, ref = run_e2e("c1_full_r16", spec, True)
     assert ref.rec.gap > 1.05
+
+
+def test_headline_layer_full_size_rank_beyond_the_subspace_block():
+    """The same layer with r = 200: ranks above 128 (the rule of Eq. 9 can ask for them) go to the dense
+    fp64 solver at any size, here with 4096 eigenvalues and stored reflectors."""
+    spec = synth.CONFIGS["c1"].with_(r=200)
+    say("e2e case c1 full size with r = 200 (dense solver)")
+    assert aser.aser_svd_plan(spec.m, spec.n, spec.r) == (aser.ASER_OK, 0, 0)
+    run_e2e("c1_full_r200", spec, True)
 
 
 @pytest.mark.parametrize("cfg", ["c2", "c3.q", "c3.k", "c3.v", "c3.o", "c3.gate", "c3.up", "c3.down", "c4"])
