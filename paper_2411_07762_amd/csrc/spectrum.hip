@@ -366,59 +366,69 @@ __device__ __forceinline__ uint32_t hash32(uint32_t x) {
     return x;
 }
 
+// One step of inverse iteration on the symmetric tridiagonal matrix (d, e): x <- (T - shift I)^-1 x by Gaussian
+// elimination with row interchanges (a zero pivot becomes `tiny`), then scaled to unit maximum.  dd, du, du2: k
+// doubles each of scratch.
+__device__ __forceinline__ void invit_solve_one(int64_t k, const double* __restrict__ d, const double* __restrict__ e,
+                                                double shift, double tiny, double* x, double* dd, double* du, double* du2) {
+    double a = d[0] - shift, b = (k > 1) ? e[0] : 0.0;       // current row: diagonal and super-diagonal
+    for (int64_t i = 0; i + 1 < k; ++i) {
+        const double sub = e[i], dn = d[i + 1] - shift, en = (i + 2 < k) ? e[i + 1] : 0.0;
+        if (fabs(a) >= fabs(sub)) {
+            if (fabs(a) < tiny) a = tiny;
+            const double mult = sub / a;
+            dd[i] = a; du[i] = b; du2[i] = 0.0;
+            x[i + 1] -= mult * x[i];
+            a = dn - mult * b;
+            b = en;
+        } else {
+            const double mult = a / sub;
+            dd[i] = sub; du[i] = dn; du2[i] = en;
+            const double xi = x[i];
+            x[i] = x[i + 1];
+            x[i + 1] = xi - mult * x[i];
+            a = b - mult * dn;
+            b = -mult * en;
+        }
+    }
+    if (fabs(a) < tiny) a = tiny;
+    dd[k - 1] = a;
+    x[k - 1] /= dd[k - 1];
+    if (k > 1) x[k - 2] = (x[k - 2] - du[k - 2] * x[k - 1]) / dd[k - 2];
+    for (int64_t i = k - 3; i >= 0; --i) x[i] = (x[i] - du[i] * x[i + 1] - du2[i] * x[i + 2]) / dd[i];
+    double mx = 0.0;
+    for (int64_t i = 0; i < k; ++i) mx = fmax(mx, fabs(x[i]));
+    const double sc = mx > 0.0 ? 1.0 / mx : 1.0;
+    for (int64_t i = 0; i < k; ++i) x[i] *= sc;
+}
+
+__device__ __forceinline__ double tridiag_norm(int64_t k, const double* __restrict__ d, const double* __restrict__ e) {
+    double tnorm = 0.0;
+    for (int64_t l = 0; l < k; ++l) tnorm = fmax(tnorm, fabs(d[l]) + (l + 1 < k ? fabs(e[l]) : 0.0) + (l > 0 ? fabs(e[l - 1]) : 0.0));
+    return tnorm;
+}
+
+__device__ __forceinline__ double invit_start_value(int64_t t) {
+    return (double)(hash32((uint32_t)t * 0x9E3779B9U + 12345u) >> 8) * (1.0 / 8388608.0) - 1.0;
+}
+
 // Eigenvectors of the symmetric tridiagonal matrix (d, e) for the r largest eigenvalues lam[0 .. r),
-// as rows of X (r x k).  One workgroup.  Three rounds of: thread c solves (T - lam_c I) y = x_c by
-// Gaussian elimination with row interchanges (a zero pivot becomes eps ||T||), then the vectors are
-// orthonormalised in order (classical Gram-Schmidt, twice).  scr: r x 3 k doubles.
+// as rows of X (r x k).  One workgroup (small problems).  Three rounds of: thread c solves (T - lam_c I) y = x_c,
+// then the vectors are orthonormalised in order (classical Gram-Schmidt, twice).  scr: r x 3 k doubles.
 __global__ __launch_bounds__(256) void tridiag_invit_kernel(int64_t k, int r, const double* __restrict__ d,
                                                             const double* __restrict__ e, const double* __restrict__ lam,
                                                             double* __restrict__ X, double* __restrict__ scr) {
     __shared__ double dots[256];                      // r <= 256
     __shared__ double red[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    double tnorm = 0.0;
-    for (int64_t l = 0; l < k; ++l) tnorm = fmax(tnorm, fabs(d[l]) + (l + 1 < k ? fabs(e[l]) : 0.0) + (l > 0 ? fabs(e[l - 1]) : 0.0));
-    const double tiny = fmax(tnorm * 2.3e-16, 1e-300);
-    for (int64_t t = tid; t < (int64_t)r * k; t += 256)
-        X[t] = (double)(hash32((uint32_t)t * 0x9E3779B9U + 12345u) >> 8) * (1.0 / 8388608.0) - 1.0;
+    const double tiny = fmax(tridiag_norm(k, d, e) * 2.3e-16, 1e-300);
+    for (int64_t t = tid; t < (int64_t)r * k; t += 256) X[t] = invit_start_value(t);
     __syncthreads();
     for (int round = 0; round < 3; ++round) {
         if (tid < r) {
             const int c = tid;
-            double* x = X + (int64_t)c * k;
             double* dd = scr + (int64_t)c * 3 * k;
-            double* du = dd + k;
-            double* du2 = du + k;
-            const double shift = lam[c];
-            double a = d[0] - shift, b = (k > 1) ? e[0] : 0.0;       // current row: diagonal and super-diagonal
-            for (int64_t i = 0; i + 1 < k; ++i) {
-                const double sub = e[i], dn = d[i + 1] - shift, en = (i + 2 < k) ? e[i + 1] : 0.0;
-                if (fabs(a) >= fabs(sub)) {
-                    if (fabs(a) < tiny) a = tiny;
-                    const double mult = sub / a;
-                    dd[i] = a; du[i] = b; du2[i] = 0.0;
-                    x[i + 1] -= mult * x[i];
-                    a = dn - mult * b;
-                    b = en;
-                } else {
-                    const double mult = a / sub;
-                    dd[i] = sub; du[i] = dn; du2[i] = en;
-                    const double xi = x[i];
-                    x[i] = x[i + 1];
-                    x[i + 1] = xi - mult * x[i];
-                    a = b - mult * dn;
-                    b = -mult * en;
-                }
-            }
-            if (fabs(a) < tiny) a = tiny;
-            dd[k - 1] = a;
-            x[k - 1] /= dd[k - 1];
-            if (k > 1) x[k - 2] = (x[k - 2] - du[k - 2] * x[k - 1]) / dd[k - 2];
-            for (int64_t i = k - 3; i >= 0; --i) x[i] = (x[i] - du[i] * x[i + 1] - du2[i] * x[i + 2]) / dd[i];
-            double mx = 0.0;
-            for (int64_t i = 0; i < k; ++i) mx = fmax(mx, fabs(x[i]));
-            const double sc = mx > 0.0 ? 1.0 / mx : 1.0;
-            for (int64_t i = 0; i < k; ++i) x[i] *= sc;
+            invit_solve_one(k, d, e, lam[c], tiny, X + (int64_t)c * k, dd, dd + k, dd + 2 * k);
         }
         __syncthreads();
         for (int c = 0; c < r; ++c) {
@@ -454,6 +464,62 @@ __global__ __launch_bounds__(256) void tridiag_invit_kernel(int64_t k, int r, co
     }
 }
 
+// The same computation for large problems, one launch per step, because the orthonormalisation is r^2 k work that
+// one workgroup takes most of a second for at k = 4096, r = 200: the start vectors, the r solves (one thread each),
+// and per vector c and pass the dots against the vectors before it (one workgroup per earlier vector), the
+// update (workgroups over the k entries) and, after the second pass, the normalisation (one workgroup).
+__global__ void invit_start_kernel(int64_t total, double* __restrict__ X) {
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x)
+        X[t] = invit_start_value(t);
+}
+
+__global__ __launch_bounds__(64) void invit_solve_kernel(int64_t k, int r, const double* __restrict__ d,
+                                                         const double* __restrict__ e, const double* __restrict__ lam,
+                                                         double* __restrict__ X, double* __restrict__ scr) {
+    const int c = blockIdx.x * 64 + threadIdx.x;
+    if (c >= r) return;
+    const double tiny = fmax(tridiag_norm(k, d, e) * 2.3e-16, 1e-300);
+    double* dd = scr + (int64_t)c * 3 * k;
+    invit_solve_one(k, d, e, lam[c], tiny, X + (int64_t)c * k, dd, dd + k, dd + 2 * k);
+}
+
+__global__ __launch_bounds__(256) void invit_dots_kernel(int64_t k, int c, const double* __restrict__ X, double* __restrict__ dots) {
+    __shared__ double red[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, j = blockIdx.x;
+    const double* y = X + (int64_t)j * k;
+    const double* x = X + (int64_t)c * k;
+    double s = 0.0;
+    for (int64_t i = tid; i < k; i += 256) s += y[i] * x[i];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    if (tid == 0) dots[j] = red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(256) void invit_update_kernel(int64_t k, int c, double* __restrict__ X, const double* __restrict__ dots) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= k) return;
+    double v = X[(int64_t)c * k + i];
+    for (int j = 0; j < c; ++j) v -= dots[j] * X[(int64_t)j * k + i];
+    X[(int64_t)c * k + i] = v;
+}
+
+__global__ __launch_bounds__(256) void invit_normalize_kernel(int64_t k, int c, double* __restrict__ X) {
+    __shared__ double red[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    double* x = X + (int64_t)c * k;
+    double s = 0.0;
+    for (int64_t i = tid; i < k; i += 256) s += x[i] * x[i];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    const double nrm = sqrt(red[0] + red[1] + red[2] + red[3]);
+    const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+    for (int64_t i = tid; i < k; i += 256) x[i] *= inv;
+}
+
 // x <- H_0 H_1 ... H_{k-3} x for every row x of X (one workgroup per row): eigenvectors of the tridiagonal
 // matrix become eigenvectors of the Gram matrix.  H_j = I - tau_j v_j v_j^T, v_j in row j of vstore.
 __global__ __launch_bounds__(256) void backtransform_kernel(int64_t k, const double* __restrict__ vstore,
@@ -482,7 +548,8 @@ __global__ __launch_bounds__(256) void backtransform_kernel(int64_t k, const dou
 // LA64: m x r fp64 scratch.  Two launches: phase 0 writes L_A (and LA64), phase 1 writes L_B, sigma and the error.
 __global__ __launch_bounds__(256) void exact_factors_kernel(int phase, int left, int64_t m, int64_t n, int64_t k, int r,
                                                             const double* __restrict__ X, const double* __restrict__ lam,
-                                                            const double* __restrict__ A64, const float* __restrict__ T,
+                                                            const double* __restrict__ A64, const float* __restrict__ A32,
+                                                            const float* __restrict__ T,
                                                             int64_t ldt, double* __restrict__ LA64, float* __restrict__ L_A,
                                                             float* __restrict__ L_B, float* __restrict__ sigma,
                                                             double* __restrict__ err2) {
@@ -497,7 +564,11 @@ __global__ __launch_bounds__(256) void exact_factors_kernel(int phase, int left,
             v = X[(int64_t)c * k + i] * sg;
         } else {
             v = 0.0;
-            for (int64_t j = 0; j < n; ++j) v = fma(A64[i * n + j], X[(int64_t)c * k + j], v);
+            if (A32) {
+                for (int64_t j = 0; j < n; ++j) v = fma((double)A32[i * n + j], X[(int64_t)c * k + j], v);
+            } else {
+                for (int64_t j = 0; j < n; ++j) v = fma(A64[i * n + j], X[(int64_t)c * k + j], v);
+            }
         }
         LA64[t] = v;
         L_A[t] = (float)v;
@@ -519,7 +590,8 @@ __global__ __launch_bounds__(256) void exact_factors_kernel(int phase, int left,
 
 struct ExactPlan {
     int64_t k;
-    size_t off_a, off_b, off_vs, off_vec, off_x, off_scr, off_la, total;
+    bool big;           // a layer beyond the small ones the solver was made for: T S from the MFMA kernel, multi-launch inverse iteration
+    size_t off_a, off_b, off_vs, off_vec, off_x, off_scr, off_la, off_tt, off_dots, total;
 };
 
 void exact_plan(int64_t m, int64_t n, int r, ExactPlan* p) {
@@ -533,6 +605,9 @@ void exact_plan(int64_t m, int64_t n, int r, ExactPlan* p) {
     p->off_x = off; off += align_up((size_t)r * p->k * 8, 256);
     p->off_scr = off; off += align_up((size_t)r * 3 * p->k * 8, 256);
     p->off_la = off; off += align_up((size_t)m * r * 8, 256);
+    p->off_dots = off; off += 2048;                                 // up to 256 dot products
+    p->big = m * n > ((int64_t)1 << 20);
+    p->off_tt = off; off += p->big ? align_up((size_t)m * n * 4, 256) : 0;    // T^T for the fp32 product (A and A^T share off_a)
     p->total = off;
 }
 
@@ -581,14 +656,33 @@ int aser_exact_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, 
     double* X = (double*)(ws + pl.off_x);
     double* scr = (double*)(ws + pl.off_scr);
     double* LA64 = (double*)(ws + pl.off_la);
-    // A = T S in fp64; for m <= n stored transposed (n x m), which is the K-major operand of A A^T
-    {
+    const float* A32 = nullptr;                            // m x n, row-major: the fp32 product of large layers
+    if (pl.big) {
+        // Large layers (a rank beyond the subspace iteration's): T S from the MFMA kernel (about 2^-16 relative per
+        // product, as in the iteration and in aser_singular_values), its Gram matrix in fp64 from the widened entries
+        float* Tt = (float*)(ws + pl.off_tt);
+        float* A = (float*)(ws + pl.off_a);
+        float* At = A + (size_t)m * n;
+        ASER_TRY(aser_transpose_f32(ctx, T, m, n, ldt, Tt, m));
+        GemmArgs g{};
+        g.A = Tt; g.lda = m; g.B = S; g.ldb = lds; g.C = A; g.ldc = n; g.Ct = At; g.ldct = m;
+        g.M = m; g.N = n; g.K = n; g.alpha = 1.f;
+        g.in_type = aser_f32_form(ctx, m * n); g.epi = GEMM_EPI_STORE; g.tiles = GEMM_TILES_ALL; g.krange = GEMM_K_GE_COL;
+        g.k_parts = 1;
+        g.pair_cols = (m > 1024 && n > 1024) ? 1 : 0;
+        g.bm = g.pair_cols ? 256 : 128; g.bn = 128;
+        ASER_TRY(aser_gemm_tn(ctx, g));
+        A32 = A;
+        if (left) ASER_TRY(gram_f64<float>(ctx, At, n, k, m, B));
+        else ASER_TRY(gram_f64<float>(ctx, A, m, k, n, B));
+    } else {
+        // A = T S in fp64; for m <= n stored transposed (n x m), which is the K-major operand of A A^T
         dim3 grid((unsigned)ceil_div64(n, 64), (unsigned)ceil_div64(m, 4));
         if (left) hipLaunchKernelGGL(ts_f64_kernel<true>, grid, dim3(256), 0, ctx->stream, T, m, n, ldt, S, lds, A64);
         else hipLaunchKernelGGL(ts_f64_kernel<false>, grid, dim3(256), 0, ctx->stream, T, m, n, ldt, S, lds, A64);
         ASER_TRY(aser_check_launch(ctx, "ts_f64"));
+        ASER_TRY(gram_f64<double>(ctx, A64, left ? n : m, k, k, B));
     }
-    ASER_TRY(gram_f64<double>(ctx, A64, left ? n : m, k, k, B));
     ASER_TRY(aser_fill_bytes(ctx, vstore, (size_t)k * k * 8));
     ASER_TRY(aser_fill_bytes(ctx, vec[0], 10 * vb));
     ASER_TRY(tridiagonalize(ctx, B, k, vec, vstore, taustore));
@@ -596,16 +690,38 @@ int aser_exact_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, 
     hipLaunchKernelGGL(tridiag_bisect_kernel, dim3((unsigned)ceil_div64(k, 64)), dim3(64), 0, ctx->stream, k, (const double*)vec[4],
                        (const double*)vec[5], sig64, lam);
     ASER_TRY(aser_check_launch(ctx, "tridiag_bisect"));
-    hipLaunchKernelGGL(tridiag_invit_kernel, dim3(1), dim3(256), 0, ctx->stream, k, r, (const double*)vec[4], (const double*)vec[5],
-                       (const double*)lam, X, scr);
-    ASER_TRY(aser_check_launch(ctx, "tridiag_invit"));
+    if (pl.big) {
+        const double* dd = vec[4];
+        const double* ee = vec[5];
+        double* dots = (double*)(ws + pl.off_dots);
+        const int64_t total = (int64_t)r * k;
+        hipLaunchKernelGGL(invit_start_kernel, dim3((unsigned)(ceil_div64(total, 256) < 1024 ? ceil_div64(total, 256) : 1024)), dim3(256),
+                           0, ctx->stream, total, X);
+        for (int round = 0; round < 3; ++round) {
+            hipLaunchKernelGGL(invit_solve_kernel, dim3((unsigned)ceil_div64(r, 64)), dim3(64), 0, ctx->stream, k, r, dd, ee,
+                               (const double*)lam, X, scr);
+            for (int c = 0; c < r; ++c) {
+                for (int pass = 0; pass < 2 && c > 0; ++pass) {
+                    hipLaunchKernelGGL(invit_dots_kernel, dim3((unsigned)c), dim3(256), 0, ctx->stream, k, c, (const double*)X, dots);
+                    hipLaunchKernelGGL(invit_update_kernel, dim3((unsigned)ceil_div64(k, 256)), dim3(256), 0, ctx->stream, k, c, X,
+                                       (const double*)dots);
+                }
+                hipLaunchKernelGGL(invit_normalize_kernel, dim3(1), dim3(256), 0, ctx->stream, k, c, X);
+            }
+            ASER_TRY(aser_check_launch(ctx, "tridiag_invit (multi-launch)"));
+        }
+    } else {
+        hipLaunchKernelGGL(tridiag_invit_kernel, dim3(1), dim3(256), 0, ctx->stream, k, r, (const double*)vec[4], (const double*)vec[5],
+                           (const double*)lam, X, scr);
+        ASER_TRY(aser_check_launch(ctx, "tridiag_invit"));
+    }
     hipLaunchKernelGGL(backtransform_kernel, dim3((unsigned)r), dim3(256), 0, ctx->stream, k, (const double*)vstore,
                        (const double*)taustore, X);
     ASER_TRY(aser_check_launch(ctx, "backtransform"));
     for (int phase = 0; phase < 2; ++phase) {
         const int64_t total = phase == 0 ? m * (int64_t)r : (int64_t)r * n;
         hipLaunchKernelGGL(exact_factors_kernel, dim3((unsigned)ceil_div64(total, 256)), dim3(256), 0, ctx->stream, phase, left ? 1 : 0,
-                           m, n, k, r, (const double*)X, (const double*)lam, (const double*)A64, T, ldt, LA64, L_A, L_B, sigma,
+                           m, n, k, r, (const double*)X, (const double*)lam, (const double*)A64, A32, T, ldt, LA64, L_A, L_B, sigma,
                            err2_dev);
         ASER_TRY(aser_check_launch(ctx, "exact_factors"));
     }
