@@ -258,6 +258,63 @@ __global__ __launch_bounds__(64) void tridiag_bisect_kernel(int64_t k, const dou
     if (lam_desc) lam_desc[k - 1 - i] = lam;
 }
 
+// The same eigenvalue by multisection, one wavefront per eigenvalue: the 64 lanes take the Sturm counts of 64
+// points that cut the current interval into 65 parts, and the interval shrinks to the part where the count
+// passes i: 11 rounds for the 60 halvings of the bisection, on k wavefronts instead of k / 64 (k = 4096: the
+// sequential recurrence of 60 x k dependent divisions per thread was 25 ms on 64 compute units).
+__global__ __launch_bounds__(64) void tridiag_multisect_kernel(int64_t k, const double* __restrict__ d,
+                                                               const double* __restrict__ e, double* __restrict__ sigma,
+                                                               double* __restrict__ lam_desc) {
+    const int64_t i = blockIdx.x;
+    const int lane = threadIdx.x;
+    double lo = 1e300, hi = -1e300, emax2 = 0.0;
+    for (int64_t l = 0; l < k; ++l) {
+        const double el = (l + 1 < k) ? fabs(e[l]) : 0.0, ep = (l > 0) ? fabs(e[l - 1]) : 0.0;
+        lo = fmin(lo, d[l] - el - ep);
+        hi = fmax(hi, d[l] + el + ep);
+        emax2 = fmax(emax2, el * el);
+    }
+    const double span = fmax(hi - lo, 1e-300);
+    lo -= 1e-12 * span;
+    hi += 1e-12 * span;
+    const double pivmin = fmax(emax2 * 2.2e-308 * 4.0, 1e-300);
+    double a = lo, b = hi;
+    for (int it = 0; it < 11; ++it) {
+        const double step = (b - a) * (1.0 / 65.0);
+        const double x = a + step * (double)(lane + 1);
+        double q = d[0] - x;
+        if (fabs(q) < pivmin) q = -pivmin;
+        int64_t cnt = q < 0.0 ? 1 : 0;
+        for (int64_t l = 1; l < k; ++l) {
+            const double el = e[l - 1];
+            q = d[l] - x - el * el / q;
+            if (fabs(q) < pivmin) q = -pivmin;
+            cnt += q < 0.0 ? 1 : 0;
+        }
+        // the count grows with x: the points with cnt <= i are the first p of them
+        const int p = __popcll(__builtin_amdgcn_ballot_w64(cnt <= i));
+        const double xa = __shfl(x, p > 0 ? p - 1 : 0, 64), xb = __shfl(x, p < 64 ? p : 63, 64);
+        const double na = p > 0 ? xa : a, nb = p < 64 ? xb : b;
+        a = na;
+        b = nb;
+    }
+    if (lane == 0) {
+        const double lam = 0.5 * (a + b);
+        sigma[k - 1 - i] = lam > 0.0 ? sqrt(lam) : 0.0;
+        if (lam_desc) lam_desc[k - 1 - i] = lam;
+    }
+}
+
+// Every eigenvalue of the tridiagonal matrix: bisection with a thread each for small matrices, multisection with a
+// wavefront each from 1024 on.
+int tridiag_eigenvalues(aser_ctx* ctx, int64_t k, const double* d, const double* e, double* sigma, double* lam_desc) {
+    if (k >= 1024)
+        hipLaunchKernelGGL(tridiag_multisect_kernel, dim3((unsigned)k), dim3(64), 0, ctx->stream, k, d, e, sigma, lam_desc);
+    else
+        hipLaunchKernelGGL(tridiag_bisect_kernel, dim3((unsigned)ceil_div64(k, 64)), dim3(64), 0, ctx->stream, k, d, e, sigma, lam_desc);
+    return aser_check_launch(ctx, "tridiag_eigenvalues");
+}
+
 // Eq. 9 on a descending spectrum: running sums in index order; r = number of leading indices whose
 // cumulative share stays below alpha, at least 1.  out: r, then sum, share(r), share(r + 1) as doubles.
 __global__ void select_rank_kernel(const double* __restrict__ sigma, int64_t k, double alpha, int32_t* __restrict__ r_out,
@@ -687,9 +744,7 @@ int aser_exact_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, 
     ASER_TRY(aser_fill_bytes(ctx, vec[0], 10 * vb));
     ASER_TRY(tridiagonalize(ctx, B, k, vec, vstore, taustore));
     double* sig64 = vec[7];
-    hipLaunchKernelGGL(tridiag_bisect_kernel, dim3((unsigned)ceil_div64(k, 64)), dim3(64), 0, ctx->stream, k, (const double*)vec[4],
-                       (const double*)vec[5], sig64, lam);
-    ASER_TRY(aser_check_launch(ctx, "tridiag_bisect"));
+    ASER_TRY(tridiag_eigenvalues(ctx, k, vec[4], vec[5], sig64, lam));
     if (pl.big) {
         const double* dd = vec[4];
         const double* ee = vec[5];
@@ -782,9 +837,7 @@ extern "C" int aser_singular_values(aser_ctx* ctx, const float* T, int64_t m, in
     ASER_TRY(gram_f64(ctx, P, K, k, ldp, B));
     ASER_TRY(aser_fill_bytes(ctx, vec[0], 8 * vb));
     ASER_TRY(tridiagonalize(ctx, B, k, vec, nullptr, nullptr));
-    hipLaunchKernelGGL(tridiag_bisect_kernel, dim3((unsigned)ceil_div64(k, 64)), dim3(64), 0, ctx->stream, k, (const double*)d,
-                       (const double*)e, sigma, (double*)nullptr);
-    return aser_check_launch(ctx, "tridiag_bisect");
+    return tridiag_eigenvalues(ctx, k, d, e, sigma, nullptr);
 }
 
 extern "C" int aser_select_rank(aser_ctx* ctx, const double* sigma, int64_t k, double alpha, int32_t* r, double* stats) {
