@@ -736,6 +736,7 @@ def main():
                            "`layers_in_flight` of them on the device at a time (aser_calibrate_layers); "
                            "one_layer_at_a_time_ms is the same pass with a host wait after every layer"},
         "one_layer_at_a_time_ms": ms_per_step,
+        "sum_of_stage_ms": round(sum(stage_ms), 4),
         "layers_per_s": 1e3 / head_ms,
         "calibration_tokens_per_s": spec.tokens * 1e3 / head_ms,
         "stage_ms": {k: round(v, 4) for k, v in zip(stage_names, stage_ms)},
