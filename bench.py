@@ -192,9 +192,8 @@ def run_block(args):
             layer_ms[i] += ev[i].elapsed_time(ev[i + 1]) / args.steps
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    # The same block with four layers in flight: the four Gram updates first (each fills the device), then the
-    # seven layers through aser_calibrate_layers on the finished statistics, the widest first, then the seven
-    # per-token quantizers spread over the same streams.
+    # The same block with four layers in flight (see block_in_flight), then the seven per-token quantizers spread
+    # over the same streams.
     in_flight = None
     counts = [int(t) for t in args.in_flight.split(",") if t.strip()]
     if counts:
@@ -208,19 +207,48 @@ def run_block(args):
         order = sorted(range(len(layers)), key=lambda i: -(layers[i][0].m * layers[i][0].n * layers[i][0].n))
         owners = [(st, buf) for (_, st, buf, _) in layers if st["owner"] is buf]
 
-        phase_ms = {"grams": 0.0, "layers": 0.0, "act_quant": 0.0}
+        phase_ms = {"widest_gram_and_other_grams": 0.0, "layers": 0.0, "act_quant": 0.0}
+        streams_f = [pool[i] for i in picked]
+        layout4 = aser.ASER_CODES_INT4_PACKED
 
         def block_in_flight():
+            # The widest layer has the longest chain by far (its Gram update is 23 of the block's 29 ms of Gram time,
+            # its whitening and reconstruction 21 ms): its Gram update goes first and its five stages follow it on the
+            # same stream, with no host wait in between.  The other Gram updates start when the wide one has ended
+            # (two of them at a time fight for the device), on a second stream; the layers that need them wait for
+            # that stream on the host and then run on the remaining contexts, next to the wide layer's chain.
             t_a = time.perf_counter()
-            for st, buf in owners:                         # one after the other: each of them fills the device
-                buf.reset_statistics()
-                ctx.check(aser.aser_gram_accumulate(ctx, st["X"], buf.G, buf.abs_sum, buf.count))
-            torch.cuda.synchronize()
+            spec_w, st_w, buf_w, W_w = layers[order[0]]
+            cA, sA = fctx[0], streams_f[0]
+            with torch.cuda.stream(sA):
+                buf_w.reset_statistics()
+            cA.check(aser.aser_gram_accumulate(cA, st_w["X"], buf_w.G, buf_w.abs_sum, buf_w.count))
+            gram_done = torch.cuda.Event()
+            gram_done.record(sA)
+            cA.check(aser.aser_smooth_outliers(cA, W_w, buf_w.abs_sum, buf_w.count, buf_w.f, buf_w.idx, buf_w.mdiag))
+            cA.check(aser.aser_quantize_rtn(cA, W_w, buf_w.idx, buf_w.mdiag, buf_w.f, buf_w.bits, layout4, buf_w.codes,
+                                            buf_w.scales, buf_w.T))
+            s1, _ = aser.aser_whiten(cA, buf_w.G, buf_w.mdiag, 0.0, buf_w.S, want_info=False)
+            cA.check(s1)
+            cA.check(aser.aser_error_reconstruct_enqueue(cA, buf_w.T, buf_w.S, buf_w.r, buf_w.L_A, buf_w.L_B, buf_w.sigma,
+                                                         idx=buf_w.idx, f=buf_w.f))
+            cB, sB = fctx[1], streams_f[1]
+            sB.wait_event(gram_done)
+            for st, buf in owners:
+                if buf is buf_w:
+                    continue
+                with torch.cuda.stream(sB):
+                    buf.reset_statistics()
+                cB.check(aser.aser_gram_accumulate(cB, st["X"], buf.G, buf.abs_sum, buf.count))
+            sB.synchronize()
             t_b = time.perf_counter()
-            descs = [aser.layer_desc(layers[i][3], layers[i][2]) for i in order]
-            s2 = aser.aser_calibrate_layers(fctx, descs)
+            rest = order[1:]
+            descs = [aser.layer_desc(layers[i][3], layers[i][2]) for i in rest]
+            s2 = aser.aser_calibrate_layers(fctx[1:], descs)
             if s2 != aser.ASER_OK:
                 raise aser.AserError(s2, "aser_calibrate_layers on the block")
+            s3, err_w, _ = aser.aser_finish(cA)
+            cA.check(s3)
             t_c = time.perf_counter()
             for k, i in enumerate(order):
                 spec, st, buf, _ = layers[i]
@@ -228,9 +256,11 @@ def run_block(args):
                 c.check(aser.aser_quantize_act_rtn(c, st["X"], buf.mdiag, 8, st["codes"], st["scales"]))
             torch.cuda.synchronize()
             t_d = time.perf_counter()
-            for key, dt in (("grams", t_b - t_a), ("layers", t_c - t_b), ("act_quant", t_d - t_c)):
+            for key, dt in (("widest_gram_and_other_grams", t_b - t_a), ("layers", t_c - t_b), ("act_quant", t_d - t_c)):
                 phase_ms[key] += dt * 1e3 / args.steps
-            return {layers[i][0].name: d.err for i, d in zip(order, descs)}
+            out_e = {layers[i][0].name: d.err for i, d in zip(rest, descs)}
+            out_e[spec_w.name] = err_w
+            return out_e
 
         block_in_flight()
         torch.cuda.synchronize()
