@@ -725,6 +725,26 @@ def main():
     act_gbs = act_bytes / (act_ms * 1e-3) / 1e9
     del act_codes
 
+    # Context for the two bandwidth kernels: what a plain device-to-device copy that moves the same number of bytes
+    # (half read, half written) reaches on this device, over buffers that rotate beyond the 256 MB cache.
+    def plain_copy_gbs(total_bytes):
+        half = int(total_bytes) // 2 // 4 * 4
+        nbuf = max(2, int((600 << 20) // max(half, 1)) + 1)
+        srcs = [torch.empty(half, dtype=torch.uint8, device=dev) for _ in range(nbuf)]
+        dsts = [torch.empty(half, dtype=torch.uint8, device=dev) for _ in range(nbuf)]
+        for i in range(4):
+            dsts[i % nbuf].copy_(srcs[i % nbuf])
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for i in range(reps):
+            dsts[i % nbuf].copy_(srcs[i % nbuf])
+        c1.record()
+        torch.cuda.synchronize()
+        return 2.0 * half / (c0.elapsed_time(c1) / reps * 1e-3) / 1e9
+
+    copy_rtn_gbs = plain_copy_gbs(rtn_bytes)
+    copy_act_gbs = plain_copy_gbs(act_bytes)
+
     # What a loop of nothing but MFMA instructions reaches on this device (the clock drops under that load):
     # one workgroup of four wavefronts per compute unit, which is the occupancy of the Gram kernel and of the
     # inference kernel (256 accumulator registers per lane), and four per compute unit.
@@ -791,10 +811,14 @@ def main():
         "roofline_hbm": {"kernel": "rtn_kernel (per-channel RTN + target T)", "bound": "hbm", "achieved": rtn_gbs,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": rtn_gbs / HBM_PEAK_GBS,
                          "traffic": traffic.get("rtn_kernel") if spec.name == "c1" else None,
-                         "algorithmic_bytes_per_launch": rtn_bytes, "avg_launch_ms": rtn_ms},
+                         "algorithmic_bytes_per_launch": rtn_bytes, "avg_launch_ms": rtn_ms,
+                         "plain_copy_of_as_many_bytes_gbs": round(copy_rtn_gbs, 1),
+                         "frac_of_plain_copy": rtn_gbs / copy_rtn_gbs},
         "roofline_act_quant": {"kernel": "act_rtn_wave_kernel (per-token A8 quantizer of X M^-1)", "bound": "hbm",
                                "achieved": act_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": act_gbs / HBM_PEAK_GBS,
-                               "traffic": None, "algorithmic_bytes_per_launch": act_bytes, "avg_launch_ms": act_ms},
+                               "traffic": None, "algorithmic_bytes_per_launch": act_bytes, "avg_launch_ms": act_ms,
+                               "plain_copy_of_as_many_bytes_gbs": round(copy_act_gbs, 1),
+                               "frac_of_plain_copy": act_gbs / copy_act_gbs},
     }
     if not args.no_extras:
         out["beyond_calibration"] = extras(ctx, aser, torch, spec, buf, Ws[0], X, reps)
