@@ -46,6 +46,11 @@ __global__ void fill_zero_kernel(uint32_t* p, int64_t words) {
         p[i] = 0u;
 }
 
+__global__ void fill_zero16_kernel(uint4* p, int64_t quads) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < quads; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
 // ------------------------------------------------------------------------------------ column |.| sums
 // A workgroup is 64 column groups (16 bytes each) x 4 row lanes over a strip of rows.  Each thread
 // sums its rows in fp64; the four row lanes are combined through LDS and one fp64 atomic per
@@ -574,6 +579,12 @@ int aser_set_i32(aser_ctx* ctx, int32_t* p, int32_t v) {
 int aser_fill_bytes(aser_ctx* ctx, void* p, size_t bytes) {
     if (bytes == 0) return ASER_OK;
     if (((uintptr_t)p & 3) || (bytes & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "fill: unaligned");
+    if ((((uintptr_t)p | bytes) & 15) == 0 && bytes >= (1u << 16)) {          // large aligned ranges: 16-byte stores
+        const int64_t quads = (int64_t)(bytes / 16);
+        const int blocks16 = (int)((quads + 255) / 256 < 8192 ? (quads + 255) / 256 : 8192);
+        hipLaunchKernelGGL(fill_zero16_kernel, dim3(blocks16), dim3(256), 0, ctx->stream, (uint4*)p, quads);
+        return aser_check_launch(ctx, "fill_zero");
+    }
     const int64_t words = (int64_t)(bytes / 4);
     const int blocks = (int)((words + 255) / 256 < 4096 ? (words + 255) / 256 : 4096);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, ctx->stream, (uint32_t*)p, words);
