@@ -603,7 +603,27 @@ def test_headline_layer_full_size():
     32 Cholesky panels and the 128-wide subspace iteration all run at their real shapes."""
     spec = synth.CONFIGS["c1"]
     say("e2e case c1 full size m=%d n=%d N=%d r=%d f=%d" % (spec.m, spec.n, spec.tokens, spec.r, spec.f))
-    run_e2e("c1_full", spec, True)
+    _, ref = run_e2e("c1_full", spec, True)
+    # the same layer twice through aser_calibrate_layers, two in flight, G / T / S in the contexts' workspaces (the
+    # configuration the bench line's `value` times): the same bars against the same oracle results
+    say("c1 full size, two layers in flight")
+    pool = [torch.cuda.Stream(device=0) for _ in range(8)]
+    st, picked = aser.aser_pick_concurrent_streams([s.cuda_stream for s in pool], 2)
+    assert st == aser.ASER_OK and len(picked) == 2
+    ctxs = [aser.Context(0, stream=pool[i].cuda_stream) for i in picked]
+    W = torch.from_numpy(synth.make_weight(spec)).to(DEV)
+    X = to_dev_x(spec, synth.make_activations(spec))
+    bufs = [aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, True, intermediates=False) for _ in range(2)]
+    descs = [aser.layer_desc(W, b, X=X) for b in bufs]
+    for c in ctxs:
+        c.ensure_workspace(aser.aser_layer_workspace_bytes(descs[0]))
+    torch.cuda.synchronize()
+    assert aser.aser_calibrate_layers(ctxs, descs) == aser.ASER_OK
+    torch.cuda.synchronize()
+    for k, (b, d) in enumerate(zip(bufs, descs)):
+        assert d.status == aser.ASER_OK and d.n_iter == 9
+        b.err = d.err
+        check_layer("c1_full_in_flight_%d" % k, spec, True, b, ref)
 
 
 def test_headline_layer_full_size_rank_at_the_spectral_gap():
