@@ -17,6 +17,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libaser.so")
+CLIENT = os.path.join(PKG, "aser_abi_client")            # tests/native/abi_client.cpp: a caller without Python or PyTorch
+CLIENT_SRC = os.path.join(ROOT, "tests", "native", "abi_client.cpp")
 OBJDIR = os.path.join(PKG, "_build")
 
 SOURCES = ["api.hip", "gemm_tn.hip", "bandwidth.hip", "smooth.hip", "dense_small.hip", "chol_block.hip", "eig_sym.hip", "whiten.hip", "reconstruct.hip", "spectrum.hip", "evaluate.hip", "forward.hip", "probe.hip", "layers.hip"]
@@ -53,6 +55,15 @@ def build_library(verbose: bool = True) -> str:
     os.replace(tmp, LIB)
     if verbose:
         print("built", LIB, file=sys.stderr)
+    if os.path.exists(CLIENT_SRC):
+        cmd = [_hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", INCLUDE, CLIENT_SRC, "-o", CLIENT + ".tmp",
+               "-L", PKG, "-laser", "-Wl,-rpath,$ORIGIN"]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("building the native client failed:\n%s\n%s" % (res.stdout, res.stderr))
+        os.replace(CLIENT + ".tmp", CLIENT)
+        if verbose:
+            print("built", CLIENT, file=sys.stderr)
     return LIB
 
 
