@@ -219,6 +219,11 @@ int aser_error_reconstruct(aser_ctx* ctx, const float* T, int64_t m, int64_t n, 
  * to pinned host memory, and returns without waiting for the device: same arguments, same results in the
  * same buffers.  aser_finish waits for the context's stream and returns what aser_error_reconstruct
  * returns: its status (with what asynchronous calls left pending), *err and *n_iter (host, may be NULL).
+ * Everything aser_error_reconstruct_enqueue and the stage calls before it enqueue is kernels and one
+ * device-to-host copy into pinned memory (no memset nodes, no allocation, no host wait), so a layer's five
+ * stages can be captured into a HIP graph on the context's stream after one eager pass (which sets function
+ * attributes and allocates the pinned status block); a replay leaves the squared whitened error as the double
+ * at byte 16 of the last 256 bytes of the workspace.
  * Between the two, the context accepts no other call that synchronises or rebinds the workspace
  * (ASER_ERR_INVALID_ARG), and the workspace and all buffers of the layer stay untouched by the caller. */
 int aser_error_reconstruct_enqueue(aser_ctx* ctx, const float* T, int64_t m, int64_t n, int64_t ldt,

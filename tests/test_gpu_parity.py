@@ -557,6 +557,67 @@ def test_layers_in_flight():
     assert aser.aser_finish(ctx)[0] == aser.ASER_ERR_INVALID_ARG
 
 
+def test_layer_chain_under_graph_capture():
+    """The five stages of a layer captured into a HIP graph on the context's stream (aser_error_reconstruct_enqueue:
+    nothing in the chain waits for the device, every clearing pass is a fill kernel) and replayed three times, with
+    eager calibrations of another layer and synchronisations between the replays: every replay gives the codes,
+    scales and outlier set of the eager run bit for bit, factors that meet the bars against the oracle, and the
+    whitened error in the status block that the graph's copy node brings to the host."""
+    name, spec, packed = E2E_CASES[5]                               # c4-shaped: the subspace iteration
+    other = E2E_CASES[3][1]
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    ref = oracle_layer(spec, W, x_np)
+    Wd, Xd = torch.from_numpy(W).to(DEV), to_dev_x(spec, x_np)
+    Wo, Xo = torch.from_numpy(synth.make_weight(other)).to(DEV), to_dev_x(other, synth.make_activations(other))
+    s = torch.cuda.Stream(device=0)
+    ctx = aser.Context(0, stream=s.cuda_stream)
+    buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, packed)
+    ctx.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, spec.r))
+    layout = aser.ASER_CODES_INT4_PACKED if packed else aser.ASER_CODES_INT8
+
+    def enqueue():
+        buf.reset_statistics()
+        ctx.check(aser.aser_gram_accumulate(ctx, Xd, buf.G, buf.abs_sum, buf.count))
+        ctx.check(aser.aser_smooth_outliers(ctx, Wd, buf.abs_sum, buf.count, buf.f, buf.idx, buf.mdiag))
+        ctx.check(aser.aser_quantize_rtn(ctx, Wd, buf.idx, buf.mdiag, buf.f, buf.bits, layout, buf.codes, buf.scales, buf.T))
+        st, _ = aser.aser_whiten(ctx, buf.G, buf.mdiag, 0.0, buf.S, want_info=False)
+        ctx.check(st)
+        ctx.check(aser.aser_error_reconstruct_enqueue(ctx, buf.T, buf.S, buf.r, buf.L_A, buf.L_B, buf.sigma, idx=buf.idx, f=buf.f))
+
+    with torch.cuda.stream(s):
+        enqueue()                                                   # eager once: function attributes, pinned status block
+        st, err_eager, _ = aser.aser_finish(ctx)
+        ctx.check(st)
+    torch.cuda.synchronize()
+    buf.err = err_eager
+    check_layer(name + " eager", spec, packed, buf, ref)
+    eager = [t.clone() for t in (buf.codes, buf.scales, buf.idx)]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        enqueue()
+    st, _, _ = aser.aser_finish(ctx)                                # nothing ran: this only ends the pending state of the capture
+    ctx.check(st)
+    ctx2 = new_ctx()
+    buf2 = aser.LayerBuffers(other.m, other.n, other.r, other.f, other.bits, True)
+    for rep in range(3):
+        for t in (buf.codes, buf.scales, buf.idx, buf.L_A, buf.L_B, buf.sigma):
+            t.zero_()
+        aser.calibrate_layer(ctx2, Wo, Xo, buf2)                    # eager work of the program between the replays
+        torch.cuda.synchronize()
+        say("graph replay %d of layer %s" % (rep, name))
+        g.replay()
+        torch.cuda.synchronize()
+        for t, e in zip((buf.codes, buf.scales, buf.idx), eager):
+            assert torch.equal(t, e)
+        # this replay's squared whitened error: the double at byte 16 of the status block, which is the last 256
+        # bytes of the bound workspace
+        off = (-ctx._ws.data_ptr()) % 256 + ctx._ws_bytes - 256
+        buf.err = float(ctx._ws[off + 16:off + 24].view(torch.float64).item()) ** 0.5
+        assert abs(buf.err - err_eager) <= 1e-4 * err_eager
+        check_layer(name + " replay %d" % rep, spec, packed, buf, ref)
+
+
 # Layers that a randomized sweep found beyond the bars while every fp32 product was three bf16 products
 # (2^-16): int8 weights with smoothed outlier columns, a few hundred channels at most and a rank near
 # half the width, so that the error left after compensation is a few 1e-5 of ||T S||_F.  Small problems
