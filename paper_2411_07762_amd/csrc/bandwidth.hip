@@ -657,6 +657,7 @@ extern "C" int aser_quantize_rtn(aser_ctx* ctx, const float* W, int64_t m, int64
                        (int)layout, (uint8_t*)codes, pitch, scales, T, ldt)
     if (groups <= 256 * 2) ASER_RTN_LAUNCH(2, 256);
     else if (groups <= 512 * 2) ASER_RTN_LAUNCH(2, 512);
+    else if (groups <= 768 * 2) ASER_RTN_LAUNCH(2, 768);       // 11008 columns: 1376 groups on 1536 slots instead of 2048
     else if (groups <= 1024 * 2) ASER_RTN_LAUNCH(2, 1024);
     else ASER_RTN_LAUNCH(4, 1024);
 #undef ASER_RTN_LAUNCH
@@ -679,12 +680,16 @@ extern "C" int aser_quantize_act_rtn(aser_ctx* ctx, const void* X, int x_dtype, 
     dim3 grid((unsigned)rows);
 #define ASER_ACT_LAUNCH(B, V, NT) \
     hipLaunchKernelGGL((act_rtn_kernel<B, V, NT>), grid, dim3(NT), 0, ctx->stream, X, n, ldx, mdiag, qmax, codes, scales)
-#define ASER_ACT_PICK(B)                                         \
-    do {                                                         \
-        if (groups <= 256 * 2) ASER_ACT_LAUNCH(B, 2, 256);       \
-        else if (groups <= 512 * 2) ASER_ACT_LAUNCH(B, 2, 512);  \
-        else if (groups <= 1024 * 2) ASER_ACT_LAUNCH(B, 2, 1024);\
-        else ASER_ACT_LAUNCH(B, 4, 1024);                        \
+    // at most four groups per thread (more cost registers and occupancy), then the fewest threads that cover the token
+#define ASER_ACT_PICK(B)                                          \
+    do {                                                          \
+        if (groups <= 256 * 2) ASER_ACT_LAUNCH(B, 2, 256);        \
+        else if (groups <= 256 * 3) ASER_ACT_LAUNCH(B, 3, 256);   \
+        else if (groups <= 256 * 4) ASER_ACT_LAUNCH(B, 4, 256);   \
+        else if (groups <= 512 * 3) ASER_ACT_LAUNCH(B, 3, 512);   \
+        else if (groups <= 512 * 4) ASER_ACT_LAUNCH(B, 4, 512);   \
+        else if (groups <= 1024 * 3) ASER_ACT_LAUNCH(B, 3, 1024); \
+        else ASER_ACT_LAUNCH(B, 4, 1024);                         \
     } while (0)
     const int esz = (x_dtype == ASER_DTYPE_BF16) ? 2 : 4;
     const bool wave_ok = n <= 4096 && (n & 15) == 0 && ((uintptr_t)X & 15) == 0 && ((ldx * esz) & 15) == 0 &&

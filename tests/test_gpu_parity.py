@@ -194,6 +194,8 @@ RTN_CASES = [
     ("very_wide_int4", synth.mini("q4", 6, 28672, 32, f=64, n_outliers=8), 4, True),
     ("no_outliers", synth.mini("q5", 33, 256, 128, f=0), 4, True),
     ("mid_width_int4", synth.mini("q6", 12, 6000, 64, f=16, n_outliers=8), 4, True),
+    ("width_11008_int4", synth.mini("q7", 10, 11008, 48, f=32, n_outliers=8), 4, True),      # 768 threads per row
+    ("width_13000_int8", synth.mini("q8", 7, 13000, 40, f=16, n_outliers=8), 8, False),      # 1024 threads, two groups each
 ]
 
 
@@ -231,7 +233,10 @@ def test_quantize_rtn(name, spec, bits, packed):
 
 ACT_CASES = [("bf16", synth.mini("a1", 8, 333, 70, f=5)), ("f32", synth.mini("a2", 8, 520, 33, x_dtype="f32", f=3)),
              ("wide_bf16", synth.mini("a3", 8, 4096, 16, f=8)), ("wave_ragged_bf16", synth.mini("a4", 8, 1000, 37, f=6)),
-             ("wave_f32", synth.mini("a5", 8, 2048, 9, x_dtype="f32", f=4)), ("very_wide_bf16", synth.mini("a6", 8, 14336, 5, f=8))]
+             ("wave_f32", synth.mini("a5", 8, 2048, 9, x_dtype="f32", f=4)), ("very_wide_bf16", synth.mini("a6", 8, 14336, 5, f=8)),
+             ("width_11008_bf16", synth.mini("a7", 8, 11008, 7, f=8)), ("width_9000_f32", synth.mini("a8", 8, 9000, 6, x_dtype="f32", f=5)),
+             ("width_6000_bf16", synth.mini("a9", 8, 6000, 9, f=6)), ("width_7000_f32", synth.mini("a12", 8, 7000, 5, x_dtype="f32", f=6)), ("width_20000_bf16", synth.mini("a10", 8, 20000, 5, f=8)),
+             ("width_32768_f32", synth.mini("a11", 8, 32768, 3, x_dtype="f32", f=4))]
 
 
 @pytest.mark.parametrize("name,spec", ACT_CASES, ids=[c[0] for c in ACT_CASES])
