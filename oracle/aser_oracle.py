@@ -38,7 +38,9 @@ exactness of W X = (W M)(M^-1 X), RTN invariants, and hand-computed RTN / smooth
 effective rank in closed form (equal values, rank one, a two-value entropy), the full spectrum
 against the eigenvalues of the Gram matrix, the overhead ratios of the paper's rank table, the
 compensated output by element-wise loops, and the output error without activation quantization
-against the whitened error of Eq. 8 on the calibration set itself.
+against the whitened error of Eq. 8 on the calibration set itself; the target of another weight
+quantizer through the exactness of W X = (W_q + T)(M^-1 X) for an arbitrary W_q, a lossless quantizer
+(T = W_o alone), a hand example, and the RTN case.
 Parity unpinned (the paper prints no worked example): which rounding/clipping convention
 Q(.) uses and the tie-break of the outlier selection follow the readings above.
 """
@@ -134,6 +136,23 @@ def quantize_rtn(W: np.ndarray, idx: np.ndarray, mdiag: np.ndarray, bits: int) -
     WM = W.astype(np.float64) * np.asarray(mdiag, dtype=np.float32).astype(np.float64)[None, :]
     T = WM - codes.astype(np.float64) * scales.astype(np.float64)[:, None]
     return Quantized(codes, scales, T)
+
+
+# ------------------------------------------------------------------ stage 3 with another weight quantizer (Sec. 4.1, closing remark)
+def smoothed_weight(W: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    """W_s, the matrix Algorithm 1 hands to the weight quantizer: W M with the I_f columns taken out.
+    M differs from 1 only on those columns, so this is W with the I_f columns set to zero."""
+    W_s = np.array(W, dtype=np.float32)
+    W_s[:, np.asarray(idx, dtype=np.int64)] = np.float32(0.0)
+    return W_s
+
+
+def target_from_dequantized(W: np.ndarray, mdiag: np.ndarray, Wq: np.ndarray) -> np.ndarray:
+    """T = W M - W_q for the dequantized result W_q of ANY weight-only quantizer run on W_s (the method
+    "is orthogonal to" the choice of that quantizer).  W X = (W_q + T)(M^-1 X) holds whatever W_q is;
+    where W_q keeps the I_f columns at zero, T = E_q + W_o as in Eq. 12."""
+    WM = np.asarray(W, dtype=np.float32).astype(np.float64) * np.asarray(mdiag, dtype=np.float32).astype(np.float64)[None, :]
+    return WM - np.asarray(Wq, dtype=np.float64)
 
 
 def pack_int4(codes: np.ndarray) -> np.ndarray:

@@ -411,6 +411,41 @@ def test_compensated_forward_by_loops_and_error_identities():
 
 
 # ---------------------------------------------------------------- generators
+# ---------------------------------------------------------------- another weight quantizer in place of RTN (Sec. 4.1, closing remark)
+def test_target_of_another_quantizer_hand_example():
+    W = np.array([[1.0, 2.0, -4.0], [3.0, 4.0, 0.5]], dtype=np.float32)
+    mdiag = np.array([1.0, 2.0, 1.0], dtype=np.float32)
+    Wq = np.array([[0.5, 0.0, -4.0], [3.0, 0.0, 1.0]])
+    assert np.array_equal(orc.target_from_dequantized(W, mdiag, Wq), [[0.5, 4.0, 0.0], [0.0, 8.0, -0.5]])
+    assert np.array_equal(orc.smoothed_weight(W, np.array([1], dtype=np.int32)), [[1.0, 0.0, -4.0], [3.0, 0.0, 0.5]])
+
+
+def test_target_of_another_quantizer_keeps_the_layer_exact_and_reduces_to_known_cases():
+    W, X, bits, f, r = _small_layer(seed=21)
+    _, abs_sum, cnt = orc.gram(X)
+    sm = orc.smooth_outliers(W, abs_sum, cnt, f)
+    rng = np.random.default_rng(22)
+    md = sm.mdiag.astype(np.float64)
+    Xs = X.astype(np.float64) / md[None, :]                       # tokens x n: rows of (M^-1 X)^T
+    # whatever the quantizer returned, W_q + T applied to the smoothed input gives back the layer
+    Wq = rng.standard_normal(W.shape)
+    T = orc.target_from_dequantized(W, sm.mdiag, Wq)
+    assert np.allclose(Xs @ (Wq + T).T, X.astype(np.float64) @ W.astype(np.float64).T, rtol=1e-12, atol=1e-12)
+    # a quantizer without error leaves the outlier columns W_o and nothing else
+    W_s = orc.smoothed_weight(W, sm.idx)
+    T0 = orc.target_from_dequantized(W, sm.mdiag, W_s)
+    rest = np.setdiff1d(np.arange(W.shape[1]), sm.idx)
+    assert not T0[:, rest].any()
+    assert np.array_equal(T0[:, sm.idx], sm.W_o)
+    assert not W_s[:, sm.idx].any() and np.array_equal(W_s[:, rest], W[:, rest])
+    # with RTN's own result it is the target of the RTN stage
+    q = orc.quantize_rtn(W, sm.idx, sm.mdiag, bits)
+    assert np.array_equal(orc.target_from_dequantized(W, sm.mdiag, orc.dequantize(q.codes, q.scales)), q.T)
+    # a planted mistake (M applied to W_q as well) breaks the exactness
+    Tbad = (W.astype(np.float64) - Wq) * md[None, :]
+    assert not np.allclose(Xs @ (Wq + Tbad).T, X.astype(np.float64) @ W.astype(np.float64).T, rtol=1e-6)
+
+
 def test_synth_is_chunk_addressable_and_bf16_exact():
     spec = synth.mini("t", 8, 32, 3 * synth.CHUNK + 100)
     full = synth.make_activations(spec)
