@@ -86,6 +86,9 @@ for _i, (_nm, _m, _n, _sid) in enumerate([
         ("down", 4096, 14336, 303)]):
     CONFIGS["c3." + _nm] = _gauss_layer("c3." + _nm, _m, _n, _C3_TOKENS, 310 + _i, _sid)
 C3_LAYERS = tuple(k for k in CONFIGS if k.startswith("c3."))
+# qkv: the block's three attention projections fused into one linear layer (the "qkv_proj" of the paper's
+# singular-value figure): 4096 + 1024 + 1024 output rows on the attention input
+CONFIGS["qkv"] = _gauss_layer("qkv", 6144, 4096, _C3_TOKENS, 320, 300)
 
 
 def mini(name: str, m: int, n: int, tokens: int, *, x_dtype="bf16", x_dist="gauss", n_outliers=3,

@@ -157,6 +157,21 @@ int aser_quantize_rtn(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64
                       const int32_t* idx, const float* mdiag, int32_t f, int32_t bits, int32_t layout,
                       void* codes, float* scales, float* T, int64_t ldt);
 
+/* Stage 3 with another weight quantizer (Sec. 4.1, closing remark: the reconstruction builds on any
+ * weight-only quantizer, not only RTN).  The caller's quantizer runs between these two calls, on the device:
+ *     aser_smoothed_weight:  W_s[o][j] = 0 for j in idx, else W[o][j]          (what Alg. 1 quantizes)
+ *     aser_quant_target:     T[o][j]   = W[o][j] * mdiag[j] - Wq[o][j]         (one fused multiply-add, fp32)
+ * Wq is the dequantized result of that quantizer on W_s (m x n fp32, ldq).  W X = (Wq + T)(M^-1 X) holds
+ * whatever Wq is; where Wq keeps the idx columns at zero, T = E_q + W_o as in Eq. 12, and T then goes to
+ * aser_error_reconstruct like the T of aser_quantize_rtn.  W_s: m x n fp32, ldws, must not overlap W.
+ * T: m x n fp32, ldt; T may be Wq itself (in place, same leading dimension).  idx may be NULL when f == 0
+ * (W_s = W); entries of idx outside [0, n) are skipped.  mdiag may be NULL (M = I).  Never synchronise,
+ * need no workspace. */
+int aser_smoothed_weight(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                         const int32_t* idx, int32_t f, float* Ws, int64_t ldws);
+int aser_quant_target(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw, const float* mdiag,
+                      const float* Wq, int64_t ldq, float* T, int64_t ldt);
+
 /* Stage 4a (Eq. 5: S^-1 X X^T S^-T = I, S by Cholesky decomposition; Alg. 1 uses M^-1 X).
  *     G'[i][j] = G[i][j] / (mdiag[i] * mdiag[j])  (+ damp * mean(diag G') on the diagonal)
  *     S = lower Cholesky factor, S S^T = G'

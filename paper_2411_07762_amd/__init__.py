@@ -40,7 +40,7 @@ EXPORTS = (
     "aser_output_error_workspace_bytes", "aser_layer_output_error",
     "aser_forward_workspace_bytes", "aser_compensated_forward", "aser_mfma_rate_probe",
     "aser_error_reconstruct_enqueue", "aser_finish", "aser_calibrate_layers", "aser_pick_concurrent_streams",
-    "aser_layer_workspace_bytes",
+    "aser_layer_workspace_bytes", "aser_smoothed_weight", "aser_quant_target",
 )
 
 
@@ -102,6 +102,10 @@ def load_library() -> ctypes.CDLL:
     lib.aser_smooth_outliers_noalloc.argtypes = lib.aser_smooth_outliers.argtypes
     lib.aser_quantize_rtn.restype = ctypes.c_int
     lib.aser_quantize_rtn.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, i32, i32, vp, vp, vp, i64]
+    lib.aser_smoothed_weight.restype = ctypes.c_int
+    lib.aser_smoothed_weight.argtypes = [vp, vp, i64, i64, i64, vp, i32, vp, i64]
+    lib.aser_quant_target.restype = ctypes.c_int
+    lib.aser_quant_target.argtypes = [vp, vp, i64, i64, i64, vp, vp, i64, vp, i64]
     lib.aser_whiten.restype = ctypes.c_int
     lib.aser_whiten.argtypes = [vp, vp, i64, i64, vp, f32, vp, i64, ctypes.POINTER(ctypes.c_int32)]
     lib.aser_error_reconstruct.restype = ctypes.c_int
@@ -273,6 +277,21 @@ def aser_quantize_rtn(ctx: Context, W, idx, mdiag, f: int, bits: int, layout: in
     return ctx._lib.aser_quantize_rtn(ctx.handle, _ptr(W), m, n, _ld(W, n) if ldw is None else ldw, _ptr(idx),
                                       _ptr(mdiag), f, bits, layout, _ptr(codes), _ptr(scales), _ptr(T),
                                       (_ld(T, n) if T is not None else n) if ldt is None else ldt)
+
+
+def aser_smoothed_weight(ctx: Context, W, idx, f: int, Ws, *, m=None, n=None, ldw=None, ldws=None) -> int:
+    m = W.shape[0] if m is None else m
+    n = W.shape[1] if n is None else n
+    return ctx._lib.aser_smoothed_weight(ctx.handle, _ptr(W), m, n, _ld(W, n) if ldw is None else ldw, _ptr(idx), f,
+                                         _ptr(Ws), _ld(Ws, n) if ldws is None else ldws)
+
+
+def aser_quant_target(ctx: Context, W, mdiag, Wq, T, *, m=None, n=None, ldw=None, ldq=None, ldt=None) -> int:
+    m = W.shape[0] if m is None else m
+    n = W.shape[1] if n is None else n
+    return ctx._lib.aser_quant_target(ctx.handle, _ptr(W), m, n, _ld(W, n) if ldw is None else ldw, _ptr(mdiag),
+                                      _ptr(Wq), _ld(Wq, n) if ldq is None else ldq, _ptr(T),
+                                      _ld(T, n) if ldt is None else ldt)
 
 
 def aser_whiten(ctx: Context, G, mdiag, damp: float, S, *, n=None, ldg=None, lds=None, want_info: bool = True):

@@ -322,6 +322,72 @@ __global__ __launch_bounds__(NT) void rtn_kernel(const float* __restrict__ W, in
     }
 }
 
+// ------------------------------------------------------------------------------------ other weight quantizers
+// The two element-wise passes around a caller's own weight quantizer (Sec. 4.1, closing remark).  A workgroup takes
+// 1024 columns of 8 rows, a thread four consecutive columns of each row (16-byte accesses where base and leading
+// dimensions allow).  TARGET: out = W * m - Wq in one fused multiply-add.  Otherwise out = W with the outlier
+// columns cleared; their bitmask for this workgroup's columns is built in LDS first.
+template <bool TARGET>
+__global__ __launch_bounds__(256) void base_quantizer_kernel(const float* __restrict__ W, int64_t m, int64_t n, int64_t ldw,
+                                                             const int32_t* __restrict__ idx, int f,
+                                                             const float* __restrict__ mdiag, const float* Wq, int64_t ldq,
+                                                             float* out, int64_t ldo, int vec) {
+    __shared__ uint32_t mask[32];
+    const int tid = threadIdx.x;
+    const int64_t c0 = (int64_t)blockIdx.x * 1024, c = c0 + 4 * tid, r0 = (int64_t)blockIdx.y * 8;
+    float mm[4] = {1.f, 1.f, 1.f, 1.f};
+    uint32_t drop = 0u;                                  // bit e: column c + e is an outlier column
+    if (TARGET) {
+        if (mdiag) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (c + e < n) mm[e] = mdiag[c + e];
+        }
+    } else {
+        if (tid < 32) mask[tid] = 0u;
+        __syncthreads();
+        for (int i = tid; i < f; i += 256) {
+            const int64_t k = (int64_t)idx[i] - c0;
+            if (idx[i] >= 0 && idx[i] < n && k >= 0 && k < 1024) atomicOr(&mask[k >> 5], 1u << (k & 31));
+        }
+        __syncthreads();
+        drop = (mask[tid >> 3] >> (4 * (tid & 7))) & 0xFu;
+    }
+    if (c >= n) return;
+    const bool full = vec && c + 4 <= n;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int64_t r = r0 + i;
+        if (r >= m) break;
+        float w[4] = {0.f, 0.f, 0.f, 0.f}, q[4] = {0.f, 0.f, 0.f, 0.f}, o[4];
+        if (full) {
+            const f32x4_t x = __builtin_nontemporal_load((const f32x4_t*)(W + r * ldw + c));
+            w[0] = x.x; w[1] = x.y; w[2] = x.z; w[3] = x.w;
+            if (TARGET) {
+                const f32x4_t y = __builtin_nontemporal_load((const f32x4_t*)(Wq + r * ldq + c));
+                q[0] = y.x; q[1] = y.y; q[2] = y.z; q[3] = y.w;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (c + e < n) {
+                    w[e] = W[r * ldw + c + e];
+                    if (TARGET) q[e] = Wq[r * ldq + c + e];
+                }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = TARGET ? __fmaf_rn(w[e], mm[e], -q[e]) : (((drop >> e) & 1u) ? 0.f : w[e]);
+        if (full) {
+            const f32x4_t z = {o[0], o[1], o[2], o[3]};
+            __builtin_nontemporal_store(z, (f32x4_t*)(out + r * ldo + c));
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (c + e < n) out[r * ldo + c + e] = o[e];
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------ activation RTN
 // One workgroup per token (256 to 1024 threads).  X' = X / m with an IEEE fp32 division, per-token
 // absmax scale.  A thread owns groups of 8 consecutive channels: one 16-byte load of bf16 (two of
@@ -662,6 +728,49 @@ extern "C" int aser_quantize_rtn(aser_ctx* ctx, const float* W, int64_t m, int64
     else ASER_RTN_LAUNCH(4, 1024);
 #undef ASER_RTN_LAUNCH
     return aser_check_launch(ctx, "rtn");
+}
+
+// ---------------------------------------------------------------------------------------- ABI: stage 3 around another quantizer
+namespace {
+int base_quantizer_launch(aser_ctx* ctx, bool target, const float* W, int64_t m, int64_t n, int64_t ldw, const int32_t* idx,
+                          int32_t f, const float* mdiag, const float* Wq, int64_t ldq, float* out, int64_t ldo) {
+    ASER_TRY(aser_prepare_device(ctx));
+    const bool vec = (((uintptr_t)W | (uintptr_t)out | (uintptr_t)Wq) & 15) == 0 && ((ldw | ldo | ldq) & 3) == 0;
+    for (int64_t r0 = 0; r0 < m; r0 += 8 * 65535) {             // the grid's second dimension holds 65535 row blocks
+        const int64_t rows = m - r0 < 8 * 65535 ? m - r0 : 8 * 65535;
+        dim3 grid((unsigned)ceil_div64(n, 1024), (unsigned)ceil_div64(rows, 8));
+        const float* q = Wq ? Wq + r0 * ldq : nullptr;
+        if (target)
+            hipLaunchKernelGGL(base_quantizer_kernel<true>, grid, dim3(256), 0, ctx->stream, W + r0 * ldw, rows, n, ldw, idx, (int)f,
+                               mdiag, q, ldq, out + r0 * ldo, ldo, vec ? 1 : 0);
+        else
+            hipLaunchKernelGGL(base_quantizer_kernel<false>, grid, dim3(256), 0, ctx->stream, W + r0 * ldw, rows, n, ldw, idx, (int)f,
+                               mdiag, q, ldq, out + r0 * ldo, ldo, vec ? 1 : 0);
+    }
+    return aser_check_launch(ctx, target ? "quant_target" : "smoothed_weight");
+}
+}  // namespace
+
+extern "C" int aser_smoothed_weight(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                                    const int32_t* idx, int32_t f, float* Ws, int64_t ldws) {
+    if (!ctx) return ASER_ERR_INVALID_ARG;
+    if (!W || !Ws) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smoothed_weight: null pointer");
+    if (m <= 0 || n <= 0 || ldw < n || ldws < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smoothed_weight: bad shape");
+    if (f < 0 || f > n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "smoothed_weight: f out of range");
+    if (f > 0 && !idx) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smoothed_weight: idx needed when f > 0");
+    if (((uintptr_t)W & 3) || ((uintptr_t)Ws & 3)) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "smoothed_weight: misaligned pointer");
+    return base_quantizer_launch(ctx, false, W, m, n, ldw, idx, f, nullptr, nullptr, 0, Ws, ldws);
+}
+
+extern "C" int aser_quant_target(aser_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw, const float* mdiag,
+                                 const float* Wq, int64_t ldq, float* T, int64_t ldt) {
+    if (!ctx) return ASER_ERR_INVALID_ARG;
+    if (!W || !Wq || !T) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "quant_target: null pointer");
+    if (m <= 0 || n <= 0 || ldw < n || ldq < n || ldt < n) ASER_FAIL(ctx, ASER_ERR_SHAPE, "quant_target: bad shape");
+    if (T == Wq && ldt != ldq) ASER_FAIL(ctx, ASER_ERR_SHAPE, "quant_target: in place needs ldt == ldq");
+    if (((uintptr_t)W & 3) || ((uintptr_t)Wq & 3) || ((uintptr_t)T & 3) || (mdiag && ((uintptr_t)mdiag & 3)))
+        ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "quant_target: misaligned pointer");
+    return base_quantizer_launch(ctx, true, W, m, n, ldw, nullptr, 0, mdiag, Wq, ldq, T, ldt);
 }
 
 // ---------------------------------------------------------------------------------------- ABI: activation RTN

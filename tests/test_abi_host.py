@@ -106,6 +106,20 @@ def test_rtn_validation(ctx):
     assert q(ctx, P, P, P, 2, 4, 0, P, P, P, m=4, n=40000) == aser.ASER_ERR_SHAPE
 
 
+def test_passes_around_another_quantizer_validation(ctx):
+    sw, qt = aser.aser_smoothed_weight, aser.aser_quant_target
+    assert sw(ctx, None, P, 2, P, m=4, n=8) == aser.ASER_ERR_INVALID_ARG
+    assert sw(ctx, P, None, 2, P, m=4, n=8) == aser.ASER_ERR_INVALID_ARG                # idx needed when f > 0
+    assert sw(ctx, P, P, 9, P, m=4, n=8) == aser.ASER_ERR_SHAPE                          # f > n
+    assert sw(ctx, P, P, 2, P, m=4, n=8, ldws=7) == aser.ASER_ERR_SHAPE
+    assert sw(ctx, P + 2, P, 2, P, m=4, n=8) == aser.ASER_ERR_INVALID_ARG               # misaligned
+    assert qt(ctx, P, P, None, P, m=4, n=8) == aser.ASER_ERR_INVALID_ARG
+    assert qt(ctx, P, P, P, P, m=0, n=8) == aser.ASER_ERR_SHAPE
+    assert qt(ctx, P, P, P, P, m=4, n=8, ldq=4) == aser.ASER_ERR_SHAPE
+    assert qt(ctx, P, P, P, P, m=4, n=8, ldq=8, ldt=12) == aser.ASER_ERR_SHAPE          # in place with another leading dimension
+    assert "in place" in ctx.last_error()
+
+
 def test_whiten_and_reconstruct_validation(ctx):
     st, _ = aser.aser_whiten(ctx, P, None, -1.0, P, n=8, ldg=8, lds=8)
     assert st == aser.ASER_ERR_INVALID_ARG

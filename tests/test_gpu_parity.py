@@ -231,6 +231,106 @@ def test_quantize_rtn(name, spec, bits, packed):
         assert ref.scales[3] == 1.0 and not got[3].any()
 
 
+BASE_QUANTIZER_CASES = [
+    ("ragged", synth.mini("bq1", 37, 333, 64, f=6, n_outliers=4), 0),
+    ("padded_rows", synth.mini("bq2", 130, 1032, 64, f=16, n_outliers=8), 4),
+    ("unaligned_rows", synth.mini("bq3", 21, 2050, 48, f=9, n_outliers=4), 3),
+    ("several_column_chunks", synth.mini("bq4", 19, 5000, 40, f=40, n_outliers=8), 0),
+    ("no_outliers", synth.mini("bq5", 16, 256, 40, f=0, n_outliers=0), 0),
+]
+
+
+def groupwise_quantizer(W_s, bits=4, group=64):
+    """A stand-in for the caller's own weight quantizer (not part of the library or of the oracle): asymmetric
+    round-to-nearest with a scale and a zero point per group of `group` input channels, in fp32.  Zero stays zero."""
+    W_s = np.asarray(W_s, dtype=np.float32)
+    out = np.empty_like(W_s)
+    levels = np.float32(2 ** bits - 1)
+    for g0 in range(0, W_s.shape[1], group):
+        blk = W_s[:, g0:g0 + group]
+        lo = np.minimum(blk.min(axis=1), np.float32(0))
+        hi = np.maximum(blk.max(axis=1), np.float32(0))
+        scale = ((hi - lo) / levels).astype(np.float32)
+        scale[scale == 0] = np.float32(1)
+        zero = np.rint(-lo / scale)
+        q = np.clip(np.rint(blk / scale[:, None]) + zero[:, None], 0, levels)
+        out[:, g0:g0 + group] = ((q - zero[:, None]) * scale[:, None]).astype(np.float32)
+    return out
+
+
+@pytest.mark.parametrize("name,spec,pad", BASE_QUANTIZER_CASES, ids=[c[0] for c in BASE_QUANTIZER_CASES])
+def test_passes_around_another_weight_quantizer(name, spec, pad):
+    """aser_smoothed_weight bit-exact, aser_quant_target within the one rounding of its fused multiply-add."""
+    say("base quantizer case %s m=%d n=%d f=%d pad=%d" % (name, spec.m, spec.n, spec.f, pad))
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    _, abs_ref, cnt = orc.gram(synth.activations_as_f32(spec, x_np))
+    sm = orc.smooth_outliers(W, abs_ref, cnt, spec.f)
+    ctx = new_ctx()
+    Wd = padded(torch.from_numpy(W).to(DEV), pad)
+    idx = torch.from_numpy(sm.idx).to(DEV) if spec.f else None
+    mdiag = torch.from_numpy(sm.mdiag).to(DEV)
+    Ws = padded(torch.full((spec.m, spec.n), 7.0, dtype=torch.float32, device=DEV), pad)
+    ctx.check(aser.aser_smoothed_weight(ctx, Wd, idx, spec.f, Ws))
+    torch.cuda.synchronize()
+    ws_np = Ws.cpu().numpy()
+    assert np.array_equal(ws_np, orc.smoothed_weight(W, sm.idx))
+    Wq_np = groupwise_quantizer(ws_np)
+    ref_T = orc.target_from_dequantized(W, sm.mdiag, Wq_np)
+    Wq = padded(torch.from_numpy(Wq_np).to(DEV), pad)
+    T = padded(torch.empty((spec.m, spec.n), dtype=torch.float32, device=DEV), pad)
+    ctx.check(aser.aser_quant_target(ctx, Wd, mdiag, Wq, T))
+    torch.cuda.synchronize()
+    Tg = T.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(Tg - ref_T) <= 2.0 ** -23 * np.abs(ref_T) + 1e-37)
+    if spec.f:
+        rest = np.setdiff1d(np.arange(spec.n), sm.idx)
+        assert np.array_equal(Tg[:, sm.idx], sm.W_o.astype(np.float32))   # exact products of two fp32 values, rounded once
+        assert np.abs(Tg[:, rest]).max() < np.abs(W).max()                # only rounding error off the outlier columns
+    # in place (T is W_q's own memory) and without a smoothing diagonal
+    ctx.check(aser.aser_quant_target(ctx, Wd, mdiag, Wq, Wq))
+    ctx.check(aser.aser_quant_target(ctx, Wd, None, Ws, T))
+    torch.cuda.synchronize()
+    assert np.array_equal(Wq.cpu().numpy().astype(np.float64), Tg)
+    assert np.array_equal(T.cpu().numpy(), (W.astype(np.float64) - ws_np).astype(np.float32))
+
+
+def test_layer_with_another_weight_quantizer():
+    """Sec. 4.1's closing remark end to end: a group-wise asymmetric quantizer takes RTN's place between
+    aser_smoothed_weight and aser_quant_target; the factors meet the same bars against the oracle run on the same W_q."""
+    from types import SimpleNamespace
+    spec = synth.CONFIGS["c1"].with_(m=640, n=1024, tokens=4096, r=32, f=16, n_outliers=8)
+    say("layer with a group-wise quantizer m=%d n=%d r=%d f=%d" % (spec.m, spec.n, spec.r, spec.f))
+    W = synth.make_weight(spec)
+    x_np = synth.make_activations(spec)
+    ref_rtn = oracle_layer(spec, W, x_np)
+    ctx = new_ctx()
+    buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, False)
+    ctx.ensure_workspace(aser.aser_workspace_bytes(spec.m, spec.n, spec.r))
+    Wd = torch.from_numpy(W).to(DEV)
+    ctx.check(aser.aser_gram_accumulate(ctx, to_dev_x(spec, x_np), buf.G, buf.abs_sum, buf.count))
+    ctx.check(aser.aser_smooth_outliers(ctx, Wd, buf.abs_sum, buf.count, spec.f, buf.idx, buf.mdiag))
+    Ws = torch.empty_like(Wd)
+    ctx.check(aser.aser_smoothed_weight(ctx, Wd, buf.idx, spec.f, Ws))
+    torch.cuda.synchronize()
+    assert buf.idx.cpu().numpy()[:spec.f].tolist() == ref_rtn.smooth.idx.tolist()
+    Wq_np = groupwise_quantizer(Ws.cpu().numpy())                     # the caller's quantizer
+    Wq = torch.from_numpy(Wq_np).to(DEV)
+    ctx.check(aser.aser_quant_target(ctx, Wd, buf.mdiag, Wq, buf.T))
+    st, info = aser.aser_whiten(ctx, buf.G, buf.mdiag, 0.0, buf.S)
+    ctx.check(st)
+    assert info == 0
+    st, err, _ = aser.aser_error_reconstruct(ctx, buf.T, buf.S, spec.r, buf.L_A, buf.L_B, buf.sigma, idx=buf.idx, f=spec.f)
+    ctx.check(st)
+    T_ref = orc.target_from_dequantized(W, ref_rtn.smooth.mdiag, Wq_np)
+    ref = SimpleNamespace(quant=SimpleNamespace(T=T_ref), S=ref_rtn.S, rec=orc.error_reconstruct(T_ref, ref_rtn.S, spec.r))
+    rec = check_reconstruction(spec, ref, buf.L_A.cpu().numpy(), buf.L_B.cpu().numpy(), buf.sigma.cpu().numpy(), err,
+                               "group-wise quantizer")
+    say("whitened error: group-wise %.5g (uncompensated %.5g), per-channel RTN %.5g (uncompensated %.5g)" %
+        (rec.err, rec.err0, ref_rtn.rec.err, ref_rtn.rec.err0))
+    assert rec.err < ref_rtn.rec.err                                  # finer scales leave less to compensate
+
+
 ACT_CASES = [("bf16", synth.mini("a1", 8, 333, 70, f=5)), ("f32", synth.mini("a2", 8, 520, 33, x_dtype="f32", f=3)),
              ("wide_bf16", synth.mini("a3", 8, 4096, 16, f=8)), ("wave_ragged_bf16", synth.mini("a4", 8, 1000, 37, f=6)),
              ("wave_f32", synth.mini("a5", 8, 2048, 9, x_dtype="f32", f=4)), ("very_wide_bf16", synth.mini("a6", 8, 14336, 5, f=8)),
@@ -712,7 +812,7 @@ def test_headline_layer_full_size_rank_beyond_the_subspace_block():
     run_e2e("c1_full_r200", spec, True)
 
 
-@pytest.mark.parametrize("cfg", ["c2", "c3.q", "c3.k", "c3.v", "c3.o", "c3.gate", "c3.up", "c3.down", "c4"])
+@pytest.mark.parametrize("cfg", ["c2", "c3.q", "c3.k", "c3.v", "c3.o", "c3.gate", "c3.up", "c3.down", "c4", "qkv"])
 def test_large_layers_full_size(cfg):
     """Full-size layers whose oracle SVD takes minutes: the 4096 x 11008 layer with 65536 tokens of
     heavy-tailed activations, the seven layers of the Llama-3-8B-shaped block with 131072 tokens per
