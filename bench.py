@@ -6,7 +6,7 @@ One step = one pass of the whole hot path over one synthetic layer whose inputs 
 HBM: reset statistics, Gram accumulation (+ channel |x| sums), outlier selection / smoothing
 diagonal, per-channel RTN and target T, Cholesky whitening, rank-r truncated SVD and L_A, L_B.
 The default workload is the 4096 x 4096 Llama-7B-shaped projection (N = 32768 bf16 tokens, W4,
-r = 64, f = 32).  `value` is the wall clock per layer over K such steps with four layers in flight
+r = 64, f = 32).  `value` is the wall clock per layer over K such steps with sixteen layers in flight
 (aser_calibrate_layers: Algorithm 1's loop over layers, one context and stream per layer in flight);
 `one_layer_at_a_time_ms` and `stage_ms` are the same pass with a host wait after every layer.
 Prints ONE JSON line.  The "roofline" object prices the dominant kernel (the
@@ -25,6 +25,12 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+
+# HIP maps a process's streams onto four hardware queues unless told otherwise, and streams that share a queue
+# run one after the other; sixteen queues let sixteen layers' chains really run side by side (more than that
+# measured slower).  Read when the runtime initialises, so it is set before torch is imported.
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 16:
+    os.environ["GPU_MAX_HW_QUEUES"] = "16"
 
 METRIC = "per-layer ASER calibration ms + Gram/GEMM MFMA util %, 4096×4096 layer"
 BF16_PEAK_TFLOPS = 2500.0
@@ -198,7 +204,7 @@ def run_block(args):
     counts = [int(t) for t in args.in_flight.split(",") if t.strip()]
     if counts:
         pool = [torch.cuda.Stream(device=0) for _ in range(16)]
-        s_, picked = aser.aser_pick_concurrent_streams([s.cuda_stream for s in pool], max(counts))
+        s_, picked = aser.aser_pick_concurrent_streams([s.cuda_stream for s in pool], min(max(counts), len(layers)))
         ctx.check(s_)
         fctx = [aser.Context(0, stream=pool[i].cuda_stream) for i in picked]
         need = max(aser.aser_workspace_bytes(sp.m, sp.n, sp.r) for sp in specs)
@@ -525,7 +531,7 @@ def layers_in_flight(aser, torch, spec, X, Ws, n_ctx, n_layers, warmup):
     thread, n_ctx contexts with their own streams, buffers and workspaces; every layer is a full pass of the
     workload from the shared X, statistics cleared first).  Returns wall-clock ms per layer and the errors."""
     # streams that really run side by side: the runtime maps streams to four hardware queues per process
-    pool = [torch.cuda.Stream(device=0) for _ in range(16)]
+    pool = [torch.cuda.Stream(device=0) for _ in range(max(16, 4 * n_ctx))]
     st, picked = aser.aser_pick_concurrent_streams([s.cuda_stream for s in pool], n_ctx)
     if st != aser.ASER_OK:
         raise aser.AserError(st, "aser_pick_concurrent_streams")
@@ -575,7 +581,7 @@ def main():
     ap.add_argument("--clock-summary", nargs=2, metavar=("RESULT_DIR", "NOTE"),
                     help="print per-kernel shader clocks of a rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE run (no GPU needed)")
     ap.add_argument("--no-extras", action="store_true", help="skip the timings of the rows beyond the calibration path")
-    ap.add_argument("--in-flight", default="4,2", help="layers in flight (aser_calibrate_layers): the first count is the "
+    ap.add_argument("--in-flight", default="16,4,2", help="layers in flight (aser_calibrate_layers): the first count is the "
                     "headline's, the others are reported beside it; 1 or empty: one layer at a time is the headline")
     args = ap.parse_args()
     if args.traffic_summary:

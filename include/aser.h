@@ -286,7 +286,8 @@ int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_layer_desc*
 /* Workspace a context needs for this layer: aser_workspace_bytes of its shape plus the intermediates left NULL. */
 size_t aser_layer_workspace_bytes(const aser_layer_desc* layer);
 
-/* Streams for aser_calibrate_layers.  A process has few hardware queues (four by default) and the runtime maps
+/* Streams for aser_calibrate_layers.  A process has few hardware queues (four by default; the environment variable
+ * GPU_MAX_HW_QUEUES, read when the HIP runtime initialises, sets another count) and the runtime maps
  * every stream to one of them; two streams on the same queue run one after the other, however independent their
  * work.  From `n_candidates` streams (hipStream_t, created by the caller, idle) this picks up to `want` that
  * run concurrently with one another: chosen[0 .. *n_chosen) are indices into `candidates` (HOST arrays).
