@@ -129,6 +129,26 @@ int main() {
         }
     if (worst > 1e-5) { printf("deq + T != W M: %g\n", worst); return 6; }
 
+    // ---- the passes around a caller's own weight quantizer (here: keep three decimal binary digits below the row maximum)
+    float* dWs = dev_alloc<float>(m * n);
+    float* dWq = dev_alloc<float>(m * n);
+    ASER_CALL(ctx, aser_smoothed_weight(ctx, dW, m, n, n, A.idx, f, dWs, n));
+    std::vector<float> Ws(m * n), Wq(m * n), T2(m * n);
+    HIP_OK(hipMemcpy(Ws.data(), dWs, m * n * 4, hipMemcpyDeviceToHost));
+    for (int64_t o = 0; o < m; ++o)
+        for (int64_t j = 0; j < n; ++j) {
+            const bool out = std::find(idx.begin(), idx.end(), (int32_t)j) != idx.end();
+            if (Ws[o * n + j] != (out ? 0.f : W[o * n + j])) { printf("W_s differs at %ld %ld\n", (long)o, (long)j); return 9; }
+            Wq[o * n + j] = ldexpf(rintf(ldexpf(Ws[o * n + j], 8)), -8);
+        }
+    HIP_OK(hipMemcpy(dWq, Wq.data(), m * n * 4, hipMemcpyHostToDevice));
+    ASER_CALL(ctx, aser_quant_target(ctx, dW, m, n, n, A.mdiag, dWq, n, dWq, n));     // in place
+    HIP_OK(hipMemcpy(T2.data(), dWq, m * n * 4, hipMemcpyDeviceToHost));
+    for (int64_t i = 0; i < m * n; ++i) {
+        const double want = (double)W[i] * (double)mdiag[i % n] - (double)Wq[i];
+        if (fabs((double)T2[i] - want) > 1.2e-7 * fabs(want)) { printf("T = W M - W_q differs at %ld\n", (long)i); return 9; }
+    }
+
     // ---- the same layer twice through aser_calibrate_layers, two contexts
     hipStream_t s1, s2;
     HIP_OK(hipStreamCreate(&s1));
