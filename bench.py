@@ -687,20 +687,23 @@ def main():
     # above stays in the line next to it, with its stage times.
     in_flight = {}
     counts = [int(t) for t in args.in_flight.split(",") if t.strip() and int(t) > 1]
-    head_n, head_ms = 1, ms_per_step
+    head_n, head_ms, head_layers = 1, ms_per_step, args.steps
     for nl in counts:
         try:
-            ms_l, errs_l, got = layers_in_flight(aser, torch, spec, X, Ws, nl, max(args.steps, nl), args.warmup)
+            # whole rounds of nl layers (at least `steps`): a last round with fewer layers in flight than the
+            # others would time a different configuration
+            timed_layers = -(-max(args.steps, nl) // nl) * nl
+            ms_l, errs_l, got = layers_in_flight(aser, torch, spec, X, Ws, nl, timed_layers, args.warmup)
         except Exception as exc:                          # the one-at-a-time figure then stays the headline; say why
             log("layers in flight %d failed: %r" % (nl, exc))
             in_flight[str(nl)] = {"failed": repr(exc)[:200]}
             continue
         in_flight[str(nl)] = {"ms_per_layer": round(ms_l, 4), "layers_per_s": round(1e3 / ms_l, 2),
-                              "concurrent_streams": got,
+                              "concurrent_streams": got, "layers_timed": timed_layers,
                               "whitened_error_max_rel_dev": max(abs(e / err - 1.0) for e in errs_l)}
         log("layers in flight %d (on %d concurrent streams): %.3f ms per layer" % (nl, got, ms_l))
         if nl == counts[0]:
-            head_n, head_ms = got, in_flight[str(nl)]["ms_per_layer"]
+            head_n, head_ms, head_layers = got, in_flight[str(nl)]["ms_per_layer"], timed_layers
 
     # Dominant kernel alone: the Gram MFMA kernel (no statistics pass), HIP events on the launch stream, one
     # pair around every launch, and a whole layer step between two launches as in the pipeline.  (Launched
@@ -818,7 +821,9 @@ def main():
         "config": {"workload": "%s: W %dx%d fp32, X %dx%d %s, W%d per-channel RTN, r=%d, f=%d" %
                                (spec.name, spec.m, spec.n, spec.tokens, spec.n, spec.x_dtype, spec.bits, spec.r, spec.f),
                    "svd_block": svd_block, "svd_iters": svd_iters, "layers_in_flight": head_n,
-                   "note": "value = wall clock per layer over `steps` layers, every one a full pass from the resident "
+                   "layers_timed": head_layers,
+                   "note": "value = wall clock per layer over `layers_timed` layers (`steps` rounded up to whole rounds "
+                           "of `layers_in_flight`), every one a full pass from the resident "
                            "X (statistics cleared, Gram update, smoothing, RTN, whitening, reconstruction), with "
                            "`layers_in_flight` of them on the device at a time (aser_calibrate_layers); "
                            "one_layer_at_a_time_ms is the same pass with a host wait after every layer"},
