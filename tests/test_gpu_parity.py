@@ -790,6 +790,33 @@ def test_headline_layer_full_size():
         assert d.status == aser.ASER_OK and d.n_iter == 9
         b.err = d.err
         check_layer("c1_full_in_flight_%d" % k, spec, True, b, ref)
+    # sixteen contexts and twenty layers, as the bench line's headline runs them (there on streams that the
+    # runtime really runs side by side; here on whatever queues sixteen streams get): contexts are reused for the
+    # last four layers.  Integer outputs of every layer equal the verified ones; the first layer and one that ran
+    # on a reused context meet every bar, the others' errors agree with theirs.
+    say("c1 full size, twenty layers on sixteen contexts")
+    for c in ctxs:
+        c.close()
+    pool = [torch.cuda.Stream(device=0) for _ in range(16)]
+    ctxs = [aser.Context(0, stream=s.cuda_stream) for s in pool]
+    many = [aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, True, intermediates=False) for _ in range(20)]
+    descs = [aser.layer_desc(W, b, X=X) for b in many]
+    for c in ctxs:
+        c.ensure_workspace(aser.aser_layer_workspace_bytes(descs[0]))
+    torch.cuda.synchronize()
+    assert aser.aser_calibrate_layers(ctxs, descs) == aser.ASER_OK
+    torch.cuda.synchronize()
+    codes0, idx0 = bufs[0].codes.cpu(), bufs[0].idx.cpu()
+    for k, (b, d) in enumerate(zip(many, descs)):
+        assert d.status == aser.ASER_OK and d.n_iter == 9
+        assert torch.equal(b.codes.cpu(), codes0) and torch.equal(b.idx.cpu(), idx0)
+        assert torch.equal(b.scales, bufs[0].scales)
+        assert abs(d.err - ref.rec.err) <= 1e-4 * ref.rec.err
+        b.err = d.err
+    check_layer("c1_full_sixteen_contexts_first", spec, True, many[0], ref)
+    check_layer("c1_full_sixteen_contexts_reused", spec, True, many[18], ref)
+    for c in ctxs:
+        c.close()
 
 
 def test_headline_layer_full_size_rank_at_the_spectral_gap():
