@@ -352,7 +352,7 @@ def trace_summary(result_dir, note):
         agg[stream is None or "Default" in stream][name].append(dur * 1e-3)
     print(note)
     for alone, title in ((True, "Launches on the default stream (kernels running alone)"),
-                         (False, "Launches on the streams of the layers in flight (kernels sharing the device)")):
+                         (False, "Launches on the streams of the layers in flight")):
         rows = sorted(agg[alone].items(), key=lambda kv: -sum(kv[1]))[:40]
         if not rows:
             continue
