@@ -8,6 +8,8 @@
  *   aser_gram_accumulate    G += X_c^T X_c over token chunks              (Eq. 5, Alg. 1)
  *   aser_smooth_outliers    outlier set I_f and smoothing diagonal m      (Sec. 4.2, Eq. 10-11)
  *   aser_quantize_rtn       Q(W_s) and the target T = W M - Q(W_s)        (Eq. 12, Sec. 3.1)
+ *   aser_smoothed_weight,   the same stage around a weight quantizer of the caller's: W_s out,
+ *   aser_quant_target       T = W M - W_q in                              (Sec. 4.1, closing remark)
  *   aser_whiten             S = chol(M^-1 G M^-1)                         (Eq. 5, Alg. 1)
  *   aser_error_reconstruct  rank-r SVD of T S, L_A = U_r Sigma_r,
  *                           L_B = V_r^T S^-1                              (Eq. 6, Sec. 4.1)
