@@ -476,7 +476,7 @@ def extras(ctx, aser, torch, spec, buf, W, X, reps):
     ctx.ensure_workspace(aser.aser_output_error_workspace_bytes(spec.m, spec.n, sample, spec.r))
     layout = aser.ASER_CODES_INT4_PACKED if buf.packed else aser.ASER_CODES_INT8
     oe = {}
-    for act_bits, comp in ((8, True), (8, False), (6, True)):
+    for act_bits, comp in ((8, True), (8, False), (6, True), (6, False)):
         st, e, yn = aser.aser_layer_output_error(ctx, W, X[:sample], buf.mdiag, buf.codes, layout, buf.scales,
                                                  buf.L_A if comp else None, buf.L_B if comp else None,
                                                  spec.r if comp else 0, act_bits)
@@ -484,6 +484,19 @@ def extras(ctx, aser, torch, spec, buf, W, X, reps):
         oe["W%dA%d_%s" % (spec.bits, act_bits, "compensated" if comp else "rtn_only")] = e / yn
     ms = timed(lambda: aser.aser_layer_output_error(ctx, W, X[:sample], buf.mdiag, buf.codes, layout, buf.scales,
                                                     buf.L_A, buf.L_B, spec.r, 8), 3)
+    # the W8 variants of Sec. 5.1 (A8, A6, A4) on the same layer, calibrated once more with 8-bit weights
+    if spec.bits != 8 and spec.m * spec.n <= (1 << 26):
+        buf8 = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, 8, packed=False)
+        aser.calibrate_layer(ctx, W, X, buf8)
+        ctx.ensure_workspace(aser.aser_output_error_workspace_bytes(spec.m, spec.n, sample, spec.r))
+        for act_bits in (8, 6, 4):
+            for comp in (True, False):
+                st, e, yn = aser.aser_layer_output_error(ctx, W, X[:sample], buf8.mdiag, buf8.codes, aser.ASER_CODES_INT8,
+                                                         buf8.scales, buf8.L_A if comp else None, buf8.L_B if comp else None,
+                                                         spec.r if comp else 0, act_bits)
+                ctx.check(st)
+                oe["W8A%d_%s" % (act_bits, "compensated" if comp else "rtn_only")] = e / yn
+        del buf8
     res["layer_output_error"] = {"ms": ms, "sample_tokens": sample, "relative_to_exact_output_norm": oe}
     # compensated inference kernel on the whole calibration stream (tokens x n int8 codes)
     if spec.n % 32 == 0:
