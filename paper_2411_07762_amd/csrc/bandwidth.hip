@@ -725,6 +725,7 @@ extern "C" int aser_quantize_rtn(aser_ctx* ctx, const float* W, int64_t m, int64
     else if (groups <= 512 * 2) ASER_RTN_LAUNCH(2, 512);
     else if (groups <= 768 * 2) ASER_RTN_LAUNCH(2, 768);       // 11008 columns: 1376 groups on 1536 slots instead of 2048
     else if (groups <= 1024 * 2) ASER_RTN_LAUNCH(2, 1024);
+    else if (groups <= 1024 * 3) ASER_RTN_LAUNCH(3, 1024);     // 20480 columns: 2560 groups on 3072 slots instead of 4096
     else ASER_RTN_LAUNCH(4, 1024);
 #undef ASER_RTN_LAUNCH
     return aser_check_launch(ctx, "rtn");

@@ -196,6 +196,8 @@ RTN_CASES = [
     ("mid_width_int4", synth.mini("q6", 12, 6000, 64, f=16, n_outliers=8), 4, True),
     ("width_11008_int4", synth.mini("q7", 10, 11008, 48, f=32, n_outliers=8), 4, True),      # 768 threads per row
     ("width_13000_int8", synth.mini("q8", 7, 13000, 40, f=16, n_outliers=8), 8, False),      # 1024 threads, two groups each
+    ("width_20000_int4", synth.mini("q9", 5, 20000, 40, f=24, n_outliers=8), 4, True),       # 1024 threads, three groups each
+    ("width_30000_int8", synth.mini("q10", 4, 30000, 40, f=24, n_outliers=8), 8, False),     # 1024 threads, four groups each
 ]
 
 
