@@ -257,7 +257,11 @@ typedef struct aser_layer_desc {
      * once, before the call).  clear_stats != 0 (with X): G (n x n, ldg), abs_sum and count are cleared first.
      * Intermediates that the caller does not keep may be NULL and then live in the context's workspace for
      * the time the layer is in flight: G (with X given; abs_sum and count are then taken from there too and
-     * cleared), T, S.  The workspace must then hold aser_layer_workspace_bytes(layer). */
+     * cleared), T, S.  The workspace must then hold aser_layer_workspace_bytes(layer).
+     * stats_from (below) == j + 1 > 0: this layer reads the input of layers[j], an EARLIER layer of the same call
+     * that accumulates its statistics in this call (X given; G, abs_sum and count in buffers of its own, not left
+     * to the workspace): X, G, abs_sum and count of this descriptor are ignored, those of layers[j] are used once
+     * its Gram update has run (q, k, v of an attention block; gate and up of an MLP).  0: none. */
     const void* X; int32_t x_dtype; int32_t clear_stats; int64_t rows; int64_t ldx;
     float* G; int64_t ldg; double* abs_sum; int64_t* count;
     /* stage 2, aser_smooth_outliers */
@@ -266,7 +270,7 @@ typedef struct aser_layer_desc {
     /* stage 3, aser_quantize_rtn */
     int32_t layout; int32_t r; void* codes; float* scales; float* T; int64_t ldt;
     /* stage 4, aser_whiten (asynchronous form) and aser_error_reconstruct */
-    float damp; int32_t reserved; float* S; int64_t lds;
+    float damp; int32_t stats_from; float* S; int64_t lds;
     const aser_svd_opts* opts; float* L_A; float* L_B; float* sigma;
     /* results (host) */
     double err; int32_t n_iter; int32_t status;
@@ -283,7 +287,10 @@ typedef struct aser_layer_desc {
  * aser_last_error of its context until that context's next layer.  Returns ASER_OK when every layer did,
  * else the first status that was not; ASER_ERR_INVALID_ARG for null arguments or n_ctx outside [1, 64].
  * Layers in flight together must not share output buffers; inputs (X, W, finished statistics) may be
- * shared.  Host code runs on the calling thread only. */
+ * shared.  Layers on one input (stats_from): the owner's Gram update is followed by an event on its stream and
+ * the others' streams wait for that event before their first launch, so they start as soon as the statistics
+ * are there and run beside the owner's later stages; a layer whose owner was refused gets ASER_ERR_INVALID_ARG.
+ * Host code runs on the calling thread only. */
 int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_layer_desc* layers, int32_t n_layers);
 /* Workspace a context needs for this layer: aser_workspace_bytes of its shape plus the intermediates left NULL. */
 size_t aser_layer_workspace_bytes(const aser_layer_desc* layer);

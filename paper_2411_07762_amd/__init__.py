@@ -56,7 +56,7 @@ class aser_layer_desc(ctypes.Structure):
                 ("W", _vp), ("m", _i64), ("n", _i64), ("ldw", _i64), ("f", _i32), ("bits", _i32),
                 ("idx", _vp), ("mdiag", _vp),
                 ("layout", _i32), ("r", _i32), ("codes", _vp), ("scales", _vp), ("T", _vp), ("ldt", _i64),
-                ("damp", ctypes.c_float), ("reserved", _i32), ("S", _vp), ("lds", _i64),
+                ("damp", ctypes.c_float), ("stats_from", _i32), ("S", _vp), ("lds", _i64),
                 ("opts", ctypes.POINTER(aser_svd_opts)), ("L_A", _vp), ("L_B", _vp), ("sigma", _vp),
                 ("err", ctypes.c_double), ("n_iter", _i32), ("status", _i32)]
 
@@ -486,13 +486,14 @@ def calibrate_layer(ctx: Context, W, X, buf: LayerBuffers, opts: Optional[aser_s
 
 
 def layer_desc(W, buf: "LayerBuffers", X=None, clear_stats: bool = False, opts: Optional[aser_svd_opts] = None,
-               damp: float = 0.0) -> aser_layer_desc:
+               damp: float = 0.0, stats_from: Optional[int] = None) -> aser_layer_desc:
     """The descriptor of one layer for aser_calibrate_layers from its weight, its buffers and (unless the
     statistics in `buf` are already finished) its activations.  The tensors must outlive the call."""
     d = aser_layer_desc()
     if X is not None:
         d.X, d.x_dtype, d.rows, d.ldx = _ptr(X), _dtype_code(X), X.shape[0], _ld(X, buf.n)
     d.clear_stats = 1 if clear_stats else 0
+    d.stats_from = 0 if stats_from is None else stats_from + 1       # index of an earlier layer of the same call
     d.G, d.ldg, d.abs_sum, d.count = _ptr(buf.G), _ld(buf.G, buf.n) if buf.G is not None else 0, _ptr(buf.abs_sum), _ptr(buf.count)
     d.W, d.m, d.n, d.ldw, d.f, d.bits = _ptr(W), buf.m, buf.n, _ld(W, buf.n), buf.f, buf.bits
     d.idx, d.mdiag = _ptr(buf.idx), _ptr(buf.mdiag)

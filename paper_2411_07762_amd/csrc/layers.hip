@@ -5,6 +5,8 @@
 // streams.  The host enqueues a whole layer without waiting and waits for a context only when it needs it
 // for the next layer.
 #include <time.h>
+#include <stdio.h>
+#include <vector>
 
 #include "aser_internal.h"
 
@@ -49,10 +51,25 @@ size_t intermediates_bytes(const aser_layer_desc& L) {
     return extra;
 }
 
-int enqueue_layer(aser_ctx* ctx, const aser_layer_desc& in) {
+// make_ready (may be null): receives a new event that is recorded on the layer's stream behind its Gram update, for
+// the layers that share its statistics (created here, behind the first argument checks; the caller destroys it).
+// wait_for (may be null): the layer's first launch waits for it (the statistics' owner runs on another stream).
+int enqueue_layer(aser_ctx* ctx, const aser_layer_desc& in, hipEvent_t* make_ready, hipEvent_t wait_for) {
     aser_layer_desc L = in;
     if (L.m <= 0 || L.n <= 0) ASER_FAIL(ctx, ASER_ERR_SHAPE, "calibrate_layers: bad shape");
     if (!L.X && !L.G) ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "calibrate_layers: neither activations nor finished statistics");
+    hipEvent_t stats_ready = nullptr;
+    if (make_ready) {
+        if (!L.X || !L.G || !L.abs_sum || !L.count)
+            ASER_FAIL(ctx, ASER_ERR_INVALID_ARG, "calibrate_layers: a layer whose statistics others share keeps G, abs_sum and count in buffers of its own");
+        ASER_TRY(aser_prepare_device(ctx));
+        ASER_HIP(ctx, hipEventCreateWithFlags(make_ready, hipEventDisableTiming));
+        stats_ready = *make_ready;
+    }
+    if (wait_for) {
+        ASER_TRY(aser_prepare_device(ctx));
+        ASER_HIP(ctx, hipStreamWaitEvent(ctx->stream, wait_for, 0));
+    }
     if (intermediates_bytes(L) > 0) {
         // intermediates that the caller does not want to keep live in the context's workspace, behind what
         // the stage calls use for this shape (the status block stays at the very end)
@@ -82,6 +99,7 @@ int enqueue_layer(aser_ctx* ctx, const aser_layer_desc& in) {
         }
         ASER_TRY(aser_gram_accumulate(ctx, L.X, L.x_dtype, L.rows, L.n, L.ldx, L.G, L.ldg, L.abs_sum, L.count));
     }
+    if (stats_ready) ASER_HIP(ctx, hipEventRecord(stats_ready, ctx->stream));
     ASER_TRY(aser_smooth_outliers(ctx, L.W, L.m, L.n, L.ldw, L.abs_sum, L.count, L.f, L.idx, L.mdiag, nullptr, nullptr));
     ASER_TRY(aser_quantize_rtn(ctx, L.W, L.m, L.n, L.ldw, L.idx, L.mdiag, L.f, L.bits, L.layout, L.codes, L.scales, L.T, L.ldt));
     ASER_TRY(aser_whiten(ctx, L.G, L.ldg, L.n, L.mdiag, L.damp, L.S, L.lds, nullptr));
@@ -100,6 +118,13 @@ extern "C" int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_
     for (int c = 0; c < n_ctx; ++c) running[c] = -1;
     int share = n_ctx < n_layers ? n_ctx : n_layers;
     for (int c = 0; c < n_ctx; ++c) ctxs[c]->share = share > 0 ? share : 1;
+    // layers whose statistics a later layer takes over (stats_from) record an event behind their Gram update
+    std::vector<hipEvent_t> ready((size_t)n_layers, (hipEvent_t)nullptr);
+    std::vector<char> wanted((size_t)n_layers, 0), stats_ok((size_t)n_layers, 0);
+    for (int k = 0; k < n_layers; ++k) {
+        const int32_t from = layers[k].stats_from;
+        if (from >= 1 && from <= k) wanted[(size_t)from - 1] = 1;
+    }
     auto finish = [&](int c) {
         if (running[c] < 0) return;
         aser_layer_desc& L = layers[running[c]];
@@ -124,12 +149,41 @@ extern "C" int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_
         aser_layer_desc& L = layers[k];
         L.err = 0.0;
         L.n_iter = 0;
-        L.status = enqueue_layer(ctxs[c], L);
-        if (ctxs[c]->rec_pending) running[c] = k;
+        aser_ctx* ctx = ctxs[c];
+        aser_layer_desc use = L;
+        hipEvent_t wait_for = nullptr;
+        L.status = ASER_OK;
+        if (L.stats_from != 0) {
+            const int32_t j = L.stats_from - 1;
+            if (j < 0 || j >= k) {
+                snprintf(ctx->err, sizeof(ctx->err), "calibrate_layers: stats_from of layer %d must name an earlier layer (1-based)", k);
+                L.status = ASER_ERR_INVALID_ARG;
+            } else if (!stats_ok[(size_t)j]) {
+                snprintf(ctx->err, sizeof(ctx->err), "calibrate_layers: layer %d shares the statistics of layer %d, which was not started", k, j);
+                L.status = ASER_ERR_INVALID_ARG;
+            } else {
+                const aser_layer_desc& O = layers[j];               // same input: same channel count
+                if (O.n != L.n) {
+                    snprintf(ctx->err, sizeof(ctx->err), "calibrate_layers: layers %d and %d share statistics but differ in n", k, j);
+                    L.status = ASER_ERR_SHAPE;
+                }
+                use.X = nullptr;
+                use.G = O.G; use.ldg = O.ldg; use.abs_sum = O.abs_sum; use.count = O.count;
+                wait_for = ready[(size_t)j];
+            }
+        }
+        if (L.status == ASER_OK) {
+            L.status = enqueue_layer(ctx, use, wanted[(size_t)k] ? &ready[(size_t)k] : nullptr, wait_for);
+            // later layers may take the statistics over when all five stages of their owner were enqueued
+            stats_ok[(size_t)k] = (char)(wanted[(size_t)k] && ready[(size_t)k] && (L.status == ASER_OK) ? 1 : 0);
+        }
+        if (ctx->rec_pending) running[c] = k;
         else if (L.status != ASER_OK && first_bad == ASER_OK) first_bad = L.status;
     }
     for (int c = 0; c < n_ctx; ++c) finish(c);
     for (int c = 0; c < n_ctx; ++c) ctxs[c]->share = 1;
+    for (hipEvent_t e : ready)
+        if (e) (void)hipEventDestroy(e);                       // every stream that waited for it has drained
     return first_bad;
 }
 

@@ -169,6 +169,15 @@ def test_layers_in_flight_validation(ctx):
     assert [d.status for d in (bad, nostats, worse, small)] == [aser.ASER_ERR_SHAPE, aser.ASER_ERR_INVALID_ARG,
                                                                 aser.ASER_ERR_DTYPE, aser.ASER_ERR_WORKSPACE]
     assert aser.aser_layer_workspace_bytes(small) == aser.aser_workspace_bytes(8, 16, 4) + 8 * 16 * 4 + 16 * 16 * 4
+    # statistics taken over from an earlier layer of the call: the reference must point backwards, and at a layer that started
+    fwd = aser.aser_layer_desc()
+    fwd.m, fwd.n, fwd.stats_from = 8, 16, 2                                            # 1-based: layer 1, which is itself
+    back = aser.aser_layer_desc()
+    back.m, back.n, back.stats_from = 8, 16, 1                                         # layer 0, which was refused
+    st = aser.aser_calibrate_layers([ctx], [bad, fwd, back])
+    assert st == aser.ASER_ERR_SHAPE
+    assert [d.status for d in (fwd, back)] == [aser.ASER_ERR_INVALID_ARG, aser.ASER_ERR_INVALID_ARG]
+    assert "was not started" in ctx.last_error()
     assert aser.aser_layer_workspace_bytes(worse) == aser.aser_workspace_bytes(8, 16, 0)
     cnt, chosen = ctypes.c_int32(0), (ctypes.c_int32 * 2)()
     assert lib.aser_pick_concurrent_streams(0, None, 2, 1, chosen, ctypes.byref(cnt)) == aser.ASER_ERR_INVALID_ARG

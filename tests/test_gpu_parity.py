@@ -664,6 +664,55 @@ def test_layers_in_flight():
     assert aser.aser_finish(ctx)[0] == aser.ASER_ERR_INVALID_ARG
 
 
+def test_layers_that_share_an_input_in_one_call():
+    """Three layers on one input stream (the q, k, v of an attention block: different weights and output widths),
+    then two on another (gate, up), all in ONE aser_calibrate_layers call on three contexts: the first layer of
+    each group accumulates the statistics, the others name it in stats_from and wait for its Gram update only.
+    Every layer meets the bars; the shared Gram matrix is accumulated once."""
+    groups = [(synth.mini("sh_q", 320, 512, 3000, r=24, f=8, seed_id=741), [(96, 742), (128, 743)]),
+              (synth.mini("sh_gate", 700, 384, 2500, x_dist="silu_prod", r=20, f=6, seed_id=751, out=(40.0, 40.0)), [(700, 752)])]
+    pool = [torch.cuda.Stream(device=0) for _ in range(12)]
+    st, picked = aser.aser_pick_concurrent_streams([s.cuda_stream for s in pool], 3)
+    assert st == aser.ASER_OK and len(picked) == 3
+    ctxs = [aser.Context(0, stream=pool[i].cuda_stream) for i in picked]
+    layers, descs = [], []
+    for owner_spec, others in groups:
+        x_np = synth.make_activations(owner_spec)
+        X = to_dev_x(owner_spec, x_np)
+        owner_index = len(layers)
+        for k, spec in enumerate([owner_spec] + [owner_spec.with_(name="%s_%d" % (owner_spec.name, lid), m=m, layer_id=lid)
+                                                for m, lid in others]):
+            W = synth.make_weight(spec)
+            buf = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, True, intermediates=(k == 0))
+            if k == 0:
+                buf.G.fill_(3.0)                                    # clear_stats has to remove this
+            Wd = torch.from_numpy(W).to(DEV)
+            layers.append(dict(spec=spec, buf=buf, W=Wd, X=X, ref=oracle_layer(spec, W, x_np)))
+            descs.append(aser.layer_desc(Wd, buf, X=X if k == 0 else None, clear_stats=(k == 0),
+                                         stats_from=None if k == 0 else owner_index))
+    need = max(aser.aser_layer_workspace_bytes(d) for d in descs)
+    for c in ctxs:
+        c.ensure_workspace(need)
+    torch.cuda.synchronize()
+    say("layers that share an input: %s" % [L["spec"].name for L in layers])
+    assert aser.aser_calibrate_layers(ctxs, descs) == aser.ASER_OK
+    torch.cuda.synchronize()
+    for L, d in zip(layers, descs):
+        assert d.status == aser.ASER_OK, (L["spec"].name, d.status)
+        L["buf"].err = d.err
+        check_layer(L["spec"].name, L["spec"], True, L["buf"], L["ref"])
+    assert int(layers[0]["buf"].count.item()) == groups[0][0].tokens   # accumulated once, not once per layer
+    # an owner that leaves its statistics to the workspace cannot be shared
+    spec = groups[0][0]
+    lone = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, True, intermediates=False)
+    other = aser.LayerBuffers(spec.m, spec.n, spec.r, spec.f, spec.bits, True, intermediates=False)
+    bad = [aser.layer_desc(layers[0]["W"], lone, X=layers[0]["X"]), aser.layer_desc(layers[0]["W"], other, stats_from=0)]
+    assert aser.aser_calibrate_layers(ctxs, bad) == aser.ASER_ERR_INVALID_ARG
+    assert [d.status for d in bad] == [aser.ASER_ERR_INVALID_ARG, aser.ASER_ERR_INVALID_ARG]
+    for c in ctxs:
+        c.close()
+
+
 def test_layer_chain_under_graph_capture():
     """The five stages of a layer captured into a HIP graph on the context's stream (aser_error_reconstruct_enqueue:
     nothing in the chain waits for the device, every clearing pass is a fill kernel) and replayed three times, with
