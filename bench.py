@@ -278,6 +278,39 @@ def run_block(args):
                      "phase_ms": {k: round(v, 3) for k, v in phase_ms.items()},
                      "whitened_error_max_rel_dev": max(abs(errs_f[sp.name] / e - 1.0) for (sp, _, _, _), e in zip(layers, errs))}
         log("block with %d layers in flight: %.2f ms" % (len(fctx), in_flight["block_ms"]))
+
+        # The same block through ONE aser_calibrate_layers call: every layer a descriptor, the layers of one input
+        # name the layer that accumulates its statistics (stats_from), widest layers first.
+        by_name = {sp.name.split(".")[-1]: i for i, (sp, _, _, _) in enumerate(layers)}
+        plan = [("down", None), ("gate", None), ("up", "gate"), ("q", None), ("k", "q"), ("v", "q"), ("o", None)]
+
+        def block_one_call():
+            pos, descs = {}, []
+            for nm, src in plan:
+                spec, st, buf, W = layers[by_name[nm]]
+                pos[nm] = len(descs)
+                if src is None:
+                    descs.append(aser.layer_desc(W, buf, X=st["X"], clear_stats=True))
+                else:
+                    descs.append(aser.layer_desc(W, buf, stats_from=pos[src]))
+            s_ = aser.aser_calibrate_layers(fctx, descs)
+            if s_ != aser.ASER_OK:
+                raise aser.AserError(s_, "aser_calibrate_layers on the whole block")
+            for k, (nm, _) in enumerate(plan):
+                spec, st, buf, _ = layers[by_name[nm]]
+                c = fctx[k % len(fctx)]
+                c.check(aser.aser_quantize_act_rtn(c, st["X"], buf.mdiag, 8, st["codes"], st["scales"]))
+            torch.cuda.synchronize()
+            return {layers[by_name[nm]][0].name: d.err for (nm, _), d in zip(plan, descs)}
+
+        if all(nm in by_name for nm, _ in plan):
+            block_one_call()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                errs_o = block_one_call()
+            in_flight["block_ms_through_one_call"] = round((time.perf_counter() - t0) * 1e3 / args.steps, 3)
+            in_flight["whitened_error_max_rel_dev_one_call"] = max(abs(errs_o[sp.name] / e - 1.0) for (sp, _, _, _), e in zip(layers, errs))
+            log("block through one aser_calibrate_layers call: %.2f ms" % in_flight["block_ms_through_one_call"])
         for c in fctx:
             c.close()
 
