@@ -119,8 +119,16 @@ extern "C" int aser_calibrate_layers(aser_ctx* const* ctxs, int32_t n_ctx, aser_
     int share = n_ctx < n_layers ? n_ctx : n_layers;
     for (int c = 0; c < n_ctx; ++c) ctxs[c]->share = share > 0 ? share : 1;
     // layers whose statistics a later layer takes over (stats_from) record an event behind their Gram update
-    std::vector<hipEvent_t> ready((size_t)n_layers, (hipEvent_t)nullptr);
-    std::vector<char> wanted((size_t)n_layers, 0), stats_ok((size_t)n_layers, 0);
+    std::vector<hipEvent_t> ready;
+    std::vector<char> wanted, stats_ok;
+    try {                                                      // no exception crosses the ABI
+        ready.assign((size_t)n_layers, (hipEvent_t)nullptr);
+        wanted.assign((size_t)n_layers, 0);
+        stats_ok.assign((size_t)n_layers, 0);
+    } catch (...) {
+        for (int c = 0; c < n_ctx; ++c) ctxs[c]->share = 1;
+        return ASER_ERR_INVALID_ARG;
+    }
     for (int k = 0; k < n_layers; ++k) {
         const int32_t from = layers[k].stats_from;
         if (from >= 1 && from <= k) wanted[(size_t)from - 1] = 1;
